@@ -1,0 +1,163 @@
+/*
+ * prac.h - C ABI of the MI355X (gfx950) PRAC hot-path library.
+ *
+ * PRAC (Principal-Random subspace Activation Compression) keeps, for a linear
+ * layer Y = X W, only the projection C = X P of the saved activation X
+ * (N tokens x d features) onto a basis P = [Q1 | Q2] with orthonormal columns:
+ * Q1 (d x k) spans the top-k right singular vectors of X, Q2 (d x r) is an
+ * orthonormal basis of (I - Q1 Q1^T) S for a Gaussian S, and the random block
+ * is weighted by the scaling factor s = (d - k) / r so that the reconstruction
+ * X~ = C_1 Q1^T + s C_2 Q2^T is unbiased (Section 4.2, Eq. (S_o), Eq. (R),
+ * Theorem 1).  The weight gradient is then X~^T dY (Lemma 1; Alg. 2).
+ *
+ * Symbols: the paper's n, r_1, r_2 and scaling factor k are d, k, r and
+ * `scale` here; c = k + r.
+ *
+ * Conventions that hold for every entry point
+ *   - Matrices are row-major with an explicit leading dimension (elements).
+ *   - Unless marked [host], a pointer is a caller-owned DEVICE pointer valid on
+ *     the ctx device.  The library never frees or keeps user buffers.
+ *   - Work is enqueued on the ctx stream and the call returns without waiting.
+ *     Scratch memory lives in the ctx and grows (hipMalloc) on demand; a ctx
+ *     must not be used from two host threads at once.
+ *   - Return value: PRAC_OK (0) or a negative prac_status.  Shape and argument
+ *     errors are detected on the host BEFORE anything is enqueued and before
+ *     the ctx is looked at, so they can be exercised without a GPU.
+ *   - bf16 fast paths need 16-byte aligned base pointers and leading
+ *     dimensions that are multiples of 8 elements; otherwise a slower generic
+ *     kernel runs (same results to rounding).
+ */
+#ifndef PRAC_H
+#define PRAC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct prac_ctx prac_ctx;
+
+typedef enum { PRAC_F32 = 0, PRAC_BF16 = 1 } prac_dtype;
+
+typedef enum {
+  PRAC_OK = 0,
+  PRAC_EINVAL = -1,       /* bad shape, rank split, leading dimension, null pointer */
+  PRAC_ENOMEM = -2,       /* device scratch allocation failed */
+  PRAC_EHIP = -3,         /* a HIP runtime call failed (see prac_last_hip_error) */
+  PRAC_ENUMERIC = -4,     /* non-finite Gram or orthonormalisation breakdown */
+  PRAC_EUNSUPPORTED = -5, /* valid request this build has no kernel for */
+  PRAC_ENOCTX = -6        /* ctx is NULL (arguments themselves were valid) */
+} prac_status;
+
+/* refresh bits of prac_fit_basis: the two lazy-update branches of Alg. 1 */
+enum { PRAC_REFRESH_PRINCIPAL = 1, PRAC_REFRESH_RANDOM = 2 };
+
+/* Options of the principal-subspace iteration (the paper only says "SVD";
+ * this library finds the same subspace by block power iteration on X^T X with
+ * orthonormalisation and a final Rayleigh-Ritz step).  Zero / NULL = defaults. */
+typedef struct {
+  int iters;           /* power iterations; 0 -> 8 */
+  int oversample;      /* extra block columns; <0 -> none, 0 -> min(k, d-k) */
+  int64_t row_stride;  /* Gram over rows 0, stride, 2*stride, ...; 0 -> 1 */
+  int warm_start;      /* 1: start the block from the Q1 already in P */
+} prac_fit_opts;
+
+/* ---- context ----------------------------------------------------------- */
+/* Bind a context to HIP device `device` and to `hip_stream` (a hipStream_t;
+ * NULL = the default stream).  *out is [host]. */
+int prac_create(prac_ctx** out, int device, void* hip_stream);
+int prac_destroy(prac_ctx* ctx);
+int prac_set_stream(prac_ctx* ctx, void* hip_stream);
+/* Block until the ctx stream is idle and return the first device-side
+ * numeric failure recorded since the last call (PRAC_OK if none). */
+int prac_sync_status(prac_ctx* ctx);
+const char* prac_strerror(int status);          /* [host] static string */
+int prac_last_hip_error(const prac_ctx* ctx);   /* last hipError_t seen */
+
+/* ---- per-kernel timing hook (for benchmarks) ---------------------------- */
+/* While a kind other than PRAC_KERNEL_NONE is selected, every launch of that
+ * kernel is bracketed by a HIP event pair on the ctx stream.  prac_profile_read
+ * waits for the stream, writes the summed duration [host, milliseconds] and the
+ * number of launches [host] since the last read, and clears both. */
+enum {
+  PRAC_KERNEL_NONE = 0,
+  PRAC_KERNEL_COMPRESS = 1,   /* C = X P */
+  PRAC_KERNEL_CT_DY = 2,      /* token-split partial sums of C^T dY */
+  PRAC_KERNEL_T_REDUCE = 3,   /* slab reduction + scaling factor + transpose */
+  PRAC_KERNEL_P_T = 4,        /* dW = P T */
+  PRAC_KERNEL_GRAM = 5,       /* X^T X partial sums */
+  PRAC_KERNEL_FUSED_FWD = 6   /* [Y | C] = X [W | P] */
+};
+int prac_profile_select(prac_ctx* ctx, int kind);
+int prac_profile_read(prac_ctx* ctx, double* total_ms, int64_t* launches);
+
+/* ---- Gaussian draw (Eq. (S_o): S_ij ~ N(0,1) i.i.d.) -------------------- */
+/* Counter-based Philox4x32-10.  Word i of stream (seed, draw, stream) is lane
+ * i%4 of the block with counter (i/4 low, i/4 high, stream, draw) and key
+ * (seed low, seed high); draw < 2^32.  uniforms: u = ((w >> 9) + 1/2) 2^-23;
+ * normals by Box-Muller on consecutive pairs (cos first, then sin).
+ * out: n elements.  stream 0 seeds the power-iteration block, 1 is S. */
+int prac_philox_words(prac_ctx* ctx, uint64_t seed, uint64_t draw, uint32_t stream,
+                      uint32_t* out, int64_t n);
+int prac_philox_normal(prac_ctx* ctx, uint64_t seed, uint64_t draw, uint32_t stream,
+                       float* out, int64_t n);
+
+/* ---- Gram matrix (first step of "top-r_1 right singular vectors of X",
+ *      Alg. 1 principal-subspace update) --------------------------------- */
+/* G (d x d, fp32, ldg >= d) = Xs^T Xs over rows 0, row_stride, ... of X
+ * (N x d, ldx >= d).  Both triangles are written. */
+int prac_gram(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d,
+              int64_t ldx, int64_t row_stride, float* G, int64_t ldg);
+
+/* ---- basis fit (Section 4.2 construction; Alg. 1 lines 1-14) ------------ */
+/* Bytes of the packed low-precision copy of a d x c basis (see below). */
+size_t prac_basis_lp_bytes(int64_t d, int c);
+/* Build the packed bf16 copy P_lp of P (d x c fp32, ldp >= c) that the bf16
+ * kernels read: P^T as c x round_up(d,64) bf16 (zero padded) followed by P as
+ * d x round_up(c,64) bf16 (zero padded). */
+int prac_pack_basis(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c,
+                    void* P_lp);
+/* Writes P = [Q1 | Q2] (d x (k+r) fp32, UNSCALED, ldp >= k+r), optionally its
+ * packed copy P_lp (may be NULL) and *scale [host] = (d-k)/r (0 when r = 0).
+ * refresh: PRAC_REFRESH_PRINCIPAL recomputes Q1 from X; if clear, Q1 is read
+ * from the first k columns of P.  PRAC_REFRESH_RANDOM redraws Q2 from
+ * (seed, draw); if clear, columns k.. of P are left as they are.
+ * Needs 0 <= k, 0 <= r, 1 <= k+r <= d.  X may be NULL when Q1 is not
+ * refreshed or k = 0. */
+int prac_fit_basis(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d,
+                   int64_t ldx, int k, int r, uint64_t seed, uint64_t draw, int refresh,
+                   const prac_fit_opts* opts /* [host], may be NULL */, float* P,
+                   int64_t ldp, void* P_lp, float* scale /* [host], may be NULL */);
+
+/* ---- compression (Alg. 1 compression step, unscaled) ------------------- */
+/* C (N x c, ldc >= c, dtype of X) = X (N x d, ldx >= d) * P (d x c).
+ * P is the fp32 master (ldp >= c); P_lp its packed copy or NULL (then it is
+ * packed into ctx scratch on every call).  fp32 X uses P directly. */
+int prac_compress(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d,
+                  int64_t ldx, const float* P, const void* P_lp, int64_t ldp, int c,
+                  void* C, int64_t ldc);
+
+/* Same C, plus the layer's forward output Y (N x m, ldy >= m, dtype of X) in
+ * one pass over X.  W has X's dtype; w_layout 0: d x m row-major (Y = X W,
+ * Lemma 1), 1: m x d row-major (Y = X W^T, the layout of Section 5.2). */
+int prac_compress_fused_fwd(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N,
+                            int64_t d, int64_t ldx, const void* W, int64_t m, int64_t ldw,
+                            int w_layout, const float* P, const void* P_lp, int64_t ldp,
+                            int c, void* Y, int64_t ldy, void* C, int64_t ldc);
+
+/* ---- weight gradient (Lemma 1; Alg. 2 backward) ------------------------- */
+/* dW (d x m, lddw >= m, dtype odt) = beta * dW + X~^T dY with
+ * X~ = C[:, :k] Q1^T + scale * C[:, k:] Q2^T, evaluated as
+ * P * diag(1..1, scale..scale) * (C^T dY).
+ * C (N x (k+r), ldc) and dY (N x m, lddy) share dtype `dt`. */
+int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt, int64_t N,
+                     int64_t m, int64_t ldc, int64_t lddy, const float* P, const void* P_lp,
+                     int64_t d, int64_t ldp, int k, int r, float scale, void* dW,
+                     prac_dtype odt, int64_t lddw, float beta);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PRAC_H */

@@ -1,0 +1,391 @@
+// Basis fit: P = [Q1 | Q2] (Section 4.2; Alg. 1, both refresh branches).
+//
+// Q1: the paper takes the top-r_1 right singular vectors of X "via SVD".  They are
+// the dominant eigenvectors of G = X^T X, found here by block power iteration
+// V <- orth(G V) on a block of b = k + oversample columns, followed by a
+// Rayleigh-Ritz step (eigenvectors of the small matrix V^T G V, by one-sided Jacobi).
+// Q2: S is drawn from the counter-based Gaussian generator, projected twice onto the
+// complement of Q1 and orthonormalised.  orth() is Cholesky-QR with an fp64 Gram
+// matrix, which yields the thin-QR factor with a positive-diagonal R, i.e. the
+// same Q2 that Householder QR with sign normalisation gives.
+#include "prac_internal.h"
+
+namespace {
+
+// ---------------------------------------------------------------- Cholesky (upper)
+// In place on the row-major b x b fp64 matrix W (only the upper triangle is read and
+// written): W = R^T R.  `shift_rel` * max diag(W) is added to the diagonal first.
+// One workgroup of 1024 threads; non-finite or non-positive pivots raise *flag.
+__global__ __launch_bounds__(1024) void chol_upper_kernel(double* W, int b, double shift_rel, int* flag) {
+  __shared__ double s_red[16];
+  __shared__ double s_piv;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  double mx = 0.0;
+  for (int i = tid; i < b; i += 1024) mx = fmax(mx, W[(int64_t)i * b + i]);
+  for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o));
+  if (lane == 0) s_red[wave] = mx;
+  __syncthreads();
+  mx = 0.0;
+  for (int w = 0; w < 16; ++w) mx = fmax(mx, s_red[w]);
+  const double shift = shift_rel * mx;
+  const double tiny = 1e-300 + 1e-30 * mx;
+  for (int i = tid; i < b; i += 1024) W[(int64_t)i * b + i] += shift;
+  __syncthreads();
+  for (int j = 0; j < b; ++j) {
+    if (tid == 0) {
+      double p = W[(int64_t)j * b + j];
+      if (!(p > tiny) || !isfinite(p)) {
+        atomicOr(flag, 1);
+        p = tiny > 0.0 ? tiny : 1e-300;
+      }
+      p = sqrt(p);
+      W[(int64_t)j * b + j] = p;
+      s_piv = 1.0 / p;
+    }
+    __syncthreads();
+    const double inv = s_piv;
+    for (int c = j + 1 + tid; c < b; c += 1024) W[(int64_t)j * b + c] *= inv;
+    __syncthreads();
+    // trailing update of rows i > j: W[i][c] -= R[j][i] * R[j][c], c >= i
+    const double* rj = W + (int64_t)j * b;
+    for (int i = j + 1 + wave; i < b; i += 16) {
+      const double rji = rj[i];
+      double* wi = W + (int64_t)i * b;
+      for (int c = i + lane; c < b; c += 64) wi[c] -= rji * rj[c];
+    }
+    __syncthreads();
+  }
+}
+
+// Inverse of the upper-triangular R (row-major b x b fp64, upper part): column j of
+// the inverse is solved by thread j (back substitution in fp64, staged in X64), then
+// written as fp32 to Rinv (row-major b x b, lower part zeroed).
+__global__ __launch_bounds__(1024) void triu_inverse_kernel(const double* __restrict__ R, double* X64, float* Rinv,
+                                                            int b) {
+  const int j = threadIdx.x;
+  if (j < b) {
+    X64[(int64_t)j * b + j] = 1.0 / R[(int64_t)j * b + j];
+  }
+  __syncthreads();
+  for (int i = b - 2; i >= 0; --i) {
+    if (j < b && i < j) {
+      double s = 0.0;
+      const double* ri = R + (int64_t)i * b;
+      for (int t = i + 1; t <= j; ++t) s += ri[t] * X64[(int64_t)t * b + j];
+      X64[(int64_t)i * b + j] = -s / ri[i];
+    }
+  }
+  __syncthreads();
+  if (j < b) {
+    for (int i = 0; i < b; ++i) Rinv[(int64_t)i * b + j] = i <= j ? (float)X64[(int64_t)i * b + j] : 0.f;
+  }
+}
+
+// ------------------------------------------------------- symmetric eigen (Jacobi)
+// One-sided (Hestenes) Jacobi on the columns of the symmetric PSD matrix H, held
+// row-major so that "column" p is the contiguous row p (H is symmetric).  Rotating
+// column pairs until all are mutually orthogonal gives H J = B with B's columns
+// lambda_i v_i, so the eigenvectors are the normalised columns and the eigenvalues
+// their norms.  One workgroup, 16 waves; each round-robin step hands b/2 disjoint
+// pairs to the waves.  Stops when a whole sweep rotates nothing (or after max_sweeps).
+__global__ __launch_bounds__(1024) void jacobi_hestenes_kernel(double* H, int b, int max_sweeps, double tol,
+                                                               double* lambda, int* flag) {
+  __shared__ int s_rot;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int be = b + (b & 1);          // even player count; index b (if any) is a bye
+  const int npairs = be / 2, nsteps = be - 1;
+  // H arrives as V^T (G V) with G V rounded to fp32: restore exact symmetry first
+  for (int e = tid; e < b * b; e += 1024) {
+    const int i = e / b, j = e % b;
+    if (i < j) {
+      const double m = 0.5 * (H[(int64_t)i * b + j] + H[(int64_t)j * b + i]);
+      H[(int64_t)i * b + j] = m;
+      H[(int64_t)j * b + i] = m;
+    }
+  }
+  __syncthreads();
+  for (int sweep = 0; sweep < max_sweeps; ++sweep) {
+    if (tid == 0) s_rot = 0;
+    __syncthreads();
+    int rotated = 0;
+    for (int s = 0; s < nsteps; ++s) {
+      for (int i = wave; i < npairs; i += 16) {
+        int p, q;
+        if (i == 0) {
+          p = s % nsteps;
+          q = be - 1;
+        } else {
+          p = (s + i) % nsteps;
+          q = (s - i + nsteps) % nsteps;
+        }
+        if (p >= b || q >= b) continue;  // bye
+        double* hp = H + (int64_t)p * b;
+        double* hq = H + (int64_t)q * b;
+        double al = 0.0, be2 = 0.0, ga = 0.0;
+        for (int t = lane; t < b; t += 64) {
+          const double x = hp[t], y = hq[t];
+          al += x * x;
+          be2 += y * y;
+          ga += x * y;
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+          al += __shfl_xor(al, o);
+          be2 += __shfl_xor(be2, o);
+          ga += __shfl_xor(ga, o);
+        }
+        if (fabs(ga) > tol * sqrt(al * be2) && fabs(ga) > 1e-300) {
+          rotated = 1;
+          const double zeta = (be2 - al) / (2.0 * ga);
+          const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+          const double cs = 1.0 / sqrt(1.0 + tt * tt), sn = cs * tt;
+          for (int t = lane; t < b; t += 64) {
+            const double x = hp[t], y = hq[t];
+            hp[t] = cs * x - sn * y;
+            hq[t] = sn * x + cs * y;
+          }
+        }
+      }
+      __syncthreads();
+    }
+    if (rotated && lane == 0) atomicOr(&s_rot, 1);
+    __syncthreads();
+    const int any = s_rot;
+    __syncthreads();
+    if (!any) break;
+    if (sweep == max_sweeps - 1) {
+      if (tid == 0) atomicOr(flag, 2);
+    }
+  }
+  // eigenvalues = column norms; normalise the columns in place
+  for (int p = wave; p < b; p += 16) {
+    double* hp = H + (int64_t)p * b;
+    double al = 0.0;
+    for (int t = lane; t < b; t += 64) al += hp[t] * hp[t];
+    for (int o = 32; o > 0; o >>= 1) al += __shfl_xor(al, o);
+    const double nrm = sqrt(al);
+    const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
+    for (int t = lane; t < b; t += 64) hp[t] *= inv;
+    if (lane == 0) lambda[p] = nrm;
+  }
+}
+
+// Z (b x k fp32, row-major) = the k eigenvectors with the largest eigenvalues, in
+// descending order; eigenvector p is row p of Hn (normalised Jacobi output).
+__global__ __launch_bounds__(1024) void select_top_kernel(const double* __restrict__ Hn, const double* __restrict__ lambda,
+                                                          int b, int k, float* Z) {
+  __shared__ int s_rank[1024];
+  const int tid = threadIdx.x;
+  if (tid < b) {
+    const double me = lambda[tid];
+    int rk = 0;
+    for (int o = 0; o < b; ++o) {
+      const double v = lambda[o];
+      rk += (v > me) || (v == me && o < tid);
+    }
+    s_rank[tid] = rk;
+  }
+  __syncthreads();
+  for (int p = 0; p < b; ++p) {
+    const int rk = s_rank[p];
+    if (rk < k)
+      for (int t = tid; t < b; t += 1024) Z[(int64_t)t * k + rk] = (float)Hn[(int64_t)p * b + t];
+  }
+}
+
+__global__ __launch_bounds__(256) void copy_cols_kernel(const float* __restrict__ src, int64_t lds, float* dst,
+                                                        int64_t ldd, int64_t rows, int cols) {
+  const int64_t total = rows * cols;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x)
+    dst[(i / cols) * ldd + i % cols] = src[(i / cols) * lds + i % cols];
+}
+
+struct FitWs {
+  size_t G, V, Y, W64, X64, Rinv, lam, Z, S, T, slabs, gram, total;
+  int b;
+  int splits_bb;  // split count of the b x b fp64 Gram products
+};
+
+int block_width(int64_t d, int k, const prac_fit_opts& o) {
+  int p = o.oversample < 0 ? 0 : (o.oversample == 0 ? k : o.oversample);
+  int64_t b = (int64_t)k + p;
+  if (b > d) b = d;
+  if (b > 1024) b = 1024;
+  if (b < k) b = k;
+  return (int)b;
+}
+
+FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool need_g, size_t gram_bytes) {
+  FitWs w{};
+  WsPlan p;
+  const int b = need_g ? block_width(d, k, o) : 0;
+  const int bb = b > r ? b : r;  // widest panel that goes through orth()
+  w.b = b;
+  w.G = p.take(need_g ? (size_t)d * d * 4 : 0);
+  w.V = p.take((size_t)d * bb * 4);
+  w.Y = p.take((size_t)d * bb * 4);
+  w.W64 = p.take((size_t)bb * bb * 8);
+  w.X64 = p.take((size_t)bb * bb * 8);
+  w.Rinv = p.take((size_t)bb * bb * 4);
+  w.lam = p.take((size_t)bb * 8);
+  w.Z = p.take((size_t)bb * (k > 0 ? k : 1) * 4);
+  w.S = p.take((size_t)d * (r > 0 ? r : 1) * 4);
+  w.T = p.take((size_t)(k > 0 ? k : 1) * (r > 0 ? r : 1) * 4);
+  const int tiles = ((bb + 63) / 64) * ((bb + 63) / 64);
+  int s = (2 * n_cu + tiles - 1) / tiles;
+  if (s > d / 64) s = (int)(d / 64);
+  if (s < 1) s = 1;
+  if (s > 64) s = 64;
+  w.splits_bb = s;
+  w.slabs = p.take((size_t)s * bb * bb * 8);
+  w.gram = p.take(gram_bytes);
+  w.total = p.off;
+  return w;
+}
+
+// V (d x n, ld = n, fp32) <- orth(Y) by `passes` rounds of Cholesky-QR; ping-pongs
+// between Y and V, result always ends in `V`.  The first round shifts the Gram matrix.
+int cholqr(prac_ctx* ctx, const FitWs& w, float* Y, float* V, int64_t d, int n, int passes, double first_shift) {
+  double* W64 = reinterpret_cast<double*>(ctx->ws + w.W64);
+  double* X64 = reinterpret_cast<double*>(ctx->ws + w.X64);
+  float* Rinv = reinterpret_cast<float*>(ctx->ws + w.Rinv);
+  float* src = Y;
+  float* dst = V;
+  for (int pass = 0; pass < passes; ++pass) {
+    GemmGenArgs g{};
+    g.A = src; g.B = src; g.adt = PRAC_F32; g.bdt = PRAC_F32;
+    g.a_rs = 1; g.a_cs = n; g.b_rs = n; g.b_cs = 1;
+    g.M = n; g.N = n; g.K = d; g.k_stride = 1;
+    g.out = nullptr; g.out64 = W64; g.ldo = n; g.alpha = 1.f; g.beta = 0.f; g.acc64 = true;
+    g.splits = w.splits_bb; g.slabs = ctx->ws + w.slabs;
+    int rc = launch_gemm_generic(ctx, g);
+    if (rc) return rc;
+    hipLaunchKernelGGL(chol_upper_kernel, dim3(1), dim3(1024), 0, ctx->stream, W64, n,
+                       pass == 0 ? first_shift : 1e-15, ctx->d_flag);
+    hipLaunchKernelGGL(triu_inverse_kernel, dim3(1), dim3(1024), 0, ctx->stream, W64, X64, Rinv, n);
+    PRAC_HIP_TRY(ctx, hipGetLastError());
+    GemmGenArgs h{};
+    h.A = src; h.B = Rinv; h.adt = PRAC_F32; h.bdt = PRAC_F32;
+    h.a_rs = n; h.a_cs = 1; h.b_rs = n; h.b_cs = 1;
+    h.M = (int)d; h.N = n; h.K = n; h.k_stride = 1;
+    h.out = dst; h.ldo = n; h.alpha = 1.f; h.beta = 0.f; h.acc64 = false; h.out64 = nullptr;
+    rc = launch_gemm_generic(ctx, h);
+    if (rc) return rc;
+    float* t = src; src = dst; dst = t;
+  }
+  // result is in `src` after the swap
+  if (src != V) {
+    hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, ctx->stream, src, (int64_t)n, V,
+                       (int64_t)n, d, n);
+    PRAC_HIP_TRY(ctx, hipGetLastError());
+  }
+  return PRAC_OK;
+}
+
+}  // namespace
+
+int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, int k, int r,
+                     uint64_t seed, uint32_t draw, int refresh, const prac_fit_opts& o, float* P, int64_t ldp) {
+  const bool do_q1 = (refresh & PRAC_REFRESH_PRINCIPAL) && k > 0;
+  const bool do_q2 = (refresh & PRAC_REFRESH_RANDOM) && r > 0;
+  if (!do_q1 && !do_q2) return PRAC_OK;
+  if (k > 1024 || r > 1024) return PRAC_EUNSUPPORTED;  // single-workgroup panel kernels
+  const size_t gram_bytes = do_q1 ? gram_scratch_bytes(ctx, X, xdt, N, d, ldx, o.row_stride, d) : 0;
+  const FitWs L = plan_fit(d, k, r, o, ctx->n_cu, do_q1, gram_bytes);
+  int rc = prac_ws_reserve(ctx, L.total);
+  if (rc) return rc;
+  float* G = reinterpret_cast<float*>(ctx->ws + L.G);
+  float* V = reinterpret_cast<float*>(ctx->ws + L.V);
+  float* Y = reinterpret_cast<float*>(ctx->ws + L.Y);
+  hipStream_t st = ctx->stream;
+
+  if (do_q1) {
+    const int b = L.b;
+    rc = gram_device(ctx, X, xdt, N, d, ldx, o.row_stride, G, d, ctx->ws + L.gram);
+    if (rc) return rc;
+
+    // start block: Gaussian (stream 0); warm start puts the previous Q1 in front
+    rc = launch_philox(ctx, seed, draw, 0u, Y, d * b, true);
+    if (rc) return rc;
+    if (o.warm_start) {
+      hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, P, ldp, Y, (int64_t)b, d, k);
+      PRAC_HIP_TRY(ctx, hipGetLastError());
+    }
+    rc = cholqr(ctx, L, Y, V, d, b, 2, 1e-11);
+    if (rc) return rc;
+    for (int it = 0; it <= o.iters; ++it) {
+      // Y = G V
+      GemmGenArgs g{};
+      g.A = G; g.B = V; g.adt = PRAC_F32; g.bdt = PRAC_F32;
+      g.a_rs = d; g.a_cs = 1; g.b_rs = b; g.b_cs = 1;
+      g.M = (int)d; g.N = b; g.K = d; g.k_stride = 1;
+      g.out = Y; g.ldo = b; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
+      rc = launch_gemm_generic(ctx, g);
+      if (rc) return rc;
+      if (it == o.iters) break;  // the last product feeds Rayleigh-Ritz
+      rc = cholqr(ctx, L, Y, V, d, b, it == o.iters - 1 ? 3 : 2, 1e-11);
+      if (rc) return rc;
+    }
+    // Rayleigh-Ritz: H = V^T (G V), eigenvectors of H, Q1 = V Z[:, :k]
+    double* H = reinterpret_cast<double*>(ctx->ws + L.W64);
+    double* lam = reinterpret_cast<double*>(ctx->ws + L.lam);
+    float* Z = reinterpret_cast<float*>(ctx->ws + L.Z);
+    {
+      GemmGenArgs g{};
+      g.A = V; g.B = Y; g.adt = PRAC_F32; g.bdt = PRAC_F32;
+      g.a_rs = 1; g.a_cs = b; g.b_rs = b; g.b_cs = 1;
+      g.M = b; g.N = b; g.K = d; g.k_stride = 1;
+      g.out = nullptr; g.out64 = H; g.ldo = b; g.alpha = 1.f; g.beta = 0.f; g.acc64 = true;
+      g.splits = L.splits_bb; g.slabs = ctx->ws + L.slabs;
+      rc = launch_gemm_generic(ctx, g);
+      if (rc) return rc;
+    }
+    hipLaunchKernelGGL(jacobi_hestenes_kernel, dim3(1), dim3(1024), 0, st, H, b, 30, 1e-14, lam, ctx->d_flag);
+    hipLaunchKernelGGL(select_top_kernel, dim3(1), dim3(1024), 0, st, H, lam, b, k, Z);
+    PRAC_HIP_TRY(ctx, hipGetLastError());
+    {
+      GemmGenArgs g{};
+      g.A = V; g.B = Z; g.adt = PRAC_F32; g.bdt = PRAC_F32;
+      g.a_rs = b; g.a_cs = 1; g.b_rs = k; g.b_cs = 1;
+      g.M = (int)d; g.N = k; g.K = b; g.k_stride = 1;
+      g.out = Y; g.ldo = k; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
+      rc = launch_gemm_generic(ctx, g);
+      if (rc) return rc;
+    }
+    // tidy the rounding of the last product, then store Q1 into P[:, :k]
+    rc = cholqr(ctx, L, Y, V, d, k, 1, 0.0);
+    if (rc) return rc;
+    hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, V, (int64_t)k, P, ldp, d, k);
+    PRAC_HIP_TRY(ctx, hipGetLastError());
+  }
+
+  if (do_q2) {
+    float* S = reinterpret_cast<float*>(ctx->ws + L.S);
+    float* T = reinterpret_cast<float*>(ctx->ws + L.T);
+    rc = launch_philox(ctx, seed, draw, 1u, S, d * r, true);
+    if (rc) return rc;
+    if (k > 0) {
+      for (int rep = 0; rep < 2; ++rep) {
+        // T = Q1^T S  (k x r), S -= Q1 T
+        GemmGenArgs g{};
+        g.A = P; g.B = S; g.adt = PRAC_F32; g.bdt = PRAC_F32;
+        g.a_rs = 1; g.a_cs = ldp; g.b_rs = r; g.b_cs = 1;
+        g.M = k; g.N = r; g.K = d; g.k_stride = 1;
+        g.out = T; g.ldo = r; g.alpha = 1.f; g.beta = 0.f; g.acc64 = true; g.out64 = nullptr;
+        rc = launch_gemm_generic(ctx, g);
+        if (rc) return rc;
+        GemmGenArgs h{};
+        h.A = P; h.B = T; h.adt = PRAC_F32; h.bdt = PRAC_F32;
+        h.a_rs = ldp; h.a_cs = 1; h.b_rs = r; h.b_cs = 1;
+        h.M = (int)d; h.N = r; h.K = k; h.k_stride = 1;
+        h.out = S; h.ldo = r; h.alpha = -1.f; h.beta = 1.f; h.acc64 = false; h.out64 = nullptr;
+        rc = launch_gemm_generic(ctx, h);
+        if (rc) return rc;
+      }
+    }
+    rc = cholqr(ctx, L, S, V, d, r, 3, 1e-13);
+    if (rc) return rc;
+    hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, V, (int64_t)r, P + k, ldp, d, r);
+    PRAC_HIP_TRY(ctx, hipGetLastError());
+  }
+  return PRAC_OK;
+}

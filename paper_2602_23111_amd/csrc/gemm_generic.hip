@@ -1,0 +1,174 @@
+// Strided GEMM on the vector ALUs: fp32 or bf16 operands with arbitrary element
+// strides, fp32 or fp64 accumulation.  It serves the fp32 data path (where bf16 MFMA
+// rounding is not allowed), unaligned bf16 inputs, and the small dense products of
+// the basis fit (G V, V^T Y with fp64 sums, Y R^-1, V Z, Q1 (Q1^T S)).
+#include "prac_internal.h"
+
+namespace {
+
+struct GArgs {
+  const void* A;
+  const void* B;
+  int64_t a_rs, a_cs, b_rs, b_cs;
+  int M, N;
+  int64_t K, k_stride;
+  float* out;
+  double* out64;
+  int64_t ldo;
+  float alpha, beta;
+  int splits;          // gridDim.z; > 1: raw partial sums go to `slabs`
+  int64_t steps_per_split;
+  void* slabs;         // splits x M x N of ACC
+};
+
+template <typename T>
+__device__ __forceinline__ float ld_f32(const void* p, int64_t idx);
+template <>
+__device__ __forceinline__ float ld_f32<float>(const void* p, int64_t idx) {
+  return reinterpret_cast<const float*>(p)[idx];
+}
+template <>
+__device__ __forceinline__ float ld_f32<bf16_t>(const void* p, int64_t idx) {
+  return __uint_as_float(((uint32_t) reinterpret_cast<const bf16_t*>(p)[idx]) << 16);
+}
+
+constexpr int TM = 64, TN = 64, TK = 16;
+
+// 256 threads, 64 x 64 output tile, 4 x 4 per thread.  A_MFAST / B_NFAST pick the
+// thread -> element map of the tile loads so that consecutive lanes walk the
+// operand's unit-stride dimension.
+template <typename TA, typename TB, typename ACC, bool A_MFAST, bool B_NFAST>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(GArgs a) {
+  __shared__ float As[TK][TM + 4];
+  __shared__ float Bs[TK][TN + 4];
+  const int tid = threadIdx.x;
+  const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+  const int tx = tid % 16, ty = tid / 16;
+  ACC acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = (ACC)0;
+
+  const int64_t nsteps_all = (a.K + a.k_stride - 1) / a.k_stride;  // visited k values
+  const int64_t sbeg = (int64_t)blockIdx.z * a.steps_per_split;
+  const int64_t nsteps = min(nsteps_all, sbeg + a.steps_per_split);
+  for (int64_t s0 = sbeg; s0 < nsteps; s0 += TK) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int q = tid + p * 256;
+      const int mm = A_MFAST ? q % TM : q / TK, kk = A_MFAST ? q / TM : q % TK;
+      const int m = m0 + mm;
+      const int64_t s = s0 + kk;
+      As[kk][mm] = (m < a.M && s < nsteps) ? ld_f32<TA>(a.A, m * a.a_rs + s * a.k_stride * a.a_cs) : 0.f;
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int q = tid + p * 256;
+      const int nn = B_NFAST ? q % TN : q / TK, kk = B_NFAST ? q / TN : q % TK;
+      const int n = n0 + nn;
+      const int64_t s = s0 + kk;
+      Bs[kk][nn] = (n < a.N && s < nsteps) ? ld_f32<TB>(a.B, s * a.k_stride * a.b_rs + n * a.b_cs) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < TK; ++kk) {
+      float av[4], bv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) av[i] = As[kk][ty + 16 * i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bv[j] = Bs[kk][tx + 16 * j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += (ACC)av[i] * (ACC)bv[j];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + ty + 16 * i, n = n0 + tx + 16 * j;
+      if (m < a.M && n < a.N) {
+        const int64_t o = (int64_t)m * a.ldo + n;
+        if (a.splits > 1) {
+          reinterpret_cast<ACC*>(a.slabs)[((int64_t)blockIdx.z * a.M + m) * a.N + n] = acc[i][j];
+        } else if (a.out64) {
+          a.out64[o] = (double)a.alpha * (double)acc[i][j] + (a.beta == 0.f ? 0.0 : (double)a.beta * a.out64[o]);
+        } else {
+          const float v = a.alpha * (float)acc[i][j];
+          a.out[o] = a.beta == 0.f ? v : v + a.beta * a.out[o];
+        }
+      }
+    }
+}
+
+template <typename TA, typename TB, typename ACC>
+void launch3(const GArgs& a, hipStream_t st) {
+  dim3 grid((a.N + TN - 1) / TN, (a.M + TM - 1) / TM, a.splits), block(256);
+  const bool a_mfast = a.a_rs == 1 || (a.a_cs != 1 && a.a_rs < a.a_cs);
+  const bool b_nfast = a.b_cs == 1 || (a.b_rs != 1 && a.b_cs < a.b_rs);
+  if (a_mfast && b_nfast) hipLaunchKernelGGL((gemm_generic_kernel<TA, TB, ACC, true, true>), grid, block, 0, st, a);
+  else if (a_mfast) hipLaunchKernelGGL((gemm_generic_kernel<TA, TB, ACC, true, false>), grid, block, 0, st, a);
+  else if (b_nfast) hipLaunchKernelGGL((gemm_generic_kernel<TA, TB, ACC, false, true>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((gemm_generic_kernel<TA, TB, ACC, false, false>), grid, block, 0, st, a);
+}
+
+template <typename TA, typename TB>
+void launch2(const GArgs& a, bool acc64, hipStream_t st) {
+  if (acc64) launch3<TA, TB, double>(a, st);
+  else launch3<TA, TB, float>(a, st);
+}
+
+// out = alpha * sum_z slab[z] + beta * out over an M x N matrix with leading dim ldo
+template <typename ACC, typename OUT>
+__global__ __launch_bounds__(256) void reduce_gen_kernel(const ACC* __restrict__ slabs, int splits, int M, int N,
+                                                         OUT* out, int64_t ldo, float alpha, float beta) {
+  const int64_t total = (int64_t)M * N;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    ACC s = (ACC)0;
+    for (int z = 0; z < splits; ++z) s += slabs[z * total + i];
+    const int64_t o = (i / N) * ldo + i % N;
+    const OUT v = (OUT)alpha * (OUT)s;
+    out[o] = beta == 0.f ? v : v + (OUT)beta * out[o];
+  }
+}
+
+}  // namespace
+
+int launch_gemm_generic(prac_ctx* ctx, const GemmGenArgs& g) {
+  if (g.M <= 0 || g.N <= 0) return PRAC_OK;
+  GArgs a;
+  a.A = g.A; a.B = g.B;
+  a.a_rs = g.a_rs; a.a_cs = g.a_cs; a.b_rs = g.b_rs; a.b_cs = g.b_cs;
+  a.M = g.M; a.N = g.N; a.K = g.K; a.k_stride = g.k_stride < 1 ? 1 : g.k_stride;
+  a.out = g.out; a.out64 = g.out64; a.ldo = g.ldo; a.alpha = g.alpha; a.beta = g.beta;
+  const int64_t nsteps = (a.K + a.k_stride - 1) / a.k_stride;
+  a.splits = (g.splits > 1 && g.slabs) ? g.splits : 1;
+  a.steps_per_split = ((nsteps + a.splits - 1) / a.splits + TK - 1) / TK * TK;
+  if (a.steps_per_split < TK) a.steps_per_split = TK;
+  a.slabs = g.slabs;
+  const bool abf = g.adt == PRAC_BF16, bbf = g.bdt == PRAC_BF16;
+  if (abf && bbf) launch2<bf16_t, bf16_t>(a, g.acc64, ctx->stream);
+  else if (abf) launch2<bf16_t, float>(a, g.acc64, ctx->stream);
+  else if (bbf) launch2<float, bf16_t>(a, g.acc64, ctx->stream);
+  else launch2<float, float>(a, g.acc64, ctx->stream);
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  if (a.splits > 1) {
+    const int64_t total = (int64_t)a.M * a.N;
+    int64_t gr = (total + 255) / 256;
+    if (gr > ctx->n_cu * 8) gr = ctx->n_cu * 8;
+    if (g.acc64 && g.out64)
+      hipLaunchKernelGGL((reduce_gen_kernel<double, double>), dim3((unsigned)gr), dim3(256), 0, ctx->stream,
+                         reinterpret_cast<const double*>(a.slabs), a.splits, a.M, a.N, g.out64, a.ldo, a.alpha, a.beta);
+    else if (g.acc64)
+      hipLaunchKernelGGL((reduce_gen_kernel<double, float>), dim3((unsigned)gr), dim3(256), 0, ctx->stream,
+                         reinterpret_cast<const double*>(a.slabs), a.splits, a.M, a.N, g.out, a.ldo, a.alpha, a.beta);
+    else
+      hipLaunchKernelGGL((reduce_gen_kernel<float, float>), dim3((unsigned)gr), dim3(256), 0, ctx->stream,
+                         reinterpret_cast<const float*>(a.slabs), a.splits, a.M, a.N, g.out, a.ldo, a.alpha, a.beta);
+    PRAC_HIP_TRY(ctx, hipGetLastError());
+  }
+  return PRAC_OK;
+}

@@ -1,0 +1,534 @@
+// C ABI of libprac (see include/prac.h): argument checks, scratch planning and the
+// sequence of kernel launches behind each entry point.
+#include <new>
+
+#include "prac_internal.h"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+inline size_t esize(prac_dtype t) { return t == PRAC_BF16 ? 2 : 4; }
+inline bool valid_dtype(int t) { return t == PRAC_F32 || t == PRAC_BF16; }
+
+struct LpLayout {
+  int64_t ldpt, ldpn;
+  size_t off_pn, bytes;
+};
+inline LpLayout lp_layout(int64_t d, int c) {
+  LpLayout l;
+  l.ldpt = round_up64(d, 64);
+  l.ldpn = round_up64(c, 64);
+  l.off_pn = (size_t)c * l.ldpt * sizeof(bf16_t);
+  l.off_pn = (l.off_pn + 255) & ~size_t(255);
+  l.bytes = l.off_pn + (size_t)d * l.ldpn * sizeof(bf16_t);
+  return l;
+}
+
+// split count for a reduction over K with `tiles` output tiles: fill the chip about
+// twice over without making slabs shorter than `min_k`.
+inline int pick_splits(int tiles, int64_t K, int n_cu, int min_k) {
+  int s = (2 * n_cu + tiles - 1) / tiles;
+  const int64_t cap = K / min_k;
+  if (s > cap) s = (int)cap;
+  if (s > 64) s = 64;
+  return s < 1 ? 1 : s;
+}
+
+}  // namespace
+
+int prac_ws_reserve(prac_ctx* ctx, size_t bytes) {
+  if (bytes <= ctx->ws_bytes) return PRAC_OK;
+  // Work already enqueued may still read the old block: wait before replacing it.
+  PRAC_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  if (ctx->ws) PRAC_HIP_TRY(ctx, hipFree(ctx->ws));
+  ctx->ws = nullptr;
+  ctx->ws_bytes = 0;
+  const size_t want = bytes + bytes / 4;
+  void* p = nullptr;
+  hipError_t e = hipMalloc(&p, want);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      ctx->last_hip = (int)e;
+      return PRAC_ENOMEM;
+    }
+    ctx->ws_bytes = bytes;
+  } else {
+    ctx->ws_bytes = want;
+  }
+  ctx->ws = reinterpret_cast<char*>(p);
+  return PRAC_OK;
+}
+
+ProfScope::ProfScope(prac_ctx* c, int kind) : ctx(c), stop(nullptr), on(false) {
+  if (c->prof_kind != kind || kind == 0) return;
+  hipEvent_t ev[2] = {nullptr, nullptr};
+  for (int i = 0; i < 2; ++i) {
+    if (!c->prof_pool.empty()) {
+      ev[i] = c->prof_pool.back();
+      c->prof_pool.pop_back();
+    } else if (hipEventCreate(&ev[i]) != hipSuccess) {
+      (void)hipGetLastError();
+      if (i == 1) c->prof_pool.push_back(ev[0]);
+      return;
+    }
+  }
+  if (hipEventRecord(ev[0], c->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    c->prof_pool.push_back(ev[0]);
+    c->prof_pool.push_back(ev[1]);
+    return;
+  }
+  c->prof_pairs.emplace_back(ev[0], ev[1]);
+  stop = ev[1];
+  on = true;
+}
+ProfScope::~ProfScope() {
+  if (on && hipEventRecord(stop, ctx->stream) != hipSuccess) (void)hipGetLastError();
+}
+
+namespace {
+inline bool gram_fast(const void* X, prac_dtype xdt, int64_t rows, int64_t ldx, int64_t row_stride) {
+  return xdt == PRAC_BF16 && aligned16(X) && ldx % 8 == 0 && rows < ((int64_t)1 << 31);
+}
+inline int gram_splits(const prac_ctx* ctx, int64_t d, int64_t rows) {
+  const int tiles = (int)(((d + 127) / 128) * ((d + 127) / 128));
+  return pick_splits(tiles, rows, ctx->n_cu, 512);
+}
+}  // namespace
+
+size_t gram_scratch_bytes(const prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
+                          int64_t row_stride, int64_t ldg) {
+  const int64_t rows = (N + row_stride - 1) / row_stride;
+  if (!gram_fast(X, xdt, rows, ldx, row_stride)) return 0;
+  const int splits = gram_splits(ctx, d, rows);
+  WsPlan plan;
+  plan.take(splits > 1 ? (size_t)splits * d * d * sizeof(float) : 0);
+  plan.take(ldg == d ? 0 : (size_t)d * d * sizeof(float));
+  return plan.off;
+}
+
+// G = Xs^T Xs with all scratch taken from `scratch` (gram_scratch_bytes of it).
+int gram_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, int64_t row_stride,
+                float* G, int64_t ldg, char* scratch) {
+  const int64_t rows = (N + row_stride - 1) / row_stride;
+  if (gram_fast(X, xdt, rows, ldx, row_stride)) {
+    const int splits = gram_splits(ctx, d, rows);
+    WsPlan plan;
+    const size_t o_part = plan.take(splits > 1 ? (size_t)splits * d * d * sizeof(float) : 0);
+    const size_t o_g = plan.take(ldg == d ? 0 : (size_t)d * d * sizeof(float));
+    float* dense = ldg == d ? G : reinterpret_cast<float*>(scratch + o_g);
+    GemmBf16Args g{};
+    g.A = reinterpret_cast<const bf16_t*>(X);
+    g.lda = ldx * row_stride;
+    g.M = (int)d;
+    g.K = (int)rows;
+    g.a_kc = false;
+    g.b_kc = false;
+    g.b0 = GemmOperandB{reinterpret_cast<const bf16_t*>(X), ldx * row_stride, (int)d, dense, d};
+    g.b1 = GemmOperandB{nullptr, 0, 0, nullptr, 0};
+    g.out_bf16 = false;
+    g.beta = 0.f;
+    g.splits = splits;
+    g.partial = splits > 1 ? reinterpret_cast<float*>(scratch + o_part) : nullptr;
+    g.tile_hint = 0;
+    int rc;
+    {
+      ProfScope ps(ctx, PRAC_KERNEL_GRAM);
+      rc = launch_gemm_bf16(ctx, g);
+    }
+    if (rc) return rc;
+    if (splits > 1) {
+      rc = launch_reduce_slabs(ctx, g.partial, splits, (int64_t)d * d, dense, (int64_t)d * d, 1.f, 0.f);
+      if (rc) return rc;
+    }
+    if (dense != G) return launch_cast_out(ctx, dense, d, G, PRAC_F32, ldg, (int)d, (int)d, 0.f);
+    return PRAC_OK;
+  }
+  GemmGenArgs g{};
+  g.A = X; g.B = X; g.adt = xdt; g.bdt = xdt;
+  g.a_rs = 1; g.a_cs = ldx; g.b_rs = ldx; g.b_cs = 1;
+  g.M = (int)d; g.N = (int)d; g.K = N; g.k_stride = row_stride;
+  g.out = G; g.ldo = ldg; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
+  return launch_gemm_generic(ctx, g);
+}
+
+extern "C" {
+
+const char* prac_strerror(int s) {
+  switch (s) {
+    case PRAC_OK: return "ok";
+    case PRAC_EINVAL: return "invalid argument";
+    case PRAC_ENOMEM: return "out of device memory";
+    case PRAC_EHIP: return "HIP runtime error";
+    case PRAC_ENUMERIC: return "numeric breakdown";
+    case PRAC_EUNSUPPORTED: return "unsupported request";
+    case PRAC_ENOCTX: return "null context";
+    default: return "unknown status";
+  }
+}
+
+int prac_create(prac_ctx** out, int device, void* hip_stream) {
+  if (!out || device < 0) return PRAC_EINVAL;
+  *out = nullptr;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) {
+    (void)hipGetLastError();
+    return PRAC_EHIP;
+  }
+  if (hipSetDevice(device) != hipSuccess) return PRAC_EHIP;
+  prac_ctx* c = new (std::nothrow) prac_ctx();
+  if (!c) return PRAC_ENOMEM;
+  c->device = device;
+  c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  c->ws = nullptr;
+  c->ws_bytes = 0;
+  c->d_flag = nullptr;
+  c->last_hip = 0;
+  c->prof_kind = 0;
+  hipDeviceProp_t prop;
+  c->n_cu = (hipGetDeviceProperties(&prop, device) == hipSuccess) ? prop.multiProcessorCount : 256;
+  if (hipMalloc(reinterpret_cast<void**>(&c->d_flag), 256) != hipSuccess ||
+      hipMemset(c->d_flag, 0, 256) != hipSuccess) {
+    delete c;
+    return PRAC_EHIP;
+  }
+  *out = c;
+  return PRAC_OK;
+}
+
+int prac_destroy(prac_ctx* ctx) {
+  if (!ctx) return PRAC_ENOCTX;
+  (void)hipStreamSynchronize(ctx->stream);
+  if (ctx->ws) (void)hipFree(ctx->ws);
+  if (ctx->d_flag) (void)hipFree(ctx->d_flag);
+  for (auto& pr : ctx->prof_pairs) {
+    (void)hipEventDestroy(pr.first);
+    (void)hipEventDestroy(pr.second);
+  }
+  for (auto& ev : ctx->prof_pool) (void)hipEventDestroy(ev);
+  delete ctx;
+  return PRAC_OK;
+}
+
+int prac_set_stream(prac_ctx* ctx, void* hip_stream) {
+  if (!ctx) return PRAC_ENOCTX;
+  ctx->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  return PRAC_OK;
+}
+
+int prac_sync_status(prac_ctx* ctx) {
+  if (!ctx) return PRAC_ENOCTX;
+  int flag = 0;
+  PRAC_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  PRAC_HIP_TRY(ctx, hipMemcpy(&flag, ctx->d_flag, sizeof(int), hipMemcpyDeviceToHost));
+  if (flag != 0) {
+    PRAC_HIP_TRY(ctx, hipMemset(ctx->d_flag, 0, sizeof(int)));
+    return PRAC_ENUMERIC;
+  }
+  return PRAC_OK;
+}
+
+int prac_last_hip_error(const prac_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+int prac_profile_select(prac_ctx* ctx, int kind) {
+  if (kind < PRAC_KERNEL_NONE || kind > PRAC_KERNEL_FUSED_FWD) return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  ctx->prof_kind = kind;
+  return PRAC_OK;
+}
+
+int prac_profile_read(prac_ctx* ctx, double* total_ms, int64_t* launches) {
+  if (!total_ms || !launches) return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  PRAC_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  double sum = 0.0;
+  int64_t n = 0;
+  for (auto& pr : ctx->prof_pairs) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) {
+      sum += ms;
+      ++n;
+    } else {
+      (void)hipGetLastError();
+    }
+    ctx->prof_pool.push_back(pr.first);
+    ctx->prof_pool.push_back(pr.second);
+  }
+  ctx->prof_pairs.clear();
+  *total_ms = sum;
+  *launches = n;
+  return PRAC_OK;
+}
+
+// ---------------------------------------------------------------- Gaussian draw
+int prac_philox_words(prac_ctx* ctx, uint64_t seed, uint64_t draw, uint32_t stream, uint32_t* out, int64_t n) {
+  if (n < 0 || (n > 0 && !out) || draw > 0xFFFFFFFFull) return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  return launch_philox(ctx, seed, (uint32_t)draw, stream, out, n, false);
+}
+
+int prac_philox_normal(prac_ctx* ctx, uint64_t seed, uint64_t draw, uint32_t stream, float* out, int64_t n) {
+  if (n < 0 || (n > 0 && !out) || draw > 0xFFFFFFFFull) return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  return launch_philox(ctx, seed, (uint32_t)draw, stream, out, n, true);
+}
+
+// ------------------------------------------------------------------------- Gram
+int prac_gram(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, int64_t row_stride,
+              float* G, int64_t ldg) {
+  if (!X || !G || !valid_dtype(xdt) || N < 1 || d < 1 || d > (1 << 20) || ldx < d || ldg < d || row_stride < 1)
+    return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  const size_t need = gram_scratch_bytes(ctx, X, xdt, N, d, ldx, row_stride, ldg);
+  int rc = prac_ws_reserve(ctx, need);
+  if (rc) return rc;
+  return gram_device(ctx, X, xdt, N, d, ldx, row_stride, G, ldg, ctx->ws);
+}
+
+// ------------------------------------------------------------------------ basis
+size_t prac_basis_lp_bytes(int64_t d, int c) {
+  if (d < 1 || c < 1) return 0;
+  return lp_layout(d, c).bytes;
+}
+
+int prac_pack_basis(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, void* P_lp) {
+  if (!P || !P_lp || d < 1 || c < 1 || c > d || ldp < c || !aligned16(P_lp)) return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  const LpLayout l = lp_layout(d, c);
+  char* base = reinterpret_cast<char*>(P_lp);
+  return launch_pack_basis(ctx, P, d, ldp, c, reinterpret_cast<bf16_t*>(base), l.ldpt,
+                           reinterpret_cast<bf16_t*>(base + l.off_pn), l.ldpn);
+}
+
+int prac_fit_basis(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, int k, int r,
+                   uint64_t seed, uint64_t draw, int refresh, const prac_fit_opts* opts, float* P, int64_t ldp,
+                   void* P_lp, float* scale) {
+  if (!P || d < 1 || d > (1 << 20) || k < 0 || r < 0 || k + r < 1 || (int64_t)k + r > d || ldp < k + r ||
+      draw > 0xFFFFFFFFull || (refresh & ~3) != 0)
+    return PRAC_EINVAL;
+  const bool need_x = (refresh & PRAC_REFRESH_PRINCIPAL) && k > 0;
+  if (need_x && (!X || !valid_dtype(xdt) || N < 1 || ldx < d)) return PRAC_EINVAL;
+  prac_fit_opts o{};
+  if (opts) o = *opts;
+  if (o.iters < 0 || o.row_stride < 0 || (o.warm_start != 0 && o.warm_start != 1)) return PRAC_EINVAL;
+  if (o.iters == 0) o.iters = 8;
+  if (o.row_stride == 0) o.row_stride = 1;
+  if (P_lp && !aligned16(P_lp)) return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  if (scale) *scale = r > 0 ? (float)((double)(d - k) / (double)r) : 0.f;
+  int rc = fit_basis_device(ctx, X, xdt, N, d, ldx, k, r, seed, (uint32_t)draw, refresh, o, P, ldp);
+  if (rc) return rc;
+  if (P_lp) return prac_pack_basis(ctx, P, d, ldp, k + r, P_lp);
+  return PRAC_OK;
+}
+
+// --------------------------------------------------------------------- compress
+static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
+                         const void* W, int64_t m, int64_t ldw, int w_layout, const float* P, const void* P_lp,
+                         int64_t ldp, int c, void* Y, int64_t ldy, void* C, int64_t ldc) {
+  const bool fused = W != nullptr;
+  const bool fast = xdt == PRAC_BF16 && aligned16(X) && ldx % 8 == 0 && N < ((int64_t)1 << 31) &&
+                    (!fused || (aligned16(W) && ldw % 8 == 0));
+  if (fast) {
+    const LpLayout l = lp_layout(d, c);
+    const char* lp = reinterpret_cast<const char*>(P_lp);
+    if (!lp) {
+      int rc = prac_ws_reserve(ctx, l.bytes);
+      if (rc) return rc;
+      rc = prac_pack_basis(ctx, P, d, ldp, c, ctx->ws);
+      if (rc) return rc;
+      lp = ctx->ws;
+    }
+    const bf16_t* Pt = reinterpret_cast<const bf16_t*>(lp);
+    const bf16_t* Pn = reinterpret_cast<const bf16_t*>(lp + l.off_pn);
+    GemmBf16Args g{};
+    g.A = reinterpret_cast<const bf16_t*>(X);
+    g.lda = ldx;
+    g.M = (int)N;
+    g.K = (int)d;
+    g.a_kc = true;
+    g.out_bf16 = true;
+    g.beta = 0.f;
+    g.splits = 1;
+    g.partial = nullptr;
+    if (!fused) {
+      g.b_kc = true;
+      g.b0 = GemmOperandB{Pt, l.ldpt, c, C, ldc};
+      g.b1 = GemmOperandB{nullptr, 0, 0, nullptr, 0};
+      g.tile_hint = 1;
+    } else {
+      g.b_kc = w_layout == 1;
+      g.b0 = GemmOperandB{reinterpret_cast<const bf16_t*>(W), ldw, (int)m, Y, ldy};
+      g.b1 = g.b_kc ? GemmOperandB{Pt, l.ldpt, c, C, ldc} : GemmOperandB{Pn, l.ldpn, c, C, ldc};
+      g.tile_hint = 0;
+    }
+    ProfScope ps(ctx, fused ? PRAC_KERNEL_FUSED_FWD : PRAC_KERNEL_COMPRESS);
+    return launch_gemm_bf16(ctx, g);
+  }
+  // generic path: fp32 data (P used in fp32) or unaligned bf16
+  const size_t es = esize(xdt);
+  WsPlan plan;
+  const bool need_tmp = xdt == PRAC_BF16;
+  const size_t o_tmp = plan.take(need_tmp ? (size_t)N * (c > m ? c : (size_t)m) * sizeof(float) : 0);
+  (void)es;
+  if (need_tmp) {
+    int rc = prac_ws_reserve(ctx, plan.off);
+    if (rc) return rc;
+  }
+  float* tmp = need_tmp ? reinterpret_cast<float*>(ctx->ws + o_tmp) : nullptr;
+  GemmGenArgs g{};
+  g.A = X; g.adt = xdt; g.a_rs = ldx; g.a_cs = 1;
+  g.M = (int)N; g.K = d; g.k_stride = 1; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
+  // C = X P
+  g.B = P; g.bdt = PRAC_F32; g.b_rs = ldp; g.b_cs = 1; g.N = c;
+  g.out = need_tmp ? tmp : reinterpret_cast<float*>(C);
+  g.ldo = need_tmp ? c : ldc;
+  int rc = launch_gemm_generic(ctx, g);
+  if (rc) return rc;
+  if (need_tmp) {
+    rc = launch_cast_out(ctx, tmp, c, C, PRAC_BF16, ldc, (int)N, c, 0.f);
+    if (rc) return rc;
+  }
+  if (fused) {
+    g.B = W; g.bdt = xdt; g.N = (int)m;
+    if (w_layout == 1) { g.b_rs = 1; g.b_cs = ldw; } else { g.b_rs = ldw; g.b_cs = 1; }
+    g.out = need_tmp ? tmp : reinterpret_cast<float*>(Y);
+    g.ldo = need_tmp ? m : ldy;
+    rc = launch_gemm_generic(ctx, g);
+    if (rc) return rc;
+    if (need_tmp) rc = launch_cast_out(ctx, tmp, m, Y, PRAC_BF16, ldy, (int)N, (int)m, 0.f);
+  }
+  return rc;
+}
+
+int prac_compress(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, const float* P,
+                  const void* P_lp, int64_t ldp, int c, void* C, int64_t ldc) {
+  if (!X || !P || !C || !valid_dtype(xdt) || N < 1 || d < 1 || d > (1 << 20) || c < 1 || c > d || ldx < d ||
+      ldp < c || ldc < c || (P_lp && !aligned16(P_lp)))
+    return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  return compress_impl(ctx, X, xdt, N, d, ldx, nullptr, 0, 0, 0, P, P_lp, ldp, c, nullptr, 0, C, ldc);
+}
+
+int prac_compress_fused_fwd(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
+                            const void* W, int64_t m, int64_t ldw, int w_layout, const float* P, const void* P_lp,
+                            int64_t ldp, int c, void* Y, int64_t ldy, void* C, int64_t ldc) {
+  if (!X || !P || !C || !W || !Y || !valid_dtype(xdt) || N < 1 || d < 1 || d > (1 << 20) || c < 1 || c > d ||
+      m < 1 || m > (1 << 20) || ldx < d || ldp < c || ldc < c || ldy < m || (w_layout != 0 && w_layout != 1) ||
+      ldw < (w_layout == 1 ? d : m) || (P_lp && !aligned16(P_lp)))
+    return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  return compress_impl(ctx, X, xdt, N, d, ldx, W, m, ldw, w_layout, P, P_lp, ldp, c, Y, ldy, C, ldc);
+}
+
+// ------------------------------------------------------------------ weight grad
+int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt, int64_t N, int64_t m, int64_t ldc,
+                     int64_t lddy, const float* P, const void* P_lp, int64_t d, int64_t ldp, int k, int r,
+                     float scale, void* dW, prac_dtype odt, int64_t lddw, float beta) {
+  if (!C || !dY || !P || !dW || !valid_dtype(dt) || !valid_dtype(odt) || N < 1 || m < 1 || m > (1 << 20) || d < 1 ||
+      d > (1 << 20) || k < 0 || r < 0 || k + r < 1 || (int64_t)k + r > d || ldc < k + r || lddy < m ||
+      ldp < k + r || lddw < m || (P_lp && !aligned16(P_lp)))
+    return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  const int c = k + r;
+  const bool fast = dt == PRAC_BF16 && aligned16(C) && aligned16(dY) && ldc % 8 == 0 && lddy % 8 == 0 &&
+                    N < ((int64_t)1 << 31);
+  if (fast) {
+    const LpLayout l = lp_layout(d, c);
+    const int tiles = ((c + 255) / 256) * (int)((m + 127) / 128);
+    const int splits = pick_splits(tiles, N, ctx->n_cu, 256);
+    const int64_t ldt = round_up64(c, 8);
+    WsPlan plan;
+    const size_t o_part = plan.take((size_t)splits * c * m * sizeof(float));
+    const size_t o_tt = plan.take((size_t)m * ldt * sizeof(bf16_t));
+    const size_t o_lp = plan.take(P_lp ? 0 : l.bytes);
+    int rc = prac_ws_reserve(ctx, plan.off);
+    if (rc) return rc;
+    const char* lp = reinterpret_cast<const char*>(P_lp);
+    if (!lp) {
+      rc = prac_pack_basis(ctx, P, d, ldp, c, ctx->ws + o_lp);
+      if (rc) return rc;
+      lp = ctx->ws + o_lp;
+    }
+    float* part = reinterpret_cast<float*>(ctx->ws + o_part);
+    bf16_t* Tt = reinterpret_cast<bf16_t*>(ctx->ws + o_tt);
+    // T = C^T dY as `splits` partial slabs over the token range
+    GemmBf16Args g{};
+    g.A = reinterpret_cast<const bf16_t*>(C);
+    g.lda = ldc;
+    g.M = c;
+    g.K = (int)N;
+    g.a_kc = false;
+    g.b_kc = false;
+    g.b0 = GemmOperandB{reinterpret_cast<const bf16_t*>(dY), lddy, (int)m, nullptr, 0};
+    g.b1 = GemmOperandB{nullptr, 0, 0, nullptr, 0};
+    g.out_bf16 = false;
+    g.beta = 0.f;
+    g.splits = splits > 1 ? splits : 2;  // always through the slab path: the reducer also scales and transposes
+    g.partial = part;
+    g.tile_hint = 1;
+    {
+      ProfScope ps(ctx, PRAC_KERNEL_CT_DY);
+      rc = launch_gemm_bf16(ctx, g);
+    }
+    if (rc) return rc;
+    // T^T (m x c, bf16) with the random rows weighted by the scaling factor
+    {
+      ProfScope ps(ctx, PRAC_KERNEL_T_REDUCE);
+      rc = launch_reduce_transpose_bf16(ctx, part, g.splits, c, (int)m, k, scale, Tt, ldt);
+    }
+    if (rc) return rc;
+    // dW = P T
+    GemmBf16Args h{};
+    h.A = reinterpret_cast<const bf16_t*>(lp + l.off_pn);
+    h.lda = l.ldpn;
+    h.M = (int)d;
+    h.K = c;
+    h.a_kc = true;
+    h.b_kc = true;
+    h.b0 = GemmOperandB{Tt, ldt, (int)m, dW, lddw};
+    h.b1 = GemmOperandB{nullptr, 0, 0, nullptr, 0};
+    h.out_bf16 = odt == PRAC_BF16;
+    h.beta = beta;
+    h.splits = 1;
+    h.partial = nullptr;
+    h.tile_hint = 0;
+    ProfScope ps(ctx, PRAC_KERNEL_P_T);
+    return launch_gemm_bf16(ctx, h);
+  }
+  // generic path: T = C^T dY (fp32), scale the random rows, dW = P T
+  WsPlan plan;
+  const size_t o_t = plan.take((size_t)c * m * sizeof(float));
+  const size_t o_dw = plan.take(odt == PRAC_BF16 ? (size_t)d * m * sizeof(float) : 0);
+  int rc = prac_ws_reserve(ctx, plan.off);
+  if (rc) return rc;
+  float* T = reinterpret_cast<float*>(ctx->ws + o_t);
+  GemmGenArgs g{};
+  g.A = C; g.adt = dt; g.a_rs = 1; g.a_cs = ldc;
+  g.B = dY; g.bdt = dt; g.b_rs = lddy; g.b_cs = 1;
+  g.M = c; g.N = (int)m; g.K = N; g.k_stride = 1;
+  g.out = T; g.ldo = m; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
+  rc = launch_gemm_generic(ctx, g);
+  if (rc) return rc;
+  rc = launch_scale_rows(ctx, T, c, (int)m, m, k, scale);
+  if (rc) return rc;
+  GemmGenArgs h{};
+  h.A = P; h.adt = PRAC_F32; h.a_rs = ldp; h.a_cs = 1;
+  h.B = T; h.bdt = PRAC_F32; h.b_rs = m; h.b_cs = 1;
+  h.M = (int)d; h.N = (int)m; h.K = c; h.k_stride = 1;
+  h.alpha = 1.f; h.acc64 = false; h.out64 = nullptr;
+  if (odt == PRAC_F32) {
+    h.out = reinterpret_cast<float*>(dW); h.ldo = lddw; h.beta = beta;
+    return launch_gemm_generic(ctx, h);
+  }
+  float* tmp = reinterpret_cast<float*>(ctx->ws + o_dw);
+  h.out = tmp; h.ldo = m; h.beta = 0.f;
+  rc = launch_gemm_generic(ctx, h);
+  if (rc) return rc;
+  return launch_cast_out(ctx, tmp, m, dW, PRAC_BF16, lddw, (int)d, (int)m, beta);
+}
+
+}  // extern "C"

@@ -1,0 +1,132 @@
+// Internal declarations shared by the HIP translation units of libprac.
+// Nothing here is part of the C ABI (see include/prac.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <utility>
+#include <vector>
+
+#include "prac.h"
+
+typedef unsigned short bf16_t;  // raw bf16 bit pattern
+
+struct prac_ctx {
+  int device;
+  hipStream_t stream;
+  char* ws;           // device scratch, grown on demand
+  size_t ws_bytes;
+  int* d_flag;        // device-side numeric failure flag (0 = fine)
+  int last_hip;       // last hipError_t that made a call fail
+  int n_cu;
+  int prof_kind;      // kernel kind bracketed by events (0: none), see prac_profile_select
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_pairs;  // recorded, not yet read
+  std::vector<hipEvent_t> prof_pool;                          // idle events
+};
+
+// Brackets the launches issued during its lifetime with a HIP event pair on the ctx
+// stream when the ctx is profiling this kernel kind.
+struct ProfScope {
+  prac_ctx* ctx;
+  hipEvent_t stop;
+  bool on;
+  ProfScope(prac_ctx* c, int kind);
+  ~ProfScope();
+};
+
+// Bump allocator over the ctx scratch for one API call.
+struct WsPlan {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t o = off;
+    off += (bytes + 255) & ~size_t(255);
+    return o;
+  }
+};
+int prac_ws_reserve(prac_ctx* ctx, size_t bytes);  // PRAC_OK / PRAC_ENOMEM / PRAC_EHIP
+
+static inline int64_t round_up64(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// ---- bf16 MFMA GEMM ---------------------------------------------------------
+// Out(M x N) = sum_k A(m,k) * B(k,n) over bf16 operands with fp32 accumulation.
+// a_kc: A is stored M x K (K contiguous, lda) else K x M (M contiguous, lda).
+// b_kc: B is stored N x K (K contiguous, ldb) else K x N (N contiguous, ldb).
+struct GemmOperandB {
+  const bf16_t* B;
+  int64_t ldb;
+  int N;
+  void* out;  // out_bf16 ? bf16 : fp32, row-major M x N
+  int64_t ldo;
+};
+struct GemmBf16Args {
+  const bf16_t* A;
+  int64_t lda;
+  int M, K;
+  bool a_kc, b_kc;
+  GemmOperandB b0;     // columns of the first output
+  GemmOperandB b1;     // optional second output sharing A (b1.B == nullptr: none)
+  bool out_bf16;       // output element type (ignored when splits > 1)
+  float beta;          // out = acc + beta * out (fp32 / bf16 out, splits == 1)
+  int splits;          // > 1: split the K range, write fp32 slabs to `partial`
+  float* partial;      // splits x M x N (b0 only), slab stride M*N
+  int tile_hint;       // 0 auto
+};
+int launch_gemm_bf16(prac_ctx* ctx, const GemmBf16Args& a);
+
+// ---- generic strided GEMM (fp32 / bf16 in, fp32 out) ----------------------------
+// Out(m,n) = alpha * sum_k A(m,k) B(k,n) + beta * Out(m,n); element (m,k) of A at
+// A[m*a_rs + k*a_cs], (k,n) of B at B[k*b_rs + n*b_cs]; accumulation in fp32 or
+// fp64 (acc64).  k_stride > 1 visits k = 0, k_stride, 2 k_stride, ... (< K).
+struct GemmGenArgs {
+  const void* A;
+  const void* B;
+  prac_dtype adt, bdt;
+  int64_t a_rs, a_cs, b_rs, b_cs;
+  int M, N;
+  int64_t K, k_stride;
+  float* out;
+  int64_t ldo;
+  float alpha, beta;
+  bool acc64;
+  double* out64;  // when non-null the fp64 result is written here instead (ldo applies)
+  int splits;     // > 1 with slabs != nullptr: split the reduction, then sum the slabs
+  void* slabs;    // splits * M * N accumulators (fp64 if acc64 else fp32)
+};
+int launch_gemm_generic(prac_ctx* ctx, const GemmGenArgs& a);
+
+// ---- small helpers -------------------------------------------------------------
+// out[i] = alpha * sum_s part[s*stride + i] + beta * out[i], i < n (fp32)
+int launch_reduce_slabs(prac_ctx* ctx, const float* part, int splits, int64_t stride, float* out,
+                        int64_t n, float alpha, float beta);
+// Tt (N x ldt bf16) = transpose of rowscale(j) * sum_s part[s][j][n], j < M; columns M..ldt-1 zeroed
+int launch_reduce_transpose_bf16(prac_ctx* ctx, const float* part, int splits, int M, int N, int k_lo,
+                                 float scale_hi, bf16_t* Tt, int64_t ldt);
+// fp32 matrix (rows x cols, ld) rows >= k_lo multiplied by s
+int launch_scale_rows(prac_ctx* ctx, float* T, int rows, int cols, int64_t ld, int k_lo, float s);
+int launch_philox(prac_ctx* ctx, uint64_t seed, uint32_t draw, uint32_t stream, void* out, int64_t n,
+                  bool normal);
+int launch_pack_basis(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, bf16_t* Pt,
+                      int64_t ldpt, bf16_t* Pn, int64_t ldpn);
+int launch_cast_out(prac_ctx* ctx, const float* src, int64_t lds, void* dst, prac_dtype odt,
+                    int64_t ldd, int rows, int cols, float beta);
+int launch_symmetrize(prac_ctx* ctx, float* G, int d, int64_t ldg);  // copy upper -> lower
+
+// ---- basis fit -----------------------------------------------------------------
+int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
+                     int k, int r, uint64_t seed, uint32_t draw, int refresh, const prac_fit_opts& o,
+                     float* P, int64_t ldp);
+size_t gram_scratch_bytes(const prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d,
+                          int64_t ldx, int64_t row_stride, int64_t ldg);
+int gram_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
+                int64_t row_stride, float* G, int64_t ldg, char* scratch);
+
+#define PRAC_HIP_TRY(ctx, expr)                 \
+  do {                                          \
+    hipError_t e__ = (expr);                    \
+    if (e__ != hipSuccess) {                    \
+      (ctx)->last_hip = (int)e__;               \
+      return PRAC_EHIP;                         \
+    }                                           \
+  } while (0)

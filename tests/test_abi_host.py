@@ -1,0 +1,121 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol that include/prac.h declares, and rejects bad arguments before it
+looks at the context or touches the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2602_23111_amd import prac
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+DUMMY = C.c_void_p(0x1000)  # never dereferenced: argument checks come first
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return prac.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "prac.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(prac_[a-z_0-9]+)\s*\(", header)))
+    assert declared == sorted(prac.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_strerror_and_lp_bytes(lib):
+    assert lib.prac_strerror(0) == b"ok"
+    assert lib.prac_strerror(-1) == b"invalid argument"
+    assert lib.prac_strerror(-99) == b"unknown status"
+    # P^T as c x round_up(d,64) plus P as d x round_up(c,64), bf16, first part 256-byte aligned
+    d, c = 100, 24
+    first = (c * 128 * 2 + 255) // 256 * 256
+    assert lib.prac_basis_lp_bytes(d, c) == first + d * 64 * 2
+    assert lib.prac_basis_lp_bytes(0, 4) == 0
+
+
+def _compress(lib, ctx=None, X=DUMMY, dt=1, N=8, d=16, ldx=16, P=DUMMY, lp=None, ldp=4, c=4, Cp=DUMMY, ldc=4):
+    return lib.prac_compress(ctx, X, dt, N, d, ldx, P, lp, ldp, c, Cp, ldc)
+
+
+def test_compress_argument_checks(lib):
+    assert _compress(lib) == -6                    # valid arguments, null ctx
+    assert _compress(lib, X=None) == -1
+    assert _compress(lib, P=None) == -1
+    assert _compress(lib, Cp=None) == -1
+    assert _compress(lib, dt=7) == -1
+    assert _compress(lib, N=0) == -1
+    assert _compress(lib, ldx=15) == -1            # ldx < d
+    assert _compress(lib, c=17, ldp=17, ldc=17) == -1  # c > d
+    assert _compress(lib, ldp=3) == -1
+    assert _compress(lib, ldc=3) == -1
+    assert _compress(lib, lp=C.c_void_p(0x1008)) == -1  # packed copy must be 16-byte aligned
+
+
+def _wgrad(lib, ctx=None, Cm=DUMMY, dY=DUMMY, dt=1, N=8, m=6, ldc=4, lddy=6, P=DUMMY, lp=None, d=16, ldp=4,
+           k=2, r=2, scale=7.0, dW=DUMMY, odt=0, lddw=6, beta=0.0):
+    return lib.prac_weight_grad(ctx, Cm, dY, dt, N, m, ldc, lddy, P, lp, d, ldp, k, r, scale, dW, odt, lddw, beta)
+
+
+def test_weight_grad_argument_checks(lib):
+    assert _wgrad(lib) == -6
+    assert _wgrad(lib, dY=None) == -1
+    assert _wgrad(lib, k=-1) == -1
+    assert _wgrad(lib, k=0, r=0) == -1
+    assert _wgrad(lib, k=10, r=7, ldc=17, ldp=17) == -1   # k + r > d
+    assert _wgrad(lib, ldc=3) == -1
+    assert _wgrad(lib, lddy=5) == -1
+    assert _wgrad(lib, lddw=5) == -1
+    assert _wgrad(lib, odt=3) == -1
+
+
+def _fit(lib, ctx=None, X=DUMMY, dt=1, N=8, d=16, ldx=16, k=2, r=2, seed=1, draw=0, refresh=3, opts=None,
+         P=DUMMY, ldp=4, lp=None):
+    scale = C.c_float(-1.0)
+    rc = lib.prac_fit_basis(ctx, X, dt, N, d, ldx, k, r, seed, draw, refresh, opts, P, ldp, lp, C.byref(scale))
+    return rc, scale.value
+
+
+def test_fit_basis_argument_checks(lib):
+    assert _fit(lib)[0] == -6
+    assert _fit(lib, P=None)[0] == -1
+    assert _fit(lib, k=9, r=8, ldp=17)[0] == -1          # k + r > d
+    assert _fit(lib, k=0, r=0)[0] == -1
+    assert _fit(lib, ldp=3)[0] == -1
+    assert _fit(lib, X=None)[0] == -1                    # Q1 refresh needs X
+    assert _fit(lib, X=None, refresh=2)[0] == -6         # ... but a Q2-only refresh does not
+    assert _fit(lib, X=None, k=0, r=4)[0] == -6          # nor does a purely random basis
+    assert _fit(lib, draw=1 << 32)[0] == -1
+    assert _fit(lib, refresh=4)[0] == -1
+    bad = prac.FitOpts(-1, 0, 0, 0)
+    assert _fit(lib, opts=C.byref(bad))[0] == -1
+
+
+def test_other_entry_points_reject_bad_arguments(lib):
+    assert lib.prac_gram(None, DUMMY, 1, 8, 16, 16, 1, DUMMY, 16) == -6
+    assert lib.prac_gram(None, DUMMY, 1, 8, 16, 16, 0, DUMMY, 16) == -1   # row_stride < 1
+    assert lib.prac_gram(None, DUMMY, 1, 8, 16, 16, 1, DUMMY, 15) == -1   # ldg < d
+    assert lib.prac_philox_words(None, 1, 0, 0, DUMMY, 16) == -6
+    assert lib.prac_philox_words(None, 1, 0, 0, None, 16) == -1
+    assert lib.prac_philox_normal(None, 1, 1 << 32, 0, DUMMY, 16) == -1
+    assert lib.prac_pack_basis(None, DUMMY, 16, 4, 4, DUMMY) == -6
+    assert lib.prac_pack_basis(None, DUMMY, 16, 3, 4, DUMMY) == -1
+    f = lib.prac_compress_fused_fwd
+    assert f(None, DUMMY, 1, 8, 16, 16, DUMMY, 6, 6, 0, DUMMY, None, 4, 4, DUMMY, 6, DUMMY, 4) == -6
+    assert f(None, DUMMY, 1, 8, 16, 16, DUMMY, 6, 6, 2, DUMMY, None, 4, 4, DUMMY, 6, DUMMY, 4) == -1  # layout
+    assert f(None, DUMMY, 1, 8, 16, 16, DUMMY, 6, 6, 1, DUMMY, None, 4, 4, DUMMY, 6, DUMMY, 4) == -1  # ldw < d
+    assert f(None, DUMMY, 1, 8, 16, 16, DUMMY, 6, 6, 0, DUMMY, None, 4, 4, DUMMY, 5, DUMMY, 4) == -1  # ldy < m
+    assert lib.prac_destroy(None) == -6 and lib.prac_sync_status(None) == -6
+
+
+def test_create_fails_cleanly_without_a_device(lib):
+    import torch
+
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible")
+    h = C.c_void_p()
+    assert lib.prac_create(C.byref(h), 0, None) == -3 and not h.value
