@@ -102,7 +102,7 @@ def main():
     import torch
 
     import synth_inputs as si
-    from paper_2602_23111_amd.prac import KERNEL_KINDS, Prac
+    from paper_2602_23111_amd.prac import C_PACKED, KERNEL_KINDS, Prac
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -118,7 +118,7 @@ def main():
     for i in range(w["n_sets"]):
         Xs.append(si.activation_torch(N, d, w["alpha"], 3000 + i, w["n_out"], w["out_scale"], torch.bfloat16, dev))
         dYs.append(si.grad_output_torch(N, m, w["dy_std"], 3100 + i, torch.bfloat16, dev))
-        Cs.append(torch.empty((N, c), dtype=torch.bfloat16, device=dev))
+        Cs.append(torch.empty(ctx.compressed_bytes(N, c) // 2, dtype=torch.bfloat16, device=dev))
     dW = torch.empty((d, m), dtype=torch.bfloat16, device=dev)
     P = torch.zeros((d, c), dtype=torch.float32, device=dev)
     state = dict(lp=None, scale=0.0, fits=0)
@@ -128,8 +128,8 @@ def main():
         if t % w["refresh_every"] == 0:
             _, state["lp"], state["scale"] = ctx.fit_basis(Xs[i], k, r, seed=1234, draw=t // w["refresh_every"], P=P)
             state["fits"] += 1
-        ctx.compress(Xs[i], P, P_lp=state["lp"], out=Cs[i])
-        ctx.weight_grad(Cs[i], dYs[i], P, k, r, state["scale"], P_lp=state["lp"], out=dW)
+        ctx.compress(Xs[i], P, P_lp=state["lp"], out=Cs[i], layout=C_PACKED)
+        ctx.weight_grad(Cs[i], dYs[i], P, k, r, state["scale"], P_lp=state["lp"], out=dW, layout=C_PACKED)
 
     # warm-up (includes the first fit so that scratch is allocated), then find the dominant kernel
     for t in range(max(args.warmup, 1)):

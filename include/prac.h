@@ -92,6 +92,10 @@ enum {
 };
 int prac_profile_select(prac_ctx* ctx, int kind);
 int prac_profile_read(prac_ctx* ctx, double* total_ms, int64_t* launches);
+/* Launch-shape override for sweeps: PRAC_TUNE_CTDY_SPLITS = number of token ranges
+ * the C^T dY reduction is split into (1..64; 0 restores the built-in choice). */
+enum { PRAC_TUNE_CTDY_SPLITS = 1 };
+int prac_set_tuning(prac_ctx* ctx, int key, int value);
 
 /* ---- Gaussian draw (Eq. (S_o): S_ij ~ N(0,1) i.i.d.) -------------------- */
 /* Counter-based Philox4x32-10.  Word i of stream (seed, draw, stream) is lane
@@ -115,8 +119,9 @@ int prac_gram(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d
 /* Bytes of the packed low-precision copy of a d x c basis (see below). */
 size_t prac_basis_lp_bytes(int64_t d, int c);
 /* Build the packed bf16 copy P_lp of P (d x c fp32, ldp >= c) that the bf16
- * kernels read: P^T as c x round_up(d,64) bf16 (zero padded) followed by P as
- * d x round_up(c,64) bf16 (zero padded). */
+ * kernels read: P^T as c x round_up(d,64) bf16, P as d x round_up(c,64) bf16,
+ * and P in 16 x 32 MFMA fragment order (all zero padded, each part 256-byte
+ * aligned). */
 int prac_pack_basis(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c,
                     void* P_lp);
 /* Writes P = [Q1 | Q2] (d x (k+r) fp32, UNSCALED, ldp >= k+r), optionally its
@@ -132,12 +137,28 @@ int prac_fit_basis(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int6
                    int64_t ldp, void* P_lp, float* scale /* [host], may be NULL */);
 
 /* ---- compression (Alg. 1 compression step, unscaled) ------------------- */
-/* C (N x c, ldc >= c, dtype of X) = X (N x d, ldx >= d) * P (d x c).
+/* Storage of the compressed activation C (N x c).
+ *   PRAC_C_ROWMAJOR  N x c row-major with leading dimension ldc >= c.
+ *   PRAC_C_PACKED    bf16 only; the layout the weight-gradient kernel reads without
+ *                    a transpose: blocks of 16 tokens x 32 columns, block (tb, cb) at
+ *                    element offset ((tb * ceil(c/32) + cb) * 64 + lane) * 8 + e with
+ *                    lane = 32 h + (column % 32) and token = 16 tb + (e < 4 ? 4 h + e
+ *                    : 8 + 4 h + e - 4), h in {0,1}, e in 0..7.  Rows / columns past
+ *                    N / c are stored as zeros; ldc is ignored.
+ * prac_compressed_bytes gives the buffer size of either layout (0 on bad arguments). */
+typedef enum { PRAC_C_ROWMAJOR = 0, PRAC_C_PACKED = 1 } prac_c_layout;
+size_t prac_compressed_bytes(int64_t N, int c, prac_dtype dt, int c_layout, int64_t ldc);
+/* Copy a packed C (bf16) into a row-major N x c bf16 matrix: a pure permutation. */
+int prac_unpack_compressed(prac_ctx* ctx, const void* C_packed, int64_t N, int c, void* C,
+                           int64_t ldc);
+
+/* C (N x c, dtype of X, layout c_layout) = X (N x d, ldx >= d) * P (d x c).
  * P is the fp32 master (ldp >= c); P_lp its packed copy or NULL (then it is
- * packed into ctx scratch on every call).  fp32 X uses P directly. */
+ * packed into ctx scratch on every call).  fp32 X uses P directly and supports
+ * the row-major layout only. */
 int prac_compress(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d,
                   int64_t ldx, const float* P, const void* P_lp, int64_t ldp, int c,
-                  void* C, int64_t ldc);
+                  void* C, int64_t ldc, int c_layout);
 
 /* Same C, plus the layer's forward output Y (N x m, ldy >= m, dtype of X) in
  * one pass over X.  W has X's dtype; w_layout 0: d x m row-major (Y = X W,
@@ -145,17 +166,17 @@ int prac_compress(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64
 int prac_compress_fused_fwd(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N,
                             int64_t d, int64_t ldx, const void* W, int64_t m, int64_t ldw,
                             int w_layout, const float* P, const void* P_lp, int64_t ldp,
-                            int c, void* Y, int64_t ldy, void* C, int64_t ldc);
+                            int c, void* Y, int64_t ldy, void* C, int64_t ldc, int c_layout);
 
 /* ---- weight gradient (Lemma 1; Alg. 2 backward) ------------------------- */
 /* dW (d x m, lddw >= m, dtype odt) = beta * dW + X~^T dY with
  * X~ = C[:, :k] Q1^T + scale * C[:, k:] Q2^T, evaluated as
  * P * diag(1..1, scale..scale) * (C^T dY).
- * C (N x (k+r), ldc) and dY (N x m, lddy) share dtype `dt`. */
+ * C (N x (k+r), layout c_layout) and dY (N x m, lddy) share dtype `dt`. */
 int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt, int64_t N,
-                     int64_t m, int64_t ldc, int64_t lddy, const float* P, const void* P_lp,
-                     int64_t d, int64_t ldp, int k, int r, float scale, void* dW,
-                     prac_dtype odt, int64_t lddw, float beta);
+                     int64_t m, int64_t ldc, int c_layout, int64_t lddy, const float* P,
+                     const void* P_lp, int64_t d, int64_t ldp, int k, int r, float scale,
+                     void* dW, prac_dtype odt, int64_t lddw, float beta);
 
 #ifdef __cplusplus
 }

@@ -13,7 +13,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libprac.so")
-SOURCES = ["prac_api.hip", "gemm_bf16.hip", "gemm_generic.hip", "misc_kernels.hip", "fit_basis.hip"]
+SOURCES = ["prac_api.hip", "gemm_bf16.hip", "hot_kernels.hip", "gemm_generic.hip", "misc_kernels.hip", "fit_basis.hip"]
 
 
 def build(verbose: bool = False) -> str:

@@ -12,16 +12,22 @@ inline bool valid_dtype(int t) { return t == PRAC_F32 || t == PRAC_BF16; }
 
 struct LpLayout {
   int64_t ldpt, ldpn;
-  size_t off_pn, bytes;
+  int nkb, ncb;  // fragment-order copy: 16-row blocks over round_up(d,64), 32-column blocks (multiple of 8)
+  size_t off_pn, off_pf, bytes;
 };
 inline LpLayout lp_layout(int64_t d, int c) {
   LpLayout l;
   l.ldpt = round_up64(d, 64);
   l.ldpn = round_up64(c, 64);
-  l.off_pn = (size_t)c * l.ldpt * sizeof(bf16_t);
-  l.off_pn = (l.off_pn + 255) & ~size_t(255);
-  l.bytes = l.off_pn + (size_t)d * l.ldpn * sizeof(bf16_t);
+  l.nkb = (int)(round_up64(d, 64) / 16);
+  l.ncb = (int)round_up64((c + 31) / 32, 8);
+  l.off_pn = ((size_t)c * l.ldpt * sizeof(bf16_t) + 255) & ~size_t(255);
+  l.off_pf = (l.off_pn + (size_t)d * l.ldpn * sizeof(bf16_t) + 255) & ~size_t(255);
+  l.bytes = l.off_pf + (size_t)l.nkb * l.ncb * 64 * 8 * sizeof(bf16_t);
   return l;
+}
+inline size_t packed_c_bytes(int64_t N, int c) {
+  return (size_t)((N + 15) / 16) * ((c + 31) / 32) * 64 * 8 * sizeof(bf16_t);
 }
 
 // split count for a reduction over K with `tiles` output tiles: fill the chip about
@@ -188,6 +194,7 @@ int prac_create(prac_ctx** out, int device, void* hip_stream) {
   c->d_flag = nullptr;
   c->last_hip = 0;
   c->prof_kind = 0;
+  c->tune_splits = 0;
   hipDeviceProp_t prop;
   c->n_cu = (hipGetDeviceProperties(&prop, device) == hipSuccess) ? prop.multiProcessorCount : 256;
   if (hipMalloc(reinterpret_cast<void**>(&c->d_flag), 256) != hipSuccess ||
@@ -237,6 +244,13 @@ int prac_profile_select(prac_ctx* ctx, int kind) {
   if (kind < PRAC_KERNEL_NONE || kind > PRAC_KERNEL_FUSED_FWD) return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
   ctx->prof_kind = kind;
+  return PRAC_OK;
+}
+
+int prac_set_tuning(prac_ctx* ctx, int key, int value) {
+  if (key != PRAC_TUNE_CTDY_SPLITS || value < 0 || value > 64) return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  ctx->tune_splits = value;
   return PRAC_OK;
 }
 
@@ -299,8 +313,10 @@ int prac_pack_basis(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c
   if (!ctx) return PRAC_ENOCTX;
   const LpLayout l = lp_layout(d, c);
   char* base = reinterpret_cast<char*>(P_lp);
-  return launch_pack_basis(ctx, P, d, ldp, c, reinterpret_cast<bf16_t*>(base), l.ldpt,
-                           reinterpret_cast<bf16_t*>(base + l.off_pn), l.ldpn);
+  int rc = launch_pack_basis(ctx, P, d, ldp, c, reinterpret_cast<bf16_t*>(base), l.ldpt,
+                             reinterpret_cast<bf16_t*>(base + l.off_pn), l.ldpn);
+  if (rc) return rc;
+  return launch_pack_pfrag(ctx, P, d, ldp, c, l.nkb, l.ncb, reinterpret_cast<bf16_t*>(base + l.off_pf));
 }
 
 int prac_fit_basis(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, int k, int r,
@@ -326,24 +342,50 @@ int prac_fit_basis(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int6
 }
 
 // --------------------------------------------------------------------- compress
+size_t prac_compressed_bytes(int64_t N, int c, prac_dtype dt, int c_layout, int64_t ldc) {
+  if (N < 1 || c < 1 || !valid_dtype(dt)) return 0;
+  if (c_layout == PRAC_C_PACKED) return dt == PRAC_BF16 ? packed_c_bytes(N, c) : 0;
+  if (c_layout != PRAC_C_ROWMAJOR || ldc < c) return 0;
+  return (size_t)N * ldc * esize(dt);
+}
+
+int prac_unpack_compressed(prac_ctx* ctx, const void* Cpk, int64_t N, int c, void* C, int64_t ldc) {
+  if (!Cpk || !C || N < 1 || N >= ((int64_t)1 << 31) || c < 1 || ldc < c || !aligned16(Cpk)) return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  return launch_unpack_c(ctx, reinterpret_cast<const bf16_t*>(Cpk), (int)N, c, reinterpret_cast<bf16_t*>(C), ldc);
+}
+
 static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
                          const void* W, int64_t m, int64_t ldw, int w_layout, const float* P, const void* P_lp,
-                         int64_t ldp, int c, void* Y, int64_t ldy, void* C, int64_t ldc) {
+                         int64_t ldp, int c, void* Y, int64_t ldy, void* C, int64_t ldc, int c_layout) {
   const bool fused = W != nullptr;
+  const bool packed = c_layout == PRAC_C_PACKED;
   const bool fast = xdt == PRAC_BF16 && aligned16(X) && ldx % 8 == 0 && N < ((int64_t)1 << 31) &&
                     (!fused || (aligned16(W) && ldw % 8 == 0));
+  if (packed && (xdt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
   if (fast) {
     const LpLayout l = lp_layout(d, c);
+    WsPlan plan;
+    const size_t o_lp = plan.take(P_lp ? 0 : l.bytes);
+    const size_t o_c = plan.take(fused && packed ? (size_t)N * round_up64(c, 8) * sizeof(bf16_t) : 0);
+    int rc = prac_ws_reserve(ctx, plan.off);
+    if (rc) return rc;
     const char* lp = reinterpret_cast<const char*>(P_lp);
     if (!lp) {
-      int rc = prac_ws_reserve(ctx, l.bytes);
+      rc = prac_pack_basis(ctx, P, d, ldp, c, ctx->ws + o_lp);
       if (rc) return rc;
-      rc = prac_pack_basis(ctx, P, d, ldp, c, ctx->ws);
-      if (rc) return rc;
-      lp = ctx->ws;
+      lp = ctx->ws + o_lp;
     }
     const bf16_t* Pt = reinterpret_cast<const bf16_t*>(lp);
     const bf16_t* Pn = reinterpret_cast<const bf16_t*>(lp + l.off_pn);
+    const bf16_t* Pf = reinterpret_cast<const bf16_t*>(lp + l.off_pf);
+    if (!fused) {
+      ProfScope ps(ctx, PRAC_KERNEL_COMPRESS);
+      return launch_compress_panel(ctx, reinterpret_cast<const bf16_t*>(X), ldx, (int)N, (int)d, Pf, l.ncb, c,
+                                   reinterpret_cast<bf16_t*>(C), ldc, packed);
+    }
+    void* Crm = packed ? static_cast<void*>(ctx->ws + o_c) : C;
+    const int64_t ldcrm = packed ? round_up64(c, 8) : ldc;
     GemmBf16Args g{};
     g.A = reinterpret_cast<const bf16_t*>(X);
     g.lda = ldx;
@@ -354,31 +396,29 @@ static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N
     g.beta = 0.f;
     g.splits = 1;
     g.partial = nullptr;
-    if (!fused) {
-      g.b_kc = true;
-      g.b0 = GemmOperandB{Pt, l.ldpt, c, C, ldc};
-      g.b1 = GemmOperandB{nullptr, 0, 0, nullptr, 0};
-      g.tile_hint = 1;
-    } else {
-      g.b_kc = w_layout == 1;
-      g.b0 = GemmOperandB{reinterpret_cast<const bf16_t*>(W), ldw, (int)m, Y, ldy};
-      g.b1 = g.b_kc ? GemmOperandB{Pt, l.ldpt, c, C, ldc} : GemmOperandB{Pn, l.ldpn, c, C, ldc};
-      g.tile_hint = 0;
+    g.b_kc = w_layout == 1;
+    g.b0 = GemmOperandB{reinterpret_cast<const bf16_t*>(W), ldw, (int)m, Y, ldy};
+    g.b1 = g.b_kc ? GemmOperandB{Pt, l.ldpt, c, Crm, ldcrm} : GemmOperandB{Pn, l.ldpn, c, Crm, ldcrm};
+    g.tile_hint = 0;
+    {
+      ProfScope ps(ctx, PRAC_KERNEL_FUSED_FWD);
+      rc = launch_gemm_bf16(ctx, g);
     }
-    ProfScope ps(ctx, fused ? PRAC_KERNEL_FUSED_FWD : PRAC_KERNEL_COMPRESS);
-    return launch_gemm_bf16(ctx, g);
+    if (rc || !packed) return rc;
+    return launch_pack_c(ctx, reinterpret_cast<const bf16_t*>(Crm), ldcrm, (int)N, c, reinterpret_cast<bf16_t*>(C));
   }
   // generic path: fp32 data (P used in fp32) or unaligned bf16
-  const size_t es = esize(xdt);
   WsPlan plan;
   const bool need_tmp = xdt == PRAC_BF16;
   const size_t o_tmp = plan.take(need_tmp ? (size_t)N * (c > m ? c : (size_t)m) * sizeof(float) : 0);
-  (void)es;
-  if (need_tmp) {
+  const size_t o_c = plan.take(packed ? (size_t)N * round_up64(c, 8) * sizeof(bf16_t) : 0);
+  if (plan.off) {
     int rc = prac_ws_reserve(ctx, plan.off);
     if (rc) return rc;
   }
   float* tmp = need_tmp ? reinterpret_cast<float*>(ctx->ws + o_tmp) : nullptr;
+  void* Crm = packed ? static_cast<void*>(ctx->ws + o_c) : C;
+  const int64_t ldcrm = packed ? round_up64(c, 8) : ldc;
   GemmGenArgs g{};
   g.A = X; g.adt = xdt; g.a_rs = ldx; g.a_cs = 1;
   g.M = (int)N; g.K = d; g.k_stride = 1; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
@@ -389,8 +429,12 @@ static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N
   int rc = launch_gemm_generic(ctx, g);
   if (rc) return rc;
   if (need_tmp) {
-    rc = launch_cast_out(ctx, tmp, c, C, PRAC_BF16, ldc, (int)N, c, 0.f);
+    rc = launch_cast_out(ctx, tmp, c, Crm, PRAC_BF16, ldcrm, (int)N, c, 0.f);
     if (rc) return rc;
+    if (packed) {
+      rc = launch_pack_c(ctx, reinterpret_cast<const bf16_t*>(Crm), ldcrm, (int)N, c, reinterpret_cast<bf16_t*>(C));
+      if (rc) return rc;
+    }
   }
   if (fused) {
     g.B = W; g.bdt = xdt; g.N = (int)m;
@@ -404,47 +448,58 @@ static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N
   return rc;
 }
 
+static bool bad_c_layout(int c_layout, int64_t ldc, int c) {
+  if (c_layout == PRAC_C_PACKED) return false;
+  return c_layout != PRAC_C_ROWMAJOR || ldc < c;
+}
+
 int prac_compress(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, const float* P,
-                  const void* P_lp, int64_t ldp, int c, void* C, int64_t ldc) {
+                  const void* P_lp, int64_t ldp, int c, void* C, int64_t ldc, int c_layout) {
   if (!X || !P || !C || !valid_dtype(xdt) || N < 1 || d < 1 || d > (1 << 20) || c < 1 || c > d || ldx < d ||
-      ldp < c || ldc < c || (P_lp && !aligned16(P_lp)))
+      ldp < c || bad_c_layout(c_layout, ldc, c) || (P_lp && !aligned16(P_lp)))
     return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
-  return compress_impl(ctx, X, xdt, N, d, ldx, nullptr, 0, 0, 0, P, P_lp, ldp, c, nullptr, 0, C, ldc);
+  return compress_impl(ctx, X, xdt, N, d, ldx, nullptr, 0, 0, 0, P, P_lp, ldp, c, nullptr, 0, C, ldc, c_layout);
 }
 
 int prac_compress_fused_fwd(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
                             const void* W, int64_t m, int64_t ldw, int w_layout, const float* P, const void* P_lp,
-                            int64_t ldp, int c, void* Y, int64_t ldy, void* C, int64_t ldc) {
+                            int64_t ldp, int c, void* Y, int64_t ldy, void* C, int64_t ldc, int c_layout) {
   if (!X || !P || !C || !W || !Y || !valid_dtype(xdt) || N < 1 || d < 1 || d > (1 << 20) || c < 1 || c > d ||
-      m < 1 || m > (1 << 20) || ldx < d || ldp < c || ldc < c || ldy < m || (w_layout != 0 && w_layout != 1) ||
-      ldw < (w_layout == 1 ? d : m) || (P_lp && !aligned16(P_lp)))
+      m < 1 || m > (1 << 20) || ldx < d || ldp < c || bad_c_layout(c_layout, ldc, c) || ldy < m ||
+      (w_layout != 0 && w_layout != 1) || ldw < (w_layout == 1 ? d : m) || (P_lp && !aligned16(P_lp)))
     return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
-  return compress_impl(ctx, X, xdt, N, d, ldx, W, m, ldw, w_layout, P, P_lp, ldp, c, Y, ldy, C, ldc);
+  return compress_impl(ctx, X, xdt, N, d, ldx, W, m, ldw, w_layout, P, P_lp, ldp, c, Y, ldy, C, ldc, c_layout);
 }
 
 // ------------------------------------------------------------------ weight grad
 int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt, int64_t N, int64_t m, int64_t ldc,
-                     int64_t lddy, const float* P, const void* P_lp, int64_t d, int64_t ldp, int k, int r,
-                     float scale, void* dW, prac_dtype odt, int64_t lddw, float beta) {
+                     int c_layout, int64_t lddy, const float* P, const void* P_lp, int64_t d, int64_t ldp, int k,
+                     int r, float scale, void* dW, prac_dtype odt, int64_t lddw, float beta) {
   if (!C || !dY || !P || !dW || !valid_dtype(dt) || !valid_dtype(odt) || N < 1 || m < 1 || m > (1 << 20) || d < 1 ||
-      d > (1 << 20) || k < 0 || r < 0 || k + r < 1 || (int64_t)k + r > d || ldc < k + r || lddy < m ||
-      ldp < k + r || lddw < m || (P_lp && !aligned16(P_lp)))
+      d > (1 << 20) || k < 0 || r < 0 || k + r < 1 || (int64_t)k + r > d || bad_c_layout(c_layout, ldc, k + r) ||
+      lddy < m || ldp < k + r || lddw < m || (P_lp && !aligned16(P_lp)))
     return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
   const int c = k + r;
-  const bool fast = dt == PRAC_BF16 && aligned16(C) && aligned16(dY) && ldc % 8 == 0 && lddy % 8 == 0 &&
-                    N < ((int64_t)1 << 31);
+  const bool packed = c_layout == PRAC_C_PACKED;
+  if (packed && (dt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
+  const bool fast = dt == PRAC_BF16 && aligned16(dY) && lddy % 8 == 0 && N < ((int64_t)1 << 31);
   if (fast) {
     const LpLayout l = lp_layout(d, c);
     const int tiles = ((c + 255) / 256) * (int)((m + 127) / 128);
-    const int splits = pick_splits(tiles, N, ctx->n_cu, 256);
-    const int64_t ldt = round_up64(c, 8);
+    int splits = (ctx->n_cu + tiles - 1) / tiles;          // about one workgroup per CU
+    if (splits > N / 256) splits = (int)(N / 256);
+    if (splits < 1) splits = 1;
+    if (splits > 64) splits = 64;
+    if (ctx->tune_splits > 0) splits = ctx->tune_splits;
+    const int64_t ldt = round_up64(m, 8);
     WsPlan plan;
     const size_t o_part = plan.take((size_t)splits * c * m * sizeof(float));
-    const size_t o_tt = plan.take((size_t)m * ldt * sizeof(bf16_t));
+    const size_t o_t = plan.take((size_t)c * ldt * sizeof(bf16_t));
     const size_t o_lp = plan.take(P_lp ? 0 : l.bytes);
+    const size_t o_cpk = plan.take(packed ? 0 : packed_c_bytes(N, c));
     int rc = prac_ws_reserve(ctx, plan.off);
     if (rc) return rc;
     const char* lp = reinterpret_cast<const char*>(P_lp);
@@ -453,32 +508,23 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
       if (rc) return rc;
       lp = ctx->ws + o_lp;
     }
+    const bf16_t* Cpk = reinterpret_cast<const bf16_t*>(C);
+    if (!packed) {
+      rc = launch_pack_c(ctx, reinterpret_cast<const bf16_t*>(C), ldc, (int)N, c,
+                         reinterpret_cast<bf16_t*>(ctx->ws + o_cpk));
+      if (rc) return rc;
+      Cpk = reinterpret_cast<const bf16_t*>(ctx->ws + o_cpk);
+    }
     float* part = reinterpret_cast<float*>(ctx->ws + o_part);
-    bf16_t* Tt = reinterpret_cast<bf16_t*>(ctx->ws + o_tt);
-    // T = C^T dY as `splits` partial slabs over the token range
-    GemmBf16Args g{};
-    g.A = reinterpret_cast<const bf16_t*>(C);
-    g.lda = ldc;
-    g.M = c;
-    g.K = (int)N;
-    g.a_kc = false;
-    g.b_kc = false;
-    g.b0 = GemmOperandB{reinterpret_cast<const bf16_t*>(dY), lddy, (int)m, nullptr, 0};
-    g.b1 = GemmOperandB{nullptr, 0, 0, nullptr, 0};
-    g.out_bf16 = false;
-    g.beta = 0.f;
-    g.splits = splits > 1 ? splits : 2;  // always through the slab path: the reducer also scales and transposes
-    g.partial = part;
-    g.tile_hint = 1;
-    {
+    bf16_t* T = reinterpret_cast<bf16_t*>(ctx->ws + o_t);
+    {  // T = C^T dY as `splits` partial slabs over the token range
       ProfScope ps(ctx, PRAC_KERNEL_CT_DY);
-      rc = launch_gemm_bf16(ctx, g);
+      rc = launch_ctdy(ctx, Cpk, c, reinterpret_cast<const bf16_t*>(dY), lddy, (int)N, (int)m, part, splits);
     }
     if (rc) return rc;
-    // T^T (m x c, bf16) with the random rows weighted by the scaling factor
-    {
+    {  // T (c x m, bf16): slabs summed, random rows weighted by the scaling factor
       ProfScope ps(ctx, PRAC_KERNEL_T_REDUCE);
-      rc = launch_reduce_transpose_bf16(ctx, part, g.splits, c, (int)m, k, scale, Tt, ldt);
+      rc = launch_reduce_scale_bf16(ctx, part, splits, c, (int)m, k, scale, T, ldt);
     }
     if (rc) return rc;
     // dW = P T
@@ -488,8 +534,8 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
     h.M = (int)d;
     h.K = c;
     h.a_kc = true;
-    h.b_kc = true;
-    h.b0 = GemmOperandB{Tt, ldt, (int)m, dW, lddw};
+    h.b_kc = false;
+    h.b0 = GemmOperandB{T, ldt, (int)m, dW, lddw};
     h.b1 = GemmOperandB{nullptr, 0, 0, nullptr, 0};
     h.out_bf16 = odt == PRAC_BF16;
     h.beta = beta;
@@ -503,11 +549,20 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
   WsPlan plan;
   const size_t o_t = plan.take((size_t)c * m * sizeof(float));
   const size_t o_dw = plan.take(odt == PRAC_BF16 ? (size_t)d * m * sizeof(float) : 0);
+  const size_t o_crm = plan.take(packed ? (size_t)N * c * sizeof(bf16_t) : 0);
   int rc = prac_ws_reserve(ctx, plan.off);
   if (rc) return rc;
+  const void* Crm = C;
+  int64_t ldcrm = ldc;
+  if (packed) {
+    rc = launch_unpack_c(ctx, reinterpret_cast<const bf16_t*>(C), (int)N, c, reinterpret_cast<bf16_t*>(ctx->ws + o_crm), c);
+    if (rc) return rc;
+    Crm = ctx->ws + o_crm;
+    ldcrm = c;
+  }
   float* T = reinterpret_cast<float*>(ctx->ws + o_t);
   GemmGenArgs g{};
-  g.A = C; g.adt = dt; g.a_rs = 1; g.a_cs = ldc;
+  g.A = Crm; g.adt = dt; g.a_rs = 1; g.a_cs = ldcrm;
   g.B = dY; g.bdt = dt; g.b_rs = lddy; g.b_cs = 1;
   g.M = c; g.N = (int)m; g.K = N; g.k_stride = 1;
   g.out = T; g.ldo = m; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;

@@ -21,6 +21,7 @@ struct prac_ctx {
   int* d_flag;        // device-side numeric failure flag (0 = fine)
   int last_hip;       // last hipError_t that made a call fail
   int n_cu;
+  int tune_splits;    // > 0: override the token-split count of C^T dY (tuning hook)
   int prof_kind;      // kernel kind bracketed by events (0: none), see prac_profile_select
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_pairs;  // recorded, not yet read
   std::vector<hipEvent_t> prof_pool;                          // idle events
@@ -112,6 +113,17 @@ int launch_pack_basis(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int
 int launch_cast_out(prac_ctx* ctx, const float* src, int64_t lds, void* dst, prac_dtype odt,
                     int64_t ldd, int rows, int cols, float beta);
 int launch_symmetrize(prac_ctx* ctx, float* G, int d, int64_t ldg);  // copy upper -> lower
+
+// ---- streaming kernels of the per-step path (hot_kernels.hip) ---------------------
+int launch_compress_panel(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d, const bf16_t* Pfrag, int ncb,
+                          int c, bf16_t* C, int64_t ldc, bool packed);
+int launch_ctdy(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, int64_t lddy, int N, int m,
+                float* slabs, int splits);
+int launch_pack_pfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nkb, int ncb, bf16_t* out);
+int launch_unpack_c(prac_ctx* ctx, const bf16_t* Cpk, int N, int c, bf16_t* C, int64_t ldc);
+int launch_pack_c(prac_ctx* ctx, const bf16_t* C, int64_t ldc, int N, int c, bf16_t* Cpk);
+int launch_reduce_scale_bf16(prac_ctx* ctx, const float* slabs, int splits, int c, int m, int k_lo,
+                             float scale_hi, bf16_t* T, int64_t ldt);
 
 // ---- basis fit -----------------------------------------------------------------
 int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,

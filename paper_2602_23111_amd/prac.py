@@ -16,12 +16,15 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libprac.so
 
 PRAC_F32, PRAC_BF16 = 0, 1
 PRAC_REFRESH_PRINCIPAL, PRAC_REFRESH_RANDOM = 1, 2
+C_ROWMAJOR, C_PACKED = 0, 1
+TUNE_CTDY_SPLITS = 1
 KERNEL_KINDS = {"compress": 1, "ct_dy": 2, "t_reduce": 3, "p_t": 4, "gram": 5, "fused_fwd": 6}
 STATUS = {0: "PRAC_OK", -1: "PRAC_EINVAL", -2: "PRAC_ENOMEM", -3: "PRAC_EHIP",
           -4: "PRAC_ENUMERIC", -5: "PRAC_EUNSUPPORTED", -6: "PRAC_ENOCTX"}
 
 EXPORTS = ["prac_create", "prac_destroy", "prac_set_stream", "prac_sync_status", "prac_strerror",
-           "prac_last_hip_error", "prac_profile_select", "prac_profile_read", "prac_philox_words", "prac_philox_normal", "prac_gram",
+           "prac_last_hip_error", "prac_profile_select", "prac_profile_read", "prac_set_tuning",
+           "prac_compressed_bytes", "prac_unpack_compressed", "prac_philox_words", "prac_philox_normal", "prac_gram",
            "prac_basis_lp_bytes", "prac_pack_basis", "prac_fit_basis", "prac_compress",
            "prac_compress_fused_fwd", "prac_weight_grad"]
 
@@ -58,6 +61,9 @@ def load_library() -> C.CDLL:
         "prac_last_hip_error": (i32, [vp]),
         "prac_profile_select": (i32, [vp, i32]),
         "prac_profile_read": (i32, [vp, C.POINTER(C.c_double), C.POINTER(i64)]),
+        "prac_set_tuning": (i32, [vp, i32, i32]),
+        "prac_compressed_bytes": (C.c_size_t, [i64, i32, i32, i32, i64]),
+        "prac_unpack_compressed": (i32, [vp, vp, i64, i32, vp, i64]),
         "prac_philox_words": (i32, [vp, u64, u64, u32, vp, i64]),
         "prac_philox_normal": (i32, [vp, u64, u64, u32, vp, i64]),
         "prac_gram": (i32, [vp, vp, i32, i64, i64, i64, i64, vp, i64]),
@@ -65,10 +71,10 @@ def load_library() -> C.CDLL:
         "prac_pack_basis": (i32, [vp, vp, i64, i64, i32, vp]),
         "prac_fit_basis": (i32, [vp, vp, i32, i64, i64, i64, i32, i32, u64, u64, i32,
                                  C.POINTER(FitOpts), vp, i64, vp, C.POINTER(f32)]),
-        "prac_compress": (i32, [vp, vp, i32, i64, i64, i64, vp, vp, i64, i32, vp, i64]),
+        "prac_compress": (i32, [vp, vp, i32, i64, i64, i64, vp, vp, i64, i32, vp, i64, i32]),
         "prac_compress_fused_fwd": (i32, [vp, vp, i32, i64, i64, i64, vp, i64, i64, i32, vp, vp, i64,
-                                          i32, vp, i64, vp, i64]),
-        "prac_weight_grad": (i32, [vp, vp, vp, i32, i64, i64, i64, i64, vp, vp, i64, i64, i32, i32,
+                                          i32, vp, i64, vp, i64, i32]),
+        "prac_weight_grad": (i32, [vp, vp, vp, i32, i64, i64, i64, i32, i64, vp, vp, i64, i64, i32, i32,
                                    f32, vp, i32, i64, f32]),
     }
     for name, (res, args) in sig.items():
@@ -189,42 +195,70 @@ class Prac:
         return P, lp, float(scale.value)
 
     # ---- compress
-    def compress(self, X: torch.Tensor, P: torch.Tensor, P_lp: torch.Tensor | None = None,
-                 out: torch.Tensor | None = None) -> torch.Tensor:
-        px, N, d, ldx = _mat(X)
-        pp, _, c, ldp = _mat(P)
+    def set_tuning(self, key: int, value: int):
+        _check(self.lib.prac_set_tuning(self._h, key, value), "prac_set_tuning")
+
+    def compressed_bytes(self, N: int, c: int, dtype: torch.dtype = torch.bfloat16, layout: int = C_PACKED,
+                         ldc: int = 0) -> int:
+        return int(self.lib.prac_compressed_bytes(N, c, PRAC_BF16 if dtype == torch.bfloat16 else PRAC_F32,
+                                                  layout, ldc))
+
+    def _c_out(self, N, c, X, out, layout):
+        """(tensor, pointer, ldc) of the compressed activation in the requested layout."""
+        if layout == C_PACKED:
+            Cm = out if out is not None else torch.empty(self.compressed_bytes(N, c) // 2, dtype=torch.bfloat16,
+                                                         device=X.device)
+            return Cm, Cm.data_ptr(), 0
         Cm = out if out is not None else torch.empty((N, c), dtype=X.dtype, device=X.device)
         pc, _, _, ldc = _mat(Cm)
+        return Cm, pc, ldc
+
+    def compress(self, X: torch.Tensor, P: torch.Tensor, P_lp: torch.Tensor | None = None,
+                 out: torch.Tensor | None = None, layout: int = C_ROWMAJOR) -> torch.Tensor:
+        px, N, d, ldx = _mat(X)
+        pp, _, c, ldp = _mat(P)
+        Cm, pc, ldc = self._c_out(N, c, X, out, layout)
         _check(self.lib.prac_compress(self._h, px, _dt(X), N, d, ldx, pp, P_lp.data_ptr() if P_lp is not None else None,
-                                      ldp, c, pc, ldc), "prac_compress")
+                                      ldp, c, pc, ldc, layout), "prac_compress")
+        return Cm
+
+    def unpack_compressed(self, Cpk: torch.Tensor, N: int, c: int, out: torch.Tensor | None = None) -> torch.Tensor:
+        Cm = out if out is not None else torch.empty((N, c), dtype=torch.bfloat16, device=Cpk.device)
+        pc, _, _, ldc = _mat(Cm)
+        _check(self.lib.prac_unpack_compressed(self._h, Cpk.data_ptr(), N, c, pc, ldc), "prac_unpack_compressed")
         return Cm
 
     def compress_fused_fwd(self, X: torch.Tensor, W: torch.Tensor, P: torch.Tensor, w_layout: int = 0,
                            P_lp: torch.Tensor | None = None, Y: torch.Tensor | None = None,
-                           out: torch.Tensor | None = None):
+                           out: torch.Tensor | None = None, layout: int = C_ROWMAJOR):
         px, N, d, ldx = _mat(X)
         pw, w0, w1, ldw = _mat(W)
         m = w1 if w_layout == 0 else w0
         pp, _, c, ldp = _mat(P)
         Ym = Y if Y is not None else torch.empty((N, m), dtype=X.dtype, device=X.device)
-        Cm = out if out is not None else torch.empty((N, c), dtype=X.dtype, device=X.device)
         py, _, _, ldy = _mat(Ym)
-        pc, _, _, ldc = _mat(Cm)
+        Cm, pc, ldc = self._c_out(N, c, X, out, layout)
         _check(self.lib.prac_compress_fused_fwd(self._h, px, _dt(X), N, d, ldx, pw, m, ldw, w_layout, pp,
                                                 P_lp.data_ptr() if P_lp is not None else None, ldp, c, py, ldy,
-                                                pc, ldc), "prac_compress_fused_fwd")
+                                                pc, ldc, layout), "prac_compress_fused_fwd")
         return Ym, Cm
 
     # ---- weight gradient
     def weight_grad(self, Cm: torch.Tensor, dY: torch.Tensor, P: torch.Tensor, k: int, r: int, scale: float,
                     P_lp: torch.Tensor | None = None, out: torch.Tensor | None = None,
-                    out_dtype: torch.dtype = torch.float32, beta: float = 0.0) -> torch.Tensor:
-        pc, N, c, ldc = _mat(Cm)
-        py, _, m, lddy = _mat(dY)
+                    out_dtype: torch.dtype = torch.float32, beta: float = 0.0,
+                    layout: int = C_ROWMAJOR) -> torch.Tensor:
+        """Cm: N x (k+r) row-major, or the flat packed buffer when layout == C_PACKED."""
+        py, N, m, lddy = _mat(dY)
         pp, d, _, ldp = _mat(P)
-        dW = out if out is not None else torch.empty((d, m), dtype=out_dtype, device=Cm.device)
+        if layout == C_PACKED:
+            pc, ldc, cdt = Cm.data_ptr(), 0, PRAC_BF16
+        else:
+            pc, _, _, ldc = _mat(Cm)
+            cdt = _dt(Cm)
+        dW = out if out is not None else torch.empty((d, m), dtype=out_dtype, device=dY.device)
         pw, _, _, lddw = _mat(dW)
-        _check(self.lib.prac_weight_grad(self._h, pc, py, _dt(Cm), N, m, ldc, lddy, pp,
+        _check(self.lib.prac_weight_grad(self._h, pc, py, cdt, N, m, ldc, layout, lddy, pp,
                                          P_lp.data_ptr() if P_lp is not None else None, d, ldp, k, r, scale, pw,
                                          _dt(dW), lddw, beta), "prac_weight_grad")
         return dW

@@ -34,12 +34,14 @@ def test_strerror_and_lp_bytes(lib):
     # P^T as c x round_up(d,64) plus P as d x round_up(c,64), bf16, first part 256-byte aligned
     d, c = 100, 24
     first = (c * 128 * 2 + 255) // 256 * 256
-    assert lib.prac_basis_lp_bytes(d, c) == first + d * 64 * 2
+    second = (first + d * 64 * 2 + 255) // 256 * 256
+    assert lib.prac_basis_lp_bytes(d, c) == second + (128 // 16) * 8 * 64 * 8 * 2
     assert lib.prac_basis_lp_bytes(0, 4) == 0
 
 
-def _compress(lib, ctx=None, X=DUMMY, dt=1, N=8, d=16, ldx=16, P=DUMMY, lp=None, ldp=4, c=4, Cp=DUMMY, ldc=4):
-    return lib.prac_compress(ctx, X, dt, N, d, ldx, P, lp, ldp, c, Cp, ldc)
+def _compress(lib, ctx=None, X=DUMMY, dt=1, N=8, d=16, ldx=16, P=DUMMY, lp=None, ldp=4, c=4, Cp=DUMMY, ldc=4,
+              layout=0):
+    return lib.prac_compress(ctx, X, dt, N, d, ldx, P, lp, ldp, c, Cp, ldc, layout)
 
 
 def test_compress_argument_checks(lib):
@@ -53,12 +55,15 @@ def test_compress_argument_checks(lib):
     assert _compress(lib, c=17, ldp=17, ldc=17) == -1  # c > d
     assert _compress(lib, ldp=3) == -1
     assert _compress(lib, ldc=3) == -1
+    assert _compress(lib, ldc=0, layout=1) == -6   # packed layout ignores ldc
+    assert _compress(lib, layout=2) == -1
     assert _compress(lib, lp=C.c_void_p(0x1008)) == -1  # packed copy must be 16-byte aligned
 
 
 def _wgrad(lib, ctx=None, Cm=DUMMY, dY=DUMMY, dt=1, N=8, m=6, ldc=4, lddy=6, P=DUMMY, lp=None, d=16, ldp=4,
-           k=2, r=2, scale=7.0, dW=DUMMY, odt=0, lddw=6, beta=0.0):
-    return lib.prac_weight_grad(ctx, Cm, dY, dt, N, m, ldc, lddy, P, lp, d, ldp, k, r, scale, dW, odt, lddw, beta)
+           k=2, r=2, scale=7.0, dW=DUMMY, odt=0, lddw=6, beta=0.0, layout=0):
+    return lib.prac_weight_grad(ctx, Cm, dY, dt, N, m, ldc, layout, lddy, P, lp, d, ldp, k, r, scale, dW, odt,
+                                lddw, beta)
 
 
 def test_weight_grad_argument_checks(lib):
@@ -68,6 +73,7 @@ def test_weight_grad_argument_checks(lib):
     assert _wgrad(lib, k=0, r=0) == -1
     assert _wgrad(lib, k=10, r=7, ldc=17, ldp=17) == -1   # k + r > d
     assert _wgrad(lib, ldc=3) == -1
+    assert _wgrad(lib, ldc=0, layout=1) == -6
     assert _wgrad(lib, lddy=5) == -1
     assert _wgrad(lib, lddw=5) == -1
     assert _wgrad(lib, odt=3) == -1
@@ -105,10 +111,18 @@ def test_other_entry_points_reject_bad_arguments(lib):
     assert lib.prac_pack_basis(None, DUMMY, 16, 4, 4, DUMMY) == -6
     assert lib.prac_pack_basis(None, DUMMY, 16, 3, 4, DUMMY) == -1
     f = lib.prac_compress_fused_fwd
-    assert f(None, DUMMY, 1, 8, 16, 16, DUMMY, 6, 6, 0, DUMMY, None, 4, 4, DUMMY, 6, DUMMY, 4) == -6
-    assert f(None, DUMMY, 1, 8, 16, 16, DUMMY, 6, 6, 2, DUMMY, None, 4, 4, DUMMY, 6, DUMMY, 4) == -1  # layout
-    assert f(None, DUMMY, 1, 8, 16, 16, DUMMY, 6, 6, 1, DUMMY, None, 4, 4, DUMMY, 6, DUMMY, 4) == -1  # ldw < d
-    assert f(None, DUMMY, 1, 8, 16, 16, DUMMY, 6, 6, 0, DUMMY, None, 4, 4, DUMMY, 5, DUMMY, 4) == -1  # ldy < m
+    assert f(None, DUMMY, 1, 8, 16, 16, DUMMY, 6, 6, 0, DUMMY, None, 4, 4, DUMMY, 6, DUMMY, 4, 0) == -6
+    assert f(None, DUMMY, 1, 8, 16, 16, DUMMY, 6, 6, 2, DUMMY, None, 4, 4, DUMMY, 6, DUMMY, 4, 0) == -1  # layout
+    assert f(None, DUMMY, 1, 8, 16, 16, DUMMY, 6, 6, 1, DUMMY, None, 4, 4, DUMMY, 6, DUMMY, 4, 0) == -1  # ldw < d
+    assert f(None, DUMMY, 1, 8, 16, 16, DUMMY, 6, 6, 0, DUMMY, None, 4, 4, DUMMY, 5, DUMMY, 4, 0) == -1  # ldy < m
+    assert lib.prac_unpack_compressed(None, DUMMY, 8, 4, DUMMY, 4) == -6
+    assert lib.prac_unpack_compressed(None, DUMMY, 8, 4, DUMMY, 3) == -1
+    assert lib.prac_set_tuning(None, 1, 8) == -6 and lib.prac_set_tuning(None, 2, 8) == -1
+    assert lib.prac_profile_select(None, 9) == -1 and lib.prac_profile_select(None, 1) == -6
+    # packed C: ceil(N/16) x ceil(c/32) blocks of 64 lanes x 8 bf16
+    assert lib.prac_compressed_bytes(100, 40, 1, 1, 0) == 7 * 2 * 64 * 8 * 2
+    assert lib.prac_compressed_bytes(100, 40, 1, 0, 48) == 100 * 48 * 2
+    assert lib.prac_compressed_bytes(100, 40, 0, 1, 0) == 0      # packed is bf16 only
     assert lib.prac_destroy(None) == -6 and lib.prac_sync_status(None) == -6
 
 

@@ -39,8 +39,11 @@ def test_compress_full_size_sampled_rows(ctx, d, ldx, k, r):
     X = si.activation_torch(N, d, 0.8, 3000, 8, 30.0, torch.bfloat16, DEV, ld=ldx)
     P32 = si.round_to(si.orthonormal_basis(d, c, seed=1), "f32")
     Pd = P32.to(DEV)
-    Cm = ctx.compress(X, Pd, P_lp=ctx.pack_basis(Pd))
+    from paper_2602_23111_amd.prac import C_PACKED
+    flat = ctx.compress(X, Pd, P_lp=ctx.pack_basis(Pd), layout=C_PACKED)      # as bench.py launches it
+    Cm = ctx.unpack_compressed(flat, N, c)
     torch.cuda.synchronize()
+    assert torch.equal(Cm, ctx.compress(X, Pd, P_lp=ctx.pack_basis(Pd)))       # row-major launch agrees
     rows = sample_rows(N, 264, seed=2)
     ref = orc.compress(si.as_f64(X[torch.from_numpy(rows).to(DEV)]), si.as_f64(P32))
     got = si.as_f64(Cm[torch.from_numpy(rows).to(DEV)])
@@ -62,8 +65,13 @@ def test_weight_grad_full_size_sampled_columns(ctx, d, m, lddy):
         Cin[r0:r0 + 4096] = (X[r0:r0 + 4096].float() @ Pd).to(torch.bfloat16)
     del X
     dY = si.grad_output_torch(N, m, 1e-3, 3101, torch.bfloat16, DEV, ld=lddy)
-    dW = ctx.weight_grad(Cin, dY, Pd, k, r, s, P_lp=ctx.pack_basis(Pd), out_dtype=torch.bfloat16)
+    from paper_2602_23111_amd.prac import C_PACKED
+    from test_gpu_parity import pack_c_reference
+    Cpk = pack_c_reference(Cin.cpu()).to(DEV)
+    dW = ctx.weight_grad(Cpk, dY, Pd, k, r, s, P_lp=ctx.pack_basis(Pd), out_dtype=torch.bfloat16, layout=C_PACKED)
+    dW_rm = ctx.weight_grad(Cin, dY, Pd, k, r, s, P_lp=ctx.pack_basis(Pd), out_dtype=torch.bfloat16)
     torch.cuda.synchronize()
+    assert torch.equal(dW, dW_rm)
     cols = np.sort(np.concatenate([np.random.default_rng(4).choice(m - 2, size=14, replace=False), [m - 2, m - 1]]))
     cols_t = torch.from_numpy(cols).to(DEV)
     ref = orc.weight_grad(si.as_f64(Cin), si.as_f64(dY[:, cols_t]), si.as_f64(P32), k, s)

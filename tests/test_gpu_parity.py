@@ -45,6 +45,33 @@ def dev_padded(t_cpu: torch.Tensor, ld: int) -> torch.Tensor:
     return buf[:, :m]
 
 
+def packed_index(N, c):
+    """Element offsets of the packed compressed-activation layout, written out from its
+    definition in include/prac.h: offset[n, col] for n < N, col < c, and the buffer length."""
+    ccb = (c + 31) // 32
+    n = np.arange(N)[:, None]
+    col = np.arange(c)[None, :]
+    tb, w = n // 16, n % 16
+    h = (w // 4) % 2
+    e = (w % 4) + 4 * (w // 8)
+    lane = 32 * h + col % 32
+    off = ((tb * ccb + col // 32) * 64 + lane) * 8 + e
+    return off, ((N + 15) // 16) * ccb * 64 * 8
+
+
+def pack_c_reference(Ct: torch.Tensor) -> torch.Tensor:
+    off, total = packed_index(*Ct.shape)
+    flat = torch.zeros(total, dtype=Ct.dtype)
+    flat[torch.from_numpy(off.reshape(-1))] = Ct.reshape(-1)
+    return flat
+
+
+def unpack_c_reference(flat: torch.Tensor, N: int, c: int) -> torch.Tensor:
+    off, total = packed_index(N, c)
+    assert flat.numel() == total
+    return flat.cpu()[torch.from_numpy(off.reshape(-1))].reshape(N, c)
+
+
 def basis32(d, c, seed):
     """A d x c orthonormal basis rounded to fp32 (the shared P of both sides)."""
     P32 = si.round_to(si.orthonormal_basis(d, c, seed), "f32")
@@ -98,6 +125,27 @@ def test_compress_matches_oracle(ctx, dt, N, d, c, ldx, ldc):
         assert rel_fro(si.as_f64(out), orc.compress(si.as_f64(Xt), P64)) < TOL[dt]
 
 
+@pytest.mark.parametrize("N,d,c", [(2048, 512, 64), (777, 328, 72), (515, 320, 256), (130, 328, 300), (17, 64, 33)])
+def test_compress_packed_layout(ctx, N, d, c):
+    # same numbers as the row-major result, stored in the documented block order, zero padded
+    Xt = si.round_to(si.activation(N, d, 0.8, seed=N + d, n_out=2, out_scale=20.0)[0], "bf16")
+    P32, P64 = basis32(d, c, seed=c)
+    from paper_2602_23111_amd.prac import C_PACKED
+    lp = ctx.pack_basis(P32.to(DEV))
+    flat = ctx.compress(Xt.to(DEV), P32.to(DEV), P_lp=lp, layout=C_PACKED)
+    rowm = ctx.compress(Xt.to(DEV), P32.to(DEV), P_lp=lp)
+    torch.cuda.synchronize()
+    assert flat.numel() * 2 == ctx.compressed_bytes(N, c)
+    got = unpack_c_reference(flat, N, c)
+    assert torch.equal(got, rowm.cpu())
+    assert torch.equal(ctx.unpack_compressed(flat, N, c).cpu(), rowm.cpu())
+    assert rel_fro(si.as_f64(got), orc.compress(si.as_f64(Xt), P64)) < 1e-2
+    off, total = packed_index(N, c)
+    pad = torch.ones(total, dtype=torch.bool)
+    pad[torch.from_numpy(off.reshape(-1))] = False
+    assert not flat.cpu()[pad].float().abs().any()          # padding rows / columns are zeros
+
+
 def test_compress_identity_columns_bit_exact(ctx):
     # P = first c columns of the identity: products by 0 and 1 only
     N, d, c = 500, 256, 40
@@ -125,6 +173,12 @@ def test_fused_forward_matches_oracle(ctx, dt, N, d, m, c, layout):
     torch.cuda.synchronize()
     assert rel_fro(si.as_f64(Y), orc.forward(si.as_f64(Xt), si.as_f64(Wt))) < TOL[dt]
     assert rel_fro(si.as_f64(Cm), orc.compress(si.as_f64(Xt), P64)) < TOL[dt]
+    if dt == "bf16":
+        from paper_2602_23111_amd.prac import C_PACKED
+        Y2, flat = ctx.compress_fused_fwd(dev_padded(Xt, (d + 7) // 8 * 8), dev_padded(Wdev, ldw), P32.to(DEV),
+                                          w_layout=layout, layout=C_PACKED)
+        torch.cuda.synchronize()
+        assert torch.equal(unpack_c_reference(flat, N, c), Cm.cpu()) and torch.equal(Y2, Y)
 
 
 # -------------------------------------------------------------- weight grad
@@ -136,7 +190,8 @@ WGRAD_CASES = [
     ("bf16", 3000, 328, 264, 40, 32, "f32"),    # several token splits, ragged tiles
     ("bf16", 1111, 200, 136, 0, 24, "f32"),     # RAC: k = 0
     ("bf16", 640, 96, 72, 16, 0, "f32"),        # PAC: r = 0 (biased, scale unused)
-    ("bf16", 900, 320, 520, 130, 130, "bf16"),  # c > 256: two row tiles of T
+    ("bf16", 900, 320, 520, 130, 130, "bf16"),  # c > 256: two row groups of T
+    ("bf16", 5000, 128, 96, 10, 23, "f32"),     # c = 33: a ragged 32-column block
     ("bf16", 700, 100, 51, 7, 6, "f32"),        # unaligned -> generic kernel
 ]
 
@@ -161,6 +216,12 @@ def test_weight_grad_matches_oracle(ctx, dt, N, d, m, k, r, odt):
     ctx.weight_grad(Cd, dYd, P32.to(DEV), k, r, s, P_lp=ctx.pack_basis(P32.to(DEV)), out=acc, beta=0.5)
     torch.cuda.synchronize()
     assert rel_fro(si.as_f64(acc), ref + 0.5 * si.as_f64(dW0)) < TOL[dt]
+    if dt == "bf16":
+        # the same C handed over in the packed layout gives the same estimate
+        from paper_2602_23111_amd.prac import C_PACKED
+        got_p = ctx.weight_grad(pack_c_reference(Ct).to(DEV), dYd, P32.to(DEV), k, r, s, layout=C_PACKED)
+        torch.cuda.synchronize()
+        assert rel_fro(si.as_f64(got_p), ref) < TOL[dt]
 
 
 def test_weight_grad_exact_gradient_when_complement_is_full(ctx):
