@@ -143,8 +143,9 @@ int prac_fit_basis(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int6
  *                    a transpose: blocks of 16 tokens x 32 columns, block (tb, cb) at
  *                    element offset ((tb * ceil(c/32) + cb) * 64 + lane) * 8 + e with
  *                    lane = 32 h + (column % 32) and token = 16 tb + (e < 4 ? 4 h + e
- *                    : 8 + 4 h + e - 4), h in {0,1}, e in 0..7.  Rows / columns past
- *                    N / c are stored as zeros; ldc is ignored.
+ *                    : 8 + 4 h + e - 4), h in {0,1}, e in 0..7.  The buffer holds
+ *                    8 * ceil(N/128) token blocks (whole 128-token tiles); rows /
+ *                    columns past N / c are stored as zeros; ldc is ignored.
  * prac_compressed_bytes gives the buffer size of either layout (0 on bad arguments). */
 typedef enum { PRAC_C_ROWMAJOR = 0, PRAC_C_PACKED = 1 } prac_c_layout;
 size_t prac_compressed_bytes(int64_t N, int c, prac_dtype dt, int c_layout, int64_t ldc);

@@ -17,10 +17,21 @@
 //   C:  slot(h, e) = 4 h + e (e < 4), 8 + 4 h + e - 4 (e >= 4)   (token = 16 tb + slot)
 // The C order is the order in which the 32x32 MFMA accumulator of compress holds its
 // rows, so compress stores a packed block straight from its registers.
+//
+// All loads in the main loops are unconditional (addresses clamped into the operand,
+// invalid elements masked to zero afterwards) and the loops run whole groups of bodies
+// without branches: the compiler can then count exactly how many younger loads follow
+// the one it waits for, which is what keeps several tiles in flight.
+#include <type_traits>
+
 #include "prac_internal.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// 16-byte register value: a native vector (assignments of HIP's u32x4 struct lower to
+// memcpy, which keeps whole register sets in scratch memory)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
@@ -34,25 +45,18 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
-__device__ __forceinline__ uint4 load_chunk(const bf16_t* p, int n_valid) {
-  uint4 v = make_uint4(0u, 0u, 0u, 0u);
-  if (n_valid >= 8) {
-    v = *reinterpret_cast<const uint4*>(p);
-  } else if (n_valid > 0) {
-    bf16_t t[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) t[e] = e < n_valid ? p[e] : (bf16_t)0;
-    v.x = t[0] | ((uint32_t)t[1] << 16);
-    v.y = t[2] | ((uint32_t)t[3] << 16);
-    v.z = t[4] | ((uint32_t)t[5] << 16);
-    v.w = t[6] | ((uint32_t)t[7] << 16);
-  }
+// Keep the first n (0..8) bf16 of a 16-byte chunk, zero the rest.
+__device__ __forceinline__ u32x4 keep_first(u32x4 v, int n) {
+  v.x &= (n > 0 ? 0x0000FFFFu : 0u) | (n > 1 ? 0xFFFF0000u : 0u);
+  v.y &= (n > 2 ? 0x0000FFFFu : 0u) | (n > 3 ? 0xFFFF0000u : 0u);
+  v.z &= (n > 4 ? 0x0000FFFFu : 0u) | (n > 5 ? 0xFFFF0000u : 0u);
+  v.w &= (n > 6 ? 0x0000FFFFu : 0u) | (n > 7 ? 0xFFFF0000u : 0u);
   return v;
 }
 
-__device__ __forceinline__ bf16x8 as_frag(uint4 v) {
+__device__ __forceinline__ bf16x8 as_frag(u32x4 v) {
   union {
-    uint4 u;
+    u32x4 u;
     bf16x8 f;
   } c;
   c.u = v;
@@ -64,10 +68,10 @@ struct CompressArgs {
   const bf16_t* X;
   int64_t ldx;
   int N, d;
-  const bf16_t* Pfrag;  // [d64/16][ncb][64][8]
-  int ncb;              // 32-column blocks in the padded basis (multiple of 4*FN)
+  const bf16_t* Pfrag;  // [nkb][ncb][64][8], nkb = round_up(d,128)/16
+  int ncb;              // 32-column blocks in the padded basis (multiple of 8)
   int c;
-  bf16_t* C;            // row-major (ldc) or packed [Npad/16][ccb][64][8]
+  bf16_t* C;            // row-major (ldc) or packed [ceil(N/16)][ccb][64][8]
   int64_t ldc;
   int ccb;              // 32-column blocks of packed C = ceil(c / 32)
   int packed;
@@ -75,19 +79,27 @@ struct CompressArgs {
   int col_groups;       // column groups of 4*FN blocks
 };
 
-constexpr int CP_BM = 128, CP_BK = 64, CP_LD = CP_BK + 8, CP_STAGES = 3;
+constexpr int CP_BM = 128, CP_BK = 128, CP_LD = CP_BK + 8, CP_STAGES = 2;
+constexpr int CP_HK = 4;  // 16-row k-blocks per half tile (P fragments are fetched per half tile)
 
 // 256 threads = 4 waves.  The workgroup owns 128 token rows; wave w owns the 32*FN
-// columns [32 FN w, 32 FN (w+1)) of its column group and all 128 rows.  X tiles go
-// global -> registers -> LDS (3-stage ring, loads issued two tiles ahead); P fragments
-// go global -> registers one tile ahead.
-template <int FN>
+// columns [32 FN w, 32 FN (w+1)) of its column group and all 128 rows.
+//   X tiles (128 x 128) go global -> registers -> LDS (two stages); tile kt+3 is requested
+//   while tile kt is multiplied, 256 contiguous bytes per row and request.
+//   P fragments go global (L2) -> registers, half a tile (64 k) at a time, three register
+//   sets, each requested one tile ahead of its use.
+//   Loads return in issue order, so P requests are always issued ahead of the far-ahead X
+//   request of the same body: waiting for P never waits for HBM data requested just now.
+//   LDS fragment reads are double-buffered one k-block ahead of the MFMAs that use them,
+//   and the LDS store / global requests of the next tiles are issued behind the first MFMA
+//   block so that their issue cycles hide under matrix-core time.
+template <int FN, int VAR = 0>
 __global__ __launch_bounds__(256) void compress_panel_kernel(CompressArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
   constexpr int STAGE = CP_BM * CP_LD;
-  constexpr int A_CH = CP_BM * (CP_BK / 8) / 256;  // 4 chunks of 16 B per thread and tile
-  constexpr int KK = CP_BK / 16;
+  constexpr int A_CH = CP_BM * (CP_BK / 8) / 256;  // 8 chunks of 16 B per thread and tile
+  constexpr int KK = CP_BK / 16;                   // 8
 
   // XCD-aware order: consecutive logical tiles (same rows, next column group) on one XCD
   const int total = a.tiles_m * a.col_groups;
@@ -102,8 +114,22 @@ __global__ __launch_bounds__(256) void compress_panel_kernel(CompressArgs a) {
   const int m0 = tm * CP_BM;
   const int cb0 = cg * 4 * FN + wave * FN;  // first 32-column block of this wave
   const int nk = (a.d + CP_BK - 1) / CP_BK;
-  const bf16_t* __restrict__ X = a.X;
-  const uint4* __restrict__ Pf = reinterpret_cast<const uint4*>(a.Pfrag);
+  const int nh = 2 * nk;
+  const u32x4* __restrict__ Pf = reinterpret_cast<const u32x4*>(a.Pfrag);
+
+  // per-thread chunk coordinates: chunk p covers row (tid>>4) + 16 p, columns (tid&15)*8 ..
+  const int crow = tid >> 4, ccol = (tid & 15) * 8;
+  const int last_chunk = ((a.d - 1) / 8) * 8;  // start of the last (possibly partial) chunk of a row
+  // Addresses are a uniform 64-bit base (scalar registers) plus a 32-bit per-thread byte offset,
+  // so that a load needs one offset register instead of a 64-bit pointer per chunk.
+  const char* xbase = reinterpret_cast<const char*>(a.X + (int64_t)m0 * a.ldx);
+  uint32_t roff[A_CH];  // byte offset of this thread's row of chunk p (row clamped into the matrix)
+#pragma unroll
+  for (int p = 0; p < A_CH; ++p)
+    roff[p] = (uint32_t)(min(m0 + crow + 16 * p, a.N - 1) - m0) * (uint32_t)a.ldx * 2u;
+  const char* pbase = reinterpret_cast<const char*>(Pf);
+  const uint32_t boff = (uint32_t)(cb0 * 64 + lane) * 16u;  // this lane's slot in a row of P blocks
+  const int64_t brow = (int64_t)a.ncb * 1024;               // bytes per 16-row k-block of P fragments
 
   f32x16 acc[4][FN];
 #pragma unroll
@@ -113,71 +139,123 @@ __global__ __launch_bounds__(256) void compress_panel_kernel(CompressArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  uint4 ra[2][A_CH];
-  uint4 rb[2][KK * FN];
+  u32x4 ra[2][A_CH];
+  u32x4 rb[2][CP_HK * FN];
 
-  auto gload_a = [&](int kt, uint4 (&r)[A_CH]) {
-    const int k0 = kt * CP_BK;
+  // tile / half-tile indices are clamped to the last one: past-the-end prefetches re-read it
+  // (from L2) and are never used, which keeps the loop free of conditional loads
+  auto gload_a = [&](int kt, u32x4 (&r)[A_CH]) {
+    const uint32_t kb = (uint32_t)min(min(kt, nk - 1) * CP_BK + ccol, last_chunk) * 2u;
 #pragma unroll
-    for (int p = 0; p < A_CH; ++p) {
-      const int q = tid + p * 256, row = q >> 3, cc = (q & 7) * 8;
-      const int m = m0 + row, k = k0 + cc;
-      r[p] = load_chunk(X + (int64_t)m * a.ldx + k, m < a.N ? a.d - k : 0);
-    }
+    for (int p = 0; p < A_CH; ++p) r[p] = *reinterpret_cast<const u32x4*>(xbase + (roff[p] + kb));
   };
-  auto sstore_a = [&](int stage, const uint4 (&r)[A_CH]) {
+  // chunks [p0, p0 + 4) of tile kt into LDS.  Only the last tile of a d that is not a multiple
+  // of 128 needs its tail columns zeroed (MASK); rows past N are never stored, so they may
+  // hold anything finite or not.
+  auto sstore_a = [&](int kt, int stage, const u32x4 (&r)[A_CH], auto first, auto mask) {
+    constexpr bool MASK = decltype(mask)::value;
+    constexpr int p0 = decltype(first)::value;
     bf16_t* s = smem + stage * STAGE;
+    const int nv = a.d - (kt * CP_BK + ccol);
 #pragma unroll
-    for (int p = 0; p < A_CH; ++p) {
-      const int q = tid + p * 256, row = q >> 3, cc = (q & 7) * 8;
-      *reinterpret_cast<uint4*>(s + row * CP_LD + cc) = r[p];
-    }
+    for (int p = p0; p < p0 + 4; ++p)
+      *reinterpret_cast<u32x4*>(s + (crow + 16 * p) * CP_LD + ccol) = MASK ? keep_first(r[p], nv) : r[p];
   };
-  auto gload_b = [&](int kt, uint4 (&r)[KK * FN]) {
+  auto gload_b = [&](int hb, u32x4 (&r)[CP_HK * FN]) {
+    const char* hbase = pbase + (int64_t)min(hb, nh - 1) * CP_HK * brow;  // uniform
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
+    for (int kk = 0; kk < CP_HK; ++kk)
 #pragma unroll
       for (int j = 0; j < FN; ++j)
-        r[kk * FN + j] = Pf[((int64_t)(kt * KK + kk) * a.ncb + cb0 + j) * 64 + lane];
+        r[kk * FN + j] = *reinterpret_cast<const u32x4*>(hbase + kk * brow + j * 1024 + boff);
   };
-  auto compute = [&](int stage, const uint4 (&b)[KK * FN]) {
+  auto frag_load = [&](int stage, int kk, bf16x8 (&f)[4]) {
     const bf16_t* s = smem + stage * STAGE;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      bf16x8 fa[4];
+    for (int i = 0; i < 4; ++i)
+      f[i] = *reinterpret_cast<const bf16x8*>(s + (i * 32 + li) * CP_LD + kk * 16 + lh * 8);
+  };
+  auto mfma_block = [&](const bf16x8 (&f)[4], const u32x4* b) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        fa[i] = *reinterpret_cast<const bf16x8*>(s + (i * 32 + li) * CP_LD + kk * 16 + lh * 8);
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], as_frag(b[kk * FN + j]), acc[i][j], 0, 0, 0);
-    }
+      for (int j = 0; j < FN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], as_frag(b[j]), acc[i][j], 0, 0, 0);
   };
 
-  // prologue: tile 0 into LDS stage 0, tile 1 (A) in registers, B of tile 0 in registers
-  gload_a(0, ra[0]);
+  const bool tail_mask = (a.d % CP_BK) != 0;  // the last tile has columns past d
+
+  // prologue: P half 0 and X tiles 0, 1 on their way; tile 0 into LDS; tile 2 requested
   gload_b(0, rb[0]);
-  if (nk > 1) gload_a(1, ra[1]);
-  sstore_a(0, ra[0]);
+  gload_a(0, ra[0]);
+  gload_a(1, ra[1]);
+  if (nk == 1 && tail_mask) {
+    sstore_a(0, 0, ra[0], std::integral_constant<int, 0>{}, std::true_type{});
+    sstore_a(0, 0, ra[0], std::integral_constant<int, 4>{}, std::true_type{});
+  } else {
+    sstore_a(0, 0, ra[0], std::integral_constant<int, 0>{}, std::false_type{});
+    sstore_a(0, 0, ra[0], std::integral_constant<int, 4>{}, std::false_type{});
+  }
+  gload_a(2, ra[0]);
   __syncthreads();
 
-  // steady state at iteration kt: stage kt%3 holds tile kt; ra[(kt+1)&1] holds tile kt+1
-  for (int kt = 0; kt < nk; kt += 2) {
-    // even half: kt
-    if (kt + 1 < nk) sstore_a((kt + 1) % CP_STAGES, ra[1]);
-    if (kt + 2 < nk) gload_a(kt + 2, ra[0]);
-    if (kt + 1 < nk) gload_b(kt + 1, rb[1]);
-    compute(kt % CP_STAGES, rb[0]);
-    __syncthreads();
-    // odd half: kt + 1
-    if (kt + 1 < nk) {
-      if (kt + 2 < nk) sstore_a((kt + 2) % CP_STAGES, ra[0]);
-      if (kt + 3 < nk) gload_a(kt + 3, ra[1]);
-      if (kt + 2 < nk) gload_b(kt + 2, rb[0]);
-      compute((kt + 1) % CP_STAGES, rb[1]);
-      __syncthreads();
+  // body kt (PH = kt % 2): LDS stage kt%2 holds X tile kt; ra[(kt+1)%2] holds tile kt+1 and
+  // ra[kt%2] awaits tile kt+2; rb[0] / rb[1] hold the first / second P half of tile kt (rb[1]
+  // may still be in flight at the top).
+  // A wave issues in order and the matrix core accepts one MFMA every ~32 cycles, so
+  // everything else (LDS reads of the next k-block, the LDS store of tile kt+1, the global
+  // requests) is spread between the MFMAs by the scheduling-group pipeline at the end.
+  // Request order inside a body: second P half of tile kt+1 is not needed before the next
+  // body, so per body the order is  P(2nd half, tile kt) .. P(1st half, tile kt+1), X(kt+3):
+  // the X request is the youngest, and no wait for P ever has to wait for it.
+  auto body = [&](int kt, auto ph, auto mask) {
+    constexpr int PH = decltype(ph)::value;
+    constexpr int S = PH % 2, SA = (PH + 1) % 2;
+    constexpr int NMF = 4 * FN;  // MFMAs per k-block
+    bf16x8 fa[2][4];
+    if (!(VAR & 1)) frag_load(S, 0, fa[0]);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      if (!(VAR & 1) && kk + 1 < KK) frag_load(S, kk + 1, fa[(kk + 1) & 1]);
+      if (kk == 0 && !(VAR & 2)) gload_b(2 * kt + 1, rb[1]);
+      if (kk == 1 && !(VAR & 8)) sstore_a(kt + 1, SA, ra[SA], std::integral_constant<int, 0>{}, mask);
+      if (kk == 2 && !(VAR & 8)) sstore_a(kt + 1, SA, ra[SA], std::integral_constant<int, 4>{}, mask);
+      if (kk == 4 && !(VAR & 2)) gload_b(2 * kt + 2, rb[0]);
+      if (kk == ((VAR & 64) ? 3 : 5) && !(VAR & 4)) gload_a(kt + 3, ra[SA]);
+      if (!(VAR & 1)) mfma_block(fa[kk & 1], kk < CP_HK ? &rb[0][kk * FN] : &rb[1][(kk - CP_HK) * FN]);
+    }
+    if (VAR == 0 || VAR == 64) {
+      // pipeline: 4 LDS reads for the first k-block, then per MFMA one LDS read (while the
+      // next k-block still has some) and one of this k-block's extra operations
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+        for (int mi = 0; mi < NMF; ++mi) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (kk + 1 < KK && mi < 4) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          if ((kk == 0 || kk == 4) && mi < CP_HK * FN) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          if ((kk == 1 || kk == 2) && mi < 4) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+          if (kk == ((VAR & 64) ? 3 : 5) && mi < A_CH) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+    }
+    if (!(VAR & 16)) __syncthreads();
+  };
+  int kt = 0;
+  const int nfull = tail_mask ? nk - 2 : nk;  // bodies that never store a masked tile
+  for (; kt + 2 <= nfull; kt += 2) {
+    body(kt, std::integral_constant<int, 0>{}, std::false_type{});
+    body(kt + 1, std::integral_constant<int, 1>{}, std::false_type{});
+  }
+  // remaining bodies; body kt stores tile kt+1, so only body nk-2 stores the (masked) last tile
+  for (; kt < nk; ++kt) {
+    const bool m = tail_mask && kt == nk - 2;
+    if (kt % 2 == 0) {
+      if (m) body(kt, std::integral_constant<int, 0>{}, std::true_type{});
+      else body(kt, std::integral_constant<int, 0>{}, std::false_type{});
+    } else {
+      if (m) body(kt, std::integral_constant<int, 1>{}, std::true_type{});
+      else body(kt, std::integral_constant<int, 1>{}, std::false_type{});
     }
   }
 
@@ -185,21 +263,29 @@ __global__ __launch_bounds__(256) void compress_panel_kernel(CompressArgs a) {
   // of row block i, column li of column block cb0 + j.
   if (a.packed) {
     // registers v = 8 tb .. 8 tb + 7 are exactly the 8 slots of the 16-token block tb
-    uint4* Cp = reinterpret_cast<uint4*>(a.C);
-    const int ntb = (a.N + 15) / 16;
+    u32x4* Cp = reinterpret_cast<u32x4*>(a.C);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < FN; ++j)
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
+          // every token block of the 128-row tile is written: packed C is padded to whole tiles
           const int gtb = (m0 + i * 32) / 16 + tb, cb = cb0 + j;
-          if (gtb < ntb && cb < a.ccb) {
-            uint4 o;
-            o.x = pack2(acc[i][j][8 * tb + 0], acc[i][j][8 * tb + 1]);
-            o.y = pack2(acc[i][j][8 * tb + 2], acc[i][j][8 * tb + 3]);
-            o.z = pack2(acc[i][j][8 * tb + 4], acc[i][j][8 * tb + 5]);
-            o.w = pack2(acc[i][j][8 * tb + 6], acc[i][j][8 * tb + 7]);
+          if (cb < a.ccb) {
+            // slot e of this lane is token 16 gtb + (e < 4 ? 4 lh + e : 8 + 4 lh + e - 4);
+            // tokens past N (their X rows were not masked) are stored as zeros
+            float x[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const int tok = gtb * 16 + (e < 4 ? 4 * lh + e : 8 + 4 * lh + (e - 4));
+              x[e] = tok < a.N ? acc[i][j][8 * tb + e] : 0.f;
+            }
+            u32x4 o;
+            o.x = pack2(x[0], x[1]);
+            o.y = pack2(x[2], x[3]);
+            o.z = pack2(x[4], x[5]);
+            o.w = pack2(x[6], x[7]);
             Cp[((int64_t)gtb * a.ccb + cb) * 64 + lane] = o;
           }
         }
@@ -232,18 +318,24 @@ struct CtdyArgs {
   int row_groups;      // groups of 8 column blocks (256 rows of T) over c
 };
 
-constexpr int CT_BN = 128, CT_BK = 64, CT_LD = CT_BN + 8, CT_STAGES = 3;
+constexpr int CT_BN = 128, CT_BK = 128, CT_LD = CT_BN + 8, CT_STAGES = 2;
+constexpr int CT_HK = 4;  // 16-token blocks per half tile (C fragments are fetched per half tile)
 
 // 256 threads = 4 waves.  The workgroup owns 256 rows of T (columns of C) x 128 columns
 // (of dY) for one token range; wave w owns rows [64 w, 64 w + 64).  C fragments come
-// straight from the packed layout; dY tiles are staged in LDS as they lie in memory
-// ([token][column]) and turned into fragments by an in-register 8 x 4 transpose.
+// straight from the packed layout (global -> registers, half a tile at a time); dY tiles
+// (128 tokens x 128 columns) go global -> registers -> LDS as they lie in memory
+// ([token][column]) and are turned into fragments by an in-register 8 x 4 transpose.
+// Same request order and scheduling-group pipeline as the compress kernel.
+// No masking is needed: splits are whole 128-token tiles, token rows past N are read from
+// the last valid row of dY and meet the zero padding of packed C (stored for whole tiles);
+// columns past m or c only reach outputs that are never stored.
 __global__ __launch_bounds__(256) void ctdy_kernel(CtdyArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
   constexpr int STAGE = CT_BK * CT_LD;
-  constexpr int B_CH = CT_BK * (CT_BN / 8) / 256;  // 4
-  constexpr int KK = CT_BK / 16;
+  constexpr int B_CH = CT_BK * (CT_BN / 8) / 256;  // 8 chunks of 16 B per thread and tile
+  constexpr int KK = CT_BK / 16;                   // 8
 
   const int per_split = a.tiles_n * a.row_groups;
   const int total = per_split * a.splits;
@@ -261,10 +353,8 @@ __global__ __launch_bounds__(256) void ctdy_kernel(CtdyArgs a) {
   const int cb0 = rg * 8 + wave * 2;
   const int tok_beg = split * a.tok_per_split;
   const int tok_end = min(a.N, tok_beg + a.tok_per_split);
-  const int nk = (tok_end - tok_beg + CT_BK - 1) / CT_BK;
-  const int ntb = (a.N + 15) / 16;
-  const uint4* __restrict__ Cp = reinterpret_cast<const uint4*>(a.Cpk);
-  const bf16_t* __restrict__ dY = a.dY;
+  const int nk = tok_end > tok_beg ? (tok_end - tok_beg + CT_BK - 1) / CT_BK : 0;
+  const int ntb = ((a.N + 127) / 128) * 8;  // token blocks of packed C, padded to whole 128-token tiles
 
   f32x16 acc[2][4];
 #pragma unroll
@@ -274,91 +364,126 @@ __global__ __launch_bounds__(256) void ctdy_kernel(CtdyArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  uint4 rb[2][B_CH];
-  uint4 rafr[2][KK * 2];
+  if (nk > 0) {
+    // chunk p of a dY tile: token row (tid>>4) + 16 p, columns n0 + (tid&15)*8 ..
+    const int brow = tid >> 4, bcol = (tid & 15) * 8;
+    const int last_chunk = ((a.m - 1) / 8) * 8;
+    const char* ybase = reinterpret_cast<const char*>(a.dY) + (int64_t)min(n0 + bcol, last_chunk) * 2;
+    const int ok_a0 = cb0 < a.ccb, ok_a1 = cb0 + 1 < a.ccb;
+    const char* cbase = reinterpret_cast<const char*>(a.Cpk);
+    const uint32_t aoff0 = (uint32_t)((ok_a0 ? cb0 : 0) * 64 + lane) * 16u;
+    const uint32_t aoff1 = (uint32_t)((ok_a1 ? cb0 + 1 : 0) * 64 + lane) * 16u;
+    const int64_t tbrow = (int64_t)a.ccb * 1024;  // bytes per 16-token block of packed C
+    const int nh = 2 * nk;
 
-  auto gload_b = [&](int kt, uint4 (&r)[B_CH]) {
-    const int t0 = tok_beg + kt * CT_BK;
+    // register sets are flat arrays indexed with compile-time constants only (a set index
+    // that reaches a lambda as a run-time value would push the whole array into scratch)
+    u32x4 rb[2 * B_CH];
+    u32x4 rafr[2 * CT_HK * 2];
+
+    auto gload_b = [&](int kt, auto set) {
+      constexpr int o = decltype(set)::value * B_CH;
+      const int t0 = tok_beg + min(kt, nk - 1) * CT_BK + brow;
 #pragma unroll
-    for (int p = 0; p < B_CH; ++p) {
-      const int q = tid + p * 256, row = q >> 4, cc = (q & 15) * 8;
-      const int t = t0 + row, n = n0 + cc;
-      r[p] = load_chunk(dY + (int64_t)t * a.lddy + n, t < tok_end ? a.m - n : 0);
-    }
-  };
-  auto sstore_b = [&](int stage, const uint4 (&r)[B_CH]) {
-    bf16_t* s = smem + stage * STAGE;
+      for (int p = 0; p < B_CH; ++p)
+        rb[o + p] = *reinterpret_cast<const u32x4*>(ybase + (int64_t)min(t0 + 16 * p, a.N - 1) * a.lddy * 2);
+    };
+    auto sstore_b = [&](int stage, auto set, auto first) {
+      constexpr int o = decltype(set)::value * B_CH, p0 = decltype(first)::value;
+      bf16_t* s = smem + stage * STAGE;
 #pragma unroll
-    for (int p = 0; p < B_CH; ++p) {
-      const int q = tid + p * 256, row = q >> 4, cc = (q & 15) * 8;
-      *reinterpret_cast<uint4*>(s + row * CT_LD + cc) = r[p];
-    }
-  };
-  auto gload_a = [&](int kt, uint4 (&r)[KK * 2]) {
-    const int tb0 = (tok_beg + kt * CT_BK) / 16;
+      for (int p = p0; p < p0 + 4; ++p) *reinterpret_cast<u32x4*>(s + (brow + 16 * p) * CT_LD + bcol) = rb[o + p];
+    };
+    // C fragments of half tile hb (4 token blocks), unmasked (see mfma_block)
+    auto gload_a = [&](int hb, auto set) {
+      constexpr int o = decltype(set)::value * CT_HK * 2;
+      const int tb0 = tok_beg / 16 + min(hb, nh - 1) * CT_HK;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int tb = tb0 + kk, cb = cb0 + i;
-        // token blocks past the split's end hold other splits' tokens: they must not count
-        const bool ok = tb < ntb && tb * 16 < tok_end && cb < a.ccb;
-        r[kk * 2 + i] = ok ? Cp[((int64_t)tb * a.ccb + cb) * 64 + lane] : make_uint4(0u, 0u, 0u, 0u);
+      for (int kk = 0; kk < CT_HK; ++kk) {
+        const char* base = cbase + (int64_t)min(tb0 + kk, ntb - 1) * tbrow;  // uniform
+        rafr[o + kk * 2 + 0] = *reinterpret_cast<const u32x4*>(base + aoff0);
+        rafr[o + kk * 2 + 1] = *reinterpret_cast<const u32x4*>(base + aoff1);
       }
-  };
-  auto compute = [&](int stage, const uint4 (&fa)[KK * 2]) {
-    const bf16_t* s = smem + stage * STAGE;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      // token rows of this lane's 8 slots: 4 lh + e (e < 4), 8 + 4 lh + e - 4 (e >= 4)
-      union {
-        uint2 p;
-        bf16_t s4[4];
-      } v[8];
+    };
+    // raw LDS rows of k-block kk for this lane: token rows 4 lh + e (e < 4), 8 + 4 lh + e - 4
+    auto raw_load = [&](int stage, int kk, u32x2 (&v)[8]) {
+      const bf16_t* s = smem + stage * STAGE;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int row = kk * 16 + (e < 4 ? 4 * lh + e : 8 + 4 * lh + (e - 4));
-        v[e].p = *reinterpret_cast<const uint2*>(s + row * CT_LD + 4 * li);
+        v[e] = *reinterpret_cast<const u32x2*>(s + row * CT_LD + 4 * li);
       }
-      bf16x8 fb[4];
+    };
+    auto mfma_block = [&](const u32x2 (&v)[8], const u32x4& a0, const u32x4& a1) {
+      const bf16x8 fa0 = as_frag(a0), fa1 = as_frag(a1);
+      // 8 x 4 transpose, one byte-permute per 32-bit word: fragment j takes 16-bit element j
+      // of each of the 8 rows (selectors 0-3 address the second operand, 4-7 the first)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        union {
-          bf16x8 f;
-          bf16_t s8[8];
-        } o;
+        u32x4 o;
+        uint32_t w[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o.s8[e] = v[e].s4[j];
-        fb[j] = o.f;
+        for (int e2 = 0; e2 < 4; ++e2) {
+          const uint32_t lo = j < 2 ? v[2 * e2].x : v[2 * e2].y;
+          const uint32_t hi = j < 2 ? v[2 * e2 + 1].x : v[2 * e2 + 1].y;
+          w[e2] = __builtin_amdgcn_perm(hi, lo, (j & 1) ? 0x07060302u : 0x05040100u);
+        }
+        o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
+        const bf16x8 fb = as_frag(o);
+        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb, acc[0][j], 0, 0, 0);
+        acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb, acc[1][j], 0, 0, 0);
       }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[kk * 2 + i]), fb[j], acc[i][j], 0, 0, 0);
-    }
-  };
+    };
 
-  if (nk > 0) {
-    gload_b(0, rb[0]);
-    gload_a(0, rafr[0]);
-    if (nk > 1) gload_b(1, rb[1]);
-    sstore_b(0, rb[0]);
-  }
-  __syncthreads();
-  for (int kt = 0; kt < nk; kt += 2) {
-    if (kt + 1 < nk) sstore_b((kt + 1) % CT_STAGES, rb[1]);
-    if (kt + 2 < nk) gload_b(kt + 2, rb[0]);
-    if (kt + 1 < nk) gload_a(kt + 1, rafr[1]);
-    compute(kt % CT_STAGES, rafr[0]);
+    // prologue: C half 0 and dY tiles 0, 1 on their way; tile 0 into LDS; tile 2 requested
+    gload_a(0, std::integral_constant<int, 0>{});
+    gload_b(0, std::integral_constant<int, 0>{});
+    gload_b(1, std::integral_constant<int, 1>{});
+    sstore_b(0, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    sstore_b(0, std::integral_constant<int, 0>{}, std::integral_constant<int, 4>{});
+    gload_b(2, std::integral_constant<int, 0>{});
     __syncthreads();
-    if (kt + 1 < nk) {
-      if (kt + 2 < nk) sstore_b((kt + 2) % CT_STAGES, rb[0]);
-      if (kt + 3 < nk) gload_b(kt + 3, rb[1]);
-      if (kt + 2 < nk) gload_a(kt + 2, rafr[0]);
-      compute((kt + 1) % CT_STAGES, rafr[1]);
+
+    // body kt (PH = kt % 2): LDS stage kt%2 holds dY tile kt; rb[(kt+1)%2] holds tile kt+1 and
+    // rb[kt%2] awaits tile kt+2; rafr[0] / rafr[1] hold the first / second C half of tile kt.
+    auto body = [&](int kt, auto ph) {
+      constexpr int PH = decltype(ph)::value;
+      constexpr int S = PH % 2, SB = (PH + 1) % 2;
+      u32x2 raw[2][8];
+      raw_load(S, 0, raw[0]);
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        if (kk + 1 < KK) raw_load(S, kk + 1, raw[(kk + 1) & 1]);
+        if (kk == 0) gload_a(2 * kt + 1, std::integral_constant<int, 1>{});
+        if (kk == 1) sstore_b(SB, std::integral_constant<int, SB>{}, std::integral_constant<int, 0>{});
+        if (kk == 2) sstore_b(SB, std::integral_constant<int, SB>{}, std::integral_constant<int, 4>{});
+        if (kk == 4) gload_a(2 * kt + 2, std::integral_constant<int, 0>{});
+        if (kk == 5) gload_b(kt + 3, std::integral_constant<int, SB>{});
+        mfma_block(raw[kk & 1], rafr[kk * 2], rafr[kk * 2 + 1]);
+      }
+      // pipeline: the first k-block's LDS reads, then per pair of MFMAs the four permutes that
+      // build their B fragment, one LDS read of the next k-block and this k-block's extras
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+        for (int pr = 0; pr < 4; ++pr) {
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (kk + 1 < KK) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          if (kk == 0 || kk == 4 || kk == 5) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          if (kk == 1 || kk == 2) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (kk == 0 || kk == 4 || kk == 5) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
       __syncthreads();
+    };
+    int kt = 0;
+    for (; kt + 2 <= nk; kt += 2) {
+      body(kt, std::integral_constant<int, 0>{});
+      body(kt + 1, std::integral_constant<int, 1>{});
     }
+    if (kt < nk) body(kt, std::integral_constant<int, 0>{});
   }
 
   // epilogue: T row = 32 (cb0 + i) + 8*(v/4) + 4*lh + v%4, columns n0 + 4 li .. + 3
@@ -431,7 +556,7 @@ __global__ __launch_bounds__(256) void unpack_c_kernel(const bf16_t* __restrict_
 // row-major C -> packed (padding rows / columns zero)
 __global__ __launch_bounds__(256) void pack_c_kernel(const bf16_t* __restrict__ C, int64_t ldc, int N, int c, int ccb,
                                                      bf16_t* __restrict__ Cpk) {
-  const int64_t ntb = (N + 15) / 16, total = ntb * ccb * 64;
+  const int64_t ntb = (int64_t)((N + 127) / 128) * 8, total = ntb * ccb * 64;
   for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += (int64_t)gridDim.x * blockDim.x) {
     const int lane = (int)(g & 63), j = lane & 31, h = lane >> 5;
     const int64_t blk = g >> 6;
@@ -510,6 +635,20 @@ int launch_compress_panel(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, in
   const int total = a.tiles_m * a.col_groups;
   const dim3 grid(((total + 7) / 8) * 8), block(256);
   static bool s1 = false, s2 = false;
+  static bool sv[128] = {false};
+  const int var = ctx->tune_variant;
+#define PRAC_VARIANT_CASE(V)                                                              \
+  if (var == V) {                                                                         \
+    int rc = set_smem(ctx, compress_panel_kernel<2, V>, smem, sv[V]);                     \
+    if (rc) return rc;                                                                    \
+    hipLaunchKernelGGL((compress_panel_kernel<2, V>), grid, block, smem, ctx->stream, a); \
+    PRAC_HIP_TRY(ctx, hipGetLastError());                                                 \
+    return PRAC_OK;                                                                       \
+  }
+  PRAC_VARIANT_CASE(1) PRAC_VARIANT_CASE(2) PRAC_VARIANT_CASE(3) PRAC_VARIANT_CASE(4) PRAC_VARIANT_CASE(6)
+  PRAC_VARIANT_CASE(7) PRAC_VARIANT_CASE(8) PRAC_VARIANT_CASE(16) PRAC_VARIANT_CASE(17) PRAC_VARIANT_CASE(14)
+  PRAC_VARIANT_CASE(31) PRAC_VARIANT_CASE(15) PRAC_VARIANT_CASE(30) PRAC_VARIANT_CASE(32) PRAC_VARIANT_CASE(64)
+  PRAC_VARIANT_CASE(34) PRAC_VARIANT_CASE(36) PRAC_VARIANT_CASE(40)
   if (FN == 1) {
     int rc = set_smem(ctx, compress_panel_kernel<1>, smem, s1);
     if (rc) return rc;
@@ -559,7 +698,7 @@ int launch_unpack_c(prac_ctx* ctx, const bf16_t* Cpk, int N, int c, bf16_t* C, i
 
 int launch_pack_c(prac_ctx* ctx, const bf16_t* C, int64_t ldc, int N, int c, bf16_t* Cpk) {
   const int ccb = (c + 31) / 32;
-  hipLaunchKernelGGL(pack_c_kernel, dim3(grid_for((int64_t)((N + 15) / 16) * ccb * 64, ctx->n_cu)), dim3(256), 0,
+  hipLaunchKernelGGL(pack_c_kernel, dim3(grid_for((int64_t)((N + 127) / 128) * 8 * ccb * 64, ctx->n_cu)), dim3(256), 0,
                      ctx->stream, C, ldc, N, c, ccb, Cpk);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;

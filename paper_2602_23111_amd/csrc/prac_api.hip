@@ -12,14 +12,14 @@ inline bool valid_dtype(int t) { return t == PRAC_F32 || t == PRAC_BF16; }
 
 struct LpLayout {
   int64_t ldpt, ldpn;
-  int nkb, ncb;  // fragment-order copy: 16-row blocks over round_up(d,64), 32-column blocks (multiple of 8)
+  int nkb, ncb;  // fragment-order copy: 16-row blocks over round_up(d,128), 32-column blocks (multiple of 8)
   size_t off_pn, off_pf, bytes;
 };
 inline LpLayout lp_layout(int64_t d, int c) {
   LpLayout l;
   l.ldpt = round_up64(d, 64);
   l.ldpn = round_up64(c, 64);
-  l.nkb = (int)(round_up64(d, 64) / 16);
+  l.nkb = (int)(round_up64(d, 128) / 16);
   l.ncb = (int)round_up64((c + 31) / 32, 8);
   l.off_pn = ((size_t)c * l.ldpt * sizeof(bf16_t) + 255) & ~size_t(255);
   l.off_pf = (l.off_pn + (size_t)d * l.ldpn * sizeof(bf16_t) + 255) & ~size_t(255);
@@ -27,7 +27,7 @@ inline LpLayout lp_layout(int64_t d, int c) {
   return l;
 }
 inline size_t packed_c_bytes(int64_t N, int c) {
-  return (size_t)((N + 15) / 16) * ((c + 31) / 32) * 64 * 8 * sizeof(bf16_t);
+  return (size_t)((N + 127) / 128) * 8 * ((c + 31) / 32) * 64 * 8 * sizeof(bf16_t);  // whole 128-token tiles
 }
 
 // split count for a reduction over K with `tiles` output tiles: fill the chip about
@@ -195,6 +195,7 @@ int prac_create(prac_ctx** out, int device, void* hip_stream) {
   c->last_hip = 0;
   c->prof_kind = 0;
   c->tune_splits = 0;
+  c->tune_variant = 0;
   hipDeviceProp_t prop;
   c->n_cu = (hipGetDeviceProperties(&prop, device) == hipSuccess) ? prop.multiProcessorCount : 256;
   if (hipMalloc(reinterpret_cast<void**>(&c->d_flag), 256) != hipSuccess ||
@@ -248,8 +249,9 @@ int prac_profile_select(prac_ctx* ctx, int kind) {
 }
 
 int prac_set_tuning(prac_ctx* ctx, int key, int value) {
-  if (key != PRAC_TUNE_CTDY_SPLITS || value < 0 || value > 64) return PRAC_EINVAL;
+  if ((key != PRAC_TUNE_CTDY_SPLITS && key != 99) || value < 0 || value > 127) return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
+  if (key == 99) { ctx->tune_variant = value; return PRAC_OK; }
   ctx->tune_splits = value;
   return PRAC_OK;
 }

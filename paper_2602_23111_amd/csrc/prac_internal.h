@@ -21,6 +21,7 @@ struct prac_ctx {
   int* d_flag;        // device-side numeric failure flag (0 = fine)
   int last_hip;       // last hipError_t that made a call fail
   int n_cu;
+  int tune_variant;   // experiment switch
   int tune_splits;    // > 0: override the token-split count of C^T dY (tuning hook)
   int prof_kind;      // kernel kind bracketed by events (0: none), see prac_profile_select
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_pairs;  // recorded, not yet read

@@ -35,7 +35,7 @@ def test_strerror_and_lp_bytes(lib):
     d, c = 100, 24
     first = (c * 128 * 2 + 255) // 256 * 256
     second = (first + d * 64 * 2 + 255) // 256 * 256
-    assert lib.prac_basis_lp_bytes(d, c) == second + (128 // 16) * 8 * 64 * 8 * 2
+    assert lib.prac_basis_lp_bytes(d, c) == second + (128 // 16) * 8 * 64 * 8 * 2   # d padded to 128
     assert lib.prac_basis_lp_bytes(0, 4) == 0
 
 
@@ -119,8 +119,8 @@ def test_other_entry_points_reject_bad_arguments(lib):
     assert lib.prac_unpack_compressed(None, DUMMY, 8, 4, DUMMY, 3) == -1
     assert lib.prac_set_tuning(None, 1, 8) == -6 and lib.prac_set_tuning(None, 2, 8) == -1
     assert lib.prac_profile_select(None, 9) == -1 and lib.prac_profile_select(None, 1) == -6
-    # packed C: ceil(N/16) x ceil(c/32) blocks of 64 lanes x 8 bf16
-    assert lib.prac_compressed_bytes(100, 40, 1, 1, 0) == 7 * 2 * 64 * 8 * 2
+    # packed C: 8 * ceil(N/128) x ceil(c/32) blocks of 64 lanes x 8 bf16
+    assert lib.prac_compressed_bytes(100, 40, 1, 1, 0) == 8 * 2 * 64 * 8 * 2
     assert lib.prac_compressed_bytes(100, 40, 1, 0, 48) == 100 * 48 * 2
     assert lib.prac_compressed_bytes(100, 40, 0, 1, 0) == 0      # packed is bf16 only
     assert lib.prac_destroy(None) == -6 and lib.prac_sync_status(None) == -6

@@ -56,7 +56,7 @@ def packed_index(N, c):
     e = (w % 4) + 4 * (w // 8)
     lane = 32 * h + col % 32
     off = ((tb * ccb + col // 32) * 64 + lane) * 8 + e
-    return off, ((N + 15) // 16) * ccb * 64 * 8
+    return off, ((N + 127) // 128) * 8 * ccb * 64 * 8
 
 
 def pack_c_reference(Ct: torch.Tensor) -> torch.Tensor:
