@@ -603,6 +603,171 @@ __global__ __launch_bounds__(256) void reduce_scale_bf16_kernel(const float* __r
   }
 }
 
+// ------------------------------------------------------------------- dW = P T
+// T in fragment order, built by the slab reducer: Tf[(kb * nmb + nb) * 64 + lane][e] =
+// bf16(w_k * sum_z slab[z][k][n]) with k = 16 kb + 8 h + e, n = 32 nb + j, lane = 32 h + j,
+// w_k = 1 for k < k_lo and scale_hi above; zero where k >= c or n >= m.
+// One workgroup per (k-block, pair of 32-column blocks): 256 threads sum a 16 x 64 patch of
+// the slabs with one float4 per thread and slab (coalesced 256-byte rows), exchange it through
+// LDS and 128 of them emit the two fragments.
+__global__ __launch_bounds__(256) void reduce_to_tfrag_kernel(const float* __restrict__ slabs, int splits, int c, int m,
+                                                              int k_lo, float scale_hi, int nkb, int nmb,
+                                                              bf16_t* __restrict__ Tf) {
+  __shared__ float patch[16][68];
+  const int pairs = nmb / 2;
+  const int kb = blockIdx.x / pairs, np = blockIdx.x % pairs;
+  const int tid = threadIdx.x;
+  const int row = tid >> 4, col = (tid & 15) * 4;
+  const int k = kb * 16 + row, n = np * 64 + col;
+  const int64_t slab = (int64_t)c * m;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (k < c && n < m) {
+    const float* p = slabs + (int64_t)k * m + n;
+    if (n + 3 < m && (m & 3) == 0) {
+#pragma unroll 8
+      for (int z = 0; z < splits; ++z) {
+        const float4 v = *reinterpret_cast<const float4*>(p + z * slab);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+      }
+    } else {
+      for (int z = 0; z < splits; ++z) {
+        s.x += p[z * slab];
+        if (n + 1 < m) s.y += p[z * slab + 1];
+        if (n + 2 < m) s.z += p[z * slab + 2];
+        if (n + 3 < m) s.w += p[z * slab + 3];
+      }
+    }
+    const float w = k >= k_lo ? scale_hi : 1.f;
+    s.x *= w; s.y *= w; s.z *= w; s.w *= w;
+  }
+  patch[row][col + 0] = s.x;
+  patch[row][col + 1] = s.y;
+  patch[row][col + 2] = s.z;
+  patch[row][col + 3] = s.w;
+  __syncthreads();
+  if (tid < 128) {
+    const int nbl = tid >> 6, lane = tid & 63, j = lane & 31, h = lane >> 5;
+    u32x4 o;
+    o.x = pack2(patch[8 * h + 0][nbl * 32 + j], patch[8 * h + 1][nbl * 32 + j]);
+    o.y = pack2(patch[8 * h + 2][nbl * 32 + j], patch[8 * h + 3][nbl * 32 + j]);
+    o.z = pack2(patch[8 * h + 4][nbl * 32 + j], patch[8 * h + 5][nbl * 32 + j]);
+    o.w = pack2(patch[8 * h + 6][nbl * 32 + j], patch[8 * h + 7][nbl * 32 + j]);
+    reinterpret_cast<u32x4*>(Tf)[((int64_t)kb * nmb + np * 2 + nbl) * 64 + lane] = o;
+  }
+}
+
+// P as an A operand in fragment order: Pa[(rb * nkb + kb) * 64 + lane][e] = bf16(P[32 rb + i][16 kb + 8 h + e]),
+// lane = 32 h + i; zero outside d x c.
+__global__ __launch_bounds__(256) void pack_pafrag_kernel(const float* __restrict__ P, int64_t d, int64_t ldp, int c,
+                                                          int nrb, int nkb, bf16_t* __restrict__ out) {
+  const int64_t total = (int64_t)nrb * nkb * 64;
+  for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += (int64_t)gridDim.x * blockDim.x) {
+    const int lane = (int)(g & 63), i = lane & 31, h = lane >> 5;
+    const int64_t blk = g >> 6;
+    const int kb = (int)(blk % nkb);
+    const int64_t row = (blk / nkb) * 32 + i;
+    float f[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int k = kb * 16 + 8 * h + e;
+      f[e] = (row < d && k < c) ? P[row * ldp + k] : 0.f;
+    }
+    u32x4 o;
+    o.x = pack2(f[0], f[1]);
+    o.y = pack2(f[2], f[3]);
+    o.z = pack2(f[4], f[5]);
+    o.w = pack2(f[6], f[7]);
+    reinterpret_cast<u32x4*>(out)[g] = o;
+  }
+}
+
+struct PtArgs {
+  const bf16_t* Pa;  // [nrb][nkb][64][8]
+  const bf16_t* Tf;  // [nkb][nmb][64][8]
+  void* dW;
+  int64_t lddw;
+  int d, m, nkb, nmb;
+  int tiles_m, tiles_n;
+  float beta;
+};
+
+// dW (d x m) = P T, K = c (a few hundred): both operands are read in fragment order
+// straight from L2, no LDS.  256 threads = 2 x 2 waves, a 128 x 128 tile per workgroup,
+// 64 x 64 per wave; fragments are requested PT_PD k-blocks ahead.
+constexpr int PT_PD = 4;
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
+  const int total = a.tiles_m * a.tiles_n;
+  const int per_xcd = (total + 7) / 8;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int logical = xcd * per_xcd + slot;
+  if (slot >= per_xcd || logical >= total) return;
+  const int tn = logical % a.tiles_n, tm = logical / a.tiles_n;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 31, lh = lane >> 5;
+  const int rb0 = tm * 4 + (wave >> 1) * 2, nb0 = tn * 4 + (wave & 1) * 2;
+  const u32x4* __restrict__ Pa = reinterpret_cast<const u32x4*>(a.Pa);
+  const u32x4* __restrict__ Tf = reinterpret_cast<const u32x4*>(a.Tf);
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  u32x4 fr[PT_PD][4];
+  auto gload = [&](int kb, u32x4 (&r)[4]) {
+    const int k = min(kb, a.nkb - 1);
+    r[0] = Pa[((int64_t)rb0 * a.nkb + k) * 64 + lane];
+    r[1] = Pa[((int64_t)(rb0 + 1) * a.nkb + k) * 64 + lane];
+    r[2] = Tf[((int64_t)k * a.nmb + nb0) * 64 + lane];
+    r[3] = Tf[((int64_t)k * a.nmb + nb0 + 1) * 64 + lane];
+  };
+  auto mfma4 = [&](const u32x4 (&r)[4]) {
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(r[0]), as_frag(r[2]), acc[0][0], 0, 0, 0);
+    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(r[0]), as_frag(r[3]), acc[0][1], 0, 0, 0);
+    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(r[1]), as_frag(r[2]), acc[1][0], 0, 0, 0);
+    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(r[1]), as_frag(r[3]), acc[1][1], 0, 0, 0);
+  };
+#pragma unroll
+  for (int t = 0; t < PT_PD; ++t) gload(t, fr[t]);
+  int kb = 0;
+  for (; kb + PT_PD <= a.nkb; kb += PT_PD) {
+#pragma unroll
+    for (int t = 0; t < PT_PD; ++t) {
+      mfma4(fr[t]);
+      gload(kb + PT_PD + t, fr[t]);
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < PT_PD; ++t)
+    if (kb + t < a.nkb) mfma4(fr[t]);
+
+  // block (i, j): register v of lane (li, lh) is row 32 (rb0 + i) + 8*(v/4) + 4 lh + v%4, column 32 (nb0 + j) + li
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = (rb0 + i) * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
+        const int col = (nb0 + j) * 32 + li;
+        if (row < a.d && col < a.m) {
+          const int64_t o = (int64_t)row * a.lddw + col;
+          const float val = acc[i][j][v];
+          if (OUT_BF16) {
+            bf16_t* q = reinterpret_cast<bf16_t*>(a.dW) + o;
+            *q = f32_to_bf16(a.beta == 0.f ? val : val + a.beta * __uint_as_float(((uint32_t)*q) << 16));
+          } else {
+            float* q = reinterpret_cast<float*>(a.dW) + o;
+            *q = a.beta == 0.f ? val : val + a.beta * *q;
+          }
+        }
+      }
+}
+
 inline int grid_for(int64_t n, int n_cu) {
   int64_t g = (n + 255) / 256;
   const int64_t cap = (int64_t)n_cu * 8;
@@ -708,6 +873,33 @@ int launch_reduce_scale_bf16(prac_ctx* ctx, const float* slabs, int splits, int 
                              bf16_t* T, int64_t ldt) {
   hipLaunchKernelGGL(reduce_scale_bf16_kernel, dim3(grid_for((int64_t)c * (ldt / 4), ctx->n_cu)), dim3(256), 0,
                      ctx->stream, slabs, splits, c, m, k_lo, scale_hi, T, ldt);
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  return PRAC_OK;
+}
+
+int launch_reduce_to_tfrag(prac_ctx* ctx, const float* slabs, int splits, int c, int m, int k_lo, float scale_hi,
+                           int nkb, int nmb, bf16_t* Tf) {
+  hipLaunchKernelGGL(reduce_to_tfrag_kernel, dim3(nkb * (nmb / 2)), dim3(256), 0, ctx->stream, slabs, splits, c, m, k_lo, scale_hi, nkb, nmb, Tf);
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  return PRAC_OK;
+}
+
+int launch_pack_pafrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nrb, int nkb, bf16_t* out) {
+  hipLaunchKernelGGL(pack_pafrag_kernel, dim3(grid_for((int64_t)nrb * nkb * 64, ctx->n_cu)), dim3(256), 0, ctx->stream,
+                     P, d, ldp, c, nrb, nkb, out);
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  return PRAC_OK;
+}
+
+int launch_pt(prac_ctx* ctx, const bf16_t* Pa, const bf16_t* Tf, int d, int m, int nkb, int nmb, void* dW,
+              int64_t lddw, bool out_bf16, float beta) {
+  PtArgs a;
+  a.Pa = Pa; a.Tf = Tf; a.dW = dW; a.lddw = lddw; a.d = d; a.m = m; a.nkb = nkb; a.nmb = nmb;
+  a.tiles_m = (d + 127) / 128; a.tiles_n = (m + 127) / 128; a.beta = beta;
+  const int total = a.tiles_m * a.tiles_n;
+  const dim3 grid(((total + 7) / 8) * 8), block(256);
+  if (out_bf16) hipLaunchKernelGGL(pt_kernel<true>, grid, block, 0, ctx->stream, a);
+  else hipLaunchKernelGGL(pt_kernel<false>, grid, block, 0, ctx->stream, a);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }

@@ -13,7 +13,8 @@ inline bool valid_dtype(int t) { return t == PRAC_F32 || t == PRAC_BF16; }
 struct LpLayout {
   int64_t ldpt, ldpn;
   int nkb, ncb;  // fragment-order copy: 16-row blocks over round_up(d,128), 32-column blocks (multiple of 8)
-  size_t off_pn, off_pf, bytes;
+  int nrb, nckb; // A-operand fragment copy: 32-row blocks over round_up(d,128), 16-column blocks over c
+  size_t off_pn, off_pf, off_pa, bytes;
 };
 inline LpLayout lp_layout(int64_t d, int c) {
   LpLayout l;
@@ -23,7 +24,10 @@ inline LpLayout lp_layout(int64_t d, int c) {
   l.ncb = (int)round_up64((c + 31) / 32, 8);
   l.off_pn = ((size_t)c * l.ldpt * sizeof(bf16_t) + 255) & ~size_t(255);
   l.off_pf = (l.off_pn + (size_t)d * l.ldpn * sizeof(bf16_t) + 255) & ~size_t(255);
-  l.bytes = l.off_pf + (size_t)l.nkb * l.ncb * 64 * 8 * sizeof(bf16_t);
+  l.nrb = (int)(round_up64(d, 128) / 32);
+  l.nckb = (c + 15) / 16;
+  l.off_pa = (l.off_pf + (size_t)l.nkb * l.ncb * 64 * 8 * sizeof(bf16_t) + 255) & ~size_t(255);
+  l.bytes = l.off_pa + (size_t)l.nrb * l.nckb * 64 * 8 * sizeof(bf16_t);
   return l;
 }
 inline size_t packed_c_bytes(int64_t N, int c) {
@@ -318,7 +322,9 @@ int prac_pack_basis(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c
   int rc = launch_pack_basis(ctx, P, d, ldp, c, reinterpret_cast<bf16_t*>(base), l.ldpt,
                              reinterpret_cast<bf16_t*>(base + l.off_pn), l.ldpn);
   if (rc) return rc;
-  return launch_pack_pfrag(ctx, P, d, ldp, c, l.nkb, l.ncb, reinterpret_cast<bf16_t*>(base + l.off_pf));
+  rc = launch_pack_pfrag(ctx, P, d, ldp, c, l.nkb, l.ncb, reinterpret_cast<bf16_t*>(base + l.off_pf));
+  if (rc) return rc;
+  return launch_pack_pafrag(ctx, P, d, ldp, c, l.nrb, l.nckb, reinterpret_cast<bf16_t*>(base + l.off_pa));
 }
 
 int prac_fit_basis(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, int k, int r,
@@ -496,10 +502,10 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
     if (splits < 1) splits = 1;
     if (splits > 64) splits = 64;
     if (ctx->tune_splits > 0) splits = ctx->tune_splits;
-    const int64_t ldt = round_up64(m, 8);
+    const int nmb = (int)round_up64((m + 31) / 32, 4);  // 32-column blocks of T, whole 128-column tiles
     WsPlan plan;
     const size_t o_part = plan.take((size_t)splits * c * m * sizeof(float));
-    const size_t o_t = plan.take((size_t)c * ldt * sizeof(bf16_t));
+    const size_t o_t = plan.take((size_t)l.nckb * nmb * 64 * 8 * sizeof(bf16_t));
     const size_t o_lp = plan.take(P_lp ? 0 : l.bytes);
     const size_t o_cpk = plan.take(packed ? 0 : packed_c_bytes(N, c));
     int rc = prac_ws_reserve(ctx, plan.off);
@@ -518,34 +524,21 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
       Cpk = reinterpret_cast<const bf16_t*>(ctx->ws + o_cpk);
     }
     float* part = reinterpret_cast<float*>(ctx->ws + o_part);
-    bf16_t* T = reinterpret_cast<bf16_t*>(ctx->ws + o_t);
+    bf16_t* Tf = reinterpret_cast<bf16_t*>(ctx->ws + o_t);
     {  // T = C^T dY as `splits` partial slabs over the token range
       ProfScope ps(ctx, PRAC_KERNEL_CT_DY);
       rc = launch_ctdy(ctx, Cpk, c, reinterpret_cast<const bf16_t*>(dY), lddy, (int)N, (int)m, part, splits);
     }
     if (rc) return rc;
-    {  // T (c x m, bf16): slabs summed, random rows weighted by the scaling factor
+    {  // T in fragment order (bf16): slabs summed, random rows weighted by the scaling factor
       ProfScope ps(ctx, PRAC_KERNEL_T_REDUCE);
-      rc = launch_reduce_scale_bf16(ctx, part, splits, c, (int)m, k, scale, T, ldt);
+      rc = launch_reduce_to_tfrag(ctx, part, splits, c, (int)m, k, scale, l.nckb, nmb, Tf);
     }
     if (rc) return rc;
     // dW = P T
-    GemmBf16Args h{};
-    h.A = reinterpret_cast<const bf16_t*>(lp + l.off_pn);
-    h.lda = l.ldpn;
-    h.M = (int)d;
-    h.K = c;
-    h.a_kc = true;
-    h.b_kc = false;
-    h.b0 = GemmOperandB{T, ldt, (int)m, dW, lddw};
-    h.b1 = GemmOperandB{nullptr, 0, 0, nullptr, 0};
-    h.out_bf16 = odt == PRAC_BF16;
-    h.beta = beta;
-    h.splits = 1;
-    h.partial = nullptr;
-    h.tile_hint = 0;
     ProfScope ps(ctx, PRAC_KERNEL_P_T);
-    return launch_gemm_bf16(ctx, h);
+    return launch_pt(ctx, reinterpret_cast<const bf16_t*>(lp + l.off_pa), Tf, (int)d, (int)m, l.nckb, nmb, dW, lddw,
+                     odt == PRAC_BF16, beta);
   }
   // generic path: T = C^T dY (fp32), scale the random rows, dW = P T
   WsPlan plan;

@@ -126,6 +126,12 @@ int launch_pack_c(prac_ctx* ctx, const bf16_t* C, int64_t ldc, int N, int c, bf1
 int launch_reduce_scale_bf16(prac_ctx* ctx, const float* slabs, int splits, int c, int m, int k_lo,
                              float scale_hi, bf16_t* T, int64_t ldt);
 
+int launch_reduce_to_tfrag(prac_ctx* ctx, const float* slabs, int splits, int c, int m, int k_lo, float scale_hi,
+                           int nkb, int nmb, bf16_t* Tf);
+int launch_pack_pafrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nrb, int nkb, bf16_t* out);
+int launch_pt(prac_ctx* ctx, const bf16_t* Pa, const bf16_t* Tf, int d, int m, int nkb, int nmb, void* dW,
+              int64_t lddw, bool out_bf16, float beta);
+
 // ---- basis fit -----------------------------------------------------------------
 int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
                      int k, int r, uint64_t seed, uint32_t draw, int refresh, const prac_fit_opts& o,
