@@ -15,10 +15,15 @@ namespace {
 // ---------------------------------------------------------------- Cholesky (upper)
 // In place on the row-major b x b fp64 matrix W (only the upper triangle is read and
 // written): W = R^T R.  `shift_rel` * max diag(W) is added to the diagonal first.
-// One workgroup of 1024 threads; non-finite or non-positive pivots raise *flag.
+// One workgroup of 1024 threads, blocked by panels of CH_NB rows that live in LDS: the
+// panel is factored there (right-looking inside the panel, across its full width), written
+// back, and applied to the trailing rows as a rank-CH_NB update.  Non-finite or
+// non-positive pivots raise *flag and are replaced by a tiny positive number.
+constexpr int CH_NB = 16;
 __global__ __launch_bounds__(1024) void chol_upper_kernel(double* W, int b, double shift_rel, int* flag) {
+  extern __shared__ __align__(16) unsigned char chol_smem[];
+  double* panel = reinterpret_cast<double*>(chol_smem);  // [CH_NB][b]
   __shared__ double s_red[16];
-  __shared__ double s_piv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   double mx = 0.0;
   for (int i = tid; i < b; i += 1024) mx = fmax(mx, W[(int64_t)i * b + i]);
@@ -29,56 +34,76 @@ __global__ __launch_bounds__(1024) void chol_upper_kernel(double* W, int b, doub
   for (int w = 0; w < 16; ++w) mx = fmax(mx, s_red[w]);
   const double shift = shift_rel * mx;
   const double tiny = 1e-300 + 1e-30 * mx;
-  for (int i = tid; i < b; i += 1024) W[(int64_t)i * b + i] += shift;
-  __syncthreads();
-  for (int j = 0; j < b; ++j) {
-    if (tid == 0) {
-      double p = W[(int64_t)j * b + j];
-      if (!(p > tiny) || !isfinite(p)) {
-        atomicOr(flag, 1);
-        p = tiny > 0.0 ? tiny : 1e-300;
-      }
-      p = sqrt(p);
-      W[(int64_t)j * b + j] = p;
-      s_piv = 1.0 / p;
+  for (int j0 = 0; j0 < b; j0 += CH_NB) {
+    const int nb = min(CH_NB, b - j0), width = b - j0;
+    // panel rows j0 .. j0+nb-1, columns j0 .. b-1 (column index relative to j0)
+    for (int e = tid; e < nb * width; e += 1024) {
+      const int u = e / width, c = e % width;
+      double v = c >= u ? W[(int64_t)(j0 + u) * b + j0 + c] : 0.0;
+      if (c == u) v += shift;
+      panel[u * b + c] = v;
     }
     __syncthreads();
-    const double inv = s_piv;
-    for (int c = j + 1 + tid; c < b; c += 1024) W[(int64_t)j * b + c] *= inv;
-    __syncthreads();
-    // trailing update of rows i > j: W[i][c] -= R[j][i] * R[j][c], c >= i
-    const double* rj = W + (int64_t)j * b;
-    for (int i = j + 1 + wave; i < b; i += 16) {
-      const double rji = rj[i];
+    for (int t = 0; t < nb; ++t) {
+      double p = panel[t * b + t];
+      const bool bad = !(p > tiny) || !isfinite(p);
+      if (bad) p = tiny;
+      const double inv = 1.0 / sqrt(p);
+      __syncthreads();  // everybody has read the pivot
+      if (bad && tid == 0) atomicOr(flag, 1);
+      for (int c = t + tid; c < width; c += 1024) panel[t * b + c] = c == t ? sqrt(p) : panel[t * b + c] * inv;
+      __syncthreads();
+      // rows u > t of the panel: panel[u][c] -= R[t][u] * R[t][c], c >= u
+      const int rem = nb - 1 - t;
+      for (int e = tid; e < rem * width; e += 1024) {
+        const int u = t + 1 + e / width, c = e % width;
+        if (c >= u) panel[u * b + c] -= panel[t * b + u] * panel[t * b + c];
+      }
+      __syncthreads();
+    }
+    for (int e = tid; e < nb * width; e += 1024) {
+      const int u = e / width, c = e % width;
+      if (c >= u) W[(int64_t)(j0 + u) * b + j0 + c] = panel[u * b + c];
+    }
+    // trailing rows i >= j0 + nb: W[i][c] -= sum_t R[t][i] R[t][c], c >= i
+    for (int i = j0 + nb + wave; i < b; i += 16) {
+      double ri[CH_NB];
+#pragma unroll
+      for (int t = 0; t < CH_NB; ++t) ri[t] = t < nb ? panel[t * b + (i - j0)] : 0.0;
       double* wi = W + (int64_t)i * b;
-      for (int c = i + lane; c < b; c += 64) wi[c] -= rji * rj[c];
+      for (int c = i + lane; c < b; c += 64) {
+        double acc = wi[c];
+#pragma unroll
+        for (int t = 0; t < CH_NB; ++t) acc -= ri[t] * (t < nb ? panel[t * b + (c - j0)] : 0.0);
+        wi[c] = acc;
+      }
     }
     __syncthreads();
   }
 }
 
-// Inverse of the upper-triangular R (row-major b x b fp64, upper part): column j of
-// the inverse is solved by thread j (back substitution in fp64, staged in X64), then
-// written as fp32 to Rinv (row-major b x b, lower part zeroed).
-__global__ __launch_bounds__(1024) void triu_inverse_kernel(const double* __restrict__ R, double* X64, float* Rinv,
-                                                            int b) {
-  const int j = threadIdx.x;
-  if (j < b) {
-    X64[(int64_t)j * b + j] = 1.0 / R[(int64_t)j * b + j];
-  }
+// dst (rows x n, fp32) = src * R^-1 for the upper-triangular R (row-major n x n fp64, upper part):
+// forward substitution along the columns, 16 rows per workgroup held in LDS, 16 threads per row.
+constexpr int TR_ROWS = 16;
+__global__ __launch_bounds__(256) void trsm_right_upper_kernel(const float* __restrict__ src, const double* __restrict__ R,
+                                                               float* __restrict__ dst, int64_t rows, int n) {
+  extern __shared__ __align__(16) unsigned char trsm_smem[];
+  float* y = reinterpret_cast<float*>(trsm_smem);  // [TR_ROWS][n]
+  const int tid = threadIdx.x, r = tid >> 4, cl = tid & 15;
+  const int64_t row = (int64_t)blockIdx.x * TR_ROWS + r;
+  const bool ok = row < rows;
+  for (int c = cl; c < n; c += 16) y[r * n + c] = ok ? src[row * n + c] : 0.f;
   __syncthreads();
-  for (int i = b - 2; i >= 0; --i) {
-    if (j < b && i < j) {
-      double s = 0.0;
-      const double* ri = R + (int64_t)i * b;
-      for (int t = i + 1; t <= j; ++t) s += ri[t] * X64[(int64_t)t * b + j];
-      X64[(int64_t)i * b + j] = -s / ri[i];
-    }
+  for (int t = 0; t < n; ++t) {
+    const double* rt = R + (int64_t)t * n;
+    const float vt = y[r * n + t] * (float)(1.0 / rt[t]);
+    __syncthreads();  // every thread of the row has read y[r][t]
+    if (cl == 0) y[r * n + t] = vt;
+    for (int c = t + 1 + cl; c < n; c += 16) y[r * n + c] -= vt * (float)rt[c];
+    __syncthreads();
   }
-  __syncthreads();
-  if (j < b) {
-    for (int i = 0; i < b; ++i) Rinv[(int64_t)i * b + j] = i <= j ? (float)X64[(int64_t)i * b + j] : 0.f;
-  }
+  if (ok)
+    for (int c = cl; c < n; c += 16) dst[row * n + c] = y[r * n + c];
 }
 
 // ------------------------------------------------------- symmetric eigen (Jacobi)
@@ -86,16 +111,28 @@ __global__ __launch_bounds__(1024) void triu_inverse_kernel(const double* __rest
 // row-major so that "column" p is the contiguous row p (H is symmetric).  Rotating
 // column pairs until all are mutually orthogonal gives H J = B with B's columns
 // lambda_i v_i, so the eigenvectors are the normalised columns and the eigenvalues
-// their norms.  One workgroup, 16 waves; each round-robin step hands b/2 disjoint
-// pairs to the waves.  Stops when a whole sweep rotates nothing (or after max_sweeps).
-__global__ __launch_bounds__(1024) void jacobi_hestenes_kernel(double* H, int b, int max_sweeps, double tol,
-                                                               double* lambda, int* flag) {
-  __shared__ int s_rot;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int be = b + (b & 1);          // even player count; index b (if any) is a bye
-  const int npairs = be / 2, nsteps = be - 1;
-  // H arrives as V^T (G V) with G V rounded to fp32: restore exact symmetry first
-  for (int e = tid; e < b * b; e += 1024) {
+// their norms.
+//
+// Block version: the b columns are cut into blocks of nbk; a round-robin tournament
+// over the blocks pairs them up, and one workgroup per pair loads its 2 nbk columns
+// into LDS, orthogonalises them there with an inner tournament (all data movement
+// of the rotations stays in LDS) and writes them back.  One launch per tournament
+// step; `counts[sweep]` collects the number of rotations of a sweep, and the launches
+// of sweep s+1 return at once when sweep s rotated nothing.
+
+__device__ __forceinline__ void tournament_pair(int step, int i, int players_even, int& p, int& q) {
+  const int n1 = players_even - 1;
+  if (i == 0) {
+    p = step % n1;
+    q = players_even - 1;
+  } else {
+    p = (step + i) % n1;
+    q = (step - i + n1) % n1;
+  }
+}
+
+__global__ __launch_bounds__(1024) void symmetrize64_kernel(double* H, int b) {
+  for (int e = blockIdx.x * 1024 + threadIdx.x; e < b * b; e += gridDim.x * 1024) {
     const int i = e / b, j = e % b;
     if (i < j) {
       const double m = 0.5 * (H[(int64_t)i * b + j] + H[(int64_t)j * b + i]);
@@ -103,24 +140,44 @@ __global__ __launch_bounds__(1024) void jacobi_hestenes_kernel(double* H, int b,
       H[(int64_t)j * b + i] = m;
     }
   }
+}
+
+__global__ __launch_bounds__(1024) void jacobi_block_kernel(double* H, int b, int nbk, int nblk_even, int step, int sweep,
+                                                            int inner_sweeps, double tol, unsigned* counts) {
+  extern __shared__ __align__(16) unsigned char jac_smem[];
+  double* cols = reinterpret_cast<double*>(jac_smem);  // [2 nbk][b]
+  __shared__ int s_rows[64];
+  __shared__ int s_rot;
+  if (sweep > 0 && counts[sweep - 1] == 0) return;  // converged in the previous sweep
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int bp, bq;
+  tournament_pair(step, blockIdx.x, nblk_even, bp, bq);
+  // global column indices of the local columns (blocks past the end are byes)
+  int m = 0;
+  if (tid == 0) {
+    for (int blk = 0; blk < 2; ++blk) {
+      const int base = (blk == 0 ? bp : bq) * nbk;
+      for (int u = 0; u < nbk; ++u)
+        if (base + u < b) s_rows[m++] = base + u;
+    }
+    s_rows[63] = m;  // nbk <= 31 columns per block keeps slot 63 free; see the host code
+    s_rot = 0;
+  }
   __syncthreads();
-  for (int sweep = 0; sweep < max_sweeps; ++sweep) {
-    if (tid == 0) s_rot = 0;
-    __syncthreads();
-    int rotated = 0;
-    for (int s = 0; s < nsteps; ++s) {
-      for (int i = wave; i < npairs; i += 16) {
+  m = s_rows[63];
+  if (m < 2) return;
+  for (int e = tid; e < m * b; e += 1024) cols[e] = H[(int64_t)s_rows[e / b] * b + e % b];
+  __syncthreads();
+  const int me = m + (m & 1);
+  int rotated = 0;
+  for (int isw = 0; isw < inner_sweeps; ++isw) {
+    for (int s = 0; s < me - 1; ++s) {
+      for (int i = wave; i < me / 2; i += 16) {
         int p, q;
-        if (i == 0) {
-          p = s % nsteps;
-          q = be - 1;
-        } else {
-          p = (s + i) % nsteps;
-          q = (s - i + nsteps) % nsteps;
-        }
-        if (p >= b || q >= b) continue;  // bye
-        double* hp = H + (int64_t)p * b;
-        double* hq = H + (int64_t)q * b;
+        tournament_pair(s, i, me, p, q);
+        if (p >= m || q >= m) continue;
+        double* hp = cols + p * b;
+        double* hq = cols + q * b;
         double al = 0.0, be2 = 0.0, ga = 0.0;
         for (int t = lane; t < b; t += 64) {
           const double x = hp[t], y = hq[t];
@@ -147,17 +204,22 @@ __global__ __launch_bounds__(1024) void jacobi_hestenes_kernel(double* H, int b,
       }
       __syncthreads();
     }
-    if (rotated && lane == 0) atomicOr(&s_rot, 1);
-    __syncthreads();
-    const int any = s_rot;
-    __syncthreads();
-    if (!any) break;
-    if (sweep == max_sweeps - 1) {
-      if (tid == 0) atomicOr(flag, 2);
-    }
   }
-  // eigenvalues = column norms; normalise the columns in place
-  for (int p = wave; p < b; p += 16) {
+  if (rotated && lane == 0) atomicOr(&s_rot, 1);
+  __syncthreads();
+  if (s_rot) {
+    for (int e = tid; e < m * b; e += 1024) H[(int64_t)s_rows[e / b] * b + e % b] = cols[e];
+    if (tid == 0) atomicAdd(&counts[sweep], 1u);
+  }
+}
+
+// eigenvalues = column norms; normalise the columns in place; raise flag bit 2 if the last
+// sweep still rotated
+__global__ __launch_bounds__(1024) void jacobi_finish_kernel(double* H, int b, double* lambda, const unsigned* counts,
+                                                             int last_sweep, int* flag) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (blockIdx.x == 0 && tid == 0 && counts[last_sweep] != 0) atomicOr(flag, 2);
+  for (int p = blockIdx.x * 16 + wave; p < b; p += gridDim.x * 16) {
     double* hp = H + (int64_t)p * b;
     double al = 0.0;
     for (int t = lane; t < b; t += 64) al += hp[t] * hp[t];
@@ -167,6 +229,10 @@ __global__ __launch_bounds__(1024) void jacobi_hestenes_kernel(double* H, int b,
     for (int t = lane; t < b; t += 64) hp[t] *= inv;
     if (lane == 0) lambda[p] = nrm;
   }
+}
+
+__global__ void zero_u32_kernel(unsigned* p, int n) {
+  for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0u;
 }
 
 // Z (b x k fp32, row-major) = the k eigenvectors with the largest eigenvalues, in
@@ -242,12 +308,23 @@ FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool n
   return w;
 }
 
+// the two panel kernels keep up to 128 KB / 64 KB in LDS (n <= 1024)
+int set_dyn_smem(prac_ctx* ctx) {
+  static bool done = false;
+  if (!done) {
+    PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_upper_kernel),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, CH_NB * 1024 * 8));
+    PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(trsm_right_upper_kernel),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, TR_ROWS * 1024 * 4));
+    done = true;
+  }
+  return PRAC_OK;
+}
+
 // V (d x n, ld = n, fp32) <- orth(Y) by `passes` rounds of Cholesky-QR; ping-pongs
 // between Y and V, result always ends in `V`.  The first round shifts the Gram matrix.
 int cholqr(prac_ctx* ctx, const FitWs& w, float* Y, float* V, int64_t d, int n, int passes, double first_shift) {
   double* W64 = reinterpret_cast<double*>(ctx->ws + w.W64);
-  double* X64 = reinterpret_cast<double*>(ctx->ws + w.X64);
-  float* Rinv = reinterpret_cast<float*>(ctx->ws + w.Rinv);
   float* src = Y;
   float* dst = V;
   for (int pass = 0; pass < passes; ++pass) {
@@ -259,17 +336,13 @@ int cholqr(prac_ctx* ctx, const FitWs& w, float* Y, float* V, int64_t d, int n, 
     g.splits = w.splits_bb; g.slabs = ctx->ws + w.slabs;
     int rc = launch_gemm_generic(ctx, g);
     if (rc) return rc;
-    hipLaunchKernelGGL(chol_upper_kernel, dim3(1), dim3(1024), 0, ctx->stream, W64, n,
-                       pass == 0 ? first_shift : 1e-15, ctx->d_flag);
-    hipLaunchKernelGGL(triu_inverse_kernel, dim3(1), dim3(1024), 0, ctx->stream, W64, X64, Rinv, n);
-    PRAC_HIP_TRY(ctx, hipGetLastError());
-    GemmGenArgs h{};
-    h.A = src; h.B = Rinv; h.adt = PRAC_F32; h.bdt = PRAC_F32;
-    h.a_rs = n; h.a_cs = 1; h.b_rs = n; h.b_cs = 1;
-    h.M = (int)d; h.N = n; h.K = n; h.k_stride = 1;
-    h.out = dst; h.ldo = n; h.alpha = 1.f; h.beta = 0.f; h.acc64 = false; h.out64 = nullptr;
-    rc = launch_gemm_generic(ctx, h);
+    rc = set_dyn_smem(ctx);
     if (rc) return rc;
+    hipLaunchKernelGGL(chol_upper_kernel, dim3(1), dim3(1024), (size_t)CH_NB * n * sizeof(double), ctx->stream, W64, n,
+                       pass == 0 ? first_shift : 1e-15, ctx->d_flag);
+    hipLaunchKernelGGL(trsm_right_upper_kernel, dim3((unsigned)((d + TR_ROWS - 1) / TR_ROWS)), dim3(256),
+                       (size_t)TR_ROWS * n * sizeof(float), ctx->stream, src, W64, dst, d, n);
+    PRAC_HIP_TRY(ctx, hipGetLastError());
     float* t = src; src = dst; dst = t;
   }
   // result is in `src` after the swap
@@ -310,7 +383,7 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, P, ldp, Y, (int64_t)b, d, k);
       PRAC_HIP_TRY(ctx, hipGetLastError());
     }
-    rc = cholqr(ctx, L, Y, V, d, b, 2, 1e-11);
+    rc = cholqr(ctx, L, Y, V, d, b, 1, 1e-11);
     if (rc) return rc;
     for (int it = 0; it <= o.iters; ++it) {
       // Y = G V
@@ -322,7 +395,8 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       rc = launch_gemm_generic(ctx, g);
       if (rc) return rc;
       if (it == o.iters) break;  // the last product feeds Rayleigh-Ritz
-      rc = cholqr(ctx, L, Y, V, d, b, it == o.iters - 1 ? 3 : 2, 1e-11);
+      // one shifted pass keeps the block well conditioned; the last iteration orthonormalises fully
+      rc = cholqr(ctx, L, Y, V, d, b, it == o.iters - 1 ? 3 : 1, 1e-11);
       if (rc) return rc;
     }
     // Rayleigh-Ritz: H = V^T (G V), eigenvectors of H, Q1 = V Z[:, :k]
@@ -339,7 +413,37 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       rc = launch_gemm_generic(ctx, g);
       if (rc) return rc;
     }
-    hipLaunchKernelGGL(jacobi_hestenes_kernel, dim3(1), dim3(1024), 0, st, H, b, 30, 1e-14, lam, ctx->d_flag);
+    {
+      // block Jacobi: 2 nbk columns of length b (fp64) per workgroup in LDS, at most 128 KB
+      int nbk = 8192 / b;
+      if (nbk > 31) nbk = 31;
+      if (nbk < 1) nbk = 1;
+      const int nblk = (b + nbk - 1) / nbk, nblk_even = nblk + (nblk & 1);
+      constexpr int MAX_SWEEPS = 12;
+      unsigned* counts = reinterpret_cast<unsigned*>(ctx->ws + L.X64);
+      static bool smem_set = false;
+      if (!smem_set) {
+        PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_block_kernel),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+        smem_set = true;
+      }
+      hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(64), 0, st, counts, MAX_SWEEPS);
+      hipLaunchKernelGGL(symmetrize64_kernel, dim3(16), dim3(1024), 0, st, H, b);
+      const size_t smem = (size_t)2 * nbk * b * sizeof(double);
+      if (nblk == 1) {
+        // a single block: one workgroup orthogonalises everything in LDS
+        hipLaunchKernelGGL(jacobi_block_kernel, dim3(1), dim3(1024), smem, st, H, b, nbk, 2, 0, 0, 30, 1e-14, counts);
+        hipLaunchKernelGGL(jacobi_finish_kernel, dim3(16), dim3(1024), 0, st, H, b, lam, counts, MAX_SWEEPS - 1,
+                           ctx->d_flag);
+      } else {
+        for (int sweep = 0; sweep < MAX_SWEEPS; ++sweep)
+          for (int step = 0; step < nblk_even - 1; ++step)
+            hipLaunchKernelGGL(jacobi_block_kernel, dim3(nblk_even / 2), dim3(1024), smem, st, H, b, nbk, nblk_even,
+                               step, sweep, 2, 1e-14, counts);
+        hipLaunchKernelGGL(jacobi_finish_kernel, dim3(16), dim3(1024), 0, st, H, b, lam, counts, MAX_SWEEPS - 1,
+                           ctx->d_flag);
+      }
+    }
     hipLaunchKernelGGL(select_top_kernel, dim3(1), dim3(1024), 0, st, H, lam, b, k, Z);
     PRAC_HIP_TRY(ctx, hipGetLastError());
     {
