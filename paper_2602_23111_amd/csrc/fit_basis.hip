@@ -83,24 +83,36 @@ __global__ __launch_bounds__(1024) void chol_upper_kernel(double* W, int b, doub
 }
 
 // dst (rows x n, fp32) = src * R^-1 for the upper-triangular R (row-major n x n fp64, upper part):
-// forward substitution along the columns, 16 rows per workgroup held in LDS, 16 threads per row.
-constexpr int TR_ROWS = 16;
+// forward substitution along the columns, 16 rows per workgroup held in LDS, 16 threads per row
+// (a row never spans two waves).  R is staged through LDS 16 rows at a time as fp32, with the
+// reciprocal of the diagonal, so that the substitution loop never waits for global memory.
+constexpr int TR_ROWS = 16, TR_CH = 16;
 __global__ __launch_bounds__(256) void trsm_right_upper_kernel(const float* __restrict__ src, const double* __restrict__ R,
                                                                float* __restrict__ dst, int64_t rows, int n) {
   extern __shared__ __align__(16) unsigned char trsm_smem[];
   float* y = reinterpret_cast<float*>(trsm_smem);  // [TR_ROWS][n]
+  float* rch = y + TR_ROWS * n;                    // [TR_CH][n]: rows t0 .. t0+15 of R, diagonal inverted
   const int tid = threadIdx.x, r = tid >> 4, cl = tid & 15;
   const int64_t row = (int64_t)blockIdx.x * TR_ROWS + r;
   const bool ok = row < rows;
   for (int c = cl; c < n; c += 16) y[r * n + c] = ok ? src[row * n + c] : 0.f;
-  __syncthreads();
-  for (int t = 0; t < n; ++t) {
-    const double* rt = R + (int64_t)t * n;
-    const float vt = y[r * n + t] * (float)(1.0 / rt[t]);
-    __syncthreads();  // every thread of the row has read y[r][t]
-    if (cl == 0) y[r * n + t] = vt;
-    for (int c = t + 1 + cl; c < n; c += 16) y[r * n + c] -= vt * (float)rt[c];
+  for (int t0 = 0; t0 < n; t0 += TR_CH) {
+    const int nt = min(TR_CH, n - t0);
+    __syncthreads();  // previous chunk fully used (and y loaded)
+    for (int e = tid; e < nt * n; e += 256) {
+      const int u = e / n, c = e % n;
+      const double v = c >= t0 + u ? R[(int64_t)(t0 + u) * n + c] : 0.0;
+      rch[u * n + c] = c == t0 + u ? (float)(1.0 / v) : (float)v;
+    }
     __syncthreads();
+    for (int u = 0; u < nt; ++u) {
+      const int t = t0 + u;
+      const float vt = y[r * n + t] * rch[u * n + t];
+      __builtin_amdgcn_wave_barrier();
+      if (cl == 0) y[r * n + t] = vt;
+      for (int c = t + 1 + cl; c < n; c += 16) y[r * n + c] -= vt * rch[u * n + c];
+      __syncthreads();
+    }
   }
   if (ok)
     for (int c = cl; c < n; c += 16) dst[row * n + c] = y[r * n + c];
@@ -315,7 +327,7 @@ int set_dyn_smem(prac_ctx* ctx) {
     PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_upper_kernel),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, CH_NB * 1024 * 8));
     PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(trsm_right_upper_kernel),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, TR_ROWS * 1024 * 4));
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (TR_ROWS + TR_CH) * 1024 * 4));
     done = true;
   }
   return PRAC_OK;
@@ -341,7 +353,7 @@ int cholqr(prac_ctx* ctx, const FitWs& w, float* Y, float* V, int64_t d, int n, 
     hipLaunchKernelGGL(chol_upper_kernel, dim3(1), dim3(1024), (size_t)CH_NB * n * sizeof(double), ctx->stream, W64, n,
                        pass == 0 ? first_shift : 1e-15, ctx->d_flag);
     hipLaunchKernelGGL(trsm_right_upper_kernel, dim3((unsigned)((d + TR_ROWS - 1) / TR_ROWS)), dim3(256),
-                       (size_t)TR_ROWS * n * sizeof(float), ctx->stream, src, W64, dst, d, n);
+                       (size_t)(TR_ROWS + TR_CH) * n * sizeof(float), ctx->stream, src, W64, dst, d, n);
     PRAC_HIP_TRY(ctx, hipGetLastError());
     float* t = src; src = dst; dst = t;
   }
@@ -415,8 +427,9 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
     }
     {
       // block Jacobi: 2 nbk columns of length b (fp64) per workgroup in LDS, at most 128 KB
+      // 16 columns per block: an inner tournament step then has at most 16 pairs, one per wave
       int nbk = 8192 / b;
-      if (nbk > 31) nbk = 31;
+      if (nbk > 16) nbk = 16;
       if (nbk < 1) nbk = 1;
       const int nblk = (b + nbk - 1) / nbk, nblk_even = nblk + (nblk & 1);
       constexpr int MAX_SWEEPS = 12;

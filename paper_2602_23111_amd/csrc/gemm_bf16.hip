@@ -298,7 +298,7 @@ int launch_cfg(prac_ctx* ctx, const GemmBf16Args& g) {
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(a.wg_per_xcd * 8), dim3(NT), SMEM, ctx->stream, a);
+  PRAC_LAUNCH(ctx, kern, dim3(a.wg_per_xcd * 8), dim3(NT), SMEM, a);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }

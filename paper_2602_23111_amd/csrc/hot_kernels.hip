@@ -817,11 +817,11 @@ int launch_compress_panel(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, in
   if (FN == 1) {
     int rc = set_smem(ctx, compress_panel_kernel<1>, smem, s1);
     if (rc) return rc;
-    hipLaunchKernelGGL(compress_panel_kernel<1>, grid, block, smem, ctx->stream, a);
+    PRAC_LAUNCH(ctx, compress_panel_kernel<1>, grid, block, smem, a);
   } else {
     int rc = set_smem(ctx, compress_panel_kernel<2>, smem, s2);
     if (rc) return rc;
-    hipLaunchKernelGGL(compress_panel_kernel<2>, grid, block, smem, ctx->stream, a);
+    PRAC_LAUNCH(ctx, compress_panel_kernel<2>, grid, block, smem, a);
   }
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
@@ -841,7 +841,7 @@ int launch_ctdy(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, int64
   static bool s = false;
   int rc = set_smem(ctx, ctdy_kernel, smem, s);
   if (rc) return rc;
-  hipLaunchKernelGGL(ctdy_kernel, dim3(((total + 7) / 8) * 8), dim3(256), smem, ctx->stream, a);
+  PRAC_LAUNCH(ctx, ctdy_kernel, dim3(((total + 7) / 8) * 8), dim3(256), smem, a);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }
@@ -879,7 +879,8 @@ int launch_reduce_scale_bf16(prac_ctx* ctx, const float* slabs, int splits, int 
 
 int launch_reduce_to_tfrag(prac_ctx* ctx, const float* slabs, int splits, int c, int m, int k_lo, float scale_hi,
                            int nkb, int nmb, bf16_t* Tf) {
-  hipLaunchKernelGGL(reduce_to_tfrag_kernel, dim3(nkb * (nmb / 2)), dim3(256), 0, ctx->stream, slabs, splits, c, m, k_lo, scale_hi, nkb, nmb, Tf);
+  PRAC_LAUNCH(ctx, reduce_to_tfrag_kernel, dim3(nkb * (nmb / 2)), dim3(256), 0, slabs, splits, c, m, k_lo, scale_hi, nkb,
+              nmb, Tf);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }
@@ -898,8 +899,8 @@ int launch_pt(prac_ctx* ctx, const bf16_t* Pa, const bf16_t* Tf, int d, int m, i
   a.tiles_m = (d + 127) / 128; a.tiles_n = (m + 127) / 128; a.beta = beta;
   const int total = a.tiles_m * a.tiles_n;
   const dim3 grid(((total + 7) / 8) * 8), block(256);
-  if (out_bf16) hipLaunchKernelGGL(pt_kernel<true>, grid, block, 0, ctx->stream, a);
-  else hipLaunchKernelGGL(pt_kernel<false>, grid, block, 0, ctx->stream, a);
+  if (out_bf16) PRAC_LAUNCH(ctx, pt_kernel<true>, grid, block, 0, a);
+  else PRAC_LAUNCH(ctx, pt_kernel<false>, grid, block, 0, a);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }

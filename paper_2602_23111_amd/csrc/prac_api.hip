@@ -72,7 +72,9 @@ int prac_ws_reserve(prac_ctx* ctx, size_t bytes) {
   return PRAC_OK;
 }
 
-ProfScope::ProfScope(prac_ctx* c, int kind) : ctx(c), stop(nullptr), on(false) {
+ProfScope::ProfScope(prac_ctx* c, int kind) : ctx(c) {
+  c->ev_start = nullptr;
+  c->ev_stop = nullptr;
   if (c->prof_kind != kind || kind == 0) return;
   hipEvent_t ev[2] = {nullptr, nullptr};
   for (int i = 0; i < 2; ++i) {
@@ -85,18 +87,14 @@ ProfScope::ProfScope(prac_ctx* c, int kind) : ctx(c), stop(nullptr), on(false) {
       return;
     }
   }
-  if (hipEventRecord(ev[0], c->stream) != hipSuccess) {
-    (void)hipGetLastError();
-    c->prof_pool.push_back(ev[0]);
-    c->prof_pool.push_back(ev[1]);
-    return;
-  }
   c->prof_pairs.emplace_back(ev[0], ev[1]);
-  stop = ev[1];
-  on = true;
+  c->ev_start = ev[0];
+  c->ev_stop = ev[1];
 }
 ProfScope::~ProfScope() {
-  if (on && hipEventRecord(stop, ctx->stream) != hipSuccess) (void)hipGetLastError();
+  // a launcher that did not take the pair leaves it unrecorded; prac_profile_read skips it
+  ctx->ev_start = nullptr;
+  ctx->ev_stop = nullptr;
 }
 
 namespace {
@@ -198,6 +196,8 @@ int prac_create(prac_ctx** out, int device, void* hip_stream) {
   c->d_flag = nullptr;
   c->last_hip = 0;
   c->prof_kind = 0;
+  c->ev_start = nullptr;
+  c->ev_stop = nullptr;
   c->tune_splits = 0;
   c->tune_variant = 0;
   hipDeviceProp_t prop;

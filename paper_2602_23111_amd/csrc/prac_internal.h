@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -24,6 +25,7 @@ struct prac_ctx {
   int tune_variant;   // experiment switch
   int tune_splits;    // > 0: override the token-split count of C^T dY (tuning hook)
   int prof_kind;      // kernel kind bracketed by events (0: none), see prac_profile_select
+  hipEvent_t ev_start, ev_stop;  // set by ProfScope: the next PRAC_LAUNCH attaches them to its kernel
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_pairs;  // recorded, not yet read
   std::vector<hipEvent_t> prof_pool;                          // idle events
 };
@@ -32,8 +34,6 @@ struct prac_ctx {
 // stream when the ctx is profiling this kernel kind.
 struct ProfScope {
   prac_ctx* ctx;
-  hipEvent_t stop;
-  bool on;
   ProfScope(prac_ctx* c, int kind);
   ~ProfScope();
 };
@@ -140,6 +140,20 @@ size_t gram_scratch_bytes(const prac_ctx* ctx, const void* X, prac_dtype xdt, in
                           int64_t ldx, int64_t row_stride, int64_t ldg);
 int gram_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
                 int64_t row_stride, float* G, int64_t ldg, char* scratch);
+
+// Launch on the ctx stream; when a ProfScope is open, the kernel's own begin / end time
+// stamps go into its event pair (so the measured time excludes launch gaps).
+#define PRAC_LAUNCH(ctx, kern, grid, block, smem, ...)                                              \
+  do {                                                                                             \
+    if ((ctx)->ev_start) {                                                                         \
+      hipExtLaunchKernelGGL(kern, grid, block, smem, (ctx)->stream, (ctx)->ev_start, (ctx)->ev_stop, 0, \
+                            __VA_ARGS__);                                                          \
+      (ctx)->ev_start = nullptr;                                                                   \
+      (ctx)->ev_stop = nullptr;                                                                    \
+    } else {                                                                                       \
+      hipLaunchKernelGGL(kern, grid, block, smem, (ctx)->stream, __VA_ARGS__);                     \
+    }                                                                                              \
+  } while (0)
 
 #define PRAC_HIP_TRY(ctx, expr)                 \
   do {                                          \

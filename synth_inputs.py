@@ -93,10 +93,13 @@ def orthonormal_basis(d: int, c: int, seed: int) -> np.ndarray:
 # ------------------------------------------------- full-size, on a torch device
 def activation_torch(N: int, d: int, alpha: float, seed: int, n_out: int,
                      out_scale: float, dtype: torch.dtype, device,
-                     ld: int | None = None, chunk: int = 4096) -> torch.Tensor:
+                     ld: int | None = None, chunk: int = 4096, batch: int = 0) -> torch.Tensor:
     """Same recipe as activation(), drawn with torch's generator on `device`
-    in fp32 and rounded to `dtype`.  Returns an (N, d) view into an (N, ld)
-    buffer when ld > d (padded leading dimension)."""
+    in fp32 and rounded to `dtype`.  `seed` fixes the layer (R, sigma, outlier
+    channels); `batch` picks the token draw Z, so that different batches of one
+    layer share their spectrum and principal subspace, as successive training
+    batches do.  Returns an (N, d) view into an (N, ld) buffer when ld > d
+    (padded leading dimension)."""
     g = torch.Generator(device=device)
     g.manual_seed(seed)
     A = torch.randn((d, d), generator=g, device=device, dtype=torch.float32)
@@ -107,11 +110,13 @@ def activation_torch(N: int, d: int, alpha: float, seed: int, n_out: int,
     if n_out:
         ch = torch.randperm(d, generator=g, device=device)[:n_out]
         M[:, ch] *= out_scale
+    gz = torch.Generator(device=device)
+    gz.manual_seed(seed * 1000003 + 17 * batch + 1)
     ld = d if ld is None else ld
     buf = torch.zeros((N, ld), device=device, dtype=dtype)
     for r0 in range(0, N, chunk):
         r1 = min(N, r0 + chunk)
-        Z = torch.randn((r1 - r0, d), generator=g, device=device, dtype=torch.float32)
+        Z = torch.randn((r1 - r0, d), generator=gz, device=device, dtype=torch.float32)
         buf[r0:r1, :d] = (Z @ M).to(dtype)
     return buf[:, :d]
 
