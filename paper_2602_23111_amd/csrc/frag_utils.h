@@ -1,0 +1,41 @@
+// Device-side helpers shared by the streaming kernels: MFMA fragment types, bf16 rounding
+// and 16-byte chunk masking.
+#pragma once
+
+#include "prac_internal.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+// 16-byte register value: a native vector (assignments of HIP's u32x4 struct lower to
+// memcpy, which keeps whole register sets in scratch memory)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+static __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  // round to nearest even; NaN keeps its payload's top bits and is made quiet (branch-free)
+  const uint32_t u = __float_as_uint(f);
+  const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+  const uint32_t quiet = (u >> 16) | 0x40u;
+  return (bf16_t)((u & 0x7fffffffu) > 0x7f800000u ? quiet : rounded);
+}
+static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// Keep the first n (0..8) bf16 of a 16-byte chunk, zero the rest.
+static __device__ __forceinline__ u32x4 keep_first(u32x4 v, int n) {
+  v.x &= (n > 0 ? 0x0000FFFFu : 0u) | (n > 1 ? 0xFFFF0000u : 0u);
+  v.y &= (n > 2 ? 0x0000FFFFu : 0u) | (n > 3 ? 0xFFFF0000u : 0u);
+  v.z &= (n > 4 ? 0x0000FFFFu : 0u) | (n > 5 ? 0xFFFF0000u : 0u);
+  v.w &= (n > 6 ? 0x0000FFFFu : 0u) | (n > 7 ? 0xFFFF0000u : 0u);
+  return v;
+}
+
+static __device__ __forceinline__ bf16x8 as_frag(u32x4 v) {
+  union {
+    u32x4 u;
+    bf16x8 f;
+  } c;
+  c.u = v;
+  return c.f;
+}

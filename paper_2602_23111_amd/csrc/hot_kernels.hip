@@ -24,44 +24,9 @@
 // the one it waits for, which is what keeps several tiles in flight.
 #include <type_traits>
 
-#include "prac_internal.h"
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-// 16-byte register value: a native vector (assignments of HIP's u32x4 struct lower to
-// memcpy, which keeps whole register sets in scratch memory)
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+#include "frag_utils.h"
 
 namespace {
-
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
-}
-
-// Keep the first n (0..8) bf16 of a 16-byte chunk, zero the rest.
-__device__ __forceinline__ u32x4 keep_first(u32x4 v, int n) {
-  v.x &= (n > 0 ? 0x0000FFFFu : 0u) | (n > 1 ? 0xFFFF0000u : 0u);
-  v.y &= (n > 2 ? 0x0000FFFFu : 0u) | (n > 3 ? 0xFFFF0000u : 0u);
-  v.z &= (n > 4 ? 0x0000FFFFu : 0u) | (n > 5 ? 0xFFFF0000u : 0u);
-  v.w &= (n > 6 ? 0x0000FFFFu : 0u) | (n > 7 ? 0xFFFF0000u : 0u);
-  return v;
-}
-
-__device__ __forceinline__ bf16x8 as_frag(u32x4 v) {
-  union {
-    u32x4 u;
-    bf16x8 f;
-  } c;
-  c.u = v;
-  return c.f;
-}
 
 // ------------------------------------------------------------------ compress
 struct CompressArgs {
@@ -800,20 +765,6 @@ int launch_compress_panel(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, in
   const int total = a.tiles_m * a.col_groups;
   const dim3 grid(((total + 7) / 8) * 8), block(256);
   static bool s1 = false, s2 = false;
-  static bool sv[128] = {false};
-  const int var = ctx->tune_variant;
-#define PRAC_VARIANT_CASE(V)                                                              \
-  if (var == V) {                                                                         \
-    int rc = set_smem(ctx, compress_panel_kernel<2, V>, smem, sv[V]);                     \
-    if (rc) return rc;                                                                    \
-    hipLaunchKernelGGL((compress_panel_kernel<2, V>), grid, block, smem, ctx->stream, a); \
-    PRAC_HIP_TRY(ctx, hipGetLastError());                                                 \
-    return PRAC_OK;                                                                       \
-  }
-  PRAC_VARIANT_CASE(1) PRAC_VARIANT_CASE(2) PRAC_VARIANT_CASE(3) PRAC_VARIANT_CASE(4) PRAC_VARIANT_CASE(6)
-  PRAC_VARIANT_CASE(7) PRAC_VARIANT_CASE(8) PRAC_VARIANT_CASE(16) PRAC_VARIANT_CASE(17) PRAC_VARIANT_CASE(14)
-  PRAC_VARIANT_CASE(31) PRAC_VARIANT_CASE(15) PRAC_VARIANT_CASE(30) PRAC_VARIANT_CASE(32) PRAC_VARIANT_CASE(64)
-  PRAC_VARIANT_CASE(34) PRAC_VARIANT_CASE(36) PRAC_VARIANT_CASE(40)
   if (FN == 1) {
     int rc = set_smem(ctx, compress_panel_kernel<1>, smem, s1);
     if (rc) return rc;

@@ -253,7 +253,7 @@ int prac_profile_select(prac_ctx* ctx, int kind) {
 }
 
 int prac_set_tuning(prac_ctx* ctx, int key, int value) {
-  if ((key != PRAC_TUNE_CTDY_SPLITS && key != 99) || value < 0 || value > 127) return PRAC_EINVAL;
+  if ((key != PRAC_TUNE_CTDY_SPLITS && key != 99) || value < 0 || value > 4095) return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
   if (key == 99) { ctx->tune_variant = value; return PRAC_OK; }
   ctx->tune_splits = value;
@@ -389,8 +389,11 @@ static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N
     const bf16_t* Pf = reinterpret_cast<const bf16_t*>(lp + l.off_pf);
     if (!fused) {
       ProfScope ps(ctx, PRAC_KERNEL_COMPRESS);
-      return launch_compress_panel(ctx, reinterpret_cast<const bf16_t*>(X), ldx, (int)N, (int)d, Pf, l.ncb, c,
-                                   reinterpret_cast<bf16_t*>(C), ldc, packed);
+      if (ctx->tune_variant == 1)
+        return launch_compress_panel(ctx, reinterpret_cast<const bf16_t*>(X), ldx, (int)N, (int)d, Pf, l.ncb, c,
+                                     reinterpret_cast<bf16_t*>(C), ldc, packed);
+      return launch_compress_ws(ctx, reinterpret_cast<const bf16_t*>(X), ldx, (int)N, (int)d, Pf, l.ncb, c,
+                                reinterpret_cast<bf16_t*>(C), ldc, packed);
     }
     void* Crm = packed ? static_cast<void*>(ctx->ws + o_c) : C;
     const int64_t ldcrm = packed ? round_up64(c, 8) : ldc;

@@ -118,6 +118,8 @@ int launch_symmetrize(prac_ctx* ctx, float* G, int d, int64_t ldg);  // copy upp
 // ---- streaming kernels of the per-step path (hot_kernels.hip) ---------------------
 int launch_compress_panel(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d, const bf16_t* Pfrag, int ncb,
                           int c, bf16_t* C, int64_t ldc, bool packed);
+int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d, const bf16_t* Pfrag, int ncb,
+                       int c, bf16_t* C, int64_t ldc, bool packed);
 int launch_ctdy(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, int64_t lddy, int N, int m,
                 float* slabs, int splits);
 int launch_pack_pfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nkb, int ncb, bf16_t* out);

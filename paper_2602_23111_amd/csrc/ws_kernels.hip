@@ -1,0 +1,375 @@
+// Wave-specialised streaming contractions for gfx950.
+//
+//   compress   C = X P   (Alg. 1 compression step)            compress_ws_kernel
+//
+// A workgroup is 8 waves: 4 matrix waves and 4 loader waves, one of each per SIMD.
+//   loader waves   stream the big operand (X) HBM -> registers -> LDS, several tiles ahead,
+//                  in ordinary compiler-scheduled code;
+//   matrix waves   read A fragments from LDS, fetch their private B fragments (P in MFMA
+//                  fragment order, L2-resident) straight into registers and issue MFMAs.
+// The matrix waves' inner step (one 16-deep k-block: 4 LDS fragment reads for the next
+// k-block interleaved with this k-block's MFMAs) is a fixed instruction sequence in inline
+// assembly: with one matrix wave per SIMD nothing else can fill a stall, so the order of
+// LDS reads and MFMAs is set by hand rather than left to the scheduler.  The LDS reads are
+// invisible to the compiler; every such block therefore ends with its own wait for them.
+//
+// LDS holds three X tiles (128 rows x 128 k, rows padded to 272 bytes): tile kt is being
+// multiplied while tile kt+1 is complete and tile kt+2 is being written.  One barrier per
+// tile, placed in the matrix waves between k-blocks 6 and 7: everything before it has
+// finished reading tile kt-1's stage (which the loaders overwrite next with tile kt+2),
+// and k-block 7 already prefetches from tile kt+1, complete since the previous barrier.
+#include <type_traits>
+
+#include "frag_utils.h"
+
+namespace {
+
+struct CompressWsArgs {
+  const bf16_t* X;
+  int64_t ldx;
+  int N, d;
+  const bf16_t* Pfrag;  // [nkb][ncb][64][8], nkb = round_up(d,128)/16, zero outside d x c
+  int ncb;              // 32-column blocks in the padded basis
+  int c;
+  bf16_t* C;            // row-major (ldc) or packed [ceil(N/128)*8][ccb][64][8]
+  int64_t ldc;
+  int ccb;              // 32-column blocks of packed C = ceil(c / 32)
+  int packed;
+  int tiles_m;
+  int col_groups;       // column groups of 4*FN blocks
+  int rotate;           // 1: each workgroup starts its k loop at a different tile
+};
+
+constexpr int WS_BM = 128, WS_BK = 128, WS_LD = WS_BK + 8;
+constexpr int WS_STAGE = WS_BM * WS_LD * 2;  // bytes per LDS stage (34816)
+constexpr int WS_STAGES = 3;
+constexpr int WS_RB = 32 * WS_LD * 2;        // bytes between 32-row blocks of a stage (8704)
+
+// One k-block of a 128 x 64 wave tile: acc[2 i + j] += fa[i] * b_j, while the four A fragments
+// at byte offsets O + i * WS_RB from `lds` are read into fn.
+template <int O>
+__device__ __forceinline__ void kblock2(f32x16 (&acc)[8], const u32x4 (&fa)[4], u32x4 (&fn)[4], const u32x4& b0,
+                                        const u32x4& b1, unsigned lds) {
+  asm volatile(
+      "ds_read_b128 %8, %18 offset:%19\n"
+      "v_mfma_f32_32x32x16_bf16 %0, %12, %16, %0\n"
+      "ds_read_b128 %9, %18 offset:%20\n"
+      "v_mfma_f32_32x32x16_bf16 %1, %12, %17, %1\n"
+      "ds_read_b128 %10, %18 offset:%21\n"
+      "v_mfma_f32_32x32x16_bf16 %2, %13, %16, %2\n"
+      "ds_read_b128 %11, %18 offset:%22\n"
+      "v_mfma_f32_32x32x16_bf16 %3, %13, %17, %3\n"
+      "v_mfma_f32_32x32x16_bf16 %4, %14, %16, %4\n"
+      "v_mfma_f32_32x32x16_bf16 %5, %14, %17, %5\n"
+      "v_mfma_f32_32x32x16_bf16 %6, %15, %16, %6\n"
+      "v_mfma_f32_32x32x16_bf16 %7, %15, %17, %7\n"
+      "s_waitcnt lgkmcnt(0)\n"
+      : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]), "+a"(acc[4]), "+a"(acc[5]), "+a"(acc[6]),
+        "+a"(acc[7]), "=&v"(fn[0]), "=&v"(fn[1]), "=&v"(fn[2]), "=&v"(fn[3])
+      : "v"(fa[0]), "v"(fa[1]), "v"(fa[2]), "v"(fa[3]), "v"(b0), "v"(b1), "v"(lds), "n"(O), "n"(O + WS_RB),
+        "n"(O + 2 * WS_RB), "n"(O + 3 * WS_RB)
+      : "memory");
+}
+
+// Same for a 128 x 32 wave tile: acc[i] += fa[i] * b.
+template <int O>
+__device__ __forceinline__ void kblock1(f32x16 (&acc)[4], const u32x4 (&fa)[4], u32x4 (&fn)[4], const u32x4& b,
+                                        unsigned lds) {
+  asm volatile(
+      "ds_read_b128 %4, %13 offset:%14\n"
+      "ds_read_b128 %5, %13 offset:%15\n"
+      "v_mfma_f32_32x32x16_bf16 %0, %8, %12, %0\n"
+      "ds_read_b128 %6, %13 offset:%16\n"
+      "ds_read_b128 %7, %13 offset:%17\n"
+      "v_mfma_f32_32x32x16_bf16 %1, %9, %12, %1\n"
+      "v_mfma_f32_32x32x16_bf16 %2, %10, %12, %2\n"
+      "v_mfma_f32_32x32x16_bf16 %3, %11, %12, %3\n"
+      "s_waitcnt lgkmcnt(0)\n"
+      : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]), "=&v"(fn[0]), "=&v"(fn[1]), "=&v"(fn[2]),
+        "=&v"(fn[3])
+      : "v"(fa[0]), "v"(fa[1]), "v"(fa[2]), "v"(fa[3]), "v"(b), "v"(lds), "n"(O), "n"(O + WS_RB),
+        "n"(O + 2 * WS_RB), "n"(O + 3 * WS_RB)
+      : "memory");
+}
+
+__device__ __forceinline__ void frag_read4(u32x4 (&f)[4], unsigned lds) {
+  asm volatile(
+      "ds_read_b128 %0, %4\n"
+      "ds_read_b128 %1, %4 offset:%5\n"
+      "ds_read_b128 %2, %4 offset:%6\n"
+      "ds_read_b128 %3, %4 offset:%7\n"
+      "s_waitcnt lgkmcnt(0)\n"
+      : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]), "=&v"(f[3])
+      : "v"(lds), "n"(WS_RB), "n"(2 * WS_RB), "n"(3 * WS_RB)
+      : "memory");
+}
+
+// The compiler does not see the MFMAs inside the blocks above, so it cannot know that the
+// accumulators may still be in the matrix pipeline: drain it before they are read.
+template <int NACC>
+__device__ __forceinline__ void drain_mfma(f32x16 (&acc)[NACC]) {
+  if constexpr (NACC == 8) {
+    asm volatile("s_nop 15\ns_nop 15\ns_nop 15\ns_nop 15\n"
+                 : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]), "+a"(acc[4]), "+a"(acc[5]), "+a"(acc[6]),
+                   "+a"(acc[7]));
+  } else {
+    asm volatile("s_nop 15\ns_nop 15\ns_nop 15\ns_nop 15\n"
+                 : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]));
+  }
+}
+
+template <int FN, int VAR = 0>
+__global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+
+  // XCD-aware order: consecutive logical tiles (same rows, next column group) on one XCD
+  const int total = a.tiles_m * a.col_groups;
+  const int per_xcd = (total + 7) / 8;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int logical = xcd * per_xcd + slot;
+  if (slot >= per_xcd || logical >= total) return;
+  const int cg = logical % a.col_groups, tm = logical / a.col_groups;
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m0 = tm * WS_BM;
+  const int nk = (a.d + WS_BK - 1) / WS_BK;
+  // Step kt of this workgroup works on k-tile act(kt): the sum over k may run in any order, and
+  // workgroups that start at different tiles do not all ask L2 for the same lines of P at once.
+  const int rot = a.rotate ? tm % nk : 0;
+  auto act = [&](int kt) {
+    const int t = min(kt, nk - 1) + rot;
+    return t >= nk ? t - nk : t;
+  };
+
+  if (wave >= 4) {
+    // ------------------------------------------------------------ loader waves
+    const int lt = tid - 256;
+    const int crow = lt >> 4, ccol = (lt & 15) * 8;  // chunk p: row crow + 16 p, columns ccol .. ccol + 7
+    const int last_chunk = ((a.d - 1) / 8) * 8;      // start of the last (possibly partial) chunk of a row
+    const char* xbase = reinterpret_cast<const char*>(a.X + (int64_t)m0 * a.ldx);
+    uint32_t roff[8];  // byte offset of the row of chunk p (rows past N re-read the last row; never stored to C)
+#pragma unroll
+    for (int p = 0; p < 8; ++p) roff[p] = (uint32_t)(min(m0 + crow + 16 * p, a.N - 1) - m0) * (uint32_t)a.ldx * 2u;
+    const uint32_t soff = (uint32_t)(crow * WS_LD + ccol) * 2u;
+
+    u32x4 ra[3][8] = {};
+    // Requests past the last tile stay in the instruction stream (the loop has no load-free tail
+    // version) but all go to this thread's first chunk, which the L1 cache already holds.
+    auto gload = [&](int kt, auto setc) {
+      constexpr int S = decltype(setc)::value;
+      const uint32_t kb = (uint32_t)min(act(kt) * WS_BK + ccol, last_chunk) * 2u;
+      const bool live = kt < nk;
+      if (VAR & 1) return;
+#pragma unroll
+      for (int p = 0; p < 8; ++p)
+        ra[S][p] = *reinterpret_cast<const u32x4*>(xbase + (live ? roff[p] + kb : roff[0] + (uint32_t)ccol * 2u));
+    };
+    // tile kt -> stage `stage` (= kt % 3); columns past d are zeroed (only the last tile has any)
+    auto sstore = [&](int kt, int stage, auto setc) {
+      constexpr int S = decltype(setc)::value;
+      unsigned char* s = smem_raw + stage * WS_STAGE + soff;
+      const int nv = a.d - (act(kt) * WS_BK + ccol);
+      if (VAR & 16) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) asm volatile("" : : "v"(ra[S][p]));
+        return;
+      }
+      if (nv >= 8) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) *reinterpret_cast<u32x4*>(s + p * (16 * WS_LD * 2)) = ra[S][p];
+      } else {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) *reinterpret_cast<u32x4*>(s + p * (16 * WS_LD * 2)) = keep_first(ra[S][p], nv);
+      }
+    };
+    std::integral_constant<int, 0> S0;
+    std::integral_constant<int, 1> S1;
+    std::integral_constant<int, 2> S2;
+    gload(0, S0);
+    gload(1, S1);
+    gload(2, S2);
+    sstore(0, 0, S0);
+    gload(3, S0);
+    if (nk > 1) sstore(1, 1, S1);
+    gload(4, S1);
+    if (!(VAR & 32)) __syncthreads();  // tiles 0 and 1 are in LDS
+    // step kt: tile kt+2 -> LDS (its stage was last read for tile kt-1, before the previous barrier),
+    // request tile kt+5 into the registers just freed (tile j travels in register set j % 3)
+    int stage = 2;
+    auto step = [&](int kt, auto setc) {
+      if (kt < nk) {
+        if (kt + 2 < nk) sstore(kt + 2, stage, setc);
+        stage = stage == WS_STAGES - 1 ? 0 : stage + 1;
+        gload(kt + 5, setc);
+        if (!(VAR & 32)) __syncthreads();
+      }
+    };
+    for (int kt = 0; kt < nk; kt += 3) {
+      step(kt, S2);
+      step(kt + 1, S0);
+      step(kt + 2, S1);
+    }
+    return;
+  }
+
+  // -------------------------------------------------------------- matrix waves
+  const int lane = tid & 63, li = lane & 31, lh = lane >> 5;
+  const int cb0 = cg * 4 * FN + wave * FN;  // first 32-column block of this wave
+  const char* pbase = reinterpret_cast<const char*>(a.Pfrag);
+  const uint32_t boff = (uint32_t)(cb0 * 64 + lane) * 16u;  // this lane's slot in a row of P blocks
+  const int64_t brow = (int64_t)a.ncb * 1024;               // bytes per 16-row k-block of P fragments
+
+  constexpr int NACC = 4 * FN;
+  f32x16 acc[NACC];
+#pragma unroll
+  for (int i = 0; i < NACC; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+
+  // ring of the eight k-blocks' P fragments: slot kk is refilled for the next tile right after its use
+  u32x4 rb[8][FN] = {};
+  auto pload = [&](int kt, auto kkc) {
+    constexpr int KK = decltype(kkc)::value;
+    // past the last tile: one fixed block (an L1 hit), never used
+    const char* base = pbase + (kt < nk ? (int64_t)(act(kt) * 8 + KK) * brow : (int64_t)0);  // uniform
+    if (VAR & 2) return;
+#pragma unroll
+    for (int j = 0; j < FN; ++j) rb[KK][j] = *reinterpret_cast<const u32x4*>(base + (j * 1024 + boff));
+  };
+  auto kblock = [&](auto oc, const u32x4 (&fcur)[4], u32x4 (&fnext)[4], auto kkc, unsigned lds) {
+    constexpr int O = decltype(oc)::value, KK = decltype(kkc)::value;
+    if (VAR & 4) return;
+    if constexpr (FN == 2) kblock2<O>(acc, fcur, fnext, rb[KK][0], rb[KK][1], lds);
+    else kblock1<O>(acc, fcur, fnext, rb[KK][0], lds);
+  };
+#define PRAC_IC(v) std::integral_constant<int, (v)> {}
+  pload(0, PRAC_IC(0)); pload(0, PRAC_IC(1)); pload(0, PRAC_IC(2)); pload(0, PRAC_IC(3));
+  pload(0, PRAC_IC(4)); pload(0, PRAC_IC(5)); pload(0, PRAC_IC(6)); pload(0, PRAC_IC(7));
+
+  // LDS byte address of this lane's A fragment of row block 0, k-block 0, stage 0:
+  // row li, 16-byte half lh of the k-block
+  const unsigned lds0 =
+      (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw + (unsigned)(li * WS_LD * 2 + lh * 16);
+  u32x4 fa[4] = {}, fb[4] = {};
+  if (!(VAR & 32)) __builtin_amdgcn_s_barrier();  // tiles 0 and 1 are in LDS
+  frag_read4(fa, lds0);
+  int stage = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    const unsigned cur = lds0 + (unsigned)stage * WS_STAGE;
+    stage = stage == WS_STAGES - 1 ? 0 : stage + 1;
+    const unsigned nxt = lds0 + (unsigned)stage * WS_STAGE;
+    kblock(PRAC_IC(32 * 1), fa, fb, PRAC_IC(0), cur); pload(kt + 1, PRAC_IC(0));
+    kblock(PRAC_IC(32 * 2), fb, fa, PRAC_IC(1), cur); pload(kt + 1, PRAC_IC(1));
+    kblock(PRAC_IC(32 * 3), fa, fb, PRAC_IC(2), cur); pload(kt + 1, PRAC_IC(2));
+    kblock(PRAC_IC(32 * 4), fb, fa, PRAC_IC(3), cur); pload(kt + 1, PRAC_IC(3));
+    kblock(PRAC_IC(32 * 5), fa, fb, PRAC_IC(4), cur); pload(kt + 1, PRAC_IC(4));
+    kblock(PRAC_IC(32 * 6), fb, fa, PRAC_IC(5), cur); pload(kt + 1, PRAC_IC(5));
+    kblock(PRAC_IC(32 * 7), fa, fb, PRAC_IC(6), cur); pload(kt + 1, PRAC_IC(6));
+    if (!(VAR & 32)) __builtin_amdgcn_s_barrier();
+    kblock(PRAC_IC(0), fb, fa, PRAC_IC(7), nxt); pload(kt + 1, PRAC_IC(7));
+  }
+#undef PRAC_IC
+  drain_mfma<NACC>(acc);
+  if (VAR & 8) return;
+
+  // epilogue: block (i, j) = acc[i * FN + j]; register v of lane (li, lh) is token row
+  // 8*(v/4) + 4*lh + v%4 of row block i, column li of column block cb0 + j.
+  if (a.packed) {
+    // registers v = 8 tb .. 8 tb + 7 are exactly the 8 slots of the 16-token block tb
+    u32x4* Cp = reinterpret_cast<u32x4*>(a.C);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        // one block at a time leaves the accumulator registers (keeps the copies short-lived)
+        asm volatile("" : "+a"(acc[i * FN + j]) : : "memory");
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+          // every token block of the 128-row tile is written: packed C is padded to whole tiles
+          const int gtb = (m0 + i * 32) / 16 + tb, cb = cb0 + j;
+          if (cb < a.ccb) {
+            // slot e of this lane is token 16 gtb + (e < 4 ? 4 lh + e : 8 + 4 lh + e - 4);
+            // tokens past N (computed from a repeated row) are stored as zeros
+            float x[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const int tok = gtb * 16 + (e < 4 ? 4 * lh + e : 8 + 4 * lh + (e - 4));
+              x[e] = tok < a.N ? acc[i * FN + j][8 * tb + e] : 0.f;
+            }
+            u32x4 o;
+            o.x = pack2(x[0], x[1]);
+            o.y = pack2(x[2], x[3]);
+            o.z = pack2(x[4], x[5]);
+            o.w = pack2(x[6], x[7]);
+            Cp[((int64_t)gtb * a.ccb + cb) * 64 + lane] = o;
+          }
+        }
+      }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        asm volatile("" : "+a"(acc[i * FN + j]) : : "memory");
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + i * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
+          const int n = (cb0 + j) * 32 + li;
+          if (m < a.N && n < a.c) a.C[(int64_t)m * a.ldc + n] = f32_to_bf16(acc[i * FN + j][v]);
+        }
+      }
+  }
+}
+
+template <typename K>
+int set_smem(prac_ctx* ctx, K kern, size_t bytes, bool& done) {
+  if (!done) {
+    PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    done = true;
+  }
+  return PRAC_OK;
+}
+
+}  // namespace
+
+int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d, const bf16_t* Pfrag, int ncb, int c,
+                       bf16_t* C, int64_t ldc, bool packed) {
+  CompressWsArgs a;
+  a.X = X; a.ldx = ldx; a.N = N; a.d = d; a.Pfrag = Pfrag; a.ncb = ncb; a.c = c;
+  a.C = C; a.ldc = ldc; a.ccb = (c + 31) / 32; a.packed = packed ? 1 : 0;
+  a.tiles_m = (N + WS_BM - 1) / WS_BM;
+  const int FN = (c <= 128) ? 1 : 2;
+  a.col_groups = (a.ccb + 4 * FN - 1) / (4 * FN);
+  if (a.col_groups * 4 * FN > ncb) return PRAC_EINVAL;  // packed basis narrower than the launch assumes
+  const size_t smem = (size_t)WS_STAGES * WS_STAGE;
+  const int total = a.tiles_m * a.col_groups;
+  const dim3 grid(((total + 7) / 8) * 8), block(512);
+  static bool s1 = false, s2 = false;
+  static bool sv[64] = {false};
+  const int var = (ctx->tune_variant >> 1) & 63;
+  a.rotate = (ctx->tune_variant & 256) ? 0 : 1;
+#define PRAC_VARIANT_CASE(V)                                                            \
+  if (var == V) {                                                                       \
+    int rc = set_smem(ctx, compress_ws_kernel<2, V>, smem, sv[V]);                      \
+    if (rc) return rc;                                                                  \
+    PRAC_LAUNCH(ctx, (compress_ws_kernel<2, V>), grid, block, smem, a);                 \
+    PRAC_HIP_TRY(ctx, hipGetLastError());                                               \
+    return PRAC_OK;                                                                     \
+  }
+  PRAC_VARIANT_CASE(1) PRAC_VARIANT_CASE(2) PRAC_VARIANT_CASE(3) PRAC_VARIANT_CASE(4) PRAC_VARIANT_CASE(5)
+  PRAC_VARIANT_CASE(6) PRAC_VARIANT_CASE(7) PRAC_VARIANT_CASE(14) PRAC_VARIANT_CASE(15) PRAC_VARIANT_CASE(22)
+  PRAC_VARIANT_CASE(30) PRAC_VARIANT_CASE(62) PRAC_VARIANT_CASE(63) PRAC_VARIANT_CASE(38) PRAC_VARIANT_CASE(39)
+  if (FN == 1) {
+    int rc = set_smem(ctx, compress_ws_kernel<1>, smem, s1);
+    if (rc) return rc;
+    PRAC_LAUNCH(ctx, compress_ws_kernel<1>, grid, block, smem, a);
+  } else {
+    int rc = set_smem(ctx, compress_ws_kernel<2>, smem, s2);
+    if (rc) return rc;
+    PRAC_LAUNCH(ctx, compress_ws_kernel<2>, grid, block, smem, a);
+  }
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  return PRAC_OK;
+}
