@@ -132,6 +132,27 @@ __global__ __launch_bounds__(256) void trsm_right_upper_kernel(const float* __re
 // step; `counts[sweep]` collects the number of rotations of a sweep, and the launches
 // of sweep s+1 return at once when sweep s rotated nothing.
 
+// Sum over the 64 lanes of a wave, result in every lane: four data-parallel-primitive steps
+// inside each row of 16 lanes (no LDS traffic), then the four row sums through scalar registers.
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x) {
+  int lo = __double2loint(x), hi = __double2hiint(x);
+  lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xF, 0xF, true);
+  hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xF, 0xF, true);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double readlane_f64(double x, int l) {
+  return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), l),
+                          __builtin_amdgcn_readlane(__double2loint(x), l));
+}
+__device__ __forceinline__ double wave_sum_f64(double v) {
+  v += dpp_f64<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_f64<0x4E>(v);   // quad_perm [2,3,0,1]
+  v += dpp_f64<0x141>(v);  // row_half_mirror
+  v += dpp_f64<0x140>(v);  // row_mirror
+  return (readlane_f64(v, 0) + readlane_f64(v, 16)) + (readlane_f64(v, 32) + readlane_f64(v, 48));
+}
+
 __device__ __forceinline__ void tournament_pair(int step, int i, int players_even, int& p, int& q) {
   const int n1 = players_even - 1;
   if (i == 0) {
@@ -197,16 +218,23 @@ __global__ __launch_bounds__(1024) void jacobi_block_kernel(double* H, int b, in
           be2 += y * y;
           ga += x * y;
         }
-        for (int o = 32; o > 0; o >>= 1) {
-          al += __shfl_xor(al, o);
-          be2 += __shfl_xor(be2, o);
-          ga += __shfl_xor(ga, o);
-        }
-        if (fabs(ga) > tol * sqrt(al * be2) && fabs(ga) > 1e-300) {
+        al = wave_sum_f64(al);
+        be2 = wave_sum_f64(be2);
+        ga = wave_sum_f64(ga);
+        // rotate when |ga| > tol sqrt(al be2), compared as squares
+        if (ga * ga > tol * tol * al * be2 && fabs(ga) > 1e-300) {
           rotated = 1;
-          const double zeta = (be2 - al) / (2.0 * ga);
-          const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-          const double cs = 1.0 / sqrt(1.0 + tt * tt), sn = cs * tt;
+          // The angle may be approximate (the iteration corrects it), so tan comes from the
+          // hardware reciprocal / square root estimates; (cs, sn) must be a rotation to full
+          // precision, so cs = (1 + tt^2)^-1/2 gets one Newton step on top of its estimate.
+          const double zeta = (be2 - al) * 0.5 * __builtin_amdgcn_rcp(ga);
+          const double az = fabs(zeta);
+          const double tt = copysign(__builtin_amdgcn_rcp(az + __builtin_amdgcn_sqrt(1.0 + az * az)), zeta);
+          const double w = 1.0 + tt * tt;
+          double cs = __builtin_amdgcn_rsq(w);
+          cs = cs * (1.5 - 0.5 * w * cs * cs);
+          cs = cs * (1.5 - 0.5 * w * cs * cs);
+          const double sn = cs * tt;
           for (int t = lane; t < b; t += 64) {
             const double x = hp[t], y = hq[t];
             hp[t] = cs * x - sn * y;

@@ -654,12 +654,14 @@ struct PtArgs {
   int d, m, nkb, nmb;
   int tiles_m, tiles_n;
   float beta;
+  int vec_ok;  // dW rows allow aligned 16-byte accesses
 };
 
 // dW (d x m) = P T, K = c (a few hundred): both operands are read in fragment order
 // straight from L2, no LDS.  256 threads = 2 x 2 waves, a 128 x 128 tile per workgroup,
 // 64 x 64 per wave; fragments are requested PT_PD k-blocks ahead.
-constexpr int PT_PD = 4;
+constexpr int PT_PD = 8;
+constexpr int PT_TLD = 128 + 4;  // floats per row of the output staging tile
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
   const int total = a.tiles_m * a.tiles_n;
@@ -710,27 +712,76 @@ __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
   for (int t = 0; t < PT_PD; ++t)
     if (kb + t < a.nkb) mfma4(fr[t]);
 
+  // The accumulators hold columns across lanes and rows across registers; the tile goes through
+  // LDS (fp32, padded rows) so that the stores to dW are 16-byte chunks along rows.
   // block (i, j): register v of lane (li, lh) is row 32 (rb0 + i) + 8*(v/4) + 4 lh + v%4, column 32 (nb0 + j) + li
+  extern __shared__ __align__(16) unsigned char pt_smem[];
+  float* tile = reinterpret_cast<float*>(pt_smem);  // [128][PT_TLD]
+  const int wr = wave >> 1, wc = wave & 1;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int row = (rb0 + i) * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
-        const int col = (nb0 + j) * 32 + li;
-        if (row < a.d && col < a.m) {
-          const int64_t o = (int64_t)row * a.lddw + col;
-          const float val = acc[i][j][v];
-          if (OUT_BF16) {
-            bf16_t* q = reinterpret_cast<bf16_t*>(a.dW) + o;
-            *q = f32_to_bf16(a.beta == 0.f ? val : val + a.beta * __uint_as_float(((uint32_t)*q) << 16));
-          } else {
-            float* q = reinterpret_cast<float*>(a.dW) + o;
-            *q = a.beta == 0.f ? val : val + a.beta * *q;
-          }
-        }
+        const int row = (wr * 2 + i) * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
+        const int col = (wc * 2 + j) * 32 + li;
+        tile[row * PT_TLD + col] = acc[i][j][v];
       }
+  __syncthreads();
+  const int row0 = tm * 128, col0 = tn * 128;
+  if (OUT_BF16) {
+    // 8 columns (16 bytes of bf16) per thread and step: 16 threads per row, 16 rows per step
+    const int cr = tid >> 4, c8 = (tid & 15) * 8;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      const int row = cr + 16 * p;
+      const int grow = row0 + row, gcol = col0 + c8;
+      if (grow >= a.d || gcol >= a.m) continue;
+      const float4 lo = *reinterpret_cast<const float4*>(tile + row * PT_TLD + c8);
+      const float4 hi = *reinterpret_cast<const float4*>(tile + row * PT_TLD + c8 + 4);
+      float x[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      bf16_t* q = reinterpret_cast<bf16_t*>(a.dW) + (int64_t)grow * a.lddw + gcol;
+      if (a.vec_ok && gcol + 8 <= a.m) {
+        if (a.beta != 0.f) {
+          const u32x4 old = *reinterpret_cast<const u32x4*>(q);
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            x[e] += a.beta * __uint_as_float(((e & 1) ? (old[e >> 1] >> 16) : (old[e >> 1] & 0xFFFFu)) << 16);
+        }
+        u32x4 o;
+        o.x = pack2(x[0], x[1]);
+        o.y = pack2(x[2], x[3]);
+        o.z = pack2(x[4], x[5]);
+        o.w = pack2(x[6], x[7]);
+        *reinterpret_cast<u32x4*>(q) = o;
+      } else {
+        for (int e = 0; e < 8 && gcol + e < a.m; ++e)
+          q[e] = f32_to_bf16(a.beta == 0.f ? x[e] : x[e] + a.beta * __uint_as_float(((uint32_t)q[e]) << 16));
+      }
+    }
+  } else {
+    // 4 columns (16 bytes of fp32) per thread and step: 32 threads per row, 8 rows per step
+    const int cr = tid >> 5, c4 = (tid & 31) * 4;
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+      const int row = cr + 8 * p;
+      const int grow = row0 + row, gcol = col0 + c4;
+      if (grow >= a.d || gcol >= a.m) continue;
+      float4 x = *reinterpret_cast<const float4*>(tile + row * PT_TLD + c4);
+      float* q = reinterpret_cast<float*>(a.dW) + (int64_t)grow * a.lddw + gcol;
+      if (a.vec_ok && gcol + 4 <= a.m) {
+        if (a.beta != 0.f) {
+          const float4 old = *reinterpret_cast<const float4*>(q);
+          x.x += a.beta * old.x; x.y += a.beta * old.y; x.z += a.beta * old.z; x.w += a.beta * old.w;
+        }
+        *reinterpret_cast<float4*>(q) = x;
+      } else {
+        const float xs[4] = {x.x, x.y, x.z, x.w};
+        for (int e = 0; e < 4 && gcol + e < a.m; ++e) q[e] = a.beta == 0.f ? xs[e] : xs[e] + a.beta * q[e];
+      }
+    }
+  }
 }
 
 inline int grid_for(int64_t n, int n_cu) {
@@ -850,8 +901,18 @@ int launch_pt(prac_ctx* ctx, const bf16_t* Pa, const bf16_t* Tf, int d, int m, i
   a.tiles_m = (d + 127) / 128; a.tiles_n = (m + 127) / 128; a.beta = beta;
   const int total = a.tiles_m * a.tiles_n;
   const dim3 grid(((total + 7) / 8) * 8), block(256);
-  if (out_bf16) PRAC_LAUNCH(ctx, pt_kernel<true>, grid, block, 0, a);
-  else PRAC_LAUNCH(ctx, pt_kernel<false>, grid, block, 0, a);
+  a.vec_ok = (reinterpret_cast<uintptr_t>(dW) % 16 == 0 && lddw % (out_bf16 ? 8 : 4) == 0) ? 1 : 0;
+  const size_t smem = (size_t)128 * PT_TLD * sizeof(float);
+  static bool sb = false, sf = false;
+  if (out_bf16) {
+    int rc = set_smem(ctx, pt_kernel<true>, smem, sb);
+    if (rc) return rc;
+    PRAC_LAUNCH(ctx, pt_kernel<true>, grid, block, smem, a);
+  } else {
+    int rc = set_smem(ctx, pt_kernel<false>, smem, sf);
+    if (rc) return rc;
+    PRAC_LAUNCH(ctx, pt_kernel<false>, grid, block, smem, a);
+  }
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }

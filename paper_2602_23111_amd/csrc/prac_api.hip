@@ -530,7 +530,10 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
     bf16_t* Tf = reinterpret_cast<bf16_t*>(ctx->ws + o_t);
     {  // T = C^T dY as `splits` partial slabs over the token range
       ProfScope ps(ctx, PRAC_KERNEL_CT_DY);
-      rc = launch_ctdy(ctx, Cpk, c, reinterpret_cast<const bf16_t*>(dY), lddy, (int)N, (int)m, part, splits);
+      if (ctx->tune_variant & 512)
+        rc = launch_ctdy(ctx, Cpk, c, reinterpret_cast<const bf16_t*>(dY), lddy, (int)N, (int)m, part, splits);
+      else
+        rc = launch_ctdy_ws(ctx, Cpk, c, reinterpret_cast<const bf16_t*>(dY), lddy, (int)N, (int)m, part, splits);
     }
     if (rc) return rc;
     {  // T in fragment order (bf16): slabs summed, random rows weighted by the scaling factor

@@ -122,6 +122,8 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
                        int c, bf16_t* C, int64_t ldc, bool packed);
 int launch_ctdy(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, int64_t lddy, int N, int m,
                 float* slabs, int splits);
+int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, int64_t lddy, int N, int m,
+                   float* slabs, int splits);
 int launch_pack_pfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nkb, int ncb, bf16_t* out);
 int launch_unpack_c(prac_ctx* ctx, const bf16_t* Cpk, int N, int c, bf16_t* C, int64_t ldc);
 int launch_pack_c(prac_ctx* ctx, const bf16_t* C, int64_t ldc, int N, int c, bf16_t* Cpk);

@@ -322,6 +322,253 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
   }
 }
 
+// ----------------------------------------------------------------------- C^T dY
+// Token-split partial sums of T = C^T dY (Lemma 1, reassociated), same workgroup shape:
+//   loader waves   stream dY tiles (128 tokens x 128 columns), transpose each 8 x 8 patch in
+//                  registers and store the tile into LDS already in MFMA fragment order;
+//   matrix waves   read those B fragments from LDS (shared by all four waves), fetch their own
+//                  A fragments (packed C, L2-resident) straight into registers, issue MFMAs.
+// LDS stage: [k-block 0..7][column block 0..3][64 lanes][16 bytes].  Column block nb holds the
+// tile's columns 4 j + nb (j = 0..31), so that a lane's four accumulators of one row are four
+// consecutive columns of T.  Lane slot (j, h) sits at 16-byte slot h*32 + ((j & 16) | ((j & 15) ^ (j >> 4)))
+// of its 1 KB block: with this swizzle both the loaders' stores (16 lanes write slots 2 cc + u of
+// four different blocks) and the fragment reads are free of bank conflicts.
+// Element e of lane half h is token 16 kb + (e < 4 ? 4 h + e : 8 + 4 h + e - 4), the slot order of
+// packed C, so both operands list the tokens of a k-block in the same order.
+struct CtdyWsArgs {
+  const bf16_t* Cpk;   // packed compressed activation [ntb][ccb][64][8]
+  int ccb;             // 32-column blocks of C
+  int c;
+  const bf16_t* dY;
+  int64_t lddy;
+  int N, m;
+  float* slabs;        // [splits][c][m]
+  int splits;
+  int tok_per_split;   // multiple of 128
+  int tiles_n;         // column tiles of 128 over m
+  int row_groups;      // groups of 8 column blocks (256 rows of T) over c
+  int rotate;
+};
+
+constexpr int CW_BK = 128, CW_BN = 128;
+constexpr int CW_STAGE = 8 * 4 * 1024;  // bytes per LDS stage
+constexpr int CW_STAGES = 3;
+
+// One k-block of a 64 x 128 wave tile: acc[4 i + j] += a_i * f_j, while the four B fragments at
+// byte offsets O + 1024 nb from `lds` are read into fn.
+template <int O>
+__device__ __forceinline__ void kblock_ct(f32x16 (&acc)[8], const u32x4 (&fc)[4], u32x4 (&fn)[4], const u32x4& a0,
+                                          const u32x4& a1, unsigned lds) {
+  asm volatile(
+      "ds_read_b128 %8, %18 offset:%19\n"
+      "v_mfma_f32_32x32x16_bf16 %0, %16, %12, %0\n"
+      "ds_read_b128 %9, %18 offset:%20\n"
+      "v_mfma_f32_32x32x16_bf16 %4, %17, %12, %4\n"
+      "ds_read_b128 %10, %18 offset:%21\n"
+      "v_mfma_f32_32x32x16_bf16 %1, %16, %13, %1\n"
+      "ds_read_b128 %11, %18 offset:%22\n"
+      "v_mfma_f32_32x32x16_bf16 %5, %17, %13, %5\n"
+      "v_mfma_f32_32x32x16_bf16 %2, %16, %14, %2\n"
+      "v_mfma_f32_32x32x16_bf16 %6, %17, %14, %6\n"
+      "v_mfma_f32_32x32x16_bf16 %3, %16, %15, %3\n"
+      "v_mfma_f32_32x32x16_bf16 %7, %17, %15, %7\n"
+      "s_waitcnt lgkmcnt(0)\n"
+      : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]), "+a"(acc[4]), "+a"(acc[5]), "+a"(acc[6]),
+        "+a"(acc[7]), "=&v"(fn[0]), "=&v"(fn[1]), "=&v"(fn[2]), "=&v"(fn[3])
+      : "v"(fc[0]), "v"(fc[1]), "v"(fc[2]), "v"(fc[3]), "v"(a0), "v"(a1), "v"(lds), "n"(O), "n"(O + 1024),
+        "n"(O + 2048), "n"(O + 3072)
+      : "memory");
+}
+
+__device__ __forceinline__ void frag_read4_ct(u32x4 (&f)[4], unsigned lds) {
+  asm volatile(
+      "ds_read_b128 %0, %4\n"
+      "ds_read_b128 %1, %4 offset:1024\n"
+      "ds_read_b128 %2, %4 offset:2048\n"
+      "ds_read_b128 %3, %4 offset:3072\n"
+      "s_waitcnt lgkmcnt(0)\n"
+      : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]), "=&v"(f[3])
+      : "v"(lds)
+      : "memory");
+}
+
+__device__ __forceinline__ int c_slot_tok(int h, int e) { return e < 4 ? 4 * h + e : 8 + 4 * h + (e - 4); }
+__device__ __forceinline__ int frag_slot(int j, int h) { return h * 32 + ((j & 16) | ((j & 15) ^ (j >> 4))); }
+
+__global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+
+  const int per_split = a.tiles_n * a.row_groups;
+  const int total = per_split * a.splits;
+  const int per_xcd = (total + 7) / 8;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int logical = xcd * per_xcd + slot;
+  if (slot >= per_xcd || logical >= total) return;
+  const int tn = logical % a.tiles_n;
+  const int rg = (logical / a.tiles_n) % a.row_groups;
+  const int split = logical / per_split;
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n0 = tn * CW_BN;
+  const int tok_beg = split * a.tok_per_split;
+  const int tok_end = min(a.N, tok_beg + a.tok_per_split);
+  const int nk = tok_end > tok_beg ? (tok_end - tok_beg + CW_BK - 1) / CW_BK : 0;
+  // workgroups of one split read the same blocks of packed C: start each at a different tile
+  const int rot = (a.rotate && nk > 0) ? tn % nk : 0;
+  auto act = [&](int kt) {
+    const int t = min(kt, nk - 1) + rot;
+    return t >= nk ? t - nk : t;
+  };
+
+  if (wave >= 4) {
+    // ------------------------------------------------------------ loader waves
+    if (nk == 0) return;
+    const int lt = tid - 256;
+    const int cc = lt & 15, tg = lt >> 4, kb = tg >> 1, h = tg & 1;
+    const int last_chunk = ((a.m - 1) / 8) * 8;
+    const char* ycol = reinterpret_cast<const char*>(a.dY) + (int64_t)min(n0 + 8 * cc, last_chunk) * 2;
+    const uint32_t rowb = (uint32_t)a.lddy * 2u;
+    // LDS byte offsets of the two lane slots this thread fills (columns 8 cc + j: j < 4 and j >= 4)
+    const uint32_t sA = (uint32_t)(kb * 4096 + frag_slot(2 * cc, h) * 16);
+    const uint32_t sB = (uint32_t)(kb * 4096 + frag_slot(2 * cc + 1, h) * 16);
+
+    u32x4 ry[3][8] = {};
+    // rows past N re-read the last row (finite data) and meet the zero padding of packed C
+    auto gload = [&](int kt, auto setc) {
+      constexpr int S = decltype(setc)::value;
+      const bool live = kt < nk;
+      const int t0 = tok_beg + act(kt) * CW_BK;
+      const char* base = ycol + (int64_t)t0 * a.lddy * 2;  // uniform part + this thread's column
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int row = min(16 * kb + c_slot_tok(h, e), a.N - 1 - t0);
+        ry[S][e] = *reinterpret_cast<const u32x4*>(base + (live ? (uint32_t)row * rowb : 0u));
+      }
+    };
+    auto sstore = [&](int stage, auto setc) {
+      constexpr int S = decltype(setc)::value;
+      unsigned char* s = smem_raw + stage * CW_STAGE;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        // column j of the 8 x 8 patch: 16-bit element j of each of the 8 token rows
+        u32x4 o;
+        uint32_t w[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+          const uint32_t lo = ry[S][2 * e2][j >> 1], hi = ry[S][2 * e2 + 1][j >> 1];
+          w[e2] = __builtin_amdgcn_perm(hi, lo, (j & 1) ? 0x07060302u : 0x05040100u);
+        }
+        o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
+        *reinterpret_cast<u32x4*>(s + ((j & 3) * 1024 + (j < 4 ? sA : sB))) = o;
+      }
+    };
+    std::integral_constant<int, 0> S0;
+    std::integral_constant<int, 1> S1;
+    std::integral_constant<int, 2> S2;
+    gload(0, S0);
+    gload(1, S1);
+    gload(2, S2);
+    sstore(0, S0);
+    gload(3, S0);
+    if (nk > 1) sstore(1, S1);
+    gload(4, S1);
+    __syncthreads();  // tiles 0 and 1 are in LDS
+    int stage = 2;
+    auto step = [&](int kt, auto setc) {
+      if (kt < nk) {
+        if (kt + 2 < nk) sstore(stage, setc);
+        stage = stage == CW_STAGES - 1 ? 0 : stage + 1;
+        gload(kt + 5, setc);
+        __syncthreads();
+      }
+    };
+    for (int kt = 0; kt < nk; kt += 3) {
+      step(kt, S2);
+      step(kt + 1, S0);
+      step(kt + 2, S1);
+    }
+    return;
+  }
+
+  // -------------------------------------------------------------- matrix waves
+  const int lane = tid & 63, li = lane & 31, lh = lane >> 5;
+  const int cb0 = rg * 8 + wave * 2;  // this wave's two 32-row blocks of T (column blocks of C)
+  f32x16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+
+  if (nk > 0) {
+    const int ntb = ((a.N + 127) / 128) * 8;  // token blocks of packed C, padded to whole 128-token tiles
+    const char* cbase = reinterpret_cast<const char*>(a.Cpk);
+    // column blocks past the end re-read block 0; their rows of T are never stored
+    const uint32_t aoff0 = (uint32_t)((cb0 < a.ccb ? cb0 : 0) * 64 + lane) * 16u;
+    const uint32_t aoff1 = (uint32_t)((cb0 + 1 < a.ccb ? cb0 + 1 : 0) * 64 + lane) * 16u;
+    const int64_t tbrow = (int64_t)a.ccb * 1024;  // bytes per 16-token block of packed C
+
+    u32x4 rc[8][2] = {};
+    auto aload = [&](int kt, auto kkc) {
+      constexpr int KK = decltype(kkc)::value;
+      const int tb = kt < nk ? tok_beg / 16 + act(kt) * 8 + KK : tok_beg / 16;
+      const char* base = cbase + (int64_t)min(tb, ntb - 1) * tbrow;  // uniform
+      rc[KK][0] = *reinterpret_cast<const u32x4*>(base + aoff0);
+      rc[KK][1] = *reinterpret_cast<const u32x4*>(base + aoff1);
+    };
+#define PRAC_IC(v) std::integral_constant<int, (v)> {}
+    aload(0, PRAC_IC(0)); aload(0, PRAC_IC(1)); aload(0, PRAC_IC(2)); aload(0, PRAC_IC(3));
+    aload(0, PRAC_IC(4)); aload(0, PRAC_IC(5)); aload(0, PRAC_IC(6)); aload(0, PRAC_IC(7));
+
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw +
+                          (unsigned)(frag_slot(li, lh) * 16);
+    u32x4 fa[4] = {}, fb[4] = {};
+    __builtin_amdgcn_s_barrier();  // tiles 0 and 1 are in LDS
+    frag_read4_ct(fa, lds0);
+    int stage = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+      const unsigned cur = lds0 + (unsigned)stage * CW_STAGE;
+      stage = stage == CW_STAGES - 1 ? 0 : stage + 1;
+      const unsigned nxt = lds0 + (unsigned)stage * CW_STAGE;
+      kblock_ct<4096 * 1>(acc, fa, fb, rc[0][0], rc[0][1], cur); aload(kt + 1, PRAC_IC(0));
+      kblock_ct<4096 * 2>(acc, fb, fa, rc[1][0], rc[1][1], cur); aload(kt + 1, PRAC_IC(1));
+      kblock_ct<4096 * 3>(acc, fa, fb, rc[2][0], rc[2][1], cur); aload(kt + 1, PRAC_IC(2));
+      kblock_ct<4096 * 4>(acc, fb, fa, rc[3][0], rc[3][1], cur); aload(kt + 1, PRAC_IC(3));
+      kblock_ct<4096 * 5>(acc, fa, fb, rc[4][0], rc[4][1], cur); aload(kt + 1, PRAC_IC(4));
+      kblock_ct<4096 * 6>(acc, fb, fa, rc[5][0], rc[5][1], cur); aload(kt + 1, PRAC_IC(5));
+      kblock_ct<4096 * 7>(acc, fa, fb, rc[6][0], rc[6][1], cur); aload(kt + 1, PRAC_IC(6));
+      __builtin_amdgcn_s_barrier();
+      kblock_ct<0>(acc, fb, fa, rc[7][0], rc[7][1], nxt); aload(kt + 1, PRAC_IC(7));
+    }
+#undef PRAC_IC
+    drain_mfma<8>(acc);
+  }
+
+  // epilogue: acc[4 i + j], register v of lane (li, lh): T row 32 (cb0 + i) + 8*(v/4) + 4*lh + v%4,
+  // column n0 + 4 li + j
+  float* out = a.slabs + (int64_t)split * a.c * a.m;
+  const int n = n0 + 4 * li;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    asm volatile("" : "+a"(acc[4 * i]), "+a"(acc[4 * i + 1]), "+a"(acc[4 * i + 2]), "+a"(acc[4 * i + 3]) : : "memory");
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = (cb0 + i) * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
+      if (row < a.c) {
+        float* o = out + (int64_t)row * a.m + n;
+        if (n + 3 < a.m && (a.m & 3) == 0) {
+          *reinterpret_cast<float4*>(o) =
+              make_float4(acc[4 * i][v], acc[4 * i + 1][v], acc[4 * i + 2][v], acc[4 * i + 3][v]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (n + j < a.m) o[j] = acc[4 * i + j][v];
+        }
+      }
+    }
+  }
+}
+
 template <typename K>
 int set_smem(prac_ctx* ctx, K kern, size_t bytes, bool& done) {
   if (!done) {
@@ -370,6 +617,26 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
     if (rc) return rc;
     PRAC_LAUNCH(ctx, compress_ws_kernel<2>, grid, block, smem, a);
   }
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  return PRAC_OK;
+}
+
+int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, int64_t lddy, int N, int m, float* slabs,
+                   int splits) {
+  CtdyWsArgs a;
+  a.Cpk = Cpk; a.ccb = (c + 31) / 32; a.c = c; a.dY = dY; a.lddy = lddy; a.N = N; a.m = m;
+  a.slabs = slabs; a.splits = splits;
+  const int ktiles = (N + CW_BK - 1) / CW_BK;
+  a.tok_per_split = ((ktiles + splits - 1) / splits) * CW_BK;
+  a.tiles_n = (m + CW_BN - 1) / CW_BN;
+  a.row_groups = (a.ccb + 7) / 8;
+  a.rotate = (ctx->tune_variant & 256) ? 0 : 1;
+  const size_t smem = (size_t)CW_STAGES * CW_STAGE;
+  const int total = a.tiles_n * a.row_groups * splits;
+  static bool s = false;
+  int rc = set_smem(ctx, ctdy_ws_kernel, smem, s);
+  if (rc) return rc;
+  PRAC_LAUNCH(ctx, ctdy_ws_kernel, dim3(((total + 7) / 8) * 8), dim3(512), smem, a);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }

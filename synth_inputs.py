@@ -100,16 +100,12 @@ def activation_torch(N: int, d: int, alpha: float, seed: int, n_out: int,
     layer share their spectrum and principal subspace, as successive training
     batches do.  Returns an (N, d) view into an (N, ld) buffer when ld > d
     (padded leading dimension)."""
-    g = torch.Generator(device=device)
-    g.manual_seed(seed)
-    A = torch.randn((d, d), generator=g, device=device, dtype=torch.float32)
-    R, T = torch.linalg.qr(A)
-    R = R * torch.where(torch.diagonal(T) < 0, -1.0, 1.0)[None, :]
-    sig = torch.arange(1, d + 1, device=device, dtype=torch.float32) ** (-alpha)
-    M = sig[:, None] * R                      # diag(sigma) R
+    # the layer's mixing matrix diag(sigma) R is built on the host (numpy QR), like activation()
+    rng = np.random.default_rng(seed)
+    M64 = power_law_sigma(d, alpha)[:, None] * haar_orthogonal(d, rng)
     if n_out:
-        ch = torch.randperm(d, generator=g, device=device)[:n_out]
-        M[:, ch] *= out_scale
+        M64[:, outlier_channels(d, n_out, rng)] *= out_scale
+    M = torch.from_numpy(M64.astype(np.float32)).to(device)
     gz = torch.Generator(device=device)
     gz.manual_seed(seed * 1000003 + 17 * batch + 1)
     ld = d if ld is None else ld
