@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 
 WORKLOAD = dict(name="llama1b_attn_proj", N=32768, d=2048, m=2048, k=128, r=128, alpha=0.8,
                 n_out=8, out_scale=30.0, dy_std=1e-3, refresh_every=500, n_sets=4, layer_seed=3000,
-                warm_iters=2)
+                warm_iters=4, warm_oversample=32)
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
@@ -143,7 +143,8 @@ def main():
             # every refresh after the first starts the subspace iteration from the previous Q1
             warm = state["lp"] is not None
             _, state["lp"], state["scale"] = ctx.fit_basis(Xs[i], k, r, seed=1234, draw=t // w["refresh_every"], P=P,
-                                                           warm_start=warm, iters=w["warm_iters"] if warm else 0)
+                                                           warm_start=warm, iters=w["warm_iters"] if warm else 0,
+                                                           oversample=w["warm_oversample"] if warm else 0)
             state["fits"] += 1
         ctx.compress(Xs[i], P, P_lp=state["lp"], out=Cs[i], layout=C_PACKED)
         ctx.weight_grad(Cs[i], dYs[i], P, k, r, state["scale"], P_lp=state["lp"], out=dW, layout=C_PACKED)
@@ -166,7 +167,8 @@ def main():
     # fit alone, for the record (not part of `value` beyond its share of the timed steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ctx.fit_basis(Xs[0], k, r, seed=1234, draw=0, P=P, warm_start=True, iters=w["warm_iters"])
+    ctx.fit_basis(Xs[0], k, r, seed=1234, draw=0, P=P, warm_start=True, iters=w["warm_iters"],
+                  oversample=w["warm_oversample"])
     torch.cuda.synchronize()
     fit_ms = 1e3 * (time.perf_counter() - t0)
 

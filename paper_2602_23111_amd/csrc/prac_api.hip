@@ -200,6 +200,7 @@ int prac_create(prac_ctx** out, int device, void* hip_stream) {
   c->ev_stop = nullptr;
   c->tune_splits = 0;
   c->tune_variant = 0;
+  c->dbg = nullptr;
   hipDeviceProp_t prop;
   c->n_cu = (hipGetDeviceProperties(&prop, device) == hipSuccess) ? prop.multiProcessorCount : 256;
   if (hipMalloc(reinterpret_cast<void**>(&c->d_flag), 256) != hipSuccess ||
@@ -257,6 +258,12 @@ int prac_set_tuning(prac_ctx* ctx, int key, int value) {
   if (!ctx) return PRAC_ENOCTX;
   if (key == 99) { ctx->tune_variant = value; return PRAC_OK; }
   ctx->tune_splits = value;
+  return PRAC_OK;
+}
+
+int prac_set_debug_buffer(prac_ctx* ctx, void* p) {
+  if (!ctx) return PRAC_ENOCTX;
+  ctx->dbg = reinterpret_cast<long long*>(p);
   return PRAC_OK;
 }
 

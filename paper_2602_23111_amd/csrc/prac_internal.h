@@ -23,6 +23,7 @@ struct prac_ctx {
   int last_hip;       // last hipError_t that made a call fail
   int n_cu;
   int tune_variant;   // experiment switch
+  long long* dbg;     // device buffer for kernel timing probes (tuning only), or null
   int tune_splits;    // > 0: override the token-split count of C^T dY (tuning hook)
   int prof_kind;      // kernel kind bracketed by events (0: none), see prac_profile_select
   hipEvent_t ev_start, ev_stop;  // set by ProfScope: the next PRAC_LAUNCH attaches them to its kernel

@@ -38,6 +38,8 @@ struct CompressWsArgs {
   int tiles_m;
   int col_groups;       // column groups of 4*FN blocks
   int rotate;           // 1: each workgroup starts its k loop at a different tile
+  int depth;            // tiles each loader thread keeps in flight in registers (1 or 3)
+  long long* dbg;       // timing probe (tuning only): [role][arrive/pass][barrier] time stamps of workgroup 8
 };
 
 constexpr int WS_BM = 128, WS_BK = 128, WS_LD = WS_BK + 8;
@@ -186,6 +188,25 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
     std::integral_constant<int, 0> S0;
     std::integral_constant<int, 1> S1;
     std::integral_constant<int, 2> S2;
+    int stage = 2;
+    if (a.depth == 1) {
+      // one tile in flight per loader wave set: fewer X requests queue in front of the P requests
+      gload(0, S0);
+      sstore(0, 0, S0);
+      gload(1, S0);
+      if (nk > 1) sstore(1, 1, S0);
+      gload(2, S0);
+      if (!(VAR & 32)) __syncthreads();
+      for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 2 < nk) sstore(kt + 2, stage, S0);
+        stage = stage == WS_STAGES - 1 ? 0 : stage + 1;
+        gload(kt + 3, S0);
+        if (a.dbg && blockIdx.x == 8 && tid == 256) a.dbg[64 + 0 + kt] = __builtin_readcyclecounter();
+        if (!(VAR & 32)) __syncthreads();
+        if (a.dbg && blockIdx.x == 8 && tid == 256) a.dbg[64 + 32 + kt] = __builtin_readcyclecounter();
+      }
+      return;
+    }
     gload(0, S0);
     gload(1, S1);
     gload(2, S2);
@@ -196,13 +217,14 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
     if (!(VAR & 32)) __syncthreads();  // tiles 0 and 1 are in LDS
     // step kt: tile kt+2 -> LDS (its stage was last read for tile kt-1, before the previous barrier),
     // request tile kt+5 into the registers just freed (tile j travels in register set j % 3)
-    int stage = 2;
     auto step = [&](int kt, auto setc) {
       if (kt < nk) {
         if (kt + 2 < nk) sstore(kt + 2, stage, setc);
         stage = stage == WS_STAGES - 1 ? 0 : stage + 1;
         gload(kt + 5, setc);
+        if (a.dbg && blockIdx.x == 8 && tid == 256) a.dbg[64 + 0 + kt] = __builtin_readcyclecounter();
         if (!(VAR & 32)) __syncthreads();
+        if (a.dbg && blockIdx.x == 8 && tid == 256) a.dbg[64 + 32 + kt] = __builtin_readcyclecounter();
       }
     };
     for (int kt = 0; kt < nk; kt += 3) {
@@ -266,7 +288,9 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
     kblock(PRAC_IC(32 * 5), fa, fb, PRAC_IC(4), cur); pload(kt + 1, PRAC_IC(4));
     kblock(PRAC_IC(32 * 6), fb, fa, PRAC_IC(5), cur); pload(kt + 1, PRAC_IC(5));
     kblock(PRAC_IC(32 * 7), fa, fb, PRAC_IC(6), cur); pload(kt + 1, PRAC_IC(6));
+    if (a.dbg && blockIdx.x == 8 && tid == 0) a.dbg[0 + kt] = __builtin_readcyclecounter();
     if (!(VAR & 32)) __builtin_amdgcn_s_barrier();
+    if (a.dbg && blockIdx.x == 8 && tid == 0) a.dbg[32 + kt] = __builtin_readcyclecounter();
     kblock(PRAC_IC(0), fb, fa, PRAC_IC(7), nxt); pload(kt + 1, PRAC_IC(7));
   }
 #undef PRAC_IC
@@ -348,6 +372,7 @@ struct CtdyWsArgs {
   int tiles_n;         // column tiles of 128 over m
   int row_groups;      // groups of 8 column blocks (256 rows of T) over c
   int rotate;
+  int depth;           // dY tiles each loader thread keeps in flight in registers (1 or 3)
 };
 
 constexpr int CW_BK = 128, CW_BN = 128;
@@ -466,6 +491,22 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
     std::integral_constant<int, 0> S0;
     std::integral_constant<int, 1> S1;
     std::integral_constant<int, 2> S2;
+    int stage = 2;
+    if (a.depth == 1) {
+      gload(0, S0);
+      sstore(0, S0);
+      gload(1, S0);
+      if (nk > 1) sstore(1, S0);
+      gload(2, S0);
+      __syncthreads();
+      for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 2 < nk) sstore(stage, S0);
+        stage = stage == CW_STAGES - 1 ? 0 : stage + 1;
+        gload(kt + 3, S0);
+        __syncthreads();
+      }
+      return;
+    }
     gload(0, S0);
     gload(1, S1);
     gload(2, S2);
@@ -474,7 +515,6 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
     if (nk > 1) sstore(1, S1);
     gload(4, S1);
     __syncthreads();  // tiles 0 and 1 are in LDS
-    int stage = 2;
     auto step = [&](int kt, auto setc) {
       if (kt < nk) {
         if (kt + 2 < nk) sstore(stage, setc);
@@ -587,6 +627,8 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
   a.X = X; a.ldx = ldx; a.N = N; a.d = d; a.Pfrag = Pfrag; a.ncb = ncb; a.c = c;
   a.C = C; a.ldc = ldc; a.ccb = (c + 31) / 32; a.packed = packed ? 1 : 0;
   a.tiles_m = (N + WS_BM - 1) / WS_BM;
+  a.dbg = ctx->dbg;
+  a.depth = (ctx->tune_variant & 1024) ? 3 : 1;
   const int FN = (c <= 128) ? 1 : 2;
   a.col_groups = (a.ccb + 4 * FN - 1) / (4 * FN);
   if (a.col_groups * 4 * FN > ncb) return PRAC_EINVAL;  // packed basis narrower than the launch assumes
@@ -630,7 +672,10 @@ int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, in
   a.tok_per_split = ((ktiles + splits - 1) / splits) * CW_BK;
   a.tiles_n = (m + CW_BN - 1) / CW_BN;
   a.row_groups = (a.ccb + 7) / 8;
-  a.rotate = (ctx->tune_variant & 256) ? 0 : 1;
+  // no rotation by default: workgroups of a split then read the same blocks of packed C at about
+  // the same time, which keeps them in L2 (rotating the start tile cost 4 % at the headline shape)
+  a.rotate = (ctx->tune_variant & 256) ? 1 : 0;
+  a.depth = (ctx->tune_variant & 1024) ? 3 : 1;
   const size_t smem = (size_t)CW_STAGES * CW_STAGE;
   const int total = a.tiles_n * a.row_groups * splits;
   static bool s = false;
