@@ -1,476 +1,21 @@
-// The two streaming contractions of the per-step path, specialised for gfx950.
+// Small kernels of the per-step path around the two streaming contractions (ws_kernels.hip):
+// packing of P and C into MFMA fragment order, the slab reduction that turns the token-split
+// partial sums of C^T dY into T (bf16, fragment order, random rows scaled), and dW = P T.
 //
-//   compress   C = X P          (Alg. 1 compression step)     compress_panel_kernel
-//   C^T dY     token-split partial sums of T = C^T dY (Lemma 1, reassociated)  ctdy_kernel
-//
-// Both are HBM-bound at PRAC's ranks (c = k + r << d), so the design goal is to read the
-// big operand (X, dY) exactly once, keep LDS traffic below the MFMA time and keep many
-// bytes in flight.  The small operand never goes through LDS: it is stored in HBM in
-// MFMA fragment order, so a wave fetches a whole 32x16 operand block with one fully
-// coalesced 1 KB load.
-//
-// Fragment order ("frag16x32"), used for P (B operand of compress) and for the packed
-// compressed activation C (A operand of C^T dY): a block of 16 reduction indices x 32
-// rows/columns is 64 lanes x 8 bf16; lane = 32 h + j holds, for row/column j, the
+// Fragment order ("frag16x32"), used for P (B operand of compress), for the packed compressed
+// activation C (A operand of C^T dY), for T and for P as an A operand: a block of 16 reduction
+// indices x 32 rows/columns is 64 lanes x 8 bf16; lane = 32 h + j holds, for row/column j, the
 // reduction indices listed by slot(h, e), e = 0..7.
-//   P:  slot(h, e) = 8 h + e                         (k = 16 kb + 8 h + e)
-//   C:  slot(h, e) = 4 h + e (e < 4), 8 + 4 h + e - 4 (e >= 4)   (token = 16 tb + slot)
-// The C order is the order in which the 32x32 MFMA accumulator of compress holds its
-// rows, so compress stores a packed block straight from its registers.
-//
-// All loads in the main loops are unconditional (addresses clamped into the operand,
-// invalid elements masked to zero afterwards) and the loops run whole groups of bodies
-// without branches: the compiler can then count exactly how many younger loads follow
-// the one it waits for, which is what keeps several tiles in flight.
+//   P, T:  slot(h, e) = 8 h + e                         (k = 16 kb + 8 h + e)
+//   C:     slot(h, e) = 4 h + e (e < 4), 8 + 4 h + e - 4 (e >= 4)   (token = 16 tb + slot)
+// The C order is the order in which the 32x32 MFMA accumulator of compress holds its rows, so
+// compress stores a packed block straight from its registers.  A wave fetches a whole 32x16
+// operand block with one fully coalesced 1 KB load.
 #include <type_traits>
 
 #include "frag_utils.h"
 
 namespace {
-
-// ------------------------------------------------------------------ compress
-struct CompressArgs {
-  const bf16_t* X;
-  int64_t ldx;
-  int N, d;
-  const bf16_t* Pfrag;  // [nkb][ncb][64][8], nkb = round_up(d,128)/16
-  int ncb;              // 32-column blocks in the padded basis (multiple of 8)
-  int c;
-  bf16_t* C;            // row-major (ldc) or packed [ceil(N/16)][ccb][64][8]
-  int64_t ldc;
-  int ccb;              // 32-column blocks of packed C = ceil(c / 32)
-  int packed;
-  int tiles_m;
-  int col_groups;       // column groups of 4*FN blocks
-};
-
-constexpr int CP_BM = 128, CP_BK = 128, CP_LD = CP_BK + 8, CP_STAGES = 2;
-constexpr int CP_HK = 4;  // 16-row k-blocks per half tile (P fragments are fetched per half tile)
-
-// 256 threads = 4 waves.  The workgroup owns 128 token rows; wave w owns the 32*FN
-// columns [32 FN w, 32 FN (w+1)) of its column group and all 128 rows.
-//   X tiles (128 x 128) go global -> registers -> LDS (two stages); tile kt+3 is requested
-//   while tile kt is multiplied, 256 contiguous bytes per row and request.
-//   P fragments go global (L2) -> registers, half a tile (64 k) at a time, three register
-//   sets, each requested one tile ahead of its use.
-//   Loads return in issue order, so P requests are always issued ahead of the far-ahead X
-//   request of the same body: waiting for P never waits for HBM data requested just now.
-//   LDS fragment reads are double-buffered one k-block ahead of the MFMAs that use them,
-//   and the LDS store / global requests of the next tiles are issued behind the first MFMA
-//   block so that their issue cycles hide under matrix-core time.
-template <int FN, int VAR = 0>
-__global__ __launch_bounds__(256) void compress_panel_kernel(CompressArgs a) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
-  constexpr int STAGE = CP_BM * CP_LD;
-  constexpr int A_CH = CP_BM * (CP_BK / 8) / 256;  // 8 chunks of 16 B per thread and tile
-  constexpr int KK = CP_BK / 16;                   // 8
-
-  // XCD-aware order: consecutive logical tiles (same rows, next column group) on one XCD
-  const int total = a.tiles_m * a.col_groups;
-  const int per_xcd = (total + 7) / 8;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int logical = xcd * per_xcd + slot;
-  if (slot >= per_xcd || logical >= total) return;
-  const int cg = logical % a.col_groups, tm = logical / a.col_groups;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int li = lane & 31, lh = lane >> 5;
-  const int m0 = tm * CP_BM;
-  const int cb0 = cg * 4 * FN + wave * FN;  // first 32-column block of this wave
-  const int nk = (a.d + CP_BK - 1) / CP_BK;
-  const int nh = 2 * nk;
-  const u32x4* __restrict__ Pf = reinterpret_cast<const u32x4*>(a.Pfrag);
-
-  // per-thread chunk coordinates: chunk p covers row (tid>>4) + 16 p, columns (tid&15)*8 ..
-  const int crow = tid >> 4, ccol = (tid & 15) * 8;
-  const int last_chunk = ((a.d - 1) / 8) * 8;  // start of the last (possibly partial) chunk of a row
-  // Addresses are a uniform 64-bit base (scalar registers) plus a 32-bit per-thread byte offset,
-  // so that a load needs one offset register instead of a 64-bit pointer per chunk.
-  const char* xbase = reinterpret_cast<const char*>(a.X + (int64_t)m0 * a.ldx);
-  uint32_t roff[A_CH];  // byte offset of this thread's row of chunk p (row clamped into the matrix)
-#pragma unroll
-  for (int p = 0; p < A_CH; ++p)
-    roff[p] = (uint32_t)(min(m0 + crow + 16 * p, a.N - 1) - m0) * (uint32_t)a.ldx * 2u;
-  const char* pbase = reinterpret_cast<const char*>(Pf);
-  const uint32_t boff = (uint32_t)(cb0 * 64 + lane) * 16u;  // this lane's slot in a row of P blocks
-  const int64_t brow = (int64_t)a.ncb * 1024;               // bytes per 16-row k-block of P fragments
-
-  f32x16 acc[4][FN];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  u32x4 ra[2][A_CH];
-  u32x4 rb[2][CP_HK * FN];
-
-  // tile / half-tile indices are clamped to the last one: past-the-end prefetches re-read it
-  // (from L2) and are never used, which keeps the loop free of conditional loads
-  auto gload_a = [&](int kt, u32x4 (&r)[A_CH]) {
-    const uint32_t kb = (uint32_t)min(min(kt, nk - 1) * CP_BK + ccol, last_chunk) * 2u;
-#pragma unroll
-    for (int p = 0; p < A_CH; ++p) r[p] = *reinterpret_cast<const u32x4*>(xbase + (roff[p] + kb));
-  };
-  // chunks [p0, p0 + 4) of tile kt into LDS.  Only the last tile of a d that is not a multiple
-  // of 128 needs its tail columns zeroed (MASK); rows past N are never stored, so they may
-  // hold anything finite or not.
-  auto sstore_a = [&](int kt, int stage, const u32x4 (&r)[A_CH], auto first, auto mask) {
-    constexpr bool MASK = decltype(mask)::value;
-    constexpr int p0 = decltype(first)::value;
-    bf16_t* s = smem + stage * STAGE;
-    const int nv = a.d - (kt * CP_BK + ccol);
-#pragma unroll
-    for (int p = p0; p < p0 + 4; ++p)
-      *reinterpret_cast<u32x4*>(s + (crow + 16 * p) * CP_LD + ccol) = MASK ? keep_first(r[p], nv) : r[p];
-  };
-  auto gload_b = [&](int hb, u32x4 (&r)[CP_HK * FN]) {
-    const char* hbase = pbase + (int64_t)min(hb, nh - 1) * CP_HK * brow;  // uniform
-#pragma unroll
-    for (int kk = 0; kk < CP_HK; ++kk)
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-        r[kk * FN + j] = *reinterpret_cast<const u32x4*>(hbase + kk * brow + j * 1024 + boff);
-  };
-  auto frag_load = [&](int stage, int kk, bf16x8 (&f)[4]) {
-    const bf16_t* s = smem + stage * STAGE;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      f[i] = *reinterpret_cast<const bf16x8*>(s + (i * 32 + li) * CP_LD + kk * 16 + lh * 8);
-  };
-  auto mfma_block = [&](const bf16x8 (&f)[4], const u32x4* b) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], as_frag(b[j]), acc[i][j], 0, 0, 0);
-  };
-
-  const bool tail_mask = (a.d % CP_BK) != 0;  // the last tile has columns past d
-
-  // prologue: P half 0 and X tiles 0, 1 on their way; tile 0 into LDS; tile 2 requested
-  gload_b(0, rb[0]);
-  gload_a(0, ra[0]);
-  gload_a(1, ra[1]);
-  if (nk == 1 && tail_mask) {
-    sstore_a(0, 0, ra[0], std::integral_constant<int, 0>{}, std::true_type{});
-    sstore_a(0, 0, ra[0], std::integral_constant<int, 4>{}, std::true_type{});
-  } else {
-    sstore_a(0, 0, ra[0], std::integral_constant<int, 0>{}, std::false_type{});
-    sstore_a(0, 0, ra[0], std::integral_constant<int, 4>{}, std::false_type{});
-  }
-  gload_a(2, ra[0]);
-  __syncthreads();
-
-  // body kt (PH = kt % 2): LDS stage kt%2 holds X tile kt; ra[(kt+1)%2] holds tile kt+1 and
-  // ra[kt%2] awaits tile kt+2; rb[0] / rb[1] hold the first / second P half of tile kt (rb[1]
-  // may still be in flight at the top).
-  // A wave issues in order and the matrix core accepts one MFMA every ~32 cycles, so
-  // everything else (LDS reads of the next k-block, the LDS store of tile kt+1, the global
-  // requests) is spread between the MFMAs by the scheduling-group pipeline at the end.
-  // Request order inside a body: second P half of tile kt+1 is not needed before the next
-  // body, so per body the order is  P(2nd half, tile kt) .. P(1st half, tile kt+1), X(kt+3):
-  // the X request is the youngest, and no wait for P ever has to wait for it.
-  auto body = [&](int kt, auto ph, auto mask) {
-    constexpr int PH = decltype(ph)::value;
-    constexpr int S = PH % 2, SA = (PH + 1) % 2;
-    constexpr int NMF = 4 * FN;  // MFMAs per k-block
-    bf16x8 fa[2][4];
-    if (!(VAR & 1)) frag_load(S, 0, fa[0]);
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      if (!(VAR & 1) && kk + 1 < KK) frag_load(S, kk + 1, fa[(kk + 1) & 1]);
-      if (kk == 0 && !(VAR & 2)) gload_b(2 * kt + 1, rb[1]);
-      if (kk == 1 && !(VAR & 8)) sstore_a(kt + 1, SA, ra[SA], std::integral_constant<int, 0>{}, mask);
-      if (kk == 2 && !(VAR & 8)) sstore_a(kt + 1, SA, ra[SA], std::integral_constant<int, 4>{}, mask);
-      if (kk == 4 && !(VAR & 2)) gload_b(2 * kt + 2, rb[0]);
-      if (kk == ((VAR & 64) ? 3 : 5) && !(VAR & 4)) gload_a(kt + 3, ra[SA]);
-      if (!(VAR & 1)) mfma_block(fa[kk & 1], kk < CP_HK ? &rb[0][kk * FN] : &rb[1][(kk - CP_HK) * FN]);
-    }
-    if (VAR == 0 || VAR == 64) {
-      // pipeline: 4 LDS reads for the first k-block, then per MFMA one LDS read (while the
-      // next k-block still has some) and one of this k-block's extra operations
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
-#pragma unroll
-        for (int mi = 0; mi < NMF; ++mi) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          if (kk + 1 < KK && mi < 4) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          if ((kk == 0 || kk == 4) && mi < CP_HK * FN) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-          if ((kk == 1 || kk == 2) && mi < 4) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-          if (kk == ((VAR & 64) ? 3 : 5) && mi < A_CH) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        }
-    }
-    if (!(VAR & 16)) __syncthreads();
-  };
-  int kt = 0;
-  const int nfull = tail_mask ? nk - 2 : nk;  // bodies that never store a masked tile
-  for (; kt + 2 <= nfull; kt += 2) {
-    body(kt, std::integral_constant<int, 0>{}, std::false_type{});
-    body(kt + 1, std::integral_constant<int, 1>{}, std::false_type{});
-  }
-  // remaining bodies; body kt stores tile kt+1, so only body nk-2 stores the (masked) last tile
-  for (; kt < nk; ++kt) {
-    const bool m = tail_mask && kt == nk - 2;
-    if (kt % 2 == 0) {
-      if (m) body(kt, std::integral_constant<int, 0>{}, std::true_type{});
-      else body(kt, std::integral_constant<int, 0>{}, std::false_type{});
-    } else {
-      if (m) body(kt, std::integral_constant<int, 1>{}, std::true_type{});
-      else body(kt, std::integral_constant<int, 1>{}, std::false_type{});
-    }
-  }
-
-  // epilogue: block (i, j) register v of lane (li, lh) is token row 8*(v/4) + 4*lh + v%4
-  // of row block i, column li of column block cb0 + j.
-  if (a.packed) {
-    // registers v = 8 tb .. 8 tb + 7 are exactly the 8 slots of the 16-token block tb
-    u32x4* Cp = reinterpret_cast<u32x4*>(a.C);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-          // every token block of the 128-row tile is written: packed C is padded to whole tiles
-          const int gtb = (m0 + i * 32) / 16 + tb, cb = cb0 + j;
-          if (cb < a.ccb) {
-            // slot e of this lane is token 16 gtb + (e < 4 ? 4 lh + e : 8 + 4 lh + e - 4);
-            // tokens past N (their X rows were not masked) are stored as zeros
-            float x[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              const int tok = gtb * 16 + (e < 4 ? 4 * lh + e : 8 + 4 * lh + (e - 4));
-              x[e] = tok < a.N ? acc[i][j][8 * tb + e] : 0.f;
-            }
-            u32x4 o;
-            o.x = pack2(x[0], x[1]);
-            o.y = pack2(x[2], x[3]);
-            o.z = pack2(x[4], x[5]);
-            o.w = pack2(x[6], x[7]);
-            Cp[((int64_t)gtb * a.ccb + cb) * 64 + lane] = o;
-          }
-        }
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + i * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
-          const int n = (cb0 + j) * 32 + li;
-          if (m < a.N && n < a.c) a.C[(int64_t)m * a.ldc + n] = f32_to_bf16(acc[i][j][v]);
-        }
-  }
-}
-
-// -------------------------------------------------------------------- C^T dY
-struct CtdyArgs {
-  const bf16_t* Cpk;   // packed compressed activation [ntb][ccb][64][8]
-  int ccb;             // 32-column blocks of C
-  int c;
-  const bf16_t* dY;
-  int64_t lddy;
-  int N, m;
-  float* slabs;        // [splits][c][m]
-  int splits;
-  int tok_per_split;   // multiple of CT_BK
-  int tiles_n;         // column tiles of 128 over m
-  int row_groups;      // groups of 8 column blocks (256 rows of T) over c
-};
-
-constexpr int CT_BN = 128, CT_BK = 128, CT_LD = CT_BN + 8, CT_STAGES = 2;
-constexpr int CT_HK = 4;  // 16-token blocks per half tile (C fragments are fetched per half tile)
-
-// 256 threads = 4 waves.  The workgroup owns 256 rows of T (columns of C) x 128 columns
-// (of dY) for one token range; wave w owns rows [64 w, 64 w + 64).  C fragments come
-// straight from the packed layout (global -> registers, half a tile at a time); dY tiles
-// (128 tokens x 128 columns) go global -> registers -> LDS as they lie in memory
-// ([token][column]) and are turned into fragments by an in-register 8 x 4 transpose.
-// Same request order and scheduling-group pipeline as the compress kernel.
-// No masking is needed: splits are whole 128-token tiles, token rows past N are read from
-// the last valid row of dY and meet the zero padding of packed C (stored for whole tiles);
-// columns past m or c only reach outputs that are never stored.
-__global__ __launch_bounds__(256) void ctdy_kernel(CtdyArgs a) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
-  constexpr int STAGE = CT_BK * CT_LD;
-  constexpr int B_CH = CT_BK * (CT_BN / 8) / 256;  // 8 chunks of 16 B per thread and tile
-  constexpr int KK = CT_BK / 16;                   // 8
-
-  const int per_split = a.tiles_n * a.row_groups;
-  const int total = per_split * a.splits;
-  const int per_xcd = (total + 7) / 8;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int logical = xcd * per_xcd + slot;
-  if (slot >= per_xcd || logical >= total) return;
-  const int tn = logical % a.tiles_n;
-  const int rg = (logical / a.tiles_n) % a.row_groups;
-  const int split = logical / per_split;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int li = lane & 31, lh = lane >> 5;
-  const int n0 = tn * CT_BN;
-  const int cb0 = rg * 8 + wave * 2;
-  const int tok_beg = split * a.tok_per_split;
-  const int tok_end = min(a.N, tok_beg + a.tok_per_split);
-  const int nk = tok_end > tok_beg ? (tok_end - tok_beg + CT_BK - 1) / CT_BK : 0;
-  const int ntb = ((a.N + 127) / 128) * 8;  // token blocks of packed C, padded to whole 128-token tiles
-
-  f32x16 acc[2][4];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  if (nk > 0) {
-    // chunk p of a dY tile: token row (tid>>4) + 16 p, columns n0 + (tid&15)*8 ..
-    const int brow = tid >> 4, bcol = (tid & 15) * 8;
-    const int last_chunk = ((a.m - 1) / 8) * 8;
-    const char* ybase = reinterpret_cast<const char*>(a.dY) + (int64_t)min(n0 + bcol, last_chunk) * 2;
-    const int ok_a0 = cb0 < a.ccb, ok_a1 = cb0 + 1 < a.ccb;
-    const char* cbase = reinterpret_cast<const char*>(a.Cpk);
-    const uint32_t aoff0 = (uint32_t)((ok_a0 ? cb0 : 0) * 64 + lane) * 16u;
-    const uint32_t aoff1 = (uint32_t)((ok_a1 ? cb0 + 1 : 0) * 64 + lane) * 16u;
-    const int64_t tbrow = (int64_t)a.ccb * 1024;  // bytes per 16-token block of packed C
-    const int nh = 2 * nk;
-
-    // register sets are flat arrays indexed with compile-time constants only (a set index
-    // that reaches a lambda as a run-time value would push the whole array into scratch)
-    u32x4 rb[2 * B_CH];
-    u32x4 rafr[2 * CT_HK * 2];
-
-    auto gload_b = [&](int kt, auto set) {
-      constexpr int o = decltype(set)::value * B_CH;
-      const int t0 = tok_beg + min(kt, nk - 1) * CT_BK + brow;
-#pragma unroll
-      for (int p = 0; p < B_CH; ++p)
-        rb[o + p] = *reinterpret_cast<const u32x4*>(ybase + (int64_t)min(t0 + 16 * p, a.N - 1) * a.lddy * 2);
-    };
-    auto sstore_b = [&](int stage, auto set, auto first) {
-      constexpr int o = decltype(set)::value * B_CH, p0 = decltype(first)::value;
-      bf16_t* s = smem + stage * STAGE;
-#pragma unroll
-      for (int p = p0; p < p0 + 4; ++p) *reinterpret_cast<u32x4*>(s + (brow + 16 * p) * CT_LD + bcol) = rb[o + p];
-    };
-    // C fragments of half tile hb (4 token blocks), unmasked (see mfma_block)
-    auto gload_a = [&](int hb, auto set) {
-      constexpr int o = decltype(set)::value * CT_HK * 2;
-      const int tb0 = tok_beg / 16 + min(hb, nh - 1) * CT_HK;
-#pragma unroll
-      for (int kk = 0; kk < CT_HK; ++kk) {
-        const char* base = cbase + (int64_t)min(tb0 + kk, ntb - 1) * tbrow;  // uniform
-        rafr[o + kk * 2 + 0] = *reinterpret_cast<const u32x4*>(base + aoff0);
-        rafr[o + kk * 2 + 1] = *reinterpret_cast<const u32x4*>(base + aoff1);
-      }
-    };
-    // raw LDS rows of k-block kk for this lane: token rows 4 lh + e (e < 4), 8 + 4 lh + e - 4
-    auto raw_load = [&](int stage, int kk, u32x2 (&v)[8]) {
-      const bf16_t* s = smem + stage * STAGE;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int row = kk * 16 + (e < 4 ? 4 * lh + e : 8 + 4 * lh + (e - 4));
-        v[e] = *reinterpret_cast<const u32x2*>(s + row * CT_LD + 4 * li);
-      }
-    };
-    auto mfma_block = [&](const u32x2 (&v)[8], const u32x4& a0, const u32x4& a1) {
-      const bf16x8 fa0 = as_frag(a0), fa1 = as_frag(a1);
-      // 8 x 4 transpose, one byte-permute per 32-bit word: fragment j takes 16-bit element j
-      // of each of the 8 rows (selectors 0-3 address the second operand, 4-7 the first)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        u32x4 o;
-        uint32_t w[4];
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-          const uint32_t lo = j < 2 ? v[2 * e2].x : v[2 * e2].y;
-          const uint32_t hi = j < 2 ? v[2 * e2 + 1].x : v[2 * e2 + 1].y;
-          w[e2] = __builtin_amdgcn_perm(hi, lo, (j & 1) ? 0x07060302u : 0x05040100u);
-        }
-        o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
-        const bf16x8 fb = as_frag(o);
-        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb, acc[0][j], 0, 0, 0);
-        acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb, acc[1][j], 0, 0, 0);
-      }
-    };
-
-    // prologue: C half 0 and dY tiles 0, 1 on their way; tile 0 into LDS; tile 2 requested
-    gload_a(0, std::integral_constant<int, 0>{});
-    gload_b(0, std::integral_constant<int, 0>{});
-    gload_b(1, std::integral_constant<int, 1>{});
-    sstore_b(0, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-    sstore_b(0, std::integral_constant<int, 0>{}, std::integral_constant<int, 4>{});
-    gload_b(2, std::integral_constant<int, 0>{});
-    __syncthreads();
-
-    // body kt (PH = kt % 2): LDS stage kt%2 holds dY tile kt; rb[(kt+1)%2] holds tile kt+1 and
-    // rb[kt%2] awaits tile kt+2; rafr[0] / rafr[1] hold the first / second C half of tile kt.
-    auto body = [&](int kt, auto ph) {
-      constexpr int PH = decltype(ph)::value;
-      constexpr int S = PH % 2, SB = (PH + 1) % 2;
-      u32x2 raw[2][8];
-      raw_load(S, 0, raw[0]);
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        if (kk + 1 < KK) raw_load(S, kk + 1, raw[(kk + 1) & 1]);
-        if (kk == 0) gload_a(2 * kt + 1, std::integral_constant<int, 1>{});
-        if (kk == 1) sstore_b(SB, std::integral_constant<int, SB>{}, std::integral_constant<int, 0>{});
-        if (kk == 2) sstore_b(SB, std::integral_constant<int, SB>{}, std::integral_constant<int, 4>{});
-        if (kk == 4) gload_a(2 * kt + 2, std::integral_constant<int, 0>{});
-        if (kk == 5) gload_b(kt + 3, std::integral_constant<int, SB>{});
-        mfma_block(raw[kk & 1], rafr[kk * 2], rafr[kk * 2 + 1]);
-      }
-      // pipeline: the first k-block's LDS reads, then per pair of MFMAs the four permutes that
-      // build their B fragment, one LDS read of the next k-block and this k-block's extras
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
-#pragma unroll
-        for (int pr = 0; pr < 4; ++pr) {
-          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          if (kk + 1 < KK) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          if (kk == 0 || kk == 4 || kk == 5) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-          if (kk == 1 || kk == 2) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          if (kk == 0 || kk == 4 || kk == 5) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        }
-      __syncthreads();
-    };
-    int kt = 0;
-    for (; kt + 2 <= nk; kt += 2) {
-      body(kt, std::integral_constant<int, 0>{});
-      body(kt + 1, std::integral_constant<int, 1>{});
-    }
-    if (kt < nk) body(kt, std::integral_constant<int, 0>{});
-  }
-
-  // epilogue: T row = 32 (cb0 + i) + 8*(v/4) + 4*lh + v%4, columns n0 + 4 li .. + 3
-  float* out = a.slabs + (int64_t)split * a.c * a.m;
-  const int n = n0 + 4 * li;
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int row = (cb0 + i) * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
-      if (row < a.c) {
-        float* o = out + (int64_t)row * a.m + n;
-        if (n + 3 < a.m && (a.m & 3) == 0) {
-          *reinterpret_cast<float4*>(o) = make_float4(acc[i][0][v], acc[i][1][v], acc[i][2][v], acc[i][3][v]);
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (n + j < a.m) o[j] = acc[i][j][v];
-        }
-      }
-    }
-}
 
 // ------------------------------------------------------------- small helpers
 // Pfrag[(kb * ncb + cb) * 64 + lane][e] = bf16(P[16 kb + 8 h + e][32 cb + j]), zero outside d x c
@@ -802,51 +347,6 @@ int set_smem(prac_ctx* ctx, K kern, size_t bytes, bool& done) {
 }
 
 }  // namespace
-
-int launch_compress_panel(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d, const bf16_t* Pfrag, int ncb,
-                          int c, bf16_t* C, int64_t ldc, bool packed) {
-  CompressArgs a;
-  a.X = X; a.ldx = ldx; a.N = N; a.d = d; a.Pfrag = Pfrag; a.ncb = ncb; a.c = c;
-  a.C = C; a.ldc = ldc; a.ccb = (c + 31) / 32; a.packed = packed ? 1 : 0;
-  a.tiles_m = (N + CP_BM - 1) / CP_BM;
-  const int FN = (c <= 128) ? 1 : 2;
-  a.col_groups = (a.ccb + 4 * FN - 1) / (4 * FN);
-  if (a.col_groups * 4 * FN > ncb) return PRAC_EINVAL;  // packed basis narrower than the launch assumes
-  const size_t smem = (size_t)CP_STAGES * CP_BM * CP_LD * sizeof(bf16_t);
-  const int total = a.tiles_m * a.col_groups;
-  const dim3 grid(((total + 7) / 8) * 8), block(256);
-  static bool s1 = false, s2 = false;
-  if (FN == 1) {
-    int rc = set_smem(ctx, compress_panel_kernel<1>, smem, s1);
-    if (rc) return rc;
-    PRAC_LAUNCH(ctx, compress_panel_kernel<1>, grid, block, smem, a);
-  } else {
-    int rc = set_smem(ctx, compress_panel_kernel<2>, smem, s2);
-    if (rc) return rc;
-    PRAC_LAUNCH(ctx, compress_panel_kernel<2>, grid, block, smem, a);
-  }
-  PRAC_HIP_TRY(ctx, hipGetLastError());
-  return PRAC_OK;
-}
-
-int launch_ctdy(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, int64_t lddy, int N, int m, float* slabs,
-                int splits) {
-  CtdyArgs a;
-  a.Cpk = Cpk; a.ccb = (c + 31) / 32; a.c = c; a.dY = dY; a.lddy = lddy; a.N = N; a.m = m;
-  a.slabs = slabs; a.splits = splits;
-  const int ktiles = (N + CT_BK - 1) / CT_BK;
-  a.tok_per_split = ((ktiles + splits - 1) / splits) * CT_BK;
-  a.tiles_n = (m + CT_BN - 1) / CT_BN;
-  a.row_groups = (a.ccb + 7) / 8;
-  const size_t smem = (size_t)CT_STAGES * CT_BK * CT_LD * sizeof(bf16_t);
-  const int total = a.tiles_n * a.row_groups * splits;
-  static bool s = false;
-  int rc = set_smem(ctx, ctdy_kernel, smem, s);
-  if (rc) return rc;
-  PRAC_LAUNCH(ctx, ctdy_kernel, dim3(((total + 7) / 8) * 8), dim3(256), smem, a);
-  PRAC_HIP_TRY(ctx, hipGetLastError());
-  return PRAC_OK;
-}
 
 int launch_pack_pfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nkb, int ncb, bf16_t* out) {
   hipLaunchKernelGGL(pack_pfrag_kernel, dim3(grid_for((int64_t)nkb * ncb * 64, ctx->n_cu)), dim3(256), 0, ctx->stream,

@@ -199,8 +199,6 @@ int prac_create(prac_ctx** out, int device, void* hip_stream) {
   c->ev_start = nullptr;
   c->ev_stop = nullptr;
   c->tune_splits = 0;
-  c->tune_variant = 0;
-  c->dbg = nullptr;
   hipDeviceProp_t prop;
   c->n_cu = (hipGetDeviceProperties(&prop, device) == hipSuccess) ? prop.multiProcessorCount : 256;
   if (hipMalloc(reinterpret_cast<void**>(&c->d_flag), 256) != hipSuccess ||
@@ -254,16 +252,9 @@ int prac_profile_select(prac_ctx* ctx, int kind) {
 }
 
 int prac_set_tuning(prac_ctx* ctx, int key, int value) {
-  if ((key != PRAC_TUNE_CTDY_SPLITS && key != 99) || value < 0 || value > 4095) return PRAC_EINVAL;
+  if (key != PRAC_TUNE_CTDY_SPLITS || value < 0 || value > 127) return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
-  if (key == 99) { ctx->tune_variant = value; return PRAC_OK; }
   ctx->tune_splits = value;
-  return PRAC_OK;
-}
-
-int prac_set_debug_buffer(prac_ctx* ctx, void* p) {
-  if (!ctx) return PRAC_ENOCTX;
-  ctx->dbg = reinterpret_cast<long long*>(p);
   return PRAC_OK;
 }
 
@@ -396,9 +387,6 @@ static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N
     const bf16_t* Pf = reinterpret_cast<const bf16_t*>(lp + l.off_pf);
     if (!fused) {
       ProfScope ps(ctx, PRAC_KERNEL_COMPRESS);
-      if (ctx->tune_variant == 1)
-        return launch_compress_panel(ctx, reinterpret_cast<const bf16_t*>(X), ldx, (int)N, (int)d, Pf, l.ncb, c,
-                                     reinterpret_cast<bf16_t*>(C), ldc, packed);
       return launch_compress_ws(ctx, reinterpret_cast<const bf16_t*>(X), ldx, (int)N, (int)d, Pf, l.ncb, c,
                                 reinterpret_cast<bf16_t*>(C), ldc, packed);
     }
@@ -537,10 +525,7 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
     bf16_t* Tf = reinterpret_cast<bf16_t*>(ctx->ws + o_t);
     {  // T = C^T dY as `splits` partial slabs over the token range
       ProfScope ps(ctx, PRAC_KERNEL_CT_DY);
-      if (ctx->tune_variant & 512)
-        rc = launch_ctdy(ctx, Cpk, c, reinterpret_cast<const bf16_t*>(dY), lddy, (int)N, (int)m, part, splits);
-      else
-        rc = launch_ctdy_ws(ctx, Cpk, c, reinterpret_cast<const bf16_t*>(dY), lddy, (int)N, (int)m, part, splits);
+      rc = launch_ctdy_ws(ctx, Cpk, c, reinterpret_cast<const bf16_t*>(dY), lddy, (int)N, (int)m, part, splits);
     }
     if (rc) return rc;
     {  // T in fragment order (bf16): slabs summed, random rows weighted by the scaling factor

@@ -22,8 +22,6 @@ struct prac_ctx {
   int* d_flag;        // device-side numeric failure flag (0 = fine)
   int last_hip;       // last hipError_t that made a call fail
   int n_cu;
-  int tune_variant;   // experiment switch
-  long long* dbg;     // device buffer for kernel timing probes (tuning only), or null
   int tune_splits;    // > 0: override the token-split count of C^T dY (tuning hook)
   int prof_kind;      // kernel kind bracketed by events (0: none), see prac_profile_select
   hipEvent_t ev_start, ev_stop;  // set by ProfScope: the next PRAC_LAUNCH attaches them to its kernel
@@ -116,13 +114,9 @@ int launch_cast_out(prac_ctx* ctx, const float* src, int64_t lds, void* dst, pra
                     int64_t ldd, int rows, int cols, float beta);
 int launch_symmetrize(prac_ctx* ctx, float* G, int d, int64_t ldg);  // copy upper -> lower
 
-// ---- streaming kernels of the per-step path (hot_kernels.hip) ---------------------
-int launch_compress_panel(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d, const bf16_t* Pfrag, int ncb,
-                          int c, bf16_t* C, int64_t ldc, bool packed);
+// ---- kernels of the per-step path (ws_kernels.hip, hot_kernels.hip) -----------------
 int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d, const bf16_t* Pfrag, int ncb,
                        int c, bf16_t* C, int64_t ldc, bool packed);
-int launch_ctdy(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, int64_t lddy, int N, int m,
-                float* slabs, int splits);
 int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, int64_t lddy, int N, int m,
                    float* slabs, int splits);
 int launch_pack_pfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nkb, int ncb, bf16_t* out);

@@ -37,9 +37,6 @@ struct CompressWsArgs {
   int packed;
   int tiles_m;
   int col_groups;       // column groups of 4*FN blocks
-  int rotate;           // 1: each workgroup starts its k loop at a different tile
-  int depth;            // tiles each loader thread keeps in flight in registers (1 or 3)
-  long long* dbg;       // timing probe (tuning only): [role][arrive/pass][barrier] time stamps of workgroup 8
 };
 
 constexpr int WS_BM = 128, WS_BK = 128, WS_LD = WS_BK + 8;
@@ -120,7 +117,7 @@ __device__ __forceinline__ void drain_mfma(f32x16 (&acc)[NACC]) {
   }
 }
 
-template <int FN, int VAR = 0>
+template <int FN>
 __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
 
@@ -138,7 +135,7 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
   const int nk = (a.d + WS_BK - 1) / WS_BK;
   // Step kt of this workgroup works on k-tile act(kt): the sum over k may run in any order, and
   // workgroups that start at different tiles do not all ask L2 for the same lines of P at once.
-  const int rot = a.rotate ? tm % nk : 0;
+  const int rot = tm % nk;
   auto act = [&](int kt) {
     const int t = min(kt, nk - 1) + rot;
     return t >= nk ? t - nk : t;
@@ -155,82 +152,44 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
     for (int p = 0; p < 8; ++p) roff[p] = (uint32_t)(min(m0 + crow + 16 * p, a.N - 1) - m0) * (uint32_t)a.ldx * 2u;
     const uint32_t soff = (uint32_t)(crow * WS_LD + ccol) * 2u;
 
-    u32x4 ra[3][8] = {};
+    u32x4 ra[8];
     // Requests past the last tile stay in the instruction stream (the loop has no load-free tail
     // version) but all go to this thread's first chunk, which the L1 cache already holds.
-    auto gload = [&](int kt, auto setc) {
-      constexpr int S = decltype(setc)::value;
+    auto gload = [&](int kt) {
       const uint32_t kb = (uint32_t)min(act(kt) * WS_BK + ccol, last_chunk) * 2u;
       const bool live = kt < nk;
-      if (VAR & 1) return;
 #pragma unroll
       for (int p = 0; p < 8; ++p)
-        ra[S][p] = *reinterpret_cast<const u32x4*>(xbase + (live ? roff[p] + kb : roff[0] + (uint32_t)ccol * 2u));
+        ra[p] = *reinterpret_cast<const u32x4*>(xbase + (live ? roff[p] + kb : roff[0] + (uint32_t)ccol * 2u));
     };
     // tile kt -> stage `stage` (= kt % 3); columns past d are zeroed (only the last tile has any)
-    auto sstore = [&](int kt, int stage, auto setc) {
-      constexpr int S = decltype(setc)::value;
+    auto sstore = [&](int kt, int stage) {
       unsigned char* s = smem_raw + stage * WS_STAGE + soff;
       const int nv = a.d - (act(kt) * WS_BK + ccol);
-      if (VAR & 16) {
-#pragma unroll
-        for (int p = 0; p < 8; ++p) asm volatile("" : : "v"(ra[S][p]));
-        return;
-      }
       if (nv >= 8) {
 #pragma unroll
-        for (int p = 0; p < 8; ++p) *reinterpret_cast<u32x4*>(s + p * (16 * WS_LD * 2)) = ra[S][p];
+        for (int p = 0; p < 8; ++p) *reinterpret_cast<u32x4*>(s + p * (16 * WS_LD * 2)) = ra[p];
       } else {
 #pragma unroll
-        for (int p = 0; p < 8; ++p) *reinterpret_cast<u32x4*>(s + p * (16 * WS_LD * 2)) = keep_first(ra[S][p], nv);
+        for (int p = 0; p < 8; ++p) *reinterpret_cast<u32x4*>(s + p * (16 * WS_LD * 2)) = keep_first(ra[p], nv);
       }
     };
-    std::integral_constant<int, 0> S0;
-    std::integral_constant<int, 1> S1;
-    std::integral_constant<int, 2> S2;
+    // One tile in flight per loader thread, two more complete in LDS.  Deeper register prefetch
+    // was slower: the requests of a CU share one L1 miss queue, and X lines queued there delay
+    // the matrix waves' P lines more than the extra depth gains.
+    gload(0);
+    sstore(0, 0);
+    gload(1);
+    if (nk > 1) sstore(1, 1);
+    gload(2);
+    __syncthreads();  // tiles 0 and 1 are in LDS
     int stage = 2;
-    if (a.depth == 1) {
-      // one tile in flight per loader wave set: fewer X requests queue in front of the P requests
-      gload(0, S0);
-      sstore(0, 0, S0);
-      gload(1, S0);
-      if (nk > 1) sstore(1, 1, S0);
-      gload(2, S0);
-      if (!(VAR & 32)) __syncthreads();
-      for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 2 < nk) sstore(kt + 2, stage, S0);
-        stage = stage == WS_STAGES - 1 ? 0 : stage + 1;
-        gload(kt + 3, S0);
-        if (a.dbg && blockIdx.x == 8 && tid == 256) a.dbg[64 + 0 + kt] = __builtin_readcyclecounter();
-        if (!(VAR & 32)) __syncthreads();
-        if (a.dbg && blockIdx.x == 8 && tid == 256) a.dbg[64 + 32 + kt] = __builtin_readcyclecounter();
-      }
-      return;
-    }
-    gload(0, S0);
-    gload(1, S1);
-    gload(2, S2);
-    sstore(0, 0, S0);
-    gload(3, S0);
-    if (nk > 1) sstore(1, 1, S1);
-    gload(4, S1);
-    if (!(VAR & 32)) __syncthreads();  // tiles 0 and 1 are in LDS
-    // step kt: tile kt+2 -> LDS (its stage was last read for tile kt-1, before the previous barrier),
-    // request tile kt+5 into the registers just freed (tile j travels in register set j % 3)
-    auto step = [&](int kt, auto setc) {
-      if (kt < nk) {
-        if (kt + 2 < nk) sstore(kt + 2, stage, setc);
-        stage = stage == WS_STAGES - 1 ? 0 : stage + 1;
-        gload(kt + 5, setc);
-        if (a.dbg && blockIdx.x == 8 && tid == 256) a.dbg[64 + 0 + kt] = __builtin_readcyclecounter();
-        if (!(VAR & 32)) __syncthreads();
-        if (a.dbg && blockIdx.x == 8 && tid == 256) a.dbg[64 + 32 + kt] = __builtin_readcyclecounter();
-      }
-    };
-    for (int kt = 0; kt < nk; kt += 3) {
-      step(kt, S2);
-      step(kt + 1, S0);
-      step(kt + 2, S1);
+    for (int kt = 0; kt < nk; ++kt) {
+      // tile kt+2 -> LDS: its stage was last read for tile kt-1, before the previous barrier
+      if (kt + 2 < nk) sstore(kt + 2, stage);
+      stage = stage == WS_STAGES - 1 ? 0 : stage + 1;
+      gload(kt + 3);
+      __syncthreads();
     }
     return;
   }
@@ -250,18 +209,16 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
     for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
   // ring of the eight k-blocks' P fragments: slot kk is refilled for the next tile right after its use
-  u32x4 rb[8][FN] = {};
+  u32x4 rb[8][FN];
   auto pload = [&](int kt, auto kkc) {
     constexpr int KK = decltype(kkc)::value;
     // past the last tile: one fixed block (an L1 hit), never used
     const char* base = pbase + (kt < nk ? (int64_t)(act(kt) * 8 + KK) * brow : (int64_t)0);  // uniform
-    if (VAR & 2) return;
 #pragma unroll
     for (int j = 0; j < FN; ++j) rb[KK][j] = *reinterpret_cast<const u32x4*>(base + (j * 1024 + boff));
   };
   auto kblock = [&](auto oc, const u32x4 (&fcur)[4], u32x4 (&fnext)[4], auto kkc, unsigned lds) {
     constexpr int O = decltype(oc)::value, KK = decltype(kkc)::value;
-    if (VAR & 4) return;
     if constexpr (FN == 2) kblock2<O>(acc, fcur, fnext, rb[KK][0], rb[KK][1], lds);
     else kblock1<O>(acc, fcur, fnext, rb[KK][0], lds);
   };
@@ -273,8 +230,8 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
   // row li, 16-byte half lh of the k-block
   const unsigned lds0 =
       (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw + (unsigned)(li * WS_LD * 2 + lh * 16);
-  u32x4 fa[4] = {}, fb[4] = {};
-  if (!(VAR & 32)) __builtin_amdgcn_s_barrier();  // tiles 0 and 1 are in LDS
+  u32x4 fa[4], fb[4];
+  __builtin_amdgcn_s_barrier();  // tiles 0 and 1 are in LDS
   frag_read4(fa, lds0);
   int stage = 0;
   for (int kt = 0; kt < nk; ++kt) {
@@ -288,14 +245,11 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
     kblock(PRAC_IC(32 * 5), fa, fb, PRAC_IC(4), cur); pload(kt + 1, PRAC_IC(4));
     kblock(PRAC_IC(32 * 6), fb, fa, PRAC_IC(5), cur); pload(kt + 1, PRAC_IC(5));
     kblock(PRAC_IC(32 * 7), fa, fb, PRAC_IC(6), cur); pload(kt + 1, PRAC_IC(6));
-    if (a.dbg && blockIdx.x == 8 && tid == 0) a.dbg[0 + kt] = __builtin_readcyclecounter();
-    if (!(VAR & 32)) __builtin_amdgcn_s_barrier();
-    if (a.dbg && blockIdx.x == 8 && tid == 0) a.dbg[32 + kt] = __builtin_readcyclecounter();
+    __builtin_amdgcn_s_barrier();
     kblock(PRAC_IC(0), fb, fa, PRAC_IC(7), nxt); pload(kt + 1, PRAC_IC(7));
   }
 #undef PRAC_IC
   drain_mfma<NACC>(acc);
-  if (VAR & 8) return;
 
   // epilogue: block (i, j) = acc[i * FN + j]; register v of lane (li, lh) is token row
   // 8*(v/4) + 4*lh + v%4 of row block i, column li of column block cb0 + j.
@@ -371,8 +325,6 @@ struct CtdyWsArgs {
   int tok_per_split;   // multiple of 128
   int tiles_n;         // column tiles of 128 over m
   int row_groups;      // groups of 8 column blocks (256 rows of T) over c
-  int rotate;
-  int depth;           // dY tiles each loader thread keeps in flight in registers (1 or 3)
 };
 
 constexpr int CW_BK = 128, CW_BN = 128;
@@ -439,12 +391,8 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
   const int tok_beg = split * a.tok_per_split;
   const int tok_end = min(a.N, tok_beg + a.tok_per_split);
   const int nk = tok_end > tok_beg ? (tok_end - tok_beg + CW_BK - 1) / CW_BK : 0;
-  // workgroups of one split read the same blocks of packed C: start each at a different tile
-  const int rot = (a.rotate && nk > 0) ? tn % nk : 0;
-  auto act = [&](int kt) {
-    const int t = min(kt, nk - 1) + rot;
-    return t >= nk ? t - nk : t;
-  };
+  // All workgroups of a split walk its tiles in the same order: they then ask for the same blocks
+  // of packed C at about the same time, which keeps those blocks in L2 between uses.
 
   if (wave >= 4) {
     // ------------------------------------------------------------ loader waves
@@ -458,21 +406,19 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
     const uint32_t sA = (uint32_t)(kb * 4096 + frag_slot(2 * cc, h) * 16);
     const uint32_t sB = (uint32_t)(kb * 4096 + frag_slot(2 * cc + 1, h) * 16);
 
-    u32x4 ry[3][8] = {};
+    u32x4 ry[8];
     // rows past N re-read the last row (finite data) and meet the zero padding of packed C
-    auto gload = [&](int kt, auto setc) {
-      constexpr int S = decltype(setc)::value;
+    auto gload = [&](int kt) {
       const bool live = kt < nk;
-      const int t0 = tok_beg + act(kt) * CW_BK;
+      const int t0 = tok_beg + min(kt, nk - 1) * CW_BK;
       const char* base = ycol + (int64_t)t0 * a.lddy * 2;  // uniform part + this thread's column
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int row = min(16 * kb + c_slot_tok(h, e), a.N - 1 - t0);
-        ry[S][e] = *reinterpret_cast<const u32x4*>(base + (live ? (uint32_t)row * rowb : 0u));
+        ry[e] = *reinterpret_cast<const u32x4*>(base + (live ? (uint32_t)row * rowb : 0u));
       }
     };
-    auto sstore = [&](int stage, auto setc) {
-      constexpr int S = decltype(setc)::value;
+    auto sstore = [&](int stage) {
       unsigned char* s = smem_raw + stage * CW_STAGE;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
@@ -481,52 +427,26 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
         uint32_t w[4];
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) {
-          const uint32_t lo = ry[S][2 * e2][j >> 1], hi = ry[S][2 * e2 + 1][j >> 1];
+          const uint32_t lo = ry[2 * e2][j >> 1], hi = ry[2 * e2 + 1][j >> 1];
           w[e2] = __builtin_amdgcn_perm(hi, lo, (j & 1) ? 0x07060302u : 0x05040100u);
         }
         o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
         *reinterpret_cast<u32x4*>(s + ((j & 3) * 1024 + (j < 4 ? sA : sB))) = o;
       }
     };
-    std::integral_constant<int, 0> S0;
-    std::integral_constant<int, 1> S1;
-    std::integral_constant<int, 2> S2;
-    int stage = 2;
-    if (a.depth == 1) {
-      gload(0, S0);
-      sstore(0, S0);
-      gload(1, S0);
-      if (nk > 1) sstore(1, S0);
-      gload(2, S0);
-      __syncthreads();
-      for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 2 < nk) sstore(stage, S0);
-        stage = stage == CW_STAGES - 1 ? 0 : stage + 1;
-        gload(kt + 3, S0);
-        __syncthreads();
-      }
-      return;
-    }
-    gload(0, S0);
-    gload(1, S1);
-    gload(2, S2);
-    sstore(0, S0);
-    gload(3, S0);
-    if (nk > 1) sstore(1, S1);
-    gload(4, S1);
+    // one tile in flight per loader thread, two more complete in LDS (see the compress kernel)
+    gload(0);
+    sstore(0);
+    gload(1);
+    if (nk > 1) sstore(1);
+    gload(2);
     __syncthreads();  // tiles 0 and 1 are in LDS
-    auto step = [&](int kt, auto setc) {
-      if (kt < nk) {
-        if (kt + 2 < nk) sstore(stage, setc);
-        stage = stage == CW_STAGES - 1 ? 0 : stage + 1;
-        gload(kt + 5, setc);
-        __syncthreads();
-      }
-    };
-    for (int kt = 0; kt < nk; kt += 3) {
-      step(kt, S2);
-      step(kt + 1, S0);
-      step(kt + 2, S1);
+    int stage = 2;
+    for (int kt = 0; kt < nk; ++kt) {
+      if (kt + 2 < nk) sstore(stage);
+      stage = stage == CW_STAGES - 1 ? 0 : stage + 1;
+      gload(kt + 3);
+      __syncthreads();
     }
     return;
   }
@@ -548,10 +468,10 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
     const uint32_t aoff1 = (uint32_t)((cb0 + 1 < a.ccb ? cb0 + 1 : 0) * 64 + lane) * 16u;
     const int64_t tbrow = (int64_t)a.ccb * 1024;  // bytes per 16-token block of packed C
 
-    u32x4 rc[8][2] = {};
+    u32x4 rc[8][2];
     auto aload = [&](int kt, auto kkc) {
       constexpr int KK = decltype(kkc)::value;
-      const int tb = kt < nk ? tok_beg / 16 + act(kt) * 8 + KK : tok_beg / 16;
+      const int tb = kt < nk ? tok_beg / 16 + kt * 8 + KK : tok_beg / 16;
       const char* base = cbase + (int64_t)min(tb, ntb - 1) * tbrow;  // uniform
       rc[KK][0] = *reinterpret_cast<const u32x4*>(base + aoff0);
       rc[KK][1] = *reinterpret_cast<const u32x4*>(base + aoff1);
@@ -562,7 +482,7 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
 
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw +
                           (unsigned)(frag_slot(li, lh) * 16);
-    u32x4 fa[4] = {}, fb[4] = {};
+    u32x4 fa[4], fb[4];
     __builtin_amdgcn_s_barrier();  // tiles 0 and 1 are in LDS
     frag_read4_ct(fa, lds0);
     int stage = 0;
@@ -627,8 +547,6 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
   a.X = X; a.ldx = ldx; a.N = N; a.d = d; a.Pfrag = Pfrag; a.ncb = ncb; a.c = c;
   a.C = C; a.ldc = ldc; a.ccb = (c + 31) / 32; a.packed = packed ? 1 : 0;
   a.tiles_m = (N + WS_BM - 1) / WS_BM;
-  a.dbg = ctx->dbg;
-  a.depth = (ctx->tune_variant & 1024) ? 3 : 1;
   const int FN = (c <= 128) ? 1 : 2;
   a.col_groups = (a.ccb + 4 * FN - 1) / (4 * FN);
   if (a.col_groups * 4 * FN > ncb) return PRAC_EINVAL;  // packed basis narrower than the launch assumes
@@ -636,20 +554,6 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
   const int total = a.tiles_m * a.col_groups;
   const dim3 grid(((total + 7) / 8) * 8), block(512);
   static bool s1 = false, s2 = false;
-  static bool sv[64] = {false};
-  const int var = (ctx->tune_variant >> 1) & 63;
-  a.rotate = (ctx->tune_variant & 256) ? 0 : 1;
-#define PRAC_VARIANT_CASE(V)                                                            \
-  if (var == V) {                                                                       \
-    int rc = set_smem(ctx, compress_ws_kernel<2, V>, smem, sv[V]);                      \
-    if (rc) return rc;                                                                  \
-    PRAC_LAUNCH(ctx, (compress_ws_kernel<2, V>), grid, block, smem, a);                 \
-    PRAC_HIP_TRY(ctx, hipGetLastError());                                               \
-    return PRAC_OK;                                                                     \
-  }
-  PRAC_VARIANT_CASE(1) PRAC_VARIANT_CASE(2) PRAC_VARIANT_CASE(3) PRAC_VARIANT_CASE(4) PRAC_VARIANT_CASE(5)
-  PRAC_VARIANT_CASE(6) PRAC_VARIANT_CASE(7) PRAC_VARIANT_CASE(14) PRAC_VARIANT_CASE(15) PRAC_VARIANT_CASE(22)
-  PRAC_VARIANT_CASE(30) PRAC_VARIANT_CASE(62) PRAC_VARIANT_CASE(63) PRAC_VARIANT_CASE(38) PRAC_VARIANT_CASE(39)
   if (FN == 1) {
     int rc = set_smem(ctx, compress_ws_kernel<1>, smem, s1);
     if (rc) return rc;
@@ -672,10 +576,6 @@ int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, in
   a.tok_per_split = ((ktiles + splits - 1) / splits) * CW_BK;
   a.tiles_n = (m + CW_BN - 1) / CW_BN;
   a.row_groups = (a.ccb + 7) / 8;
-  // no rotation by default: workgroups of a split then read the same blocks of packed C at about
-  // the same time, which keeps them in L2 (rotating the start tile cost 4 % at the headline shape)
-  a.rotate = (ctx->tune_variant & 256) ? 1 : 0;
-  a.depth = (ctx->tune_variant & 1024) ? 3 : 1;
   const size_t smem = (size_t)CW_STAGES * CW_STAGE;
   const int total = a.tiles_n * a.row_groups * splits;
   static bool s = false;
