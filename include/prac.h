@@ -121,7 +121,8 @@ size_t prac_basis_lp_bytes(int64_t d, int c);
 /* Build the packed bf16 copy P_lp of P (d x c fp32, ldp >= c) that the bf16
  * kernels read: P^T as c x round_up(d,64) bf16, P as d x round_up(c,64) bf16,
  * and P in MFMA fragment order both as a B operand (compress) and as an A
- * operand (dW = P T); all zero padded, each part 256-byte aligned. */
+ * operand (dW = P T); all zero padded (the B-operand fragments to a multiple
+ * of 256 rows), each part 256-byte aligned. */
 int prac_pack_basis(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c,
                     void* P_lp);
 /* Writes P = [Q1 | Q2] (d x (k+r) fp32, UNSCALED, ldp >= k+r), optionally its

@@ -22,6 +22,20 @@ static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
+// Two fp32 -> packed bf16 with the hardware conversion of gfx950 (v_cvt_pk_bf16_f32: round to
+// nearest even, NaN stays NaN); `lo` lands in the low half.
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+static __device__ __forceinline__ uint32_t pack2_hw(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  union {
+    bf16x2_t b;
+    uint32_t u;
+  } c;
+  c.b = __builtin_convertvector(v, bf16x2_t);
+  return c.u;
+}
+
 // Keep the first n (0..8) bf16 of a 16-byte chunk, zero the rest.
 static __device__ __forceinline__ u32x4 keep_first(u32x4 v, int n) {
   v.x &= (n > 0 ? 0x0000FFFFu : 0u) | (n > 1 ? 0xFFFF0000u : 0u);

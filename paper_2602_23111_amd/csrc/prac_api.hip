@@ -12,7 +12,7 @@ inline bool valid_dtype(int t) { return t == PRAC_F32 || t == PRAC_BF16; }
 
 struct LpLayout {
   int64_t ldpt, ldpn;
-  int nkb, ncb;  // fragment-order copy: 16-row blocks over round_up(d,128), 32-column blocks (multiple of 8)
+  int nkb, ncb;  // fragment-order copy: 16-row blocks over round_up(d,256), 32-column blocks (multiple of 8)
   int nrb, nckb; // A-operand fragment copy: 32-row blocks over round_up(d,128), 16-column blocks over c
   size_t off_pn, off_pf, off_pa, bytes;
 };
@@ -20,7 +20,7 @@ inline LpLayout lp_layout(int64_t d, int c) {
   LpLayout l;
   l.ldpt = round_up64(d, 64);
   l.ldpn = round_up64(c, 64);
-  l.nkb = (int)(round_up64(d, 128) / 16);
+  l.nkb = (int)(round_up64(d, 256) / 16);
   l.ncb = (int)round_up64((c + 31) / 32, 8);
   l.off_pn = ((size_t)c * l.ldpt * sizeof(bf16_t) + 255) & ~size_t(255);
   l.off_pf = (l.off_pn + (size_t)d * l.ldpn * sizeof(bf16_t) + 255) & ~size_t(255);

@@ -3,8 +3,8 @@
 //   compress   C = X P   (Alg. 1 compression step)            compress_ws_kernel
 //
 // A workgroup is 8 waves: 4 matrix waves and 4 loader waves, one of each per SIMD.
-//   loader waves   stream the big operand (X) HBM -> registers -> LDS, several tiles ahead,
-//                  in ordinary compiler-scheduled code;
+//   loader waves   stream the big operand (X) HBM -> registers -> LDS in ordinary
+//                  compiler-scheduled code;
 //   matrix waves   read A fragments from LDS, fetch their private B fragments (P in MFMA
 //                  fragment order, L2-resident) straight into registers and issue MFMAs.
 // The matrix waves' inner step (one 16-deep k-block: 4 LDS fragment reads for the next
@@ -13,22 +13,34 @@
 // LDS reads and MFMAs is set by hand rather than left to the scheduler.  The LDS reads are
 // invisible to the compiler; every such block therefore ends with its own wait for them.
 //
-// LDS holds three X tiles (128 rows x 128 k, rows padded to 272 bytes): tile kt is being
-// multiplied while tile kt+1 is complete and tile kt+2 is being written.  One barrier per
-// tile, placed in the matrix waves between k-blocks 6 and 7: everything before it has
-// finished reading tile kt-1's stage (which the loaders overwrite next with tile kt+2),
-// and k-block 7 already prefetches from tile kt+1, complete since the previous barrier.
+// A k-tile is 128 rows x 256 k: every row contributes a 512-byte run.  HBM delivers runs of
+// 512 bytes about a quarter faster than runs of 256 (measured with a plain reader over the
+// same panel shape), which is why the tile is deep rather than the ring long.  LDS holds
+// two tiles (rows padded to 528 bytes): tile kt is multiplied while tile kt+1 is written
+// and tile kt+2 is in flight to the loaders' registers.  One barrier per tile, placed in
+// the matrix waves between k-blocks 14 and 15: everything before it has finished reading
+// tile kt's stage (which the loaders overwrite next with tile kt+2), and k-block 15 already
+// prefetches from tile kt+1, complete since the loaders reached the same barrier.
 #include <type_traits>
 
 #include "frag_utils.h"
 
 namespace {
 
+// f(integral_constant<int, 0>{}), ..., f(integral_constant<int, N - 1>{})
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (N > 0) {
+    static_for<N - 1>(f);
+    f(std::integral_constant<int, N - 1>{});
+  }
+}
+
 struct CompressWsArgs {
   const bf16_t* X;
   int64_t ldx;
   int N, d;
-  const bf16_t* Pfrag;  // [nkb][ncb][64][8], nkb = round_up(d,128)/16, zero outside d x c
+  const bf16_t* Pfrag;  // [nkb][ncb][64][8], nkb = round_up(d,256)/16, zero outside d x c
   int ncb;              // 32-column blocks in the padded basis
   int c;
   bf16_t* C;            // row-major (ldc) or packed [ceil(N/128)*8][ccb][64][8]
@@ -39,10 +51,12 @@ struct CompressWsArgs {
   int col_groups;       // column groups of 4*FN blocks
 };
 
-constexpr int WS_BM = 128, WS_BK = 128, WS_LD = WS_BK + 8;
-constexpr int WS_STAGE = WS_BM * WS_LD * 2;  // bytes per LDS stage (34816)
-constexpr int WS_STAGES = 3;
-constexpr int WS_RB = 32 * WS_LD * 2;        // bytes between 32-row blocks of a stage (8704)
+constexpr int WS_BM = 128, WS_BK = 256, WS_LD = WS_BK + 8;
+constexpr int WS_STAGE = WS_BM * WS_LD * 2;  // bytes per LDS stage (67584)
+constexpr int WS_STAGES = 2;
+constexpr int WS_RB = 32 * WS_LD * 2;        // bytes between 32-row blocks of a stage (16896)
+constexpr int WS_KB = WS_BK / 16;            // k-blocks per tile
+constexpr int WS_NCH = 4, WS_NIF = 2;        // chunks per tile, chunks in flight
 
 // One k-block of a 128 x 64 wave tile: acc[2 i + j] += fa[i] * b_j, while the four A fragments
 // at byte offsets O + i * WS_RB from `lds` are read into fn.
@@ -117,7 +131,7 @@ __device__ __forceinline__ void drain_mfma(f32x16 (&acc)[NACC]) {
   }
 }
 
-template <int FN>
+template <int FN, int NCH, int NIF>
 __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
 
@@ -134,7 +148,8 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
   const int m0 = tm * WS_BM;
   const int nk = (a.d + WS_BK - 1) / WS_BK;
   // Step kt of this workgroup works on k-tile act(kt): the sum over k may run in any order, and
-  // workgroups that start at different tiles do not all ask L2 for the same lines of P at once.
+  // workgroups that start at different tiles neither ask L2 for the same lines of P at once nor
+  // all pull on the same memory channels (their row panels have the same alignment).
   const int rot = tm % nk;
   auto act = [&](int kt) {
     const int t = min(kt, nk - 1) + rot;
@@ -144,53 +159,66 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
   if (wave >= 4) {
     // ------------------------------------------------------------ loader waves
     const int lt = tid - 256;
-    const int crow = lt >> 4, ccol = (lt & 15) * 8;  // chunk p: row crow + 16 p, columns ccol .. ccol + 7
+    const int crow = lt >> 5, ccol = (lt & 31) * 8;  // chunk q: row crow + 8 q, columns ccol .. ccol + 7
     const int last_chunk = ((a.d - 1) / 8) * 8;      // start of the last (possibly partial) chunk of a row
     const char* xbase = reinterpret_cast<const char*>(a.X + (int64_t)m0 * a.ldx);
-    uint32_t roff[8];  // byte offset of the row of chunk p (rows past N re-read the last row; never stored to C)
+    uint32_t roff[16];  // byte offset of the row of chunk q (rows past N re-read the last row; never stored to C)
 #pragma unroll
-    for (int p = 0; p < 8; ++p) roff[p] = (uint32_t)(min(m0 + crow + 16 * p, a.N - 1) - m0) * (uint32_t)a.ldx * 2u;
+    for (int q = 0; q < 16; ++q) roff[q] = (uint32_t)(min(m0 + crow + 8 * q, a.N - 1) - m0) * (uint32_t)a.ldx * 2u;
     const uint32_t soff = (uint32_t)(crow * WS_LD + ccol) * 2u;
 
-    u32x4 ra[8];
+    // The tile is fetched in NCH chunks of 128 / NCH rows, one chunk per barrier interval, with
+    // NIF chunks in flight: the vector L1 returns data in request order, so the matrix waves'
+    // P loads wait behind every X request issued before them.  Requests for X issued in one burst
+    // per tile stall the matrix waves for the length of that burst; spread evenly they delay each
+    // P load by about one memory latency, which the P ring covers.
+    constexpr int CR = 16 / NCH;  // 16-byte loads per thread and chunk
+    u32x4 ra[16];                 // chunk g lives in ra[(g % NCH) * CR ...]
     // Requests past the last tile stay in the instruction stream (the loop has no load-free tail
     // version) but all go to this thread's first chunk, which the L1 cache already holds.
-    auto gload = [&](int kt) {
+    auto cload = [&](int g, auto qc) {
+      constexpr int Q = decltype(qc)::value;  // g % NCH
+      const int kt = g / NCH;
       const uint32_t kb = (uint32_t)min(act(kt) * WS_BK + ccol, last_chunk) * 2u;
       const bool live = kt < nk;
 #pragma unroll
-      for (int p = 0; p < 8; ++p)
-        ra[p] = *reinterpret_cast<const u32x4*>(xbase + (live ? roff[p] + kb : roff[0] + (uint32_t)ccol * 2u));
+      for (int j = 0; j < CR; ++j)
+        ra[Q * CR + j] =
+            *reinterpret_cast<const u32x4*>(xbase + (live ? roff[Q * CR + j] + kb : roff[0] + (uint32_t)ccol * 2u));
     };
-    // tile kt -> stage `stage` (= kt % 3); columns past d are zeroed (only the last tile has any)
-    auto sstore = [&](int kt, int stage) {
-      unsigned char* s = smem_raw + stage * WS_STAGE + soff;
+    // chunk g -> stage (g / NCH) % 2; columns past d are zeroed (only the last tile has any)
+    auto cstore = [&](int g, auto qc) {
+      constexpr int Q = decltype(qc)::value;
+      const int kt = g / NCH;
+      unsigned char* s = smem_raw + (kt & 1) * WS_STAGE + soff;
       const int nv = a.d - (act(kt) * WS_BK + ccol);
       if (nv >= 8) {
 #pragma unroll
-        for (int p = 0; p < 8; ++p) *reinterpret_cast<u32x4*>(s + p * (16 * WS_LD * 2)) = ra[p];
+        for (int j = 0; j < CR; ++j) *reinterpret_cast<u32x4*>(s + (Q * CR + j) * (8 * WS_LD * 2)) = ra[Q * CR + j];
       } else {
 #pragma unroll
-        for (int p = 0; p < 8; ++p) *reinterpret_cast<u32x4*>(s + p * (16 * WS_LD * 2)) = keep_first(ra[p], nv);
+        for (int j = 0; j < CR; ++j)
+          *reinterpret_cast<u32x4*>(s + (Q * CR + j) * (8 * WS_LD * 2)) = keep_first(ra[Q * CR + j], nv);
       }
     };
-    // One tile in flight per loader thread, two more complete in LDS.  Deeper register prefetch
-    // was slower: the requests of a CU share one L1 miss queue, and X lines queued there delay
-    // the matrix waves' P lines more than the extra depth gains.
-    gload(0);
-    sstore(0, 0);
-    gload(1);
-    if (nk > 1) sstore(1, 1);
-    gload(2);
-    __syncthreads();  // tiles 0 and 1 are in LDS
-    int stage = 2;
+#define PRAC_IC(v) std::integral_constant<int, (v)> {}
+    // tile 0 at once, then the first NIF chunks of tile 1
+    static_for<NCH>([&](auto q) { cload(decltype(q)::value, q); });
+    static_for<NCH>([&](auto q) { cstore(decltype(q)::value, q); });
+    static_for<NIF>([&](auto q) { cload(NCH + decltype(q)::value, q); });
+    __syncthreads();  // tile 0 is in LDS
     for (int kt = 0; kt < nk; ++kt) {
-      // tile kt+2 -> LDS: its stage was last read for tile kt-1, before the previous barrier
-      if (kt + 2 < nk) sstore(kt + 2, stage);
-      stage = stage == WS_STAGES - 1 ? 0 : stage + 1;
-      gload(kt + 3);
-      __syncthreads();
+      // interval q of tile kt: chunk q of tile kt+1 -> LDS (its stage was last read for tile kt-1, before
+      // the previous tile's last barrier), then chunk q + NIF of tile kt+1 is requested
+      static_for<NCH>([&](auto q) {
+        constexpr int Q = decltype(q)::value;
+        const int g = (kt + 1) * NCH + Q;
+        if (kt + 1 < nk) cstore(g, q);
+        cload(g + NIF, PRAC_IC((Q + NIF) % NCH));
+        __syncthreads();
+      });
     }
+#undef PRAC_IC
     return;
   }
 
@@ -208,19 +236,20 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
-  // ring of the eight k-blocks' P fragments: slot kk is refilled for the next tile right after its use
+  // ring of eight k-blocks' P fragments: slot kk % 8 is refilled, right after its use, with the
+  // k-block eight steps ahead
   u32x4 rb[8][FN];
   auto pload = [&](int kt, auto kkc) {
-    constexpr int KK = decltype(kkc)::value;
+    constexpr int KK = decltype(kkc)::value;  // k-block within the tile, 0 .. 15
     // past the last tile: one fixed block (an L1 hit), never used
-    const char* base = pbase + (kt < nk ? (int64_t)(act(kt) * 8 + KK) * brow : (int64_t)0);  // uniform
+    const char* base = pbase + (kt < nk ? (int64_t)(act(kt) * WS_KB + KK) * brow : (int64_t)0);  // uniform
 #pragma unroll
-    for (int j = 0; j < FN; ++j) rb[KK][j] = *reinterpret_cast<const u32x4*>(base + (j * 1024 + boff));
+    for (int j = 0; j < FN; ++j) rb[KK & 7][j] = *reinterpret_cast<const u32x4*>(base + (j * 1024 + boff));
   };
   auto kblock = [&](auto oc, const u32x4 (&fcur)[4], u32x4 (&fnext)[4], auto kkc, unsigned lds) {
     constexpr int O = decltype(oc)::value, KK = decltype(kkc)::value;
-    if constexpr (FN == 2) kblock2<O>(acc, fcur, fnext, rb[KK][0], rb[KK][1], lds);
-    else kblock1<O>(acc, fcur, fnext, rb[KK][0], lds);
+    if constexpr (FN == 2) kblock2<O>(acc, fcur, fnext, rb[KK & 7][0], rb[KK & 7][1], lds);
+    else kblock1<O>(acc, fcur, fnext, rb[KK & 7][0], lds);
   };
 #define PRAC_IC(v) std::integral_constant<int, (v)> {}
   pload(0, PRAC_IC(0)); pload(0, PRAC_IC(1)); pload(0, PRAC_IC(2)); pload(0, PRAC_IC(3));
@@ -231,22 +260,24 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
   const unsigned lds0 =
       (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw + (unsigned)(li * WS_LD * 2 + lh * 16);
   u32x4 fa[4], fb[4];
-  __builtin_amdgcn_s_barrier();  // tiles 0 and 1 are in LDS
+  __builtin_amdgcn_s_barrier();  // tile 0 is in LDS
   frag_read4(fa, lds0);
-  int stage = 0;
   for (int kt = 0; kt < nk; ++kt) {
-    const unsigned cur = lds0 + (unsigned)stage * WS_STAGE;
-    stage = stage == WS_STAGES - 1 ? 0 : stage + 1;
-    const unsigned nxt = lds0 + (unsigned)stage * WS_STAGE;
-    kblock(PRAC_IC(32 * 1), fa, fb, PRAC_IC(0), cur); pload(kt + 1, PRAC_IC(0));
-    kblock(PRAC_IC(32 * 2), fb, fa, PRAC_IC(1), cur); pload(kt + 1, PRAC_IC(1));
-    kblock(PRAC_IC(32 * 3), fa, fb, PRAC_IC(2), cur); pload(kt + 1, PRAC_IC(2));
-    kblock(PRAC_IC(32 * 4), fb, fa, PRAC_IC(3), cur); pload(kt + 1, PRAC_IC(3));
-    kblock(PRAC_IC(32 * 5), fa, fb, PRAC_IC(4), cur); pload(kt + 1, PRAC_IC(4));
-    kblock(PRAC_IC(32 * 6), fb, fa, PRAC_IC(5), cur); pload(kt + 1, PRAC_IC(5));
-    kblock(PRAC_IC(32 * 7), fa, fb, PRAC_IC(6), cur); pload(kt + 1, PRAC_IC(6));
-    __builtin_amdgcn_s_barrier();
-    kblock(PRAC_IC(0), fb, fa, PRAC_IC(7), nxt); pload(kt + 1, PRAC_IC(7));
+    const unsigned cur = lds0 + (unsigned)(kt & 1) * WS_STAGE;
+    const unsigned nxt = lds0 + (unsigned)((kt + 1) & 1) * WS_STAGE;
+    // k-block j multiplies while the fragments of k-block j+1 are read; its P slot is then refilled.
+    // Barriers: one per chunk interval of the loaders; the last one of a tile sits before k-block 15,
+    // whose fragment reads are the first from the next stage.
+    static_for<WS_KB>([&](auto jc) {
+      constexpr int J = decltype(jc)::value;
+      constexpr int IV = WS_KB / NCH;  // k-blocks per barrier interval
+      if constexpr (J == WS_KB - 1) __builtin_amdgcn_s_barrier();
+      if constexpr (J % 2 == 0) kblock(PRAC_IC(32 * ((J + 1) % WS_KB)), fa, fb, jc, J == WS_KB - 1 ? nxt : cur);
+      else kblock(PRAC_IC(32 * ((J + 1) % WS_KB)), fb, fa, jc, J == WS_KB - 1 ? nxt : cur);
+      if constexpr (J < 8) pload(kt, PRAC_IC(J + 8));
+      else pload(kt + 1, PRAC_IC(J - 8));
+      if constexpr (J % IV == IV - 1 && J != WS_KB - 1) __builtin_amdgcn_s_barrier();
+    });
   }
 #undef PRAC_IC
   drain_mfma<NACC>(acc);
@@ -276,10 +307,10 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
               x[e] = tok < a.N ? acc[i * FN + j][8 * tb + e] : 0.f;
             }
             u32x4 o;
-            o.x = pack2(x[0], x[1]);
-            o.y = pack2(x[2], x[3]);
-            o.z = pack2(x[4], x[5]);
-            o.w = pack2(x[6], x[7]);
+            o.x = pack2_hw(x[0], x[1]);
+            o.y = pack2_hw(x[2], x[3]);
+            o.z = pack2_hw(x[4], x[5]);
+            o.w = pack2_hw(x[6], x[7]);
             Cp[((int64_t)gtb * a.ccb + cb) * 64 + lane] = o;
           }
         }
@@ -554,14 +585,16 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
   const int total = a.tiles_m * a.col_groups;
   const dim3 grid(((total + 7) / 8) * 8), block(512);
   static bool s1 = false, s2 = false;
+  constexpr auto kern1 = compress_ws_kernel<1, WS_NCH, WS_NIF>;
+  constexpr auto kern2 = compress_ws_kernel<2, WS_NCH, WS_NIF>;
   if (FN == 1) {
-    int rc = set_smem(ctx, compress_ws_kernel<1>, smem, s1);
+    int rc = set_smem(ctx, kern1, smem, s1);
     if (rc) return rc;
-    PRAC_LAUNCH(ctx, compress_ws_kernel<1>, grid, block, smem, a);
+    PRAC_LAUNCH(ctx, kern1, grid, block, smem, a);
   } else {
-    int rc = set_smem(ctx, compress_ws_kernel<2>, smem, s2);
+    int rc = set_smem(ctx, kern2, smem, s2);
     if (rc) return rc;
-    PRAC_LAUNCH(ctx, compress_ws_kernel<2>, grid, block, smem, a);
+    PRAC_LAUNCH(ctx, kern2, grid, block, smem, a);
   }
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;

@@ -35,7 +35,7 @@ def test_strerror_and_lp_bytes(lib):
     d, c = 100, 24
     first = (c * 128 * 2 + 255) // 256 * 256
     second = (first + d * 64 * 2 + 255) // 256 * 256
-    third = (second + (128 // 16) * 8 * 64 * 8 * 2 + 255) // 256 * 256   # P fragments, d padded to 128
+    third = (second + (256 // 16) * 8 * 64 * 8 * 2 + 255) // 256 * 256   # P fragments, d padded to 256
     assert lib.prac_basis_lp_bytes(d, c) == third + (128 // 32) * 2 * 64 * 8 * 2
     assert lib.prac_basis_lp_bytes(0, 4) == 0
 
