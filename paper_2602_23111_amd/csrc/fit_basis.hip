@@ -423,20 +423,26 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, P, ldp, Y, (int64_t)b, d, k);
       PRAC_HIP_TRY(ctx, hipGetLastError());
     }
-    rc = cholqr(ctx, L, Y, V, d, b, 1, 1e-11);
-    if (rc) return rc;
+    // The start block goes into the first product as it is: a Gaussian block and the previous
+    // (orthonormal) Q1 are both well conditioned, and every product is orthonormalised anyway.
     for (int it = 0; it <= o.iters; ++it) {
-      // Y = G V
+      // Y = G V  (first round: V is the start block, still in Y's buffer, so the roles swap)
       GemmGenArgs g{};
-      g.A = G; g.B = V; g.adt = PRAC_F32; g.bdt = PRAC_F32;
+      g.A = G; g.B = it == 0 ? Y : V; g.adt = PRAC_F32; g.bdt = PRAC_F32;
       g.a_rs = d; g.a_cs = 1; g.b_rs = b; g.b_cs = 1;
       g.M = (int)d; g.N = b; g.K = d; g.k_stride = 1;
-      g.out = Y; g.ldo = b; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
+      g.out = it == 0 ? V : Y; g.ldo = b; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
       rc = launch_gemm_generic(ctx, g);
       if (rc) return rc;
+      if (it == 0) {
+        // product landed in V: move it to Y so that orth() below reads Y and writes V as always
+        hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, V, (int64_t)b, Y, (int64_t)b, d, b);
+        PRAC_HIP_TRY(ctx, hipGetLastError());
+      }
       if (it == o.iters) break;  // the last product feeds Rayleigh-Ritz
       // one shifted pass keeps the block well conditioned; the last iteration orthonormalises fully
-      rc = cholqr(ctx, L, Y, V, d, b, it == o.iters - 1 ? 3 : 1, 1e-11);
+      // (two passes: the second starts from a block whose condition number is already near one)
+      rc = cholqr(ctx, L, Y, V, d, b, it == o.iters - 1 ? 2 : 1, 1e-11);
       if (rc) return rc;
     }
     // Rayleigh-Ritz: H = V^T (G V), eigenvectors of H, Q1 = V Z[:, :k]
@@ -461,6 +467,9 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       if (nbk < 1) nbk = 1;
       const int nblk = (b + nbk - 1) / nbk, nblk_even = nblk + (nblk & 1);
       constexpr int MAX_SWEEPS = 12;
+      // columns count as orthogonal below this cosine: the Ritz vectors are re-orthonormalised in
+      // fp32 afterwards, so anything far below fp32 rounding is spent effort
+      constexpr double JACOBI_TOL = 1e-10;
       unsigned* counts = reinterpret_cast<unsigned*>(ctx->ws + L.X64);
       static bool smem_set = false;
       if (!smem_set) {
@@ -473,14 +482,14 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       const size_t smem = (size_t)2 * nbk * b * sizeof(double);
       if (nblk == 1) {
         // a single block: one workgroup orthogonalises everything in LDS
-        hipLaunchKernelGGL(jacobi_block_kernel, dim3(1), dim3(1024), smem, st, H, b, nbk, 2, 0, 0, 30, 1e-14, counts);
+        hipLaunchKernelGGL(jacobi_block_kernel, dim3(1), dim3(1024), smem, st, H, b, nbk, 2, 0, 0, 30, JACOBI_TOL, counts);
         hipLaunchKernelGGL(jacobi_finish_kernel, dim3(16), dim3(1024), 0, st, H, b, lam, counts, MAX_SWEEPS - 1,
                            ctx->d_flag);
       } else {
         for (int sweep = 0; sweep < MAX_SWEEPS; ++sweep)
           for (int step = 0; step < nblk_even - 1; ++step)
             hipLaunchKernelGGL(jacobi_block_kernel, dim3(nblk_even / 2), dim3(1024), smem, st, H, b, nbk, nblk_even,
-                               step, sweep, 2, 1e-14, counts);
+                               step, sweep, 2, JACOBI_TOL, counts);
         hipLaunchKernelGGL(jacobi_finish_kernel, dim3(16), dim3(1024), 0, st, H, b, lam, counts, MAX_SWEEPS - 1,
                            ctx->d_flag);
       }
@@ -527,7 +536,7 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
         if (rc) return rc;
       }
     }
-    rc = cholqr(ctx, L, S, V, d, r, 3, 1e-13);
+    rc = cholqr(ctx, L, S, V, d, r, 2, 1e-13);
     if (rc) return rc;
     hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, V, (int64_t)r, P + k, ldp, d, r);
     PRAC_HIP_TRY(ctx, hipGetLastError());

@@ -437,19 +437,19 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
     const uint32_t sA = (uint32_t)(kb * 4096 + frag_slot(2 * cc, h) * 16);
     const uint32_t sB = (uint32_t)(kb * 4096 + frag_slot(2 * cc + 1, h) * 16);
 
-    u32x4 ry[8];
+    u32x4 ry[8], rz[8];
     // rows past N re-read the last row (finite data) and meet the zero padding of packed C
-    auto gload = [&](int kt) {
+    auto gload = [&](int kt, u32x4 (&rr)[8]) {
       const bool live = kt < nk;
       const int t0 = tok_beg + min(kt, nk - 1) * CW_BK;
       const char* base = ycol + (int64_t)t0 * a.lddy * 2;  // uniform part + this thread's column
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int row = min(16 * kb + c_slot_tok(h, e), a.N - 1 - t0);
-        ry[e] = *reinterpret_cast<const u32x4*>(base + (live ? (uint32_t)row * rowb : 0u));
+        rr[e] = *reinterpret_cast<const u32x4*>(base + (live ? (uint32_t)row * rowb : 0u));
       }
     };
-    auto sstore = [&](int stage) {
+    auto sstore = [&](int stage, const u32x4 (&rr)[8]) {
       unsigned char* s = smem_raw + stage * CW_STAGE;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
@@ -458,25 +458,26 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
         uint32_t w[4];
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) {
-          const uint32_t lo = ry[2 * e2][j >> 1], hi = ry[2 * e2 + 1][j >> 1];
+          const uint32_t lo = rr[2 * e2][j >> 1], hi = rr[2 * e2 + 1][j >> 1];
           w[e2] = __builtin_amdgcn_perm(hi, lo, (j & 1) ? 0x07060302u : 0x05040100u);
         }
         o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
         *reinterpret_cast<u32x4*>(s + ((j & 3) * 1024 + (j < 4 ? sA : sB))) = o;
       }
     };
-    // one tile in flight per loader thread, two more complete in LDS (see the compress kernel)
-    gload(0);
-    sstore(0);
-    gload(1);
-    if (nk > 1) sstore(1);
-    gload(2);
+    // the first two tiles are requested together (one memory round trip before the first
+    // barrier); afterwards one tile is in flight per loader thread and two more are complete in LDS
+    gload(0, ry);
+    gload(1, rz);
+    sstore(0, ry);
+    gload(2, ry);
+    if (nk > 1) sstore(1, rz);
     __syncthreads();  // tiles 0 and 1 are in LDS
     int stage = 2;
     for (int kt = 0; kt < nk; ++kt) {
-      if (kt + 2 < nk) sstore(stage);
+      if (kt + 2 < nk) sstore(stage, ry);
       stage = stage == CW_STAGES - 1 ? 0 : stage + 1;
-      gload(kt + 3);
+      gload(kt + 3, ry);
       __syncthreads();
     }
     return;
