@@ -41,6 +41,39 @@ __global__ __launch_bounds__(256) void pack_pfrag_kernel(const float* __restrict
   }
 }
 
+// The same fragment order for a bf16 weight matrix (pure permutation, zero padded): element
+// (k, n) of W is W[k * ldw + n] (w_layout 0, d x m) or W[n * ldw + k] (w_layout 1, m x d).
+__global__ __launch_bounds__(256) void pack_wfrag_kernel(const bf16_t* __restrict__ W, int64_t ldw, int w_layout,
+                                                         int64_t d, int m, int nkb, int ncb,
+                                                         bf16_t* __restrict__ out) {
+  const int64_t total = (int64_t)nkb * ncb * 64;
+  for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += (int64_t)gridDim.x * blockDim.x) {
+    const int lane = (int)(g & 63), j = lane & 31, h = lane >> 5;
+    const int64_t blk = g >> 6;
+    const int cb = (int)(blk % ncb);
+    const int64_t kb = blk / ncb;
+    const int col = cb * 32 + j;
+    const int64_t k0 = kb * 16 + 8 * h;
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    if (col < m) {
+      if (w_layout == 1 && k0 + 8 <= d && (ldw & 7) == 0 && (reinterpret_cast<uintptr_t>(W) & 15) == 0) {
+        const uint4 v = *reinterpret_cast<const uint4*>(W + (int64_t)col * ldw + k0);
+        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int64_t kk = k0 + e;
+          if (kk < d) {
+            const uint32_t x = w_layout == 1 ? W[(int64_t)col * ldw + kk] : W[kk * ldw + col];
+            w[e >> 1] |= x << (16 * (e & 1));
+          }
+        }
+      }
+    }
+    reinterpret_cast<uint4*>(out)[g] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
 __device__ __forceinline__ int c_slot(int h, int e) { return e < 4 ? 4 * h + e : 8 + 4 * h + (e - 4); }
 
 // packed C -> row-major (bit-exact copy of the elements)
@@ -351,6 +384,14 @@ int set_smem(prac_ctx* ctx, K kern, size_t bytes, bool& done) {
 int launch_pack_pfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nkb, int ncb, bf16_t* out) {
   hipLaunchKernelGGL(pack_pfrag_kernel, dim3(grid_for((int64_t)nkb * ncb * 64, ctx->n_cu)), dim3(256), 0, ctx->stream,
                      P, d, ldp, c, nkb, ncb, out);
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  return PRAC_OK;
+}
+
+int launch_pack_wfrag(prac_ctx* ctx, const bf16_t* W, int64_t ldw, int w_layout, int64_t d, int m, int nkb,
+                      int ncb_w, bf16_t* out) {
+  hipLaunchKernelGGL(pack_wfrag_kernel, dim3(grid_for((int64_t)nkb * ncb_w * 64, ctx->n_cu)), dim3(256), 0,
+                     ctx->stream, W, ldw, w_layout, d, m, nkb, ncb_w, out);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }

@@ -366,14 +366,14 @@ static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N
                          int64_t ldp, int c, void* Y, int64_t ldy, void* C, int64_t ldc, int c_layout) {
   const bool fused = W != nullptr;
   const bool packed = c_layout == PRAC_C_PACKED;
-  const bool fast = xdt == PRAC_BF16 && aligned16(X) && ldx % 8 == 0 && N < ((int64_t)1 << 31) &&
-                    (!fused || (aligned16(W) && ldw % 8 == 0));
+  const bool fast = xdt == PRAC_BF16 && aligned16(X) && ldx % 8 == 0 && N < ((int64_t)1 << 31);
   if (packed && (xdt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
   if (fast) {
     const LpLayout l = lp_layout(d, c);
     WsPlan plan;
     const size_t o_lp = plan.take(P_lp ? 0 : l.bytes);
-    const size_t o_c = plan.take(fused && packed ? (size_t)N * round_up64(c, 8) * sizeof(bf16_t) : 0);
+    const int ncb_w = fused ? (int)round_up64((m + 31) / 32, 8) : 0;  // whole 256-column groups
+    const size_t o_w = plan.take(fused ? (size_t)l.nkb * ncb_w * 64 * 8 * sizeof(bf16_t) : 0);
     int rc = prac_ws_reserve(ctx, plan.off);
     if (rc) return rc;
     const char* lp = reinterpret_cast<const char*>(P_lp);
@@ -382,36 +382,21 @@ static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N
       if (rc) return rc;
       lp = ctx->ws + o_lp;
     }
-    const bf16_t* Pt = reinterpret_cast<const bf16_t*>(lp);
-    const bf16_t* Pn = reinterpret_cast<const bf16_t*>(lp + l.off_pn);
     const bf16_t* Pf = reinterpret_cast<const bf16_t*>(lp + l.off_pf);
     if (!fused) {
       ProfScope ps(ctx, PRAC_KERNEL_COMPRESS);
       return launch_compress_ws(ctx, reinterpret_cast<const bf16_t*>(X), ldx, (int)N, (int)d, Pf, l.ncb, c,
-                                reinterpret_cast<bf16_t*>(C), ldc, packed);
+                                reinterpret_cast<bf16_t*>(C), ldc, packed, nullptr, 0, 0, nullptr, 0);
     }
-    void* Crm = packed ? static_cast<void*>(ctx->ws + o_c) : C;
-    const int64_t ldcrm = packed ? round_up64(c, 8) : ldc;
-    GemmBf16Args g{};
-    g.A = reinterpret_cast<const bf16_t*>(X);
-    g.lda = ldx;
-    g.M = (int)N;
-    g.K = (int)d;
-    g.a_kc = true;
-    g.out_bf16 = true;
-    g.beta = 0.f;
-    g.splits = 1;
-    g.partial = nullptr;
-    g.b_kc = w_layout == 1;
-    g.b0 = GemmOperandB{reinterpret_cast<const bf16_t*>(W), ldw, (int)m, Y, ldy};
-    g.b1 = g.b_kc ? GemmOperandB{Pt, l.ldpt, c, Crm, ldcrm} : GemmOperandB{Pn, l.ldpn, c, Crm, ldcrm};
-    g.tile_hint = 0;
-    {
-      ProfScope ps(ctx, PRAC_KERNEL_FUSED_FWD);
-      rc = launch_gemm_bf16(ctx, g);
-    }
-    if (rc || !packed) return rc;
-    return launch_pack_c(ctx, reinterpret_cast<const bf16_t*>(Crm), ldcrm, (int)N, c, reinterpret_cast<bf16_t*>(C));
+    // W changes every step, so it is put into fragment order on every call (a pure permutation
+    // of its d x m elements), then one launch forms Y and C
+    bf16_t* Wf = reinterpret_cast<bf16_t*>(ctx->ws + o_w);
+    rc = launch_pack_wfrag(ctx, reinterpret_cast<const bf16_t*>(W), ldw, w_layout, d, (int)m, l.nkb, ncb_w, Wf);
+    if (rc) return rc;
+    ProfScope ps(ctx, PRAC_KERNEL_FUSED_FWD);
+    return launch_compress_ws(ctx, reinterpret_cast<const bf16_t*>(X), ldx, (int)N, (int)d, Pf, l.ncb, c,
+                              reinterpret_cast<bf16_t*>(C), ldc, packed, Wf, ncb_w, (int)m,
+                              reinterpret_cast<bf16_t*>(Y), ldy);
   }
   // generic path: fp32 data (P used in fp32) or unaligned bf16
   WsPlan plan;

@@ -115,8 +115,13 @@ int launch_cast_out(prac_ctx* ctx, const float* src, int64_t lds, void* dst, pra
 int launch_symmetrize(prac_ctx* ctx, float* G, int d, int64_t ldg);  // copy upper -> lower
 
 // ---- kernels of the per-step path (ws_kernels.hip, hot_kernels.hip) -----------------
+// Wfrag != nullptr: also Y (N x m, ldy) = X W, W in the fragment order of Pfrag with ncb_w column blocks
 int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d, const bf16_t* Pfrag, int ncb,
-                       int c, bf16_t* C, int64_t ldc, bool packed);
+                       int c, bf16_t* C, int64_t ldc, bool packed, const bf16_t* Wfrag, int ncb_w, int m,
+                       bf16_t* Y, int64_t ldy);
+// W (bf16; w_layout 0: d x m, 1: m x d; ldw) -> [nkb][ncb_w][64][8] fragment order, zero padded
+int launch_pack_wfrag(prac_ctx* ctx, const bf16_t* W, int64_t ldw, int w_layout, int64_t d, int m, int nkb,
+                      int ncb_w, bf16_t* out);
 int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, int64_t lddy, int N, int m,
                    float* slabs, int splits);
 int launch_pack_pfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nkb, int ncb, bf16_t* out);

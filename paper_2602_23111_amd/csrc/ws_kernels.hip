@@ -21,6 +21,11 @@
 // the matrix waves between k-blocks 14 and 15: everything before it has finished reading
 // tile kt's stage (which the loaders overwrite next with tile kt+2), and k-block 15 already
 // prefetches from tile kt+1, complete since the loaders reached the same barrier.
+//
+// The same kernel forms the layer's forward output Y = X W in the same launch (not in the
+// paper; forward of Lemma 1): W is handed over in the fragment order of P, and the column
+// groups of Y come before those of C in the grid.  Workgroups of one row tile sit next to
+// each other on one XCD, so X comes from HBM once and from that XCD's L2 afterwards.
 #include <type_traits>
 
 #include "frag_utils.h"
@@ -48,7 +53,14 @@ struct CompressWsArgs {
   int ccb;              // 32-column blocks of packed C = ceil(c / 32)
   int packed;
   int tiles_m;
-  int col_groups;       // column groups of 4*FN blocks
+  int col_groups;       // column groups of 4*FN blocks (forward output first, then C)
+  // fused forward Y = X W: the first w_groups column groups multiply by W instead of P
+  const bf16_t* Wfrag;  // [nkb][ncb_w][64][8], same fragment order as Pfrag; nullptr: no forward output
+  int ncb_w;            // 32-column blocks in the padded W (multiple of 4*FN)
+  int w_groups;
+  int m;                // columns of Y
+  bf16_t* Y;            // row-major N x m
+  int64_t ldy;
 };
 
 constexpr int WS_BM = 128, WS_BK = 256, WS_LD = WS_BK + 8;
@@ -150,7 +162,9 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
   // Step kt of this workgroup works on k-tile act(kt): the sum over k may run in any order, and
   // workgroups that start at different tiles neither ask L2 for the same lines of P at once nor
   // all pull on the same memory channels (their row panels have the same alignment).
-  const int rot = tm % nk;
+  // (not with a forward output: there workgroups of different row tiles share W through L2 and
+  // should ask for it in the same order)
+  const int rot = a.Wfrag ? 0 : tm % nk;
   auto act = [&](int kt) {
     const int t = min(kt, nk - 1) + rot;
     return t >= nk ? t - nk : t;
@@ -224,10 +238,11 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
 
   // -------------------------------------------------------------- matrix waves
   const int lane = tid & 63, li = lane & 31, lh = lane >> 5;
-  const int cb0 = cg * 4 * FN + wave * FN;  // first 32-column block of this wave
-  const char* pbase = reinterpret_cast<const char*>(a.Pfrag);
-  const uint32_t boff = (uint32_t)(cb0 * 64 + lane) * 16u;  // this lane's slot in a row of P blocks
-  const int64_t brow = (int64_t)a.ncb * 1024;               // bytes per 16-row k-block of P fragments
+  const bool fwd = cg < a.w_groups;  // this workgroup's columns belong to Y
+  const int cb0 = (fwd ? cg : cg - a.w_groups) * 4 * FN + wave * FN;  // first 32-column block of this wave
+  const char* pbase = reinterpret_cast<const char*>(fwd ? a.Wfrag : a.Pfrag);
+  const uint32_t boff = (uint32_t)(cb0 * 64 + lane) * 16u;     // this lane's slot in a row of blocks
+  const int64_t brow = (int64_t)(fwd ? a.ncb_w : a.ncb) * 1024;  // bytes per 16-row k-block of fragments
 
   constexpr int NACC = 4 * FN;
   f32x16 acc[NACC];
@@ -284,7 +299,7 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
 
   // epilogue: block (i, j) = acc[i * FN + j]; register v of lane (li, lh) is token row
   // 8*(v/4) + 4*lh + v%4 of row block i, column li of column block cb0 + j.
-  if (a.packed) {
+  if (a.packed && !fwd) {
     // registers v = 8 tb .. 8 tb + 7 are exactly the 8 slots of the 16-token block tb
     u32x4* Cp = reinterpret_cast<u32x4*>(a.C);
 #pragma unroll
@@ -316,6 +331,15 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
         }
       }
   } else {
+    // Row-major output: the wave's 128 x (32 FN) tile goes through LDS (the X stages are free
+    // once every matrix wave has left the loop) so that global stores are 16 bytes per lane
+    // along a row.  LDS tile: [128][32 FN] bf16, rows padded by 16 bytes.
+    constexpr int TW = 32 * FN, TLD = TW * 2 + 16;
+    bf16_t* out = fwd ? a.Y : a.C;
+    const int64_t ldo = fwd ? a.ldy : a.ldc;
+    const int ncols = fwd ? a.m : a.c;
+    __builtin_amdgcn_s_barrier();  // the loader waves have exited; they no longer count
+    unsigned char* tile = smem_raw + wave * (128 * TLD);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -323,11 +347,33 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
         asm volatile("" : "+a"(acc[i * FN + j]) : : "memory");
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int m = m0 + i * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
-          const int n = (cb0 + j) * 32 + li;
-          if (m < a.N && n < a.c) a.C[(int64_t)m * a.ldc + n] = f32_to_bf16(acc[i * FN + j][v]);
+          const int row = i * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
+          *reinterpret_cast<bf16_t*>(tile + row * TLD + (j * 32 + li) * 2) =
+              (bf16_t)(pack2_hw(acc[i * FN + j][v], 0.f) & 0xFFFFu);
         }
       }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    constexpr int CPR = TW / 8;  // 16-byte chunks per row
+    const int n0 = cb0 * 32;
+    const bool vec_ok = (ldo % 8 == 0) && ((reinterpret_cast<uintptr_t>(out) & 15) == 0);
+#pragma unroll
+    for (int it = 0; it < 128 * CPR / 64; ++it) {
+      const int q = it * 64 + lane, row = q / CPR, ch = q % CPR;
+      const int mrow = m0 + row, n = n0 + ch * 8;
+      if (mrow < a.N && n < ncols) {
+        const u32x4 val = *reinterpret_cast<const u32x4*>(tile + row * TLD + ch * 16);
+        bf16_t* o = out + (int64_t)mrow * ldo + n;
+        if (vec_ok && n + 8 <= ncols) {
+          *reinterpret_cast<u32x4*>(o) = val;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (n + e < ncols) o[e] = (bf16_t)((val[e >> 1] >> (16 * (e & 1))) & 0xFFFFu);
+        }
+      }
+    }
   }
 }
 
@@ -574,14 +620,20 @@ int set_smem(prac_ctx* ctx, K kern, size_t bytes, bool& done) {
 }  // namespace
 
 int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d, const bf16_t* Pfrag, int ncb, int c,
-                       bf16_t* C, int64_t ldc, bool packed) {
+                       bf16_t* C, int64_t ldc, bool packed, const bf16_t* Wfrag, int ncb_w, int m, bf16_t* Y,
+                       int64_t ldy) {
   CompressWsArgs a;
   a.X = X; a.ldx = ldx; a.N = N; a.d = d; a.Pfrag = Pfrag; a.ncb = ncb; a.c = c;
   a.C = C; a.ldc = ldc; a.ccb = (c + 31) / 32; a.packed = packed ? 1 : 0;
   a.tiles_m = (N + WS_BM - 1) / WS_BM;
-  const int FN = (c <= 128) ? 1 : 2;
-  a.col_groups = (a.ccb + 4 * FN - 1) / (4 * FN);
-  if (a.col_groups * 4 * FN > ncb) return PRAC_EINVAL;  // packed basis narrower than the launch assumes
+  // with a forward output the wide (64-column) wave tile is used throughout
+  const int FN = (c <= 128 && !Wfrag) ? 1 : 2;
+  const int p_groups = (a.ccb + 4 * FN - 1) / (4 * FN);
+  if (p_groups * 4 * FN > ncb) return PRAC_EINVAL;  // packed basis narrower than the launch assumes
+  a.Wfrag = Wfrag; a.ncb_w = ncb_w; a.m = m; a.Y = Y; a.ldy = ldy;
+  a.w_groups = Wfrag ? ((m + 31) / 32 + 4 * FN - 1) / (4 * FN) : 0;
+  if (a.w_groups * 4 * FN > ncb_w) return PRAC_EINVAL;
+  a.col_groups = a.w_groups + p_groups;
   const size_t smem = (size_t)WS_STAGES * WS_STAGE;
   const int total = a.tiles_m * a.col_groups;
   const dim3 grid(((total + 7) / 8) * 8), block(512);
