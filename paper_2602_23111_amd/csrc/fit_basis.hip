@@ -309,6 +309,7 @@ struct FitWs {
   size_t G, V, Y, W64, X64, Rinv, lam, Z, S, T, slabs, gram, total;
   int b;
   int splits_bb;  // split count of the b x b fp64 Gram products
+  int splits_gv;  // split count of G V
 };
 
 int block_width(int64_t d, int k, const prac_fit_opts& o) {
@@ -342,7 +343,15 @@ FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool n
   if (s < 1) s = 1;
   if (s > 64) s = 64;
   w.splits_bb = s;
-  w.slabs = p.take((size_t)s * bb * bb * 8);
+  // G V (d x b, fp32): split the sum over k until the tiles fill the chip
+  const int tiles_gv = (int)((d + 63) / 64) * ((b + 63) / 64);
+  int sg = need_g ? (n_cu + tiles_gv - 1) / tiles_gv : 1;
+  if (sg > d / 256) sg = (int)(d / 256);
+  if (sg < 1) sg = 1;
+  if (sg > 16) sg = 16;
+  w.splits_gv = sg;
+  const size_t slab_bb = (size_t)s * bb * bb * 8, slab_gv = sg > 1 ? (size_t)sg * d * b * 4 : 0;
+  w.slabs = p.take(slab_bb > slab_gv ? slab_bb : slab_gv);
   w.gram = p.take(gram_bytes);
   w.total = p.off;
   return w;
@@ -429,8 +438,9 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       // Y = G V  (first round: V is the start block, still in Y's buffer, so the roles swap)
       GemmGenArgs g{};
       g.A = G; g.B = it == 0 ? Y : V; g.adt = PRAC_F32; g.bdt = PRAC_F32;
-      g.a_rs = d; g.a_cs = 1; g.b_rs = b; g.b_cs = 1;
+      g.a_rs = 1; g.a_cs = d; g.b_rs = b; g.b_cs = 1;  // G(m, k) read as G[k][m]: G is symmetric
       g.M = (int)d; g.N = b; g.K = d; g.k_stride = 1;
+      g.splits = L.splits_gv; g.slabs = ctx->ws + L.slabs;
       g.out = it == 0 ? V : Y; g.ldo = b; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
       rc = launch_gemm_generic(ctx, g);
       if (rc) return rc;

@@ -104,6 +104,80 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GArgs a) {
     }
 }
 
+// ---- fp32 on the matrix cores ------------------------------------------------------
+// Same contract for fp32 operands with fp32 sums whose m (A) and n (B) strides are one
+// element (the basis fit's G V with G read through its symmetry, and Q1 T): 64 x 64 tile per
+// workgroup, one 32 x 32 block of v_mfma_f32_32x32x2_f32 per wave, k in steps of 32 through
+// double-buffered LDS.  Lane l holds A(m = l % 32, k = l / 32) and B(k = l / 32, n = l % 32); rows
+// are padded by 32 floats so that the two half-waves of a fragment read hit disjoint banks.
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+constexpr int FK = 32, FLD = 64 + 32;
+
+__global__ __launch_bounds__(256) void gemm_f32_mfma_kernel(GArgs a) {
+  __shared__ float As[2][FK][FLD];
+  __shared__ float Bs[2][FK][FLD];
+  const float* __restrict__ A = reinterpret_cast<const float*>(a.A);
+  const float* __restrict__ B = reinterpret_cast<const float*>(a.B);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
+  const int64_t kbeg = (int64_t)blockIdx.z * a.steps_per_split;
+  const int64_t kend = min(a.K, kbeg + a.steps_per_split);
+  // tile loads: 8 elements per thread and operand, thread t -> k rows t / 64 + 4 p, column t % 64
+  const int lc = tid & 63, lr = tid >> 6;
+  float ra[8], rb[8];
+  auto gload = [&](int64_t k0) {
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      const int64_t k = k0 + lr + 4 * p;
+      const bool kin = k < kend;
+      ra[p] = (kin && m0 + lc < a.M) ? A[k * a.a_cs + (m0 + lc)] : 0.f;
+      rb[p] = (kin && n0 + lc < a.N) ? B[k * a.b_rs + (n0 + lc)] : 0.f;
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      As[buf][lr + 4 * p][lc] = ra[p];
+      Bs[buf][lr + 4 * p][lc] = rb[p];
+    }
+  };
+  f32x16_t acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  const int fi = lane & 31, fk = lane >> 5;
+  if (kbeg < kend) {
+    gload(kbeg);
+    sstore(0);
+    __syncthreads();
+    int buf = 0;
+    for (int64_t k0 = kbeg; k0 < kend; k0 += FK) {
+      const bool more = k0 + FK < kend;
+      if (more) gload(k0 + FK);
+#pragma unroll
+      for (int kk = 0; kk < FK; kk += 2)
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[buf][kk + fk][wm + fi], Bs[buf][kk + fk][wn + fi], acc, 0, 0, 0);
+      if (more) sstore(buf ^ 1);  // last read by the MFMAs two steps ago, before the previous barrier
+      __syncthreads();
+      buf ^= 1;
+    }
+  }
+  // register v of lane (fi, fk): row wm + 8 (v / 4) + 4 fk + v % 4, column wn + fi
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int m = m0 + wm + 8 * (v / 4) + 4 * fk + (v % 4), n = n0 + wn + fi;
+    if (m < a.M && n < a.N) {
+      const int64_t o = (int64_t)m * a.ldo + n;
+      if (a.splits > 1) {
+        reinterpret_cast<float*>(a.slabs)[((int64_t)blockIdx.z * a.M + m) * a.N + n] = acc[v];
+      } else {
+        const float x = a.alpha * acc[v];
+        a.out[o] = a.beta == 0.f ? x : x + a.beta * a.out[o];
+      }
+    }
+  }
+}
+
 template <typename TA, typename TB, typename ACC>
 void launch3(const GArgs& a, hipStream_t st) {
   dim3 grid((a.N + TN - 1) / TN, (a.M + TM - 1) / TM, a.splits), block(256);
@@ -150,7 +224,13 @@ int launch_gemm_generic(prac_ctx* ctx, const GemmGenArgs& g) {
   if (a.steps_per_split < TK) a.steps_per_split = TK;
   a.slabs = g.slabs;
   const bool abf = g.adt == PRAC_BF16, bbf = g.bdt == PRAC_BF16;
-  if (abf && bbf) launch2<bf16_t, bf16_t>(a, g.acc64, ctx->stream);
+  const bool mfma = !abf && !bbf && !g.acc64 && !g.out64 && a.a_rs == 1 && a.b_cs == 1 && a.k_stride == 1 &&
+                    (int64_t)a.M * a.N >= 64 * 64 && a.K >= 64;
+  if (mfma) {
+    a.steps_per_split = ((a.K + a.splits - 1) / a.splits + FK - 1) / FK * FK;
+    hipLaunchKernelGGL(gemm_f32_mfma_kernel, dim3((a.N + 63) / 64, (a.M + 63) / 64, a.splits), dim3(256), 0, ctx->stream,
+                       a);
+  } else if (abf && bbf) launch2<bf16_t, bf16_t>(a, g.acc64, ctx->stream);
   else if (abf) launch2<bf16_t, float>(a, g.acc64, ctx->stream);
   else if (bbf) launch2<float, bf16_t>(a, g.acc64, ctx->stream);
   else launch2<float, float>(a, g.acc64, ctx->stream);
