@@ -88,7 +88,8 @@ enum {
   PRAC_KERNEL_T_REDUCE = 3,   /* slab reduction + scaling factor + transpose */
   PRAC_KERNEL_P_T = 4,        /* dW = P T */
   PRAC_KERNEL_GRAM = 5,       /* X^T X partial sums */
-  PRAC_KERNEL_FUSED_FWD = 6   /* [Y | C] = X [W | P] */
+  PRAC_KERNEL_FUSED_FWD = 6,  /* [Y | C] = X [W | P] */
+  PRAC_KERNEL_RECONSTRUCT = 7 /* Xh = C Ps^T */
 };
 int prac_profile_select(prac_ctx* ctx, int kind);
 int prac_profile_read(prac_ctx* ctx, double* total_ms, int64_t* launches);
@@ -179,6 +180,19 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
                      int64_t m, int64_t ldc, int c_layout, int64_t lddy, const float* P,
                      const void* P_lp, int64_t d, int64_t ldp, int k, int r, float scale,
                      void* dW, prac_dtype odt, int64_t lddw, float beta);
+
+/* ---- reconstruction (Section 5.1 formula; Alg. 2 backward, first step) ------ */
+/* Xh (N x d, ldxh >= d, dtype dt) = C[:, :k] Q1^T + scale * C[:, k:] Q2^T: the
+ * unbiased estimate of the saved activation, for layers whose backward needs
+ * the activation itself (normalisation and activation-function inputs,
+ * Section 5.1 / Appendix B) rather than only X^T dY.
+ * C (N x (k+r), layout c_layout, dtype dt); P is the fp32 master (d x (k+r),
+ * ldp).  bf16 data runs on the matrix cores with a bf16 copy of P whose random
+ * columns already carry `scale` (built in ctx scratch on every call); fp32
+ * data is evaluated in fp32. */
+int prac_reconstruct(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int64_t ldc,
+                     int c_layout, const float* P, int64_t d, int64_t ldp, int k, int r,
+                     float scale, void* Xh, int64_t ldxh);
 
 #ifdef __cplusplus
 }

@@ -74,6 +74,33 @@ __global__ __launch_bounds__(256) void pack_wfrag_kernel(const bf16_t* __restric
   }
 }
 
+// Fragment order of Ps^T for the reconstruction Xh = C Ps^T (Section 5.1): the sum runs over the
+// columns of P, the output columns are the rows of P; the random columns carry the scaling factor.
+__global__ __launch_bounds__(256) void pack_ptfrag_kernel(const float* __restrict__ P, int64_t d, int64_t ldp, int c,
+                                                          int k_lo, float scale_hi, int nkb, int ncb,
+                                                          bf16_t* __restrict__ out) {
+  const int64_t total = (int64_t)nkb * ncb * 64;
+  for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += (int64_t)gridDim.x * blockDim.x) {
+    const int lane = (int)(g & 63), j = lane & 31, h = lane >> 5;
+    const int64_t blk = g >> 6;
+    const int cb = (int)(blk % ncb);
+    const int64_t kb = blk / ncb;
+    const int64_t row = (int64_t)cb * 32 + j;  // row of P = output column
+    uint32_t w[4];
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      float f[2] = {0.f, 0.f};
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int64_t kk = kb * 16 + 8 * h + 2 * e2 + u;  // column of P
+        if (row < d && kk < c) f[u] = P[row * ldp + kk] * (kk >= k_lo ? scale_hi : 1.f);
+      }
+      w[e2] = pack2(f[0], f[1]);
+    }
+    reinterpret_cast<uint4*>(out)[g] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
 __device__ __forceinline__ int c_slot(int h, int e) { return e < 4 ? 4 * h + e : 8 + 4 * h + (e - 4); }
 
 // packed C -> row-major (bit-exact copy of the elements)
@@ -392,6 +419,14 @@ int launch_pack_wfrag(prac_ctx* ctx, const bf16_t* W, int64_t ldw, int w_layout,
                       int ncb_w, bf16_t* out) {
   hipLaunchKernelGGL(pack_wfrag_kernel, dim3(grid_for((int64_t)nkb * ncb_w * 64, ctx->n_cu)), dim3(256), 0,
                      ctx->stream, W, ldw, w_layout, d, m, nkb, ncb_w, out);
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  return PRAC_OK;
+}
+
+int launch_pack_ptfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int k_lo, float scale_hi,
+                       int nkb, int ncb, bf16_t* out) {
+  hipLaunchKernelGGL(pack_ptfrag_kernel, dim3(grid_for((int64_t)nkb * ncb * 64, ctx->n_cu)), dim3(256), 0, ctx->stream,
+                     P, d, ldp, c, k_lo, scale_hi, nkb, ncb, out);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }

@@ -245,7 +245,7 @@ int prac_sync_status(prac_ctx* ctx) {
 int prac_last_hip_error(const prac_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
 
 int prac_profile_select(prac_ctx* ctx, int kind) {
-  if (kind < PRAC_KERNEL_NONE || kind > PRAC_KERNEL_FUSED_FWD) return PRAC_EINVAL;
+  if (kind < PRAC_KERNEL_NONE || kind > PRAC_KERNEL_RECONSTRUCT) return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
   ctx->prof_kind = kind;
   return PRAC_OK;
@@ -565,3 +565,80 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
 }
 
 }  // extern "C"
+
+// ------------------------------------------------------------------ reconstruction
+int prac_reconstruct(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int64_t ldc, int c_layout, const float* P,
+                     int64_t d, int64_t ldp, int k, int r, float scale, void* Xh, int64_t ldxh) {
+  if (!C || !P || !Xh || !valid_dtype(dt) || N < 1 || d < 1 || d > (1 << 20) || k < 0 || r < 0 || k + r < 1 ||
+      (int64_t)k + r > d || bad_c_layout(c_layout, ldc, k + r) || ldp < k + r || ldxh < d)
+    return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  const int c = k + r;
+  const bool packed = c_layout == PRAC_C_PACKED;
+  if (packed && (dt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
+  const bool rm_ok = !packed && aligned16(C) && ldc % 8 == 0;
+  const bool fast = dt == PRAC_BF16 && (packed || rm_ok) && N < ((int64_t)1 << 31);
+  if (fast) {
+    // Xh = C Ps^T is the forward-output launch of the compress kernel with C in the role of X
+    // (its "feature" dimension is c) and Ps^T in the role of W.
+    const int nkb = (int)(round_up64(c, 256) / 16);
+    const int ncb = (int)round_up64((d + 31) / 32, 8);
+    const int64_t ldcrm = packed ? round_up64(c, 8) : ldc;
+    WsPlan plan;
+    const size_t o_pt = plan.take((size_t)nkb * ncb * 64 * 8 * sizeof(bf16_t));
+    const size_t o_c = plan.take(packed ? (size_t)N * ldcrm * sizeof(bf16_t) : 0);
+    int rc = prac_ws_reserve(ctx, plan.off);
+    if (rc) return rc;
+    bf16_t* Pt = reinterpret_cast<bf16_t*>(ctx->ws + o_pt);
+    rc = launch_pack_ptfrag(ctx, P, d, ldp, c, k, scale, nkb, ncb, Pt);
+    if (rc) return rc;
+    const bf16_t* Crm = reinterpret_cast<const bf16_t*>(C);
+    if (packed) {
+      rc = launch_unpack_c(ctx, reinterpret_cast<const bf16_t*>(C), (int)N, c, reinterpret_cast<bf16_t*>(ctx->ws + o_c),
+                           ldcrm);
+      if (rc) return rc;
+      Crm = reinterpret_cast<const bf16_t*>(ctx->ws + o_c);
+    }
+    ProfScope ps(ctx, PRAC_KERNEL_RECONSTRUCT);
+    return launch_compress_ws(ctx, Crm, ldcrm, (int)N, c, nullptr, 0, 0, nullptr, 0, false, Pt, ncb, (int)d,
+                              reinterpret_cast<bf16_t*>(Xh), ldxh);
+  }
+  // generic path: Xh = C1 Q1^T, then Xh += scale * C2 Q2^T (fp32 sums)
+  WsPlan plan;
+  const bool need_tmp = dt == PRAC_BF16;
+  const size_t o_tmp = plan.take(need_tmp ? (size_t)N * d * sizeof(float) : 0);
+  const size_t o_crm = plan.take(packed ? (size_t)N * c * sizeof(bf16_t) : 0);
+  if (plan.off) {
+    int rc = prac_ws_reserve(ctx, plan.off);
+    if (rc) return rc;
+  }
+  const void* Crm = C;
+  int64_t ldcrm = ldc;
+  if (packed) {
+    int rc = launch_unpack_c(ctx, reinterpret_cast<const bf16_t*>(C), (int)N, c,
+                             reinterpret_cast<bf16_t*>(ctx->ws + o_crm), c);
+    if (rc) return rc;
+    Crm = ctx->ws + o_crm;
+    ldcrm = c;
+  }
+  float* out = need_tmp ? reinterpret_cast<float*>(ctx->ws + o_tmp) : reinterpret_cast<float*>(Xh);
+  const int64_t ldo = need_tmp ? d : ldxh;
+  const size_t es = esize(dt);
+  bool first = true;
+  for (int part = 0; part < 2; ++part) {
+    const int k0 = part == 0 ? 0 : k, kn = part == 0 ? k : r;
+    if (kn == 0) continue;
+    GemmGenArgs g{};
+    g.A = reinterpret_cast<const char*>(Crm) + (size_t)k0 * es; g.adt = dt; g.a_rs = ldcrm; g.a_cs = 1;
+    g.B = P + k0; g.bdt = PRAC_F32; g.b_rs = 1; g.b_cs = ldp;  // B(kk, n) = P[n][k0 + kk]
+    g.M = (int)N; g.N = (int)d; g.K = kn; g.k_stride = 1;
+    g.out = out; g.ldo = ldo; g.acc64 = false; g.out64 = nullptr;
+    g.alpha = part == 0 ? 1.f : scale;
+    g.beta = first ? 0.f : 1.f;
+    first = false;
+    int rc = launch_gemm_generic(ctx, g);
+    if (rc) return rc;
+  }
+  if (need_tmp) return launch_cast_out(ctx, out, d, Xh, PRAC_BF16, ldxh, (int)N, (int)d, 0.f);
+  return PRAC_OK;
+}

@@ -136,6 +136,11 @@ int launch_pack_pafrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, in
 int launch_pt(prac_ctx* ctx, const bf16_t* Pa, const bf16_t* Tf, int d, int m, int nkb, int nmb, void* dW,
               int64_t lddw, bool out_bf16, float beta);
 
+// P (d x c fp32, ldp) -> B operand of Xh = C Ps^T in fragment order [nkb][ncb][64][8] (bf16, zero padded):
+// element (k = column of P, n = row of P) = P[n][k] * (k >= k_lo ? scale_hi : 1)
+int launch_pack_ptfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int k_lo, float scale_hi,
+                       int nkb, int ncb, bf16_t* out);
+
 // ---- basis fit -----------------------------------------------------------------
 int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
                      int k, int r, uint64_t seed, uint32_t draw, int refresh, const prac_fit_opts& o,

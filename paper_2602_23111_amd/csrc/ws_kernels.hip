@@ -628,8 +628,9 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
   a.tiles_m = (N + WS_BM - 1) / WS_BM;
   // with a forward output the wide (64-column) wave tile is used throughout
   const int FN = (c <= 128 && !Wfrag) ? 1 : 2;
-  const int p_groups = (a.ccb + 4 * FN - 1) / (4 * FN);
-  if (p_groups * 4 * FN > ncb) return PRAC_EINVAL;  // packed basis narrower than the launch assumes
+  // Pfrag == nullptr (only with a forward output): no C part, the launch is a plain Y = X W
+  const int p_groups = Pfrag ? (a.ccb + 4 * FN - 1) / (4 * FN) : 0;
+  if (p_groups * 4 * FN > ncb || (!Pfrag && !Wfrag)) return PRAC_EINVAL;  // packed basis narrower than assumed
   a.Wfrag = Wfrag; a.ncb_w = ncb_w; a.m = m; a.Y = Y; a.ldy = ldy;
   a.w_groups = Wfrag ? ((m + 31) / 32 + 4 * FN - 1) / (4 * FN) : 0;
   if (a.w_groups * 4 * FN > ncb_w) return PRAC_EINVAL;

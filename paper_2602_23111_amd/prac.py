@@ -18,7 +18,7 @@ PRAC_F32, PRAC_BF16 = 0, 1
 PRAC_REFRESH_PRINCIPAL, PRAC_REFRESH_RANDOM = 1, 2
 C_ROWMAJOR, C_PACKED = 0, 1
 TUNE_CTDY_SPLITS = 1
-KERNEL_KINDS = {"compress": 1, "ct_dy": 2, "t_reduce": 3, "p_t": 4, "gram": 5, "fused_fwd": 6}
+KERNEL_KINDS = {"compress": 1, "ct_dy": 2, "t_reduce": 3, "p_t": 4, "gram": 5, "fused_fwd": 6, "reconstruct": 7}
 STATUS = {0: "PRAC_OK", -1: "PRAC_EINVAL", -2: "PRAC_ENOMEM", -3: "PRAC_EHIP",
           -4: "PRAC_ENUMERIC", -5: "PRAC_EUNSUPPORTED", -6: "PRAC_ENOCTX"}
 
@@ -26,7 +26,7 @@ EXPORTS = ["prac_create", "prac_destroy", "prac_set_stream", "prac_sync_status",
            "prac_last_hip_error", "prac_profile_select", "prac_profile_read", "prac_set_tuning",
            "prac_compressed_bytes", "prac_unpack_compressed", "prac_philox_words", "prac_philox_normal", "prac_gram",
            "prac_basis_lp_bytes", "prac_pack_basis", "prac_fit_basis", "prac_compress",
-           "prac_compress_fused_fwd", "prac_weight_grad"]
+           "prac_compress_fused_fwd", "prac_weight_grad", "prac_reconstruct"]
 
 
 class PracError(RuntimeError):
@@ -76,6 +76,7 @@ def load_library() -> C.CDLL:
                                           i32, vp, i64, vp, i64, i32]),
         "prac_weight_grad": (i32, [vp, vp, vp, i32, i64, i64, i64, i32, i64, vp, vp, i64, i64, i32, i32,
                                    f32, vp, i32, i64, f32]),
+        "prac_reconstruct": (i32, [vp, vp, i32, i64, i64, i32, vp, i64, i64, i32, i32, f32, vp, i64]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -262,3 +263,20 @@ class Prac:
                                          P_lp.data_ptr() if P_lp is not None else None, d, ldp, k, r, scale, pw,
                                          _dt(dW), lddw, beta), "prac_weight_grad")
         return dW
+
+    # ---- reconstruction
+    def reconstruct(self, Cm: torch.Tensor, P: torch.Tensor, k: int, r: int, scale: float, N: int | None = None,
+                    out: torch.Tensor | None = None, layout: int = C_ROWMAJOR) -> torch.Tensor:
+        """Xh = C[:, :k] Q1^T + scale * C[:, k:] Q2^T.  Cm: N x (k+r) row-major, or the flat packed
+        buffer (then N must be given) when layout == C_PACKED."""
+        pp, d, _, ldp = _mat(P)
+        if layout == C_PACKED:
+            pc, ldc, cdt, dt = Cm.data_ptr(), 0, PRAC_BF16, torch.bfloat16
+        else:
+            pc, N, _, ldc = _mat(Cm)
+            cdt, dt = _dt(Cm), Cm.dtype
+        Xh = out if out is not None else torch.empty((N, d), dtype=dt, device=Cm.device)
+        px, _, _, ldxh = _mat(Xh)
+        _check(self.lib.prac_reconstruct(self._h, pc, cdt, N, ldc, layout, pp, d, ldp, k, r, scale, px, ldxh),
+               "prac_reconstruct")
+        return Xh

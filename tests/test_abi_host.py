@@ -124,6 +124,12 @@ def test_other_entry_points_reject_bad_arguments(lib):
     assert lib.prac_compressed_bytes(100, 40, 1, 1, 0) == 8 * 2 * 64 * 8 * 2
     assert lib.prac_compressed_bytes(100, 40, 1, 0, 48) == 100 * 48 * 2
     assert lib.prac_compressed_bytes(100, 40, 0, 1, 0) == 0      # packed is bf16 only
+    rec = lib.prac_reconstruct
+    assert rec(None, DUMMY, 1, 8, 4, 0, DUMMY, 16, 4, 2, 2, 7.0, DUMMY, 16) == -6
+    assert rec(None, DUMMY, 1, 8, 3, 0, DUMMY, 16, 4, 2, 2, 7.0, DUMMY, 16) == -1    # ldc < k + r
+    assert rec(None, DUMMY, 1, 8, 4, 0, DUMMY, 16, 4, 2, 2, 7.0, DUMMY, 15) == -1    # ldxh < d
+    assert rec(None, DUMMY, 1, 8, 4, 0, DUMMY, 3, 4, 2, 2, 7.0, DUMMY, 16) == -1     # k + r > d
+    assert rec(None, DUMMY, 1, 8, 0, 1, DUMMY, 16, 4, 2, 2, 7.0, DUMMY, 16) == -6    # packed C ignores ldc
     assert lib.prac_destroy(None) == -6 and lib.prac_sync_status(None) == -6
 
 

@@ -155,6 +155,59 @@ def test_compress_identity_columns_bit_exact(ctx):
     assert torch.equal(got.cpu(), Xt[:, :c])
 
 
+# ------------------------------------------------------------- reconstruction
+RECON_CASES = [
+    # dtype, N, d, k, r, ldc, ldxh
+    ("f32", 300, 200, 12, 12, 24, 200),
+    ("f32", 300, 200, 0, 24, 24, 208),        # random part only
+    ("f32", 300, 200, 24, 0, 24, 200),        # principal part only (scale unused)
+    ("bf16", 2048, 512, 32, 32, 64, 512),     # configs[0] shape
+    ("bf16", 777, 328, 40, 32, 72, 328),      # ragged rows, sum over 72 columns, padded tiles
+    ("bf16", 130, 600, 150, 150, 304, 600),   # sum over two 256-deep tiles, three column groups
+    ("bf16", 200, 101, 20, 13, 33, 101),      # unaligned leading dims -> generic kernel
+    ("bf16", 1, 64, 4, 4, 8, 64),
+]
+
+
+@pytest.mark.parametrize("dt,N,d,k,r,ldc,ldxh", RECON_CASES)
+def test_reconstruct_matches_oracle(ctx, dt, N, d, k, r, ldc, ldxh):
+    c = k + r
+    scale = (d - k) / r if r else 0.0
+    rng = np.random.default_rng(N + d + c)
+    Ct = si.round_to(rng.standard_normal((N, c)), dt)
+    P32, P64 = basis32(d, c, seed=c)
+    out = dev_padded(torch.zeros((N, d), dtype=TORCH_DT[dt]), ldxh)
+    ctx.reconstruct(dev_padded(Ct, ldc), P32.to(DEV), k, r, scale, out=out)
+    torch.cuda.synchronize()
+    assert rel_fro(si.as_f64(out), orc.reconstruct(si.as_f64(Ct), P64, k, scale)) < TOL[dt]
+
+
+def test_reconstruct_packed_equals_rowmajor(ctx):
+    from paper_2602_23111_amd.prac import C_PACKED
+    N, d, k, r = 515, 384, 48, 24
+    Xt = si.round_to(si.activation(N, d, 0.8, seed=9, n_out=2, out_scale=20.0)[0], "bf16")
+    P32, _ = basis32(d, k + r, seed=3)
+    lp = ctx.pack_basis(P32.to(DEV))
+    flat = ctx.compress(Xt.to(DEV), P32.to(DEV), P_lp=lp, layout=C_PACKED)
+    rowm = ctx.compress(Xt.to(DEV), P32.to(DEV), P_lp=lp)
+    a = ctx.reconstruct(flat, P32.to(DEV), k, r, (d - k) / r, N=N, layout=C_PACKED)
+    b = ctx.reconstruct(rowm, P32.to(DEV), k, r, (d - k) / r)
+    torch.cuda.synchronize()
+    assert torch.equal(a.cpu(), b.cpu())
+
+
+def test_reconstruct_is_exact_for_a_full_basis(ctx):
+    # r = d - k: scale 1 and P square orthogonal, so Xh = X up to rounding (Theorem 1 with zero variance)
+    N, d, k = 260, 96, 40
+    X64, _ = si.activation(N, d, 0.8, seed=21)
+    Xt = si.round_to(X64, "f32")
+    P32, _ = basis32(d, d, seed=8)
+    Cm = ctx.compress(Xt.to(DEV), P32.to(DEV))
+    Xh = ctx.reconstruct(Cm, P32.to(DEV), k, d - k, 1.0)
+    torch.cuda.synchronize()
+    assert rel_fro(si.as_f64(Xh), si.as_f64(Xt)) < 1e-5
+
+
 # ------------------------------------------------------------- fused forward
 @pytest.mark.parametrize("dt,N,d,m,c,layout", [
     ("f32", 300, 200, 150, 24, 0), ("f32", 300, 200, 150, 24, 1),
