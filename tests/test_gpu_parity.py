@@ -406,3 +406,60 @@ def test_fit_basis_row_subsample_and_warm_start(ctx):
     ctx.sync_status()
     assert np.abs(si.as_f64(P2)[:, :k] @ si.as_f64(P2)[:, :k].T - Q1 @ Q1.T).max() < 1e-3
     assert not torch.equal(P2[:, k:], P[:, k:])          # a new draw gives a new random block
+
+
+# ------------------------------------------------- estimator statistics on the GPU path
+def _gpu_monte_carlo(ctx, Xt, dYt, k, r, draws, scale_factor=1.0):
+    """Mean of Xh and of dW, and the squared errors of Xh, over `draws` redraws of Q2 (Q1 fixed):
+    fit (random branch only) -> compress -> reconstruct / weight_grad, all through the C ABI."""
+    from paper_2602_23111_amd.prac import PRAC_REFRESH_RANDOM
+    N, d = Xt.shape
+    Xd, dYd = Xt.to(DEV), dYt.to(DEV)
+    P, _, s = ctx.fit_basis(Xd, k, r, seed=77, draw=0, pack=False)
+    mean_x = torch.zeros((N, d), dtype=torch.float64, device=DEV)
+    mean_w = torch.zeros((d, dYt.shape[1]), dtype=torch.float64, device=DEV)
+    err2 = torch.zeros(draws, dtype=torch.float64, device=DEV)
+    for t in range(draws):
+        ctx.fit_basis(None, k, r, seed=77, draw=t + 1, refresh=PRAC_REFRESH_RANDOM, P=P, d=d, pack=False)
+        Cm = ctx.compress(Xd, P)
+        Xh = ctx.reconstruct(Cm, P, k, r, scale_factor * s)
+        dW = ctx.weight_grad(Cm, dYd, P, k, r, scale_factor * s)
+        mean_x += Xh.double()
+        mean_w += dW.double()
+        err2[t] = ((Xh.double() - Xd.double()) ** 2).sum()
+    ctx.sync_status()
+    Q1 = si.as_f64(P.cpu())[:, :k]
+    return Q1, s, (mean_x / draws).cpu().numpy(), (mean_w / draws).cpu().numpy(), err2.cpu().numpy()
+
+
+def test_gpu_path_is_unbiased_with_the_closed_form_variance(ctx):
+    # Theorem 1, the variance identity of Theorem 2's proof (equality) and Lemma 1, measured on what the
+    # library computes (fp32 data): 4000 redraws of Q2 around a fixed Q1.
+    N, d, m, k, r, draws = 24, 40, 16, 5, 7, 4000
+    X64, _ = si.activation(N, d, 0.8, seed=31)
+    Xt, dYt = si.round_to(X64, "f32"), si.round_to(si.grad_output(N, m, 1e-2, seed=32), "f32")
+    Q1, s, mean_x, mean_w, err2 = _gpu_monte_carlo(ctx, Xt, dYt, k, r, draws)
+    X, dY = si.as_f64(Xt), si.as_f64(dYt)
+    tailX = X - X @ Q1 @ Q1.T
+    closed = (s - 1.0) * np.sum(tailX ** 2)
+    assert abs(s - (d - k) / r) < 1e-6
+    assert abs(err2.mean() / closed - 1.0) < 0.03
+    se = np.sqrt(closed / draws)
+    assert np.linalg.norm(mean_x - X) < 4.0 * se
+    # dW = Xh^T dY is linear in Xh: its mean tends to X^T dY with the same relative standard error
+    exact = X.T @ dY
+    assert np.linalg.norm(mean_w - exact) < 4.0 * se * np.linalg.norm(dY, 2)
+
+
+def test_gpu_path_wrong_scale_is_biased_as_predicted(ctx):
+    # the paper's scale ablation at estimator level: scale = f s gives E[Xh] = X Q1 Q1^T + f X (I - Q1 Q1^T)
+    N, d, m, k, r, draws, f = 24, 40, 8, 5, 7, 2000, 0.5
+    X64, _ = si.activation(N, d, 0.8, seed=33)
+    Xt, dYt = si.round_to(X64, "f32"), si.round_to(si.grad_output(N, m, 1e-2, seed=34), "f32")
+    Q1, s, mean_x, _, _ = _gpu_monte_carlo(ctx, Xt, dYt, k, r, draws, scale_factor=f)
+    X = si.as_f64(Xt)
+    tailX = X - X @ Q1 @ Q1.T
+    predicted = X @ Q1 @ Q1.T + f * tailX
+    se = np.sqrt(f * f * (s - 1.0) * np.sum(tailX ** 2) / draws)
+    assert np.linalg.norm(mean_x - predicted) < 4.0 * se
+    assert np.linalg.norm(mean_x - X) > 10.0 * se
