@@ -71,50 +71,71 @@ constexpr int WS_KB = WS_BK / 16;            // k-blocks per tile
 constexpr int WS_NCH = 4, WS_NIF = 2;        // chunks per tile, chunks in flight
 
 // One k-block of a 128 x 64 wave tile: acc[2 i + j] += fa[i] * b_j, while the four A fragments
-// at byte offsets O + i * WS_RB from `lds` are read into fn.
-template <int O>
+// at byte offsets O + i * WS_RB from `lds` are read into fn.  The block also issues the two
+// 1 KB requests that refill another slot of the P ring (n0, n1 <- fragments at `src` + lane
+// offset `voff`, and 1 KB further): the matrix pipeline runs while they are issued, and the
+// address is an SGPR pair plus one VGPR, so no vector arithmetic sits between the blocks.
+// The compiler cannot see these loads.  The block therefore starts with its own wait: all
+// but the VM youngest requests of this wave have arrived (the ring's distance times the
+// requests per block; b0 / b1 were requested that long ago), and n0 / n1 may only be read
+// by a later block, after that block's wait.
+template <int O, int VM>
 __device__ __forceinline__ void kblock2(f32x16 (&acc)[8], const u32x4 (&fa)[4], u32x4 (&fn)[4], const u32x4& b0,
-                                        const u32x4& b1, unsigned lds) {
+                                        const u32x4& b1, unsigned lds, u32x4& n0, u32x4& n1, uint32_t voff,
+                                        const char* src) {
   asm volatile(
-      "ds_read_b128 %8, %18 offset:%19\n"
-      "v_mfma_f32_32x32x16_bf16 %0, %12, %16, %0\n"
-      "ds_read_b128 %9, %18 offset:%20\n"
-      "v_mfma_f32_32x32x16_bf16 %1, %12, %17, %1\n"
-      "ds_read_b128 %10, %18 offset:%21\n"
-      "v_mfma_f32_32x32x16_bf16 %2, %13, %16, %2\n"
-      "ds_read_b128 %11, %18 offset:%22\n"
-      "v_mfma_f32_32x32x16_bf16 %3, %13, %17, %3\n"
-      "v_mfma_f32_32x32x16_bf16 %4, %14, %16, %4\n"
-      "v_mfma_f32_32x32x16_bf16 %5, %14, %17, %5\n"
-      "v_mfma_f32_32x32x16_bf16 %6, %15, %16, %6\n"
-      "v_mfma_f32_32x32x16_bf16 %7, %15, %17, %7\n"
+      "s_waitcnt vmcnt(%27)\n"
+      "ds_read_b128 %8, %20 offset:%23\n"
+      "v_mfma_f32_32x32x16_bf16 %0, %14, %18, %0\n"
+      "ds_read_b128 %9, %20 offset:%24\n"
+      "v_mfma_f32_32x32x16_bf16 %1, %14, %19, %1\n"
+      "global_load_dwordx4 %12, %21, %22\n"
+      "ds_read_b128 %10, %20 offset:%25\n"
+      "v_mfma_f32_32x32x16_bf16 %2, %15, %18, %2\n"
+      "global_load_dwordx4 %13, %21, %22 offset:1024\n"
+      "ds_read_b128 %11, %20 offset:%26\n"
+      "v_mfma_f32_32x32x16_bf16 %3, %15, %19, %3\n"
+      "v_mfma_f32_32x32x16_bf16 %4, %16, %18, %4\n"
+      "v_mfma_f32_32x32x16_bf16 %5, %16, %19, %5\n"
+      "v_mfma_f32_32x32x16_bf16 %6, %17, %18, %6\n"
+      "v_mfma_f32_32x32x16_bf16 %7, %17, %19, %7\n"
       "s_waitcnt lgkmcnt(0)\n"
       : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]), "+a"(acc[4]), "+a"(acc[5]), "+a"(acc[6]),
-        "+a"(acc[7]), "=&v"(fn[0]), "=&v"(fn[1]), "=&v"(fn[2]), "=&v"(fn[3])
-      : "v"(fa[0]), "v"(fa[1]), "v"(fa[2]), "v"(fa[3]), "v"(b0), "v"(b1), "v"(lds), "n"(O), "n"(O + WS_RB),
-        "n"(O + 2 * WS_RB), "n"(O + 3 * WS_RB)
+        "+a"(acc[7]), "=&v"(fn[0]), "=&v"(fn[1]), "=&v"(fn[2]), "=&v"(fn[3]), "=&v"(n0), "=&v"(n1)
+      : "v"(fa[0]), "v"(fa[1]), "v"(fa[2]), "v"(fa[3]), "v"(b0), "v"(b1), "v"(lds), "v"(voff), "s"(src), "n"(O),
+        "n"(O + WS_RB), "n"(O + 2 * WS_RB), "n"(O + 3 * WS_RB), "n"(VM)
       : "memory");
 }
 
-// Same for a 128 x 32 wave tile: acc[i] += fa[i] * b.
-template <int O>
+// Same for a 128 x 32 wave tile: acc[i] += fa[i] * b, one refill request.
+template <int O, int VM>
 __device__ __forceinline__ void kblock1(f32x16 (&acc)[4], const u32x4 (&fa)[4], u32x4 (&fn)[4], const u32x4& b,
-                                        unsigned lds) {
+                                        unsigned lds, u32x4& n0, uint32_t voff, const char* src) {
   asm volatile(
-      "ds_read_b128 %4, %13 offset:%14\n"
-      "ds_read_b128 %5, %13 offset:%15\n"
-      "v_mfma_f32_32x32x16_bf16 %0, %8, %12, %0\n"
-      "ds_read_b128 %6, %13 offset:%16\n"
-      "ds_read_b128 %7, %13 offset:%17\n"
-      "v_mfma_f32_32x32x16_bf16 %1, %9, %12, %1\n"
-      "v_mfma_f32_32x32x16_bf16 %2, %10, %12, %2\n"
-      "v_mfma_f32_32x32x16_bf16 %3, %11, %12, %3\n"
+      "s_waitcnt vmcnt(%21)\n"
+      "ds_read_b128 %4, %14 offset:%17\n"
+      "ds_read_b128 %5, %14 offset:%18\n"
+      "v_mfma_f32_32x32x16_bf16 %0, %9, %13, %0\n"
+      "global_load_dwordx4 %8, %15, %16\n"
+      "ds_read_b128 %6, %14 offset:%19\n"
+      "ds_read_b128 %7, %14 offset:%20\n"
+      "v_mfma_f32_32x32x16_bf16 %1, %10, %13, %1\n"
+      "v_mfma_f32_32x32x16_bf16 %2, %11, %13, %2\n"
+      "v_mfma_f32_32x32x16_bf16 %3, %12, %13, %3\n"
       "s_waitcnt lgkmcnt(0)\n"
       : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]), "=&v"(fn[0]), "=&v"(fn[1]), "=&v"(fn[2]),
-        "=&v"(fn[3])
-      : "v"(fa[0]), "v"(fa[1]), "v"(fa[2]), "v"(fa[3]), "v"(b), "v"(lds), "n"(O), "n"(O + WS_RB),
-        "n"(O + 2 * WS_RB), "n"(O + 3 * WS_RB)
+        "=&v"(fn[3]), "=&v"(n0)
+      : "v"(fa[0]), "v"(fa[1]), "v"(fa[2]), "v"(fa[3]), "v"(b), "v"(lds), "v"(voff), "s"(src), "n"(O),
+        "n"(O + WS_RB), "n"(O + 2 * WS_RB), "n"(O + 3 * WS_RB), "n"(VM)
       : "memory");
+}
+
+// One 1 KB ring request outside the k-blocks (the first fills): n <- 16 bytes at src + voff (+ OFF).
+// Issued in assembly like the blocks' own requests, so that the compiler keeps no count of
+// outstanding loads for the ring at all (its own waits would drain the ring once per tile).
+template <int OFF>
+__device__ __forceinline__ void ring_request(u32x4& n, uint32_t voff, const char* src) {
+  asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3\n" : "=&v"(n) : "v"(voff), "s"(src), "n"(OFF) : "memory");
 }
 
 __device__ __forceinline__ void frag_read4(u32x4 (&f)[4], unsigned lds) {
@@ -130,16 +151,32 @@ __device__ __forceinline__ void frag_read4(u32x4 (&f)[4], unsigned lds) {
 }
 
 // The compiler does not see the MFMAs inside the blocks above, so it cannot know that the
-// accumulators may still be in the matrix pipeline: drain it before they are read.
-template <int NACC>
-__device__ __forceinline__ void drain_mfma(f32x16 (&acc)[NACC]) {
+// accumulators may still be in the matrix pipeline: drain it before they are read.  The ring's
+// last requests are still in flight as well, and nothing reads their results: without the ring
+// among the operands here the compiler would treat those registers as free from the moment of
+// the request and hand them to other values, which the late data would then overwrite.
+template <int NACC, int NR>
+__device__ __forceinline__ void drain_mfma(f32x16 (&acc)[NACC], u32x4 (&ring)[8][NR]) {
+  asm volatile("s_waitcnt vmcnt(0)\n" : "+v"(ring[0][0]), "+v"(ring[1][0]), "+v"(ring[2][0]), "+v"(ring[3][0]),
+               "+v"(ring[4][0]), "+v"(ring[5][0]), "+v"(ring[6][0]), "+v"(ring[7][0])
+               :
+               : "memory");
+  if constexpr (NR == 2)
+    asm volatile("" : "+v"(ring[0][1]), "+v"(ring[1][1]), "+v"(ring[2][1]), "+v"(ring[3][1]), "+v"(ring[4][1]),
+                 "+v"(ring[5][1]), "+v"(ring[6][1]), "+v"(ring[7][1])
+                 :
+                 : "memory");
   if constexpr (NACC == 8) {
     asm volatile("s_nop 15\ns_nop 15\ns_nop 15\ns_nop 15\n"
                  : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]), "+a"(acc[4]), "+a"(acc[5]), "+a"(acc[6]),
-                   "+a"(acc[7]));
+                   "+a"(acc[7])
+                 :
+                 : "memory");
   } else {
     asm volatile("s_nop 15\ns_nop 15\ns_nop 15\ns_nop 15\n"
-                 : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]));
+                 : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3])
+                 :
+                 : "memory");
   }
 }
 
@@ -251,24 +288,36 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
-  // ring of eight k-blocks' P fragments: slot kk % 8 is refilled, right after its use, with the
-  // k-block eight steps ahead
+  // Ring of eight k-blocks' P fragments.  Block j multiplies with slot j % 8 and requests k-block
+  // j + 7 into slot (j + 7) % 8, the slot block j - 1 has just used: seven k-blocks of distance.
+  // `preq` is the address of the next k-block to request: it walks down a tile's 16 k-blocks
+  // and jumps to the next tile's base after the tile's last one.
   u32x4 rb[8][FN];
-  auto pload = [&](int kt, auto kkc) {
-    constexpr int KK = decltype(kkc)::value;  // k-block within the tile, 0 .. 15
-    // past the last tile: one fixed block (an L1 hit), never used
-    const char* base = pbase + (kt < nk ? (int64_t)(act(kt) * WS_KB + KK) * brow : (int64_t)0);  // uniform
-#pragma unroll
-    for (int j = 0; j < FN; ++j) rb[KK & 7][j] = *reinterpret_cast<const u32x4*>(base + (j * 1024 + boff));
+  auto tile_base = [&](int kt) {
+    // past the last tile: tile 0's fragments again (valid memory, an L2 hit, never used)
+    return pbase + (kt < nk ? (int64_t)act(kt) * WS_KB * brow : (int64_t)0);  // uniform
   };
+  const char* preq = tile_base(0);
+  const char* next_base = tile_base(1);
+#pragma unroll
+  for (int kk = 0; kk < 7; ++kk) {
+    ring_request<0>(rb[kk][0], boff, preq);
+    if constexpr (FN == 2) ring_request<1024>(rb[kk][FN - 1], boff, preq);
+    preq += brow;
+  }
+  constexpr int VM = 6 * FN;  // requests younger than the ones a block is about to use
   auto kblock = [&](auto oc, const u32x4 (&fcur)[4], u32x4 (&fnext)[4], auto kkc, unsigned lds) {
     constexpr int O = decltype(oc)::value, KK = decltype(kkc)::value;
-    if constexpr (FN == 2) kblock2<O>(acc, fcur, fnext, rb[KK & 7][0], rb[KK & 7][1], lds);
-    else kblock1<O>(acc, fcur, fnext, rb[KK & 7][0], lds);
+    if constexpr (FN == 2)
+      kblock2<O, VM>(acc, fcur, fnext, rb[KK & 7][0], rb[KK & 7][1], lds, rb[(KK + 7) & 7][0], rb[(KK + 7) & 7][1],
+                     boff, preq);
+    else
+      kblock1<O, VM>(acc, fcur, fnext, rb[KK & 7][0], lds, rb[(KK + 7) & 7][0], boff, preq);
+    // the next request is k-block KK + 8 of this tile, or the next tile's first one
+    if constexpr (KK == 8) preq = next_base;
+    else preq += brow;
   };
 #define PRAC_IC(v) std::integral_constant<int, (v)> {}
-  pload(0, PRAC_IC(0)); pload(0, PRAC_IC(1)); pload(0, PRAC_IC(2)); pload(0, PRAC_IC(3));
-  pload(0, PRAC_IC(4)); pload(0, PRAC_IC(5)); pload(0, PRAC_IC(6)); pload(0, PRAC_IC(7));
 
   // LDS byte address of this lane's A fragment of row block 0, k-block 0, stage 0:
   // row li, 16-byte half lh of the k-block
@@ -289,13 +338,15 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
       if constexpr (J == WS_KB - 1) __builtin_amdgcn_s_barrier();
       if constexpr (J % 2 == 0) kblock(PRAC_IC(32 * ((J + 1) % WS_KB)), fa, fb, jc, J == WS_KB - 1 ? nxt : cur);
       else kblock(PRAC_IC(32 * ((J + 1) % WS_KB)), fb, fa, jc, J == WS_KB - 1 ? nxt : cur);
-      if constexpr (J < 8) pload(kt, PRAC_IC(J + 8));
-      else pload(kt + 1, PRAC_IC(J - 8));
       if constexpr (J % IV == IV - 1 && J != WS_KB - 1) __builtin_amdgcn_s_barrier();
     });
+    next_base = tile_base(kt + 2);
+    // Drain inside the loop: at the loop's exit the compiler may move accumulators between
+    // registers (it has no idea that matrix instructions are still writing them), and such
+    // moves must find the pipeline empty.
+    if (kt == nk - 1) drain_mfma<NACC, FN>(acc, rb);
   }
 #undef PRAC_IC
-  drain_mfma<NACC>(acc);
 
   // epilogue: block (i, j) = acc[i * FN + j]; register v of lane (li, lh) is token row
   // 8*(v/4) + 4*lh + v%4 of row block i, column li of column block cb0 + j.
@@ -409,28 +460,34 @@ constexpr int CW_STAGE = 8 * 4 * 1024;  // bytes per LDS stage
 constexpr int CW_STAGES = 3;
 
 // One k-block of a 64 x 128 wave tile: acc[4 i + j] += a_i * f_j, while the four B fragments at
-// byte offsets O + 1024 nb from `lds` are read into fn.
-template <int O>
+// byte offsets O + 1024 nb from `lds` are read into fn.  Like the compress kernel's blocks it
+// issues the two requests that refill another slot of the ring of C fragments (n0 <- src + v0,
+// n1 <- src + v1) and starts with its own wait for the fragments it multiplies.
+template <int O, int VM>
 __device__ __forceinline__ void kblock_ct(f32x16 (&acc)[8], const u32x4 (&fc)[4], u32x4 (&fn)[4], const u32x4& a0,
-                                          const u32x4& a1, unsigned lds) {
+                                          const u32x4& a1, unsigned lds, u32x4& n0, u32x4& n1, uint32_t v0,
+                                          uint32_t v1, const char* src) {
   asm volatile(
-      "ds_read_b128 %8, %18 offset:%19\n"
-      "v_mfma_f32_32x32x16_bf16 %0, %16, %12, %0\n"
-      "ds_read_b128 %9, %18 offset:%20\n"
-      "v_mfma_f32_32x32x16_bf16 %4, %17, %12, %4\n"
-      "ds_read_b128 %10, %18 offset:%21\n"
-      "v_mfma_f32_32x32x16_bf16 %1, %16, %13, %1\n"
-      "ds_read_b128 %11, %18 offset:%22\n"
-      "v_mfma_f32_32x32x16_bf16 %5, %17, %13, %5\n"
-      "v_mfma_f32_32x32x16_bf16 %2, %16, %14, %2\n"
-      "v_mfma_f32_32x32x16_bf16 %6, %17, %14, %6\n"
-      "v_mfma_f32_32x32x16_bf16 %3, %16, %15, %3\n"
-      "v_mfma_f32_32x32x16_bf16 %7, %17, %15, %7\n"
+      "s_waitcnt vmcnt(%28)\n"
+      "ds_read_b128 %8, %20 offset:%24\n"
+      "v_mfma_f32_32x32x16_bf16 %0, %18, %14, %0\n"
+      "ds_read_b128 %9, %20 offset:%25\n"
+      "v_mfma_f32_32x32x16_bf16 %4, %19, %14, %4\n"
+      "global_load_dwordx4 %12, %21, %23\n"
+      "ds_read_b128 %10, %20 offset:%26\n"
+      "v_mfma_f32_32x32x16_bf16 %1, %18, %15, %1\n"
+      "global_load_dwordx4 %13, %22, %23\n"
+      "ds_read_b128 %11, %20 offset:%27\n"
+      "v_mfma_f32_32x32x16_bf16 %5, %19, %15, %5\n"
+      "v_mfma_f32_32x32x16_bf16 %2, %18, %16, %2\n"
+      "v_mfma_f32_32x32x16_bf16 %6, %19, %16, %6\n"
+      "v_mfma_f32_32x32x16_bf16 %3, %18, %17, %3\n"
+      "v_mfma_f32_32x32x16_bf16 %7, %19, %17, %7\n"
       "s_waitcnt lgkmcnt(0)\n"
       : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]), "+a"(acc[4]), "+a"(acc[5]), "+a"(acc[6]),
-        "+a"(acc[7]), "=&v"(fn[0]), "=&v"(fn[1]), "=&v"(fn[2]), "=&v"(fn[3])
-      : "v"(fc[0]), "v"(fc[1]), "v"(fc[2]), "v"(fc[3]), "v"(a0), "v"(a1), "v"(lds), "n"(O), "n"(O + 1024),
-        "n"(O + 2048), "n"(O + 3072)
+        "+a"(acc[7]), "=&v"(fn[0]), "=&v"(fn[1]), "=&v"(fn[2]), "=&v"(fn[3]), "=&v"(n0), "=&v"(n1)
+      : "v"(fc[0]), "v"(fc[1]), "v"(fc[2]), "v"(fc[3]), "v"(a0), "v"(a1), "v"(lds), "v"(v0), "v"(v1), "s"(src), "n"(O),
+        "n"(O + 1024), "n"(O + 2048), "n"(O + 3072), "n"(VM)
       : "memory");
 }
 
@@ -546,17 +603,31 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
     const uint32_t aoff1 = (uint32_t)((cb0 + 1 < a.ccb ? cb0 + 1 : 0) * 64 + lane) * 16u;
     const int64_t tbrow = (int64_t)a.ccb * 1024;  // bytes per 16-token block of packed C
 
+    // Ring of eight k-blocks' C fragments (16 tokens each): block j multiplies with slot j % 8 and
+    // requests token block j + 7 into the slot block j - 1 has just used.  Token blocks follow each
+    // other in memory, so the request address just advances; it stops at the last token block of
+    // packed C (requests past the split's end are never used).
     u32x4 rc[8][2];
-    auto aload = [&](int kt, auto kkc) {
-      constexpr int KK = decltype(kkc)::value;
-      const int tb = kt < nk ? tok_beg / 16 + kt * 8 + KK : tok_beg / 16;
-      const char* base = cbase + (int64_t)min(tb, ntb - 1) * tbrow;  // uniform
-      rc[KK][0] = *reinterpret_cast<const u32x4*>(base + aoff0);
-      rc[KK][1] = *reinterpret_cast<const u32x4*>(base + aoff1);
+    const char* creq = cbase + (int64_t)(tok_beg / 16) * tbrow;  // uniform
+    const char* const clast = cbase + (int64_t)(ntb - 1) * tbrow;
+    auto advance = [&]() {
+      creq += tbrow;
+      if (creq > clast) creq = clast;
     };
+#pragma unroll
+    for (int kk = 0; kk < 7; ++kk) {
+      ring_request<0>(rc[kk][0], aoff0, creq);
+      ring_request<0>(rc[kk][1], aoff1, creq);
+      advance();
+    }
+    constexpr int VM = 12;  // requests younger than the ones a block is about to use
 #define PRAC_IC(v) std::integral_constant<int, (v)> {}
-    aload(0, PRAC_IC(0)); aload(0, PRAC_IC(1)); aload(0, PRAC_IC(2)); aload(0, PRAC_IC(3));
-    aload(0, PRAC_IC(4)); aload(0, PRAC_IC(5)); aload(0, PRAC_IC(6)); aload(0, PRAC_IC(7));
+    auto kblock = [&](auto oc, const u32x4 (&fcur)[4], u32x4 (&fnext)[4], auto kkc, unsigned lds) {
+      constexpr int O = decltype(oc)::value, KK = decltype(kkc)::value;
+      kblock_ct<O, VM>(acc, fcur, fnext, rc[KK][0], rc[KK][1], lds, rc[(KK + 7) & 7][0], rc[(KK + 7) & 7][1], aoff0,
+                       aoff1, creq);
+      advance();
+    };
 
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw +
                           (unsigned)(frag_slot(li, lh) * 16);
@@ -568,18 +639,18 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
       const unsigned cur = lds0 + (unsigned)stage * CW_STAGE;
       stage = stage == CW_STAGES - 1 ? 0 : stage + 1;
       const unsigned nxt = lds0 + (unsigned)stage * CW_STAGE;
-      kblock_ct<4096 * 1>(acc, fa, fb, rc[0][0], rc[0][1], cur); aload(kt + 1, PRAC_IC(0));
-      kblock_ct<4096 * 2>(acc, fb, fa, rc[1][0], rc[1][1], cur); aload(kt + 1, PRAC_IC(1));
-      kblock_ct<4096 * 3>(acc, fa, fb, rc[2][0], rc[2][1], cur); aload(kt + 1, PRAC_IC(2));
-      kblock_ct<4096 * 4>(acc, fb, fa, rc[3][0], rc[3][1], cur); aload(kt + 1, PRAC_IC(3));
-      kblock_ct<4096 * 5>(acc, fa, fb, rc[4][0], rc[4][1], cur); aload(kt + 1, PRAC_IC(4));
-      kblock_ct<4096 * 6>(acc, fb, fa, rc[5][0], rc[5][1], cur); aload(kt + 1, PRAC_IC(5));
-      kblock_ct<4096 * 7>(acc, fa, fb, rc[6][0], rc[6][1], cur); aload(kt + 1, PRAC_IC(6));
+      kblock(PRAC_IC(4096 * 1), fa, fb, PRAC_IC(0), cur);
+      kblock(PRAC_IC(4096 * 2), fb, fa, PRAC_IC(1), cur);
+      kblock(PRAC_IC(4096 * 3), fa, fb, PRAC_IC(2), cur);
+      kblock(PRAC_IC(4096 * 4), fb, fa, PRAC_IC(3), cur);
+      kblock(PRAC_IC(4096 * 5), fa, fb, PRAC_IC(4), cur);
+      kblock(PRAC_IC(4096 * 6), fb, fa, PRAC_IC(5), cur);
+      kblock(PRAC_IC(4096 * 7), fa, fb, PRAC_IC(6), cur);
       __builtin_amdgcn_s_barrier();
-      kblock_ct<0>(acc, fb, fa, rc[7][0], rc[7][1], nxt); aload(kt + 1, PRAC_IC(7));
+      kblock(PRAC_IC(0), fb, fa, PRAC_IC(7), nxt);
+      if (kt == nk - 1) drain_mfma<8, 2>(acc, rc);  // inside the loop, see the compress kernel
     }
 #undef PRAC_IC
-    drain_mfma<8>(acc);
   }
 
   // epilogue: acc[4 i + j], register v of lane (li, lh): T row 32 (cb0 + i) + 8*(v/4) + 4*lh + v%4,
