@@ -102,6 +102,8 @@ def main():
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--cpu-sample", type=int, default=1, help="0: skip the oracle's timed run on the host")
+    ap.add_argument("--others", type=int, default=1,
+                    help="0: skip timing the fused forward and the reconstruction (outside the timed region)")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="after the timed region, also run three plain device copies of this many MB "
                          "(a kernel of known traffic, for scaling rocprofv3 --pmc byte counters)")
@@ -172,6 +174,30 @@ def main():
     torch.cuda.synchronize()
     fit_ms = 1e3 * (time.perf_counter() - t0)
 
+    # the other entry points of the path at the same shape, outside the timed region: forward
+    # fused with the compression (W stored m x d, the layout of Section 5.2) and the reconstruction
+    other_us = {}
+    if args.others:
+        g = torch.Generator(device=dev)
+        g.manual_seed(3200)
+        W = (torch.randn((m, d), generator=g, device=dev) * 0.02).to(torch.bfloat16)
+        Y = torch.empty((N, m), dtype=torch.bfloat16, device=dev)
+        for kind, fn in (("fused_fwd", lambda i: ctx.compress_fused_fwd(Xs[i], W, P, w_layout=1, P_lp=state["lp"], Y=Y,
+                                                                        out=Cs[i], layout=C_PACKED)),
+                         ("reconstruct", lambda i: ctx.reconstruct(Cs[i], P, k, r, state["scale"], N=N, out=Y,
+                                                                   layout=C_PACKED))):
+            fn(0)
+            ctx.profile_select(KERNEL_KINDS[kind])
+            for t in range(8):
+                fn(t % w["n_sets"])
+            ms, n = ctx.profile_read()
+            other_us[kind] = 1e3 * ms / max(n, 1)
+        del W, Y
+        ctx.profile_select(KERNEL_KINDS[dominant])
+        ctx.profile_read()
+        for i in range(w["n_sets"]):  # C was overwritten by the fused launches with the same values
+            ctx.compress(Xs[i], P, P_lp=state["lp"], out=Cs[i], layout=C_PACKED)
+
     state["fits"] = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -221,6 +247,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels_us": per_kernel_us,
+        "other_entry_points_us": other_us,
         "fit_basis_ms": fit_ms,
     }
     print(json.dumps(out))
