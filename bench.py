@@ -193,6 +193,26 @@ def main():
             ms, n = ctx.profile_read()
             other_us[kind] = 1e3 * ms / max(n, 1)
         del W, Y
+        # query / key / value gradients from the one compressed activation they share (Section 5.1):
+        # one call for the three against three calls, wall clock over 8 repetitions each
+        dY3 = [dYs[0], dYs[1], dYs[2]]
+        dW3 = [torch.empty((d, m), dtype=torch.bfloat16, device=dev) for _ in range(3)]
+        ctx.profile_select(0)
+
+        def wall(fn, reps=8):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return 1e6 * (time.perf_counter() - t0) / reps
+
+        other_us["wgrad_qkv_shared"] = wall(lambda: ctx.weight_grad_shared(
+            Cs[0], dY3, P, k, r, state["scale"], P_lp=state["lp"], outs=dW3, layout=C_PACKED))
+        other_us["wgrad_qkv_three_calls"] = wall(lambda: [ctx.weight_grad(
+            Cs[0], y, P, k, r, state["scale"], P_lp=state["lp"], out=o, layout=C_PACKED) for y, o in zip(dY3, dW3)])
+        del dW3
         ctx.profile_select(KERNEL_KINDS[dominant])
         ctx.profile_read()
         for i in range(w["n_sets"]):  # C was overwritten by the fused launches with the same values

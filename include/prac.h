@@ -181,6 +181,21 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
                      const void* P_lp, int64_t d, int64_t ldp, int k, int r, float scale,
                      void* dW, prac_dtype odt, int64_t lddw, float beta);
 
+/* Several layers that read the same input share one compressed activation
+ * (Section 5.1, "activation subspace sharing": the query / key / value or the
+ * up / gate projections).  n_out (1..PRAC_MAX_SHARED) weight gradients
+ * dW_h = beta * dW_h + X~^T dY_h from one C: the token-split partial sums of all
+ * C^T dY_h are formed in one launch, so C is streamed once and the split can
+ * be coarser than for one output alone.  dY, m, lddy, dW, lddw are [host] arrays
+ * of n_out entries (dY[h], dW[h] device pointers; dW_h is d x m[h]); everything
+ * else as in prac_weight_grad, which is this call with n_out = 1. */
+#define PRAC_MAX_SHARED 4
+int prac_weight_grad_shared(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int64_t ldc,
+                            int c_layout, int n_out, const void* const* dY, const int64_t* m,
+                            const int64_t* lddy, const float* P, const void* P_lp, int64_t d,
+                            int64_t ldp, int k, int r, float scale, void* const* dW,
+                            prac_dtype odt, const int64_t* lddw, float beta);
+
 /* ---- reconstruction (Section 5.1 formula; Alg. 2 backward, first step) ------ */
 /* Xh (N x d, ldxh >= d, dtype dt) = C[:, :k] Q1^T + scale * C[:, k:] Q2^T: the
  * unbiased estimate of the saved activation, for layers whose backward needs

@@ -464,66 +464,17 @@ int prac_compress_fused_fwd(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_
   return compress_impl(ctx, X, xdt, N, d, ldx, W, m, ldw, w_layout, P, P_lp, ldp, c, Y, ldy, C, ldc, c_layout);
 }
 
+}  // extern "C"
+
 // ------------------------------------------------------------------ weight grad
-int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt, int64_t N, int64_t m, int64_t ldc,
-                     int c_layout, int64_t lddy, const float* P, const void* P_lp, int64_t d, int64_t ldp, int k,
-                     int r, float scale, void* dW, prac_dtype odt, int64_t lddw, float beta) {
-  if (!C || !dY || !P || !dW || !valid_dtype(dt) || !valid_dtype(odt) || N < 1 || m < 1 || m > (1 << 20) || d < 1 ||
-      d > (1 << 20) || k < 0 || r < 0 || k + r < 1 || (int64_t)k + r > d || bad_c_layout(c_layout, ldc, k + r) ||
-      lddy < m || ldp < k + r || lddw < m || (P_lp && !aligned16(P_lp)))
-    return PRAC_EINVAL;
-  if (!ctx) return PRAC_ENOCTX;
+namespace {
+
+// One gradient through the strided kernels (fp32 data, unaligned bf16): T = C^T dY (fp32), scale
+// the random rows, dW = P T.
+int weight_grad_generic(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt, int64_t N, int64_t m, int64_t ldc,
+                        bool packed, int64_t lddy, const float* P, int64_t d, int64_t ldp, int k, int r, float scale,
+                        void* dW, prac_dtype odt, int64_t lddw, float beta) {
   const int c = k + r;
-  const bool packed = c_layout == PRAC_C_PACKED;
-  if (packed && (dt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
-  const bool fast = dt == PRAC_BF16 && aligned16(dY) && lddy % 8 == 0 && N < ((int64_t)1 << 31);
-  if (fast) {
-    const LpLayout l = lp_layout(d, c);
-    const int tiles = ((c + 255) / 256) * (int)((m + 127) / 128);
-    int splits = (ctx->n_cu + tiles - 1) / tiles;          // about one workgroup per CU
-    if (splits > N / 256) splits = (int)(N / 256);
-    if (splits < 1) splits = 1;
-    if (splits > 64) splits = 64;
-    if (ctx->tune_splits > 0) splits = ctx->tune_splits;
-    const int nmb = (int)round_up64((m + 31) / 32, 4);  // 32-column blocks of T, whole 128-column tiles
-    WsPlan plan;
-    const size_t o_part = plan.take((size_t)splits * c * m * sizeof(float));
-    const size_t o_t = plan.take((size_t)l.nckb * nmb * 64 * 8 * sizeof(bf16_t));
-    const size_t o_lp = plan.take(P_lp ? 0 : l.bytes);
-    const size_t o_cpk = plan.take(packed ? 0 : packed_c_bytes(N, c));
-    int rc = prac_ws_reserve(ctx, plan.off);
-    if (rc) return rc;
-    const char* lp = reinterpret_cast<const char*>(P_lp);
-    if (!lp) {
-      rc = prac_pack_basis(ctx, P, d, ldp, c, ctx->ws + o_lp);
-      if (rc) return rc;
-      lp = ctx->ws + o_lp;
-    }
-    const bf16_t* Cpk = reinterpret_cast<const bf16_t*>(C);
-    if (!packed) {
-      rc = launch_pack_c(ctx, reinterpret_cast<const bf16_t*>(C), ldc, (int)N, c,
-                         reinterpret_cast<bf16_t*>(ctx->ws + o_cpk));
-      if (rc) return rc;
-      Cpk = reinterpret_cast<const bf16_t*>(ctx->ws + o_cpk);
-    }
-    float* part = reinterpret_cast<float*>(ctx->ws + o_part);
-    bf16_t* Tf = reinterpret_cast<bf16_t*>(ctx->ws + o_t);
-    {  // T = C^T dY as `splits` partial slabs over the token range
-      ProfScope ps(ctx, PRAC_KERNEL_CT_DY);
-      rc = launch_ctdy_ws(ctx, Cpk, c, reinterpret_cast<const bf16_t*>(dY), lddy, (int)N, (int)m, part, splits);
-    }
-    if (rc) return rc;
-    {  // T in fragment order (bf16): slabs summed, random rows weighted by the scaling factor
-      ProfScope ps(ctx, PRAC_KERNEL_T_REDUCE);
-      rc = launch_reduce_to_tfrag(ctx, part, splits, c, (int)m, k, scale, l.nckb, nmb, Tf);
-    }
-    if (rc) return rc;
-    // dW = P T
-    ProfScope ps(ctx, PRAC_KERNEL_P_T);
-    return launch_pt(ctx, reinterpret_cast<const bf16_t*>(lp + l.off_pa), Tf, (int)d, (int)m, l.nckb, nmb, dW, lddw,
-                     odt == PRAC_BF16, beta);
-  }
-  // generic path: T = C^T dY (fp32), scale the random rows, dW = P T
   WsPlan plan;
   const size_t o_t = plan.take((size_t)c * m * sizeof(float));
   const size_t o_dw = plan.take(odt == PRAC_BF16 ? (size_t)d * m * sizeof(float) : 0);
@@ -562,6 +513,110 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
   rc = launch_gemm_generic(ctx, h);
   if (rc) return rc;
   return launch_cast_out(ctx, tmp, m, dW, PRAC_BF16, lddw, (int)d, (int)m, beta);
+}
+
+// n_out gradients from one C on the bf16 kernels: one launch forms the token-split slabs of every
+// C^T dY_h, then each output gets its slab reduction and its dW_h = P T_h.
+int weight_grad_fast(prac_ctx* ctx, const void* C, int64_t N, int64_t ldc, bool packed, int n_out,
+                     const void* const* dY, const int64_t* m, const int64_t* lddy, const float* P, const void* P_lp,
+                     int64_t d, int64_t ldp, int k, int r, float scale, void* const* dW, prac_dtype odt,
+                     const int64_t* lddw, float beta) {
+  const int c = k + r;
+  const LpLayout l = lp_layout(d, c);
+  int tiles = 0;
+  for (int h = 0; h < n_out; ++h) tiles += ((c + 255) / 256) * (int)((m[h] + 127) / 128);
+  // one workgroup per CU at most: a second, partly filled round would cost a whole workgroup time
+  int splits = ctx->n_cu / tiles;
+  if (splits > N / 256) splits = (int)(N / 256);
+  if (splits < 1) splits = 1;
+  if (splits > 64) splits = 64;
+  if (ctx->tune_splits > 0) splits = ctx->tune_splits;
+  WsPlan plan;
+  size_t o_part[PRAC_CTDY_MAX_OUT], o_t[PRAC_CTDY_MAX_OUT];
+  int nmb[PRAC_CTDY_MAX_OUT];
+  for (int h = 0; h < n_out; ++h) {
+    nmb[h] = (int)round_up64((m[h] + 31) / 32, 4);  // 32-column blocks of T, whole 128-column tiles
+    o_part[h] = plan.take((size_t)splits * c * m[h] * sizeof(float));
+    o_t[h] = plan.take((size_t)l.nckb * nmb[h] * 64 * 8 * sizeof(bf16_t));
+  }
+  const size_t o_lp = plan.take(P_lp ? 0 : l.bytes);
+  const size_t o_cpk = plan.take(packed ? 0 : packed_c_bytes(N, c));
+  int rc = prac_ws_reserve(ctx, plan.off);
+  if (rc) return rc;
+  const char* lp = reinterpret_cast<const char*>(P_lp);
+  if (!lp) {
+    rc = prac_pack_basis(ctx, P, d, ldp, c, ctx->ws + o_lp);
+    if (rc) return rc;
+    lp = ctx->ws + o_lp;
+  }
+  const bf16_t* Cpk = reinterpret_cast<const bf16_t*>(C);
+  if (!packed) {
+    rc = launch_pack_c(ctx, reinterpret_cast<const bf16_t*>(C), ldc, (int)N, c, reinterpret_cast<bf16_t*>(ctx->ws + o_cpk));
+    if (rc) return rc;
+    Cpk = reinterpret_cast<const bf16_t*>(ctx->ws + o_cpk);
+  }
+  const bf16_t* dYp[PRAC_CTDY_MAX_OUT];
+  float* part[PRAC_CTDY_MAX_OUT];
+  int mi[PRAC_CTDY_MAX_OUT];
+  for (int h = 0; h < n_out; ++h) {
+    dYp[h] = reinterpret_cast<const bf16_t*>(dY[h]);
+    part[h] = reinterpret_cast<float*>(ctx->ws + o_part[h]);
+    mi[h] = (int)m[h];
+  }
+  {  // T_h = C^T dY_h as `splits` partial slabs over the token range
+    ProfScope ps(ctx, PRAC_KERNEL_CT_DY);
+    rc = launch_ctdy_ws(ctx, Cpk, c, (int)N, n_out, dYp, lddy, mi, part, splits);
+  }
+  if (rc) return rc;
+  for (int h = 0; h < n_out; ++h) {
+    bf16_t* Tf = reinterpret_cast<bf16_t*>(ctx->ws + o_t[h]);
+    {  // T in fragment order (bf16): slabs summed, random rows weighted by the scaling factor
+      ProfScope ps(ctx, PRAC_KERNEL_T_REDUCE);
+      rc = launch_reduce_to_tfrag(ctx, part[h], splits, c, mi[h], k, scale, l.nckb, nmb[h], Tf);
+    }
+    if (rc) return rc;
+    ProfScope ps(ctx, PRAC_KERNEL_P_T);  // dW = P T
+    rc = launch_pt(ctx, reinterpret_cast<const bf16_t*>(lp + l.off_pa), Tf, (int)d, mi[h], l.nckb, nmb[h], dW[h], lddw[h],
+                   odt == PRAC_BF16, beta);
+    if (rc) return rc;
+  }
+  return PRAC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt, int64_t N, int64_t m, int64_t ldc,
+                     int c_layout, int64_t lddy, const float* P, const void* P_lp, int64_t d, int64_t ldp, int k,
+                     int r, float scale, void* dW, prac_dtype odt, int64_t lddw, float beta) {
+  return prac_weight_grad_shared(ctx, C, dt, N, ldc, c_layout, 1, &dY, &m, &lddy, P, P_lp, d, ldp, k, r, scale, &dW, odt,
+                                 &lddw, beta);
+}
+
+int prac_weight_grad_shared(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int64_t ldc, int c_layout, int n_out,
+                            const void* const* dY, const int64_t* m, const int64_t* lddy, const float* P,
+                            const void* P_lp, int64_t d, int64_t ldp, int k, int r, float scale, void* const* dW,
+                            prac_dtype odt, const int64_t* lddw, float beta) {
+  if (!C || !dY || !m || !lddy || !dW || !lddw || !P || n_out < 1 || n_out > PRAC_MAX_SHARED || !valid_dtype(dt) ||
+      !valid_dtype(odt) || N < 1 || d < 1 || d > (1 << 20) || k < 0 || r < 0 || k + r < 1 || (int64_t)k + r > d ||
+      bad_c_layout(c_layout, ldc, k + r) || ldp < k + r || (P_lp && !aligned16(P_lp)))
+    return PRAC_EINVAL;
+  for (int h = 0; h < n_out; ++h)
+    if (!dY[h] || !dW[h] || m[h] < 1 || m[h] > (1 << 20) || lddy[h] < m[h] || lddw[h] < m[h]) return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  const bool packed = c_layout == PRAC_C_PACKED;
+  if (packed && (dt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
+  bool fast = dt == PRAC_BF16 && N < ((int64_t)1 << 31);
+  for (int h = 0; h < n_out; ++h) fast = fast && aligned16(dY[h]) && lddy[h] % 8 == 0;
+  if (fast)
+    return weight_grad_fast(ctx, C, N, ldc, packed, n_out, dY, m, lddy, P, P_lp, d, ldp, k, r, scale, dW, odt, lddw, beta);
+  for (int h = 0; h < n_out; ++h) {
+    int rc = weight_grad_generic(ctx, C, dY[h], dt, N, m[h], ldc, packed, lddy[h], P, d, ldp, k, r, scale, dW[h], odt,
+                                 lddw[h], beta);
+    if (rc) return rc;
+  }
+  return PRAC_OK;
 }
 
 }  // extern "C"

@@ -122,8 +122,10 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
 // W (bf16; w_layout 0: d x m, 1: m x d; ldw) -> [nkb][ncb_w][64][8] fragment order, zero padded
 int launch_pack_wfrag(prac_ctx* ctx, const bf16_t* W, int64_t ldw, int w_layout, int64_t d, int m, int nkb,
                       int ncb_w, bf16_t* out);
-int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, int64_t lddy, int N, int m,
-                   float* slabs, int splits);
+// token-split partial sums of C^T dY_h for n_out outputs that share C; slabs[h] is splits x c x m[h]
+#define PRAC_CTDY_MAX_OUT 4
+int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, int N, int n_out, const bf16_t* const* dY,
+                   const int64_t* lddy, const int* m, float* const* slabs, int splits);
 int launch_pack_pfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nkb, int ncb, bf16_t* out);
 int launch_unpack_c(prac_ctx* ctx, const bf16_t* Cpk, int N, int c, bf16_t* C, int64_t ldc);
 int launch_pack_c(prac_ctx* ctx, const bf16_t* C, int64_t ldc, int N, int c, bf16_t* Cpk);

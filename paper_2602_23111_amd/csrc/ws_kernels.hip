@@ -445,13 +445,18 @@ struct CtdyWsArgs {
   const bf16_t* Cpk;   // packed compressed activation [ntb][ccb][64][8]
   int ccb;             // 32-column blocks of C
   int c;
-  const bf16_t* dY;
-  int64_t lddy;
-  int N, m;
-  float* slabs;        // [splits][c][m]
+  int N;
+  // up to PRAC_CTDY_MAX_OUT gradients dY_h (N x m_h) that share C (layers reading the same input,
+  // Section 5.1): output h owns the column tiles tile0[h] .. tile0[h+1]-1 of the launch
+  int n_out;
+  const bf16_t* dY[PRAC_CTDY_MAX_OUT];
+  int64_t lddy[PRAC_CTDY_MAX_OUT];
+  int m[PRAC_CTDY_MAX_OUT];
+  int tile0[PRAC_CTDY_MAX_OUT + 1];
+  float* slabs[PRAC_CTDY_MAX_OUT];  // [splits][c][m_h] each
   int splits;
   int tok_per_split;   // multiple of 128
-  int tiles_n;         // column tiles of 128 over m
+  int tiles_n;         // column tiles of 128 over all outputs
   int row_groups;      // groups of 8 column blocks (256 rows of T) over c
 };
 
@@ -521,7 +526,15 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int n0 = tn * CW_BN;
+  // which output this column tile belongs to
+  int h = 0;
+#pragma unroll
+  for (int q = 1; q < PRAC_CTDY_MAX_OUT; ++q)
+    if (q < a.n_out && tn >= a.tile0[q]) h = q;
+  const bf16_t* const dYh = a.dY[h];
+  const int64_t lddyh = a.lddy[h];
+  const int mh = a.m[h];
+  const int n0 = (tn - a.tile0[h]) * CW_BN;
   const int tok_beg = split * a.tok_per_split;
   const int tok_end = min(a.N, tok_beg + a.tok_per_split);
   const int nk = tok_end > tok_beg ? (tok_end - tok_beg + CW_BK - 1) / CW_BK : 0;
@@ -533,9 +546,9 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
     if (nk == 0) return;
     const int lt = tid - 256;
     const int cc = lt & 15, tg = lt >> 4, kb = tg >> 1, h = tg & 1;
-    const int last_chunk = ((a.m - 1) / 8) * 8;
-    const char* ycol = reinterpret_cast<const char*>(a.dY) + (int64_t)min(n0 + 8 * cc, last_chunk) * 2;
-    const uint32_t rowb = (uint32_t)a.lddy * 2u;
+    const int last_chunk = ((mh - 1) / 8) * 8;
+    const char* ycol = reinterpret_cast<const char*>(dYh) + (int64_t)min(n0 + 8 * cc, last_chunk) * 2;
+    const uint32_t rowb = (uint32_t)lddyh * 2u;
     // LDS byte offsets of the two lane slots this thread fills (columns 8 cc + j: j < 4 and j >= 4)
     const uint32_t sA = (uint32_t)(kb * 4096 + frag_slot(2 * cc, h) * 16);
     const uint32_t sB = (uint32_t)(kb * 4096 + frag_slot(2 * cc + 1, h) * 16);
@@ -545,7 +558,7 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
     auto gload = [&](int kt, u32x4 (&rr)[8]) {
       const bool live = kt < nk;
       const int t0 = tok_beg + min(kt, nk - 1) * CW_BK;
-      const char* base = ycol + (int64_t)t0 * a.lddy * 2;  // uniform part + this thread's column
+      const char* base = ycol + (int64_t)t0 * lddyh * 2;  // uniform part + this thread's column
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int row = min(16 * kb + c_slot_tok(h, e), a.N - 1 - t0);
@@ -655,7 +668,7 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
 
   // epilogue: acc[4 i + j], register v of lane (li, lh): T row 32 (cb0 + i) + 8*(v/4) + 4*lh + v%4,
   // column n0 + 4 li + j
-  float* out = a.slabs + (int64_t)split * a.c * a.m;
+  float* out = a.slabs[h] + (int64_t)split * a.c * mh;
   const int n = n0 + 4 * li;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
@@ -664,14 +677,14 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
     for (int v = 0; v < 16; ++v) {
       const int row = (cb0 + i) * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
       if (row < a.c) {
-        float* o = out + (int64_t)row * a.m + n;
-        if (n + 3 < a.m && (a.m & 3) == 0) {
+        float* o = out + (int64_t)row * mh + n;
+        if (n + 3 < mh && (mh & 3) == 0) {
           *reinterpret_cast<float4*>(o) =
               make_float4(acc[4 * i][v], acc[4 * i + 1][v], acc[4 * i + 2][v], acc[4 * i + 3][v]);
         } else {
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            if (n + j < a.m) o[j] = acc[4 * i + j][v];
+            if (n + j < mh) o[j] = acc[4 * i + j][v];
         }
       }
     }
@@ -725,14 +738,21 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
   return PRAC_OK;
 }
 
-int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, const bf16_t* dY, int64_t lddy, int N, int m, float* slabs,
-                   int splits) {
-  CtdyWsArgs a;
-  a.Cpk = Cpk; a.ccb = (c + 31) / 32; a.c = c; a.dY = dY; a.lddy = lddy; a.N = N; a.m = m;
-  a.slabs = slabs; a.splits = splits;
+int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, int N, int n_out, const bf16_t* const* dY,
+                   const int64_t* lddy, const int* m, float* const* slabs, int splits) {
+  if (n_out < 1 || n_out > PRAC_CTDY_MAX_OUT) return PRAC_EINVAL;
+  CtdyWsArgs a{};
+  a.Cpk = Cpk; a.ccb = (c + 31) / 32; a.c = c; a.N = N; a.n_out = n_out; a.splits = splits;
+  int tiles = 0;
+  for (int h = 0; h < n_out; ++h) {
+    a.dY[h] = dY[h]; a.lddy[h] = lddy[h]; a.m[h] = m[h]; a.slabs[h] = slabs[h];
+    a.tile0[h] = tiles;
+    tiles += (m[h] + CW_BN - 1) / CW_BN;
+  }
+  for (int h = n_out; h <= PRAC_CTDY_MAX_OUT; ++h) a.tile0[h] = tiles;
   const int ktiles = (N + CW_BK - 1) / CW_BK;
   a.tok_per_split = ((ktiles + splits - 1) / splits) * CW_BK;
-  a.tiles_n = (m + CW_BN - 1) / CW_BN;
+  a.tiles_n = tiles;
   a.row_groups = (a.ccb + 7) / 8;
   const size_t smem = (size_t)CW_STAGES * CW_STAGE;
   const int total = a.tiles_n * a.row_groups * splits;

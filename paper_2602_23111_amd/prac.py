@@ -26,7 +26,7 @@ EXPORTS = ["prac_create", "prac_destroy", "prac_set_stream", "prac_sync_status",
            "prac_last_hip_error", "prac_profile_select", "prac_profile_read", "prac_set_tuning",
            "prac_compressed_bytes", "prac_unpack_compressed", "prac_philox_words", "prac_philox_normal", "prac_gram",
            "prac_basis_lp_bytes", "prac_pack_basis", "prac_fit_basis", "prac_compress",
-           "prac_compress_fused_fwd", "prac_weight_grad", "prac_reconstruct"]
+           "prac_compress_fused_fwd", "prac_weight_grad", "prac_weight_grad_shared", "prac_reconstruct"]
 
 
 class PracError(RuntimeError):
@@ -77,6 +77,9 @@ def load_library() -> C.CDLL:
         "prac_weight_grad": (i32, [vp, vp, vp, i32, i64, i64, i64, i32, i64, vp, vp, i64, i64, i32, i32,
                                    f32, vp, i32, i64, f32]),
         "prac_reconstruct": (i32, [vp, vp, i32, i64, i64, i32, vp, i64, i64, i32, i32, f32, vp, i64]),
+        "prac_weight_grad_shared": (i32, [vp, vp, i32, i64, i64, i32, i32, C.POINTER(vp), C.POINTER(i64),
+                                          C.POINTER(i64), vp, vp, i64, i64, i32, i32, f32, C.POINTER(vp), i32,
+                                          C.POINTER(i64), f32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -263,6 +266,30 @@ class Prac:
                                          P_lp.data_ptr() if P_lp is not None else None, d, ldp, k, r, scale, pw,
                                          _dt(dW), lddw, beta), "prac_weight_grad")
         return dW
+
+    def weight_grad_shared(self, Cm: torch.Tensor, dYs, P: torch.Tensor, k: int, r: int, scale: float,
+                           P_lp: torch.Tensor | None = None, outs=None, out_dtype: torch.dtype = torch.float32,
+                           beta: float = 0.0, layout: int = C_ROWMAJOR, N: int | None = None):
+        """Weight gradients of several layers that share one compressed activation: list of dW_h."""
+        n = len(dYs)
+        pp, d, _, ldp = _mat(P)
+        if layout == C_PACKED:
+            pc, ldc, cdt = Cm.data_ptr(), 0, PRAC_BF16
+        else:
+            pc, _, _, ldc = _mat(Cm)
+            cdt = _dt(Cm)
+        ys = [_mat(y) for y in dYs]
+        Nn = ys[0][1]
+        if outs is None:
+            outs = [torch.empty((d, y[2]), dtype=out_dtype, device=dYs[0].device) for y in ys]
+        ws = [_mat(w) for w in outs]
+        arr_p = (C.c_void_p * n)
+        arr_i = (C.c_int64 * n)
+        _check(self.lib.prac_weight_grad_shared(
+            self._h, pc, cdt, Nn, ldc, layout, n, arr_p(*[y[0] for y in ys]), arr_i(*[y[2] for y in ys]),
+            arr_i(*[y[3] for y in ys]), pp, P_lp.data_ptr() if P_lp is not None else None, d, ldp, k, r, scale,
+            arr_p(*[w[0] for w in ws]), _dt(outs[0]), arr_i(*[w[3] for w in ws]), beta), "prac_weight_grad_shared")
+        return outs
 
     # ---- reconstruction
     def reconstruct(self, Cm: torch.Tensor, P: torch.Tensor, k: int, r: int, scale: float, N: int | None = None,

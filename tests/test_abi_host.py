@@ -124,6 +124,13 @@ def test_other_entry_points_reject_bad_arguments(lib):
     assert lib.prac_compressed_bytes(100, 40, 1, 1, 0) == 8 * 2 * 64 * 8 * 2
     assert lib.prac_compressed_bytes(100, 40, 1, 0, 48) == 100 * 48 * 2
     assert lib.prac_compressed_bytes(100, 40, 0, 1, 0) == 0      # packed is bf16 only
+    wgs = lib.prac_weight_grad_shared
+    ptrs, i64s = (C.c_void_p * 2)(DUMMY, DUMMY), (C.c_int64 * 2)(6, 6)
+    args = lambda n_out, lds: (None, DUMMY, 1, 8, 4, 0, n_out, ptrs, i64s, lds, DUMMY, None, 16, 4, 2, 2, 7.0, ptrs, 1,
+                               i64s, 0.0)
+    assert wgs(*args(2, i64s)) == -6
+    assert wgs(*args(0, i64s)) == -1 and wgs(*args(5, i64s)) == -1          # 1 .. PRAC_MAX_SHARED outputs
+    assert wgs(*args(2, (C.c_int64 * 2)(6, 5))) == -1                       # lddy[1] < m[1]
     rec = lib.prac_reconstruct
     assert rec(None, DUMMY, 1, 8, 4, 0, DUMMY, 16, 4, 2, 2, 7.0, DUMMY, 16) == -6
     assert rec(None, DUMMY, 1, 8, 3, 0, DUMMY, 16, 4, 2, 2, 7.0, DUMMY, 16) == -1    # ldc < k + r

@@ -155,6 +155,28 @@ def test_compress_identity_columns_bit_exact(ctx):
     assert torch.equal(got.cpu(), Xt[:, :c])
 
 
+# ------------------------------------------- several gradients from one shared C
+@pytest.mark.parametrize("dt,N,d,k,r,ms,ldy_pad", [
+    ("bf16", 2048, 512, 32, 32, (512, 512, 512), 0),        # q / k / v
+    ("bf16", 777, 328, 40, 32, (200, 136), 8),              # ragged tokens and columns, padded leading dims
+    ("bf16", 1500, 256, 128, 128, (384, 128, 128, 640), 0), # four outputs, full-width C
+    ("f32", 300, 200, 12, 12, (150, 96), 0),                # generic kernels, one output at a time
+])
+def test_weight_grad_shared_matches_oracle(ctx, dt, N, d, k, r, ms, ldy_pad):
+    c = k + r
+    s = (d - k) / r
+    rng = np.random.default_rng(N + d)
+    Ct = si.round_to(rng.standard_normal((N, c)), dt)
+    P32, P64 = basis32(d, c, seed=c)
+    dYs = [si.round_to(si.grad_output(N, m, 1e-2, seed=40 + i), dt) for i, m in enumerate(ms)]
+    dev_dY = [dev_padded(y, y.shape[1] + ldy_pad) for y in dYs]
+    outs = ctx.weight_grad_shared(Ct.to(DEV), dev_dY, P32.to(DEV), k, r, s, P_lp=ctx.pack_basis(P32.to(DEV)))
+    torch.cuda.synchronize()
+    for y, dW in zip(dYs, outs):
+        ref = orc.weight_grad(si.as_f64(Ct), si.as_f64(y), P64, k, s)
+        assert rel_fro(si.as_f64(dW), ref) < TOL[dt]
+
+
 # ------------------------------------------------------------- reconstruction
 RECON_CASES = [
     # dtype, N, d, k, r, ldc, ldxh
