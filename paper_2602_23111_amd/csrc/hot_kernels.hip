@@ -218,10 +218,10 @@ __global__ __launch_bounds__(256) void reduce_to_tfrag_kernel(const float* __res
   if (tid < 128) {
     const int nbl = tid >> 6, lane = tid & 63, j = lane & 31, h = lane >> 5;
     u32x4 o;
-    o.x = pack2(patch[8 * h + 0][nbl * 32 + j], patch[8 * h + 1][nbl * 32 + j]);
-    o.y = pack2(patch[8 * h + 2][nbl * 32 + j], patch[8 * h + 3][nbl * 32 + j]);
-    o.z = pack2(patch[8 * h + 4][nbl * 32 + j], patch[8 * h + 5][nbl * 32 + j]);
-    o.w = pack2(patch[8 * h + 6][nbl * 32 + j], patch[8 * h + 7][nbl * 32 + j]);
+    o.x = pack2_hw(patch[8 * h + 0][nbl * 32 + j], patch[8 * h + 1][nbl * 32 + j]);
+    o.y = pack2_hw(patch[8 * h + 2][nbl * 32 + j], patch[8 * h + 3][nbl * 32 + j]);
+    o.z = pack2_hw(patch[8 * h + 4][nbl * 32 + j], patch[8 * h + 5][nbl * 32 + j]);
+    o.w = pack2_hw(patch[8 * h + 6][nbl * 32 + j], patch[8 * h + 7][nbl * 32 + j]);
     reinterpret_cast<u32x4*>(Tf)[((int64_t)kb * nmb + np * 2 + nbl) * 64 + lane] = o;
   }
 }
@@ -264,8 +264,9 @@ struct PtArgs {
 
 // dW (d x m) = P T, K = c (a few hundred): both operands are read in fragment order
 // straight from L2, no LDS.  256 threads = 2 x 2 waves, a 128 x 128 tile per workgroup,
-// 64 x 64 per wave; fragments are requested PT_PD k-blocks ahead.
-constexpr int PT_PD = 8;
+// 64 x 64 per wave; fragments are requested PT_PD k-blocks ahead (c = 256 is 16 k-blocks: one round
+// of requests, one memory latency).
+constexpr int PT_PD = 16;
 constexpr int PT_TLD = 128 + 4;  // floats per row of the output staging tile
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
 #pragma unroll
     for (int t = 0; t < PT_PD; ++t) {
       mfma4(fr[t]);
-      gload(kb + PT_PD + t, fr[t]);
+      if (kb + PT_PD + t < a.nkb) gload(kb + PT_PD + t, fr[t]);
     }
   }
 #pragma unroll
@@ -355,10 +356,10 @@ __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
             x[e] += a.beta * __uint_as_float(((e & 1) ? (old[e >> 1] >> 16) : (old[e >> 1] & 0xFFFFu)) << 16);
         }
         u32x4 o;
-        o.x = pack2(x[0], x[1]);
-        o.y = pack2(x[2], x[3]);
-        o.z = pack2(x[4], x[5]);
-        o.w = pack2(x[6], x[7]);
+        o.x = pack2_hw(x[0], x[1]);
+        o.y = pack2_hw(x[2], x[3]);
+        o.z = pack2_hw(x[4], x[5]);
+        o.w = pack2_hw(x[6], x[7]);
         *reinterpret_cast<u32x4*>(q) = o;
       } else {
         for (int e = 0; e < 8 && gcol + e < a.m; ++e)
