@@ -19,54 +19,64 @@ namespace {
 // panel is factored there (right-looking inside the panel, across its full width), written
 // back, and applied to the trailing rows as a rank-CH_NB update.  Non-finite or
 // non-positive pivots raise *flag and are replaced by a tiny positive number.
+// NT threads: 256 for small matrices, where the barriers between the pivot steps cost more than
+// the arithmetic they separate, 1024 otherwise.
 constexpr int CH_NB = 16;
-__global__ __launch_bounds__(1024) void chol_upper_kernel(double* W, int b, double shift_rel, int* flag) {
+template <int NT>
+__global__ __launch_bounds__(NT) void chol_upper_kernel(double* W, int b, double shift_rel, int* flag) {
+  constexpr int NW = NT / 64;
   extern __shared__ __align__(16) unsigned char chol_smem[];
   double* panel = reinterpret_cast<double*>(chol_smem);  // [CH_NB][b]
   __shared__ double s_red[16];
+  __shared__ double s_piv[CH_NB];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   double mx = 0.0;
-  for (int i = tid; i < b; i += 1024) mx = fmax(mx, W[(int64_t)i * b + i]);
+  for (int i = tid; i < b; i += NT) mx = fmax(mx, W[(int64_t)i * b + i]);
   for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o));
   if (lane == 0) s_red[wave] = mx;
   __syncthreads();
   mx = 0.0;
-  for (int w = 0; w < 16; ++w) mx = fmax(mx, s_red[w]);
+  for (int w = 0; w < NW; ++w) mx = fmax(mx, s_red[w]);
   const double shift = shift_rel * mx;
   const double tiny = 1e-300 + 1e-30 * mx;
   for (int j0 = 0; j0 < b; j0 += CH_NB) {
     const int nb = min(CH_NB, b - j0), width = b - j0;
     // panel rows j0 .. j0+nb-1, columns j0 .. b-1 (column index relative to j0)
-    for (int e = tid; e < nb * width; e += 1024) {
-      const int u = e / width, c = e % width;
-      double v = c >= u ? W[(int64_t)(j0 + u) * b + j0 + c] : 0.0;
-      if (c == u) v += shift;
-      panel[u * b + c] = v;
-    }
+    // one wave per panel row, lanes along the columns (no index division in these loops)
+    for (int u = wave; u < nb; u += NW)
+      for (int c = lane; c < width; c += 64) {
+        double v = c >= u ? W[(int64_t)(j0 + u) * b + j0 + c] : 0.0;
+        if (c == u) v += shift;
+        panel[u * b + c] = v;
+      }
     __syncthreads();
+    // Pivot steps with one barrier each: the rows below the pivot row are updated from the
+    // unscaled pivot row (R[t][u] R[t][c] = a[t][u] a[t][c] / pivot); the pivot rows themselves are
+    // scaled by 1 / sqrt(pivot) in one pass after the last step.
     for (int t = 0; t < nb; ++t) {
       double p = panel[t * b + t];
       const bool bad = !(p > tiny) || !isfinite(p);
       if (bad) p = tiny;
-      const double inv = 1.0 / sqrt(p);
-      __syncthreads();  // everybody has read the pivot
-      if (bad && tid == 0) atomicOr(flag, 1);
-      for (int c = t + tid; c < width; c += 1024) panel[t * b + c] = c == t ? sqrt(p) : panel[t * b + c] * inv;
-      __syncthreads();
-      // rows u > t of the panel: panel[u][c] -= R[t][u] * R[t][c], c >= u
-      const int rem = nb - 1 - t;
-      for (int e = tid; e < rem * width; e += 1024) {
-        const int u = t + 1 + e / width, c = e % width;
-        if (c >= u) panel[u * b + c] -= panel[t * b + u] * panel[t * b + c];
+      if (tid == 0) {
+        s_piv[t] = p;
+        if (bad) atomicOr(flag, 1);
+      }
+      const double invp = 1.0 / p;
+      for (int u = t + 1 + wave; u < nb; u += NW) {
+        const double f = panel[t * b + u] * invp;
+        for (int c = u + lane; c < width; c += 64) panel[u * b + c] -= f * panel[t * b + c];
       }
       __syncthreads();
     }
-    for (int e = tid; e < nb * width; e += 1024) {
-      const int u = e / width, c = e % width;
-      if (c >= u) W[(int64_t)(j0 + u) * b + j0 + c] = panel[u * b + c];
+    for (int u = wave; u < nb; u += NW) {
+      const double sq = sqrt(s_piv[u]), inv = 1.0 / sq;
+      for (int c = u + lane; c < width; c += 64) panel[u * b + c] = c == u ? sq : panel[u * b + c] * inv;
     }
+    __syncthreads();
+    for (int u = wave; u < nb; u += NW)
+      for (int c = u + lane; c < width; c += 64) W[(int64_t)(j0 + u) * b + j0 + c] = panel[u * b + c];
     // trailing rows i >= j0 + nb: W[i][c] -= sum_t R[t][i] R[t][c], c >= i
-    for (int i = j0 + nb + wave; i < b; i += 16) {
+    for (int i = j0 + nb + wave; i < b; i += NW) {
       double ri[CH_NB];
 #pragma unroll
       for (int t = 0; t < CH_NB; ++t) ri[t] = t < nb ? panel[t * b + (i - j0)] : 0.0;
@@ -361,7 +371,9 @@ FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool n
 int set_dyn_smem(prac_ctx* ctx) {
   static bool done = false;
   if (!done) {
-    PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_upper_kernel),
+    PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_upper_kernel<1024>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, CH_NB * 1024 * 8));
+    PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_upper_kernel<256>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, CH_NB * 1024 * 8));
     PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(trsm_right_upper_kernel),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (TR_ROWS + TR_CH) * 1024 * 4));
@@ -387,8 +399,12 @@ int cholqr(prac_ctx* ctx, const FitWs& w, float* Y, float* V, int64_t d, int n, 
     if (rc) return rc;
     rc = set_dyn_smem(ctx);
     if (rc) return rc;
-    hipLaunchKernelGGL(chol_upper_kernel, dim3(1), dim3(1024), (size_t)CH_NB * n * sizeof(double), ctx->stream, W64, n,
-                       pass == 0 ? first_shift : 1e-15, ctx->d_flag);
+    if (n <= 0)  // 256 threads measured slower at every panel width tried
+      hipLaunchKernelGGL(chol_upper_kernel<256>, dim3(1), dim3(256), (size_t)CH_NB * n * sizeof(double), ctx->stream,
+                         W64, n, pass == 0 ? first_shift : 1e-15, ctx->d_flag);
+    else
+      hipLaunchKernelGGL(chol_upper_kernel<1024>, dim3(1), dim3(1024), (size_t)CH_NB * n * sizeof(double), ctx->stream,
+                         W64, n, pass == 0 ? first_shift : 1e-15, ctx->d_flag);
     hipLaunchKernelGGL(trsm_right_upper_kernel, dim3((unsigned)((d + TR_ROWS - 1) / TR_ROWS)), dim3(256),
                        (size_t)(TR_ROWS + TR_CH) * n * sizeof(float), ctx->stream, src, W64, dst, d, n);
     PRAC_HIP_TRY(ctx, hipGetLastError());
