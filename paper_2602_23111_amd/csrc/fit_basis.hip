@@ -190,6 +190,7 @@ __global__ __launch_bounds__(1024) void jacobi_block_kernel(double* H, int b, in
   extern __shared__ __align__(16) unsigned char jac_smem[];
   double* cols = reinterpret_cast<double*>(jac_smem);  // [2 nbk][b]
   __shared__ int s_rows[64];
+  __shared__ double s_n2[64];
   __shared__ int s_rot;
   if (sweep > 0 && counts[sweep - 1] == 0) return;  // converged in the previous sweep
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -211,6 +212,17 @@ __global__ __launch_bounds__(1024) void jacobi_block_kernel(double* H, int b, in
   if (m < 2) return;
   for (int e = tid; e < m * b; e += 1024) cols[e] = H[(int64_t)s_rows[e / b] * b + e % b];
   __syncthreads();
+  // squared norms of the local columns, kept up to date through the rotations (a rotation by
+  // tan = tt moves tt * <p, q> from one squared norm to the other), so that a pair step needs
+  // one inner product instead of three
+  for (int p = wave; p < m; p += 16) {
+    const double* hp = cols + p * b;
+    double al = 0.0;
+    for (int t = lane; t < b; t += 64) al += hp[t] * hp[t];
+    al = wave_sum_f64(al);
+    if (lane == 0) s_n2[p] = al;
+  }
+  __syncthreads();
   const int me = m + (m & 1);
   int rotated = 0;
   for (int isw = 0; isw < inner_sweeps; ++isw) {
@@ -221,22 +233,16 @@ __global__ __launch_bounds__(1024) void jacobi_block_kernel(double* H, int b, in
         if (p >= m || q >= m) continue;
         double* hp = cols + p * b;
         double* hq = cols + q * b;
-        double al = 0.0, be2 = 0.0, ga = 0.0;
-        for (int t = lane; t < b; t += 64) {
-          const double x = hp[t], y = hq[t];
-          al += x * x;
-          be2 += y * y;
-          ga += x * y;
-        }
-        al = wave_sum_f64(al);
-        be2 = wave_sum_f64(be2);
+        double ga = 0.0;
+        for (int t = lane; t < b; t += 64) ga += hp[t] * hq[t];
         ga = wave_sum_f64(ga);
+        const double al = s_n2[p], be2 = s_n2[q];
         // rotate when |ga| > tol sqrt(al be2), compared as squares
         if (ga * ga > tol * tol * al * be2 && fabs(ga) > 1e-300) {
           rotated = 1;
           // The angle may be approximate (the iteration corrects it), so tan comes from the
           // hardware reciprocal / square root estimates; (cs, sn) must be a rotation to full
-          // precision, so cs = (1 + tt^2)^-1/2 gets one Newton step on top of its estimate.
+          // precision, so cs = (1 + tt^2)^-1/2 gets Newton steps on top of its estimate.
           const double zeta = (be2 - al) * 0.5 * __builtin_amdgcn_rcp(ga);
           const double az = fabs(zeta);
           const double tt = copysign(__builtin_amdgcn_rcp(az + __builtin_amdgcn_sqrt(1.0 + az * az)), zeta);
@@ -249,6 +255,11 @@ __global__ __launch_bounds__(1024) void jacobi_block_kernel(double* H, int b, in
             const double x = hp[t], y = hq[t];
             hp[t] = cs * x - sn * y;
             hq[t] = sn * x + cs * y;
+          }
+          if (lane == 0) {
+            // exact for the rotation actually applied: |p'|^2 = cs^2 al - 2 cs sn ga + sn^2 be2
+            s_n2[p] = cs * cs * al - 2.0 * cs * sn * ga + sn * sn * be2;
+            s_n2[q] = sn * sn * al + 2.0 * cs * sn * ga + cs * cs * be2;
           }
         }
       }
@@ -515,7 +526,7 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
         for (int sweep = 0; sweep < MAX_SWEEPS; ++sweep)
           for (int step = 0; step < nblk_even - 1; ++step)
             hipLaunchKernelGGL(jacobi_block_kernel, dim3(nblk_even / 2), dim3(1024), smem, st, H, b, nbk, nblk_even,
-                               step, sweep, 2, JACOBI_TOL, counts);
+                               step, sweep, 1, JACOBI_TOL, counts);
         hipLaunchKernelGGL(jacobi_finish_kernel, dim3(16), dim3(1024), 0, st, H, b, lam, counts, MAX_SWEEPS - 1,
                            ctx->d_flag);
       }
