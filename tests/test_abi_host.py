@@ -147,3 +147,29 @@ def test_create_fails_cleanly_without_a_device(lib):
         pytest.skip("a GPU is visible")
     h = C.c_void_p()
     assert lib.prac_create(C.byref(h), 0, None) == -3 and not h.value
+
+
+def test_ws_kernels_isa_keeps_hands_off_ring_and_accumulators():
+    """The inline-assembly matrix blocks hide in-flight loads and MFMAs from the compiler; the compiled
+    code must not move those registers where it cannot know better (see lint_isa.py)."""
+    import shutil
+
+    if not (shutil.which("hipcc") or os.path.exists("/opt/rocm/bin/hipcc")):
+        pytest.skip("hipcc not available")
+    from paper_2602_23111_amd import lint_isa
+
+    assert lint_isa.lint_text(lint_isa.compile_isa()) == []
+    # the check itself: an accumulator copy between matrix blocks must be reported
+    planted = """_Zfake_ws_kernelv: ; @fake
+\t;;#ASMSTART
+v_mfma_f32_32x32x16_bf16 a[0:15], v[2:5], v[6:9], a[0:15]
+global_load_dwordx4 v[10:13], v20, s[2:3]
+\t;;#ASMEND
+\tv_accvgpr_read_b32 v30, a3
+\tv_mov_b32_e32 v11, v40
+\t;;#ASMSTART
+s_waitcnt vmcnt(0)
+\t;;#ASMEND
+.Lfunc_end0:
+"""
+    assert len(lint_isa.lint_text(planted)) == 2
