@@ -33,7 +33,8 @@ def sample_rows(n, count, seed):
     return np.sort(np.concatenate([idx, np.arange(n - 8, n)]))      # always include the last rows
 
 
-@pytest.mark.parametrize("d,ldx,k,r", [(2048, 2048, 128, 128), (5461, 5464, 128, 128), (2048, 2048, 512, 512)])
+@pytest.mark.parametrize("d,ldx,k,r", [(2048, 2048, 128, 128), (5461, 5464, 128, 128), (2048, 2048, 512, 512),
+                                       (768, 768, 64, 64), (2048, 2048, 0, 256)])   # LLaMA-130M shape; random-only basis
 def test_compress_full_size_sampled_rows(ctx, d, ldx, k, r):
     c = k + r
     X = si.activation_torch(N, d, 0.8, 3000, 8, 30.0, torch.bfloat16, DEV, ld=ldx)
@@ -52,9 +53,10 @@ def test_compress_full_size_sampled_rows(ctx, d, ldx, k, r):
     assert torch.isfinite(Cm.float()).all()
 
 
-@pytest.mark.parametrize("d,m,lddy", [(2048, 2048, 2048), (2048, 5461, 5464), (5461, 2048, 2048)])
-def test_weight_grad_full_size_sampled_columns(ctx, d, m, lddy):
-    k = r = 128
+@pytest.mark.parametrize("d,m,lddy,k,r", [(2048, 2048, 2048, 128, 128), (2048, 5461, 5464, 128, 128),
+                                          (5461, 2048, 2048, 128, 128), (768, 768, 768, 64, 64),
+                                          (2048, 2048, 2048, 0, 256)])
+def test_weight_grad_full_size_sampled_columns(ctx, d, m, lddy, k, r):
     c = k + r
     s = orc.scaling_factor(d, k, r)
     X = si.activation_torch(N, d, 0.8, 3001, 8, 30.0, torch.bfloat16, DEV)
