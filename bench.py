@@ -8,7 +8,7 @@ compress the saved activation (C = X P) and form the weight gradient
 a power-law spectrum and outlier channels, rotated over four independent input
 sets so that no step finds its inputs in the 256 MB last-level cache.
 
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line: metric, value (tokens/s), roofline of the dominant kernel, the oracle timed on the host.
 """
 from __future__ import annotations
 

@@ -99,7 +99,7 @@ def test_philox_normal_matches_and_edges(ctx):
 # ----------------------------------------------------------------- compress
 COMPRESS_CASES = [
     # dtype, N, d, c, ldx, ldc     (several 128-row tiles, ragged tails, padded leading dims)
-    ("f32", 2048, 512, 64, 512, 64),       # configs[0]
+    ("f32", 2048, 512, 64, 512, 64),       # the tiny single-layer configuration
     ("f32", 1000, 300, 37, 304, 40),
     ("bf16", 2048, 512, 64, 512, 64),
     ("bf16", 777, 328, 72, 328, 72),       # ragged rows, K tail of 8, N tail
@@ -183,7 +183,7 @@ RECON_CASES = [
     ("f32", 300, 200, 12, 12, 24, 200),
     ("f32", 300, 200, 0, 24, 24, 208),        # random part only
     ("f32", 300, 200, 24, 0, 24, 200),        # principal part only (scale unused)
-    ("bf16", 2048, 512, 32, 32, 64, 512),     # configs[0] shape
+    ("bf16", 2048, 512, 32, 32, 64, 512),     # the tiny single-layer configuration (N=2048, d=512)
     ("bf16", 777, 328, 40, 32, 72, 328),      # ragged rows, sum over 72 columns, padded tiles
     ("bf16", 130, 600, 150, 150, 304, 600),   # sum over two 256-deep tiles, three column groups
     ("bf16", 200, 101, 20, 13, 33, 101),      # unaligned leading dims -> generic kernel
@@ -259,7 +259,7 @@ def test_fused_forward_matches_oracle(ctx, dt, N, d, m, c, layout):
 # -------------------------------------------------------------- weight grad
 WGRAD_CASES = [
     # dtype, N, d, m, k, r, out dtype
-    ("f32", 2048, 512, 1376, 32, 32, "f32"),    # configs[0]
+    ("f32", 2048, 512, 1376, 32, 32, "f32"),    # the tiny single-layer configuration
     ("f32", 999, 120, 77, 5, 9, "f32"),
     ("bf16", 2048, 512, 1376, 32, 32, "f32"),
     ("bf16", 3000, 328, 264, 40, 32, "f32"),    # several token splits, ragged tiles
@@ -397,7 +397,7 @@ def test_fit_basis_without_gap_captures_the_energy(ctx):
     # no eigenvalue gap at k: the subspace is not unique, so check what is:
     # orthonormality, Q1 _|_ Q2 and the energy captured by Q1 against the oracle's top-k sum
     N, d, k, r = 2048, 512, 32, 32
-    Xt = si.round_to(si.activation(N, d, 0.8, seed=0)[0], "f32")       # configs[0] recipe
+    Xt = si.round_to(si.activation(N, d, 0.8, seed=0)[0], "f32")       # the tiny configuration's recipe (alpha 0.8, seed 0)
     P, _, _ = ctx.fit_basis(Xt.to(DEV), k, r, seed=0, draw=0, pack=False)
     ctx.sync_status()
     P64, X64 = si.as_f64(P), si.as_f64(Xt)
