@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 
 WORKLOAD = dict(name="llama1b_attn_proj", N=32768, d=2048, m=2048, k=128, r=128, alpha=0.8,
                 n_out=8, out_scale=30.0, dy_std=1e-3, refresh_every=500, n_sets=4, layer_seed=3000,
-                warm_iters=4, warm_oversample=32)
+                warm_iters=2, warm_oversample=16)
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
