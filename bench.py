@@ -192,6 +192,16 @@ def main():
                 fn(t % w["n_sets"])
             ms, n = ctx.profile_read()
             other_us[kind] = 1e3 * ms / max(n, 1)
+        # for scale: the vendor library's forward alone (torch.matmul, hipBLASLt); unfused = this + compress
+        for _ in range(3):
+            torch.matmul(Xs[0], W.t(), out=Y)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for t in range(8):
+            torch.matmul(Xs[t % w["n_sets"]], W.t(), out=Y)
+        e1.record()
+        torch.cuda.synchronize()
+        other_us["fwd_vendor_gemm"] = 1e3 * e0.elapsed_time(e1) / 8
         del W, Y
         # query / key / value gradients from the one compressed activation they share (Section 5.1):
         # one call for the three against three calls, wall clock over 8 repetitions each
