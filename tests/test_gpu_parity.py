@@ -265,7 +265,8 @@ WGRAD_CASES = [
     ("bf16", 3000, 328, 264, 40, 32, "f32"),    # several token splits, ragged tiles
     ("bf16", 1111, 200, 136, 0, 24, "f32"),     # RAC: k = 0
     ("bf16", 640, 96, 72, 16, 0, "f32"),        # PAC: r = 0 (biased, scale unused)
-    ("bf16", 900, 320, 520, 130, 130, "bf16"),  # c > 256: two row groups of T
+    ("bf16", 900, 320, 520, 130, 130, "bf16"),  # c > 256: two row groups of T, LDS-staged P T
+    ("bf16", 1500, 300, 200, 150, 140, "f32"),  # c = 290: 19 k-blocks of P T (a ragged last chunk), fp32 dW
     ("bf16", 5000, 128, 96, 10, 23, "f32"),     # c = 33: a ragged 32-column block
     ("bf16", 700, 100, 51, 7, 6, "f32"),        # unaligned -> generic kernel
 ]
