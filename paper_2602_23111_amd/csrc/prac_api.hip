@@ -655,6 +655,8 @@ int prac_reconstruct(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int
       Crm = reinterpret_cast<const bf16_t*>(ctx->ws + o_c);
     }
     ProfScope ps(ctx, PRAC_KERNEL_RECONSTRUCT);
+    if (c <= 256)
+      return launch_reconstruct_ws(ctx, Crm, ldcrm, (int)N, c, (int)d, Pt, ncb, reinterpret_cast<bf16_t*>(Xh), ldxh);
     return launch_compress_ws(ctx, Crm, ldcrm, (int)N, c, nullptr, 0, 0, nullptr, 0, false, Pt, ncb, (int)d,
                               reinterpret_cast<bf16_t*>(Xh), ldxh);
   }

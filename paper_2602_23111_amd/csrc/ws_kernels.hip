@@ -85,14 +85,14 @@ __device__ __forceinline__ void kblock2(f32x16 (&acc)[8], const u32x4 (&fa)[4], 
                                         const char* src) {
   asm volatile(
       "s_waitcnt vmcnt(%27)\n"
+      "global_load_dwordx4 %12, %21, %22\n"
+      "global_load_dwordx4 %13, %21, %22 offset:1024\n"
       "ds_read_b128 %8, %20 offset:%23\n"
       "v_mfma_f32_32x32x16_bf16 %0, %14, %18, %0\n"
       "ds_read_b128 %9, %20 offset:%24\n"
       "v_mfma_f32_32x32x16_bf16 %1, %14, %19, %1\n"
-      "global_load_dwordx4 %12, %21, %22\n"
       "ds_read_b128 %10, %20 offset:%25\n"
       "v_mfma_f32_32x32x16_bf16 %2, %15, %18, %2\n"
-      "global_load_dwordx4 %13, %21, %22 offset:1024\n"
       "ds_read_b128 %11, %20 offset:%26\n"
       "v_mfma_f32_32x32x16_bf16 %3, %15, %19, %3\n"
       "v_mfma_f32_32x32x16_bf16 %4, %16, %18, %4\n"
@@ -113,10 +113,10 @@ __device__ __forceinline__ void kblock1(f32x16 (&acc)[4], const u32x4 (&fa)[4], 
                                         unsigned lds, u32x4& n0, uint32_t voff, const char* src) {
   asm volatile(
       "s_waitcnt vmcnt(%21)\n"
+      "global_load_dwordx4 %8, %15, %16\n"
       "ds_read_b128 %4, %14 offset:%17\n"
       "ds_read_b128 %5, %14 offset:%18\n"
       "v_mfma_f32_32x32x16_bf16 %0, %9, %13, %0\n"
-      "global_load_dwordx4 %8, %15, %16\n"
       "ds_read_b128 %6, %14 offset:%19\n"
       "ds_read_b128 %7, %14 offset:%20\n"
       "v_mfma_f32_32x32x16_bf16 %1, %10, %13, %1\n"
@@ -428,6 +428,222 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
   }
 }
 
+// ------------------------------------------------------------------ reconstruction
+// X~ = C Ps^T (Section 5.1; first step of the backward pass in Alg. 2) for c <= 256: the K dimension
+// is one k-tile.  A workgroup owns 128 token rows: its C tile is put into LDS once, then the
+// matrix waves walk over the column groups (256 columns of X~ each, 64 per wave) with the same
+// k-blocks as the compress kernel, Ps^T streaming through the fragment ring.  The MFMA operands
+// are swapped (the fragment of Ps^T is the A operand), so that a lane ends up with four
+// consecutive columns of one token row per accumulator quad: after each group the matrix waves
+// write their tile as bf16 into an LDS staging tile (8 bytes per lane and store), and the other
+// four waves - idle once C is in LDS - read it back along rows and store 16 bytes per lane to
+// HBM, with their own memory counter, while the matrix waves multiply the next group.
+struct ReconWsArgs {
+  const bf16_t* C;       // row-major N x c
+  int64_t ldc;
+  int N, c, d;
+  const bf16_t* Ptfrag;  // [16][ncb][64][8]: fragments of Ps^T (k-block over c, 32-column block over d)
+  int ncb;               // multiple of 8
+  bf16_t* Xh;            // row-major N x d
+  int64_t ldxh;
+  int tiles_m;
+  int groups;            // ceil(d / 256)
+};
+
+// kblock2 with the operand roles swapped: acc[2 i + j] += b_j (as A) * fa[i] (as B).  ZERO: the
+// accumulators start from zero instead of their old contents (first k-block of a column group).
+template <int O, int VM, bool ZERO>
+__device__ __forceinline__ void kblock2t(f32x16 (&acc)[8], const u32x4 (&fa)[4], u32x4 (&fn)[4], const u32x4& b0,
+                                         const u32x4& b1, unsigned lds, u32x4& n0, u32x4& n1, uint32_t voff,
+                                         const char* src) {
+  if constexpr (ZERO) {
+    asm volatile(
+        "s_waitcnt vmcnt(%27)\n"
+        "global_load_dwordx4 %12, %21, %22\n"
+        "global_load_dwordx4 %13, %21, %22 offset:1024\n"
+        "ds_read_b128 %8, %20 offset:%23\n"
+        "v_mfma_f32_32x32x16_bf16 %0, %18, %14, 0\n"
+        "ds_read_b128 %9, %20 offset:%24\n"
+        "v_mfma_f32_32x32x16_bf16 %1, %19, %14, 0\n"
+        "ds_read_b128 %10, %20 offset:%25\n"
+        "v_mfma_f32_32x32x16_bf16 %2, %18, %15, 0\n"
+        "ds_read_b128 %11, %20 offset:%26\n"
+        "v_mfma_f32_32x32x16_bf16 %3, %19, %15, 0\n"
+        "v_mfma_f32_32x32x16_bf16 %4, %18, %16, 0\n"
+        "v_mfma_f32_32x32x16_bf16 %5, %19, %16, 0\n"
+        "v_mfma_f32_32x32x16_bf16 %6, %18, %17, 0\n"
+        "v_mfma_f32_32x32x16_bf16 %7, %19, %17, 0\n"
+        "s_waitcnt lgkmcnt(0)\n"
+        : "=&a"(acc[0]), "=&a"(acc[1]), "=&a"(acc[2]), "=&a"(acc[3]), "=&a"(acc[4]), "=&a"(acc[5]), "=&a"(acc[6]),
+          "=&a"(acc[7]), "=&v"(fn[0]), "=&v"(fn[1]), "=&v"(fn[2]), "=&v"(fn[3]), "=&v"(n0), "=&v"(n1)
+        : "v"(fa[0]), "v"(fa[1]), "v"(fa[2]), "v"(fa[3]), "v"(b0), "v"(b1), "v"(lds), "v"(voff), "s"(src), "n"(O),
+          "n"(O + WS_RB), "n"(O + 2 * WS_RB), "n"(O + 3 * WS_RB), "n"(VM)
+        : "memory");
+  } else {
+    asm volatile(
+        "s_waitcnt vmcnt(%27)\n"
+        "global_load_dwordx4 %12, %21, %22\n"
+        "global_load_dwordx4 %13, %21, %22 offset:1024\n"
+        "ds_read_b128 %8, %20 offset:%23\n"
+        "v_mfma_f32_32x32x16_bf16 %0, %18, %14, %0\n"
+        "ds_read_b128 %9, %20 offset:%24\n"
+        "v_mfma_f32_32x32x16_bf16 %1, %19, %14, %1\n"
+        "ds_read_b128 %10, %20 offset:%25\n"
+        "v_mfma_f32_32x32x16_bf16 %2, %18, %15, %2\n"
+        "ds_read_b128 %11, %20 offset:%26\n"
+        "v_mfma_f32_32x32x16_bf16 %3, %19, %15, %3\n"
+        "v_mfma_f32_32x32x16_bf16 %4, %18, %16, %4\n"
+        "v_mfma_f32_32x32x16_bf16 %5, %19, %16, %5\n"
+        "v_mfma_f32_32x32x16_bf16 %6, %18, %17, %6\n"
+        "v_mfma_f32_32x32x16_bf16 %7, %19, %17, %7\n"
+        "s_waitcnt lgkmcnt(0)\n"
+        : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]), "+a"(acc[4]), "+a"(acc[5]), "+a"(acc[6]),
+          "+a"(acc[7]), "=&v"(fn[0]), "=&v"(fn[1]), "=&v"(fn[2]), "=&v"(fn[3]), "=&v"(n0), "=&v"(n1)
+        : "v"(fa[0]), "v"(fa[1]), "v"(fa[2]), "v"(fa[3]), "v"(b0), "v"(b1), "v"(lds), "v"(voff), "s"(src), "n"(O),
+          "n"(O + WS_RB), "n"(O + 2 * WS_RB), "n"(O + 3 * WS_RB), "n"(VM)
+        : "memory");
+  }
+}
+
+constexpr int RW_OLD = 512 + 16;              // bytes per token row of the output staging tile
+constexpr int RW_OUT = WS_STAGE;              // it follows the C stage in LDS
+constexpr int RW_SMEM = WS_STAGE + WS_BM * RW_OLD;
+
+__global__ __launch_bounds__(512) void reconstruct_ws_kernel(ReconWsArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int per_xcd = (a.tiles_m + 7) / 8;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int tm = xcd * per_xcd + slot;
+  if (slot >= per_xcd || tm >= a.tiles_m) return;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m0 = tm * WS_BM;
+  const int G = a.groups;
+
+  if (wave >= 4) {
+    // ------------------------------------------------ loader, then store waves
+    const int lt = tid - 256;
+    const int crow = lt >> 5, ccol = (lt & 31) * 8;  // row crow + 8 q, 16-byte chunk at column ccol
+    {
+      const char* cbase = reinterpret_cast<const char*>(a.C + (int64_t)m0 * a.ldc);
+      const int last_chunk = ((a.c - 1) / 8) * 8;
+      const int nv = a.c - ccol;  // valid columns of this thread's chunk (<= 0: none)
+      u32x4 rc[16];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int row = min(m0 + crow + 8 * q, a.N - 1) - m0;  // rows past N repeat the last one, never stored
+        rc[q] = *reinterpret_cast<const u32x4*>(cbase + ((int64_t)row * a.ldc + min(ccol, last_chunk)) * 2);
+      }
+      unsigned char* st = smem_raw + (crow * WS_LD + ccol) * 2;
+#pragma unroll
+      for (int q = 0; q < 16; ++q)
+        *reinterpret_cast<u32x4*>(st + q * (8 * WS_LD * 2)) = nv >= 8 ? rc[q] : keep_first(rc[q], nv > 0 ? nv : 0);
+    }
+    __syncthreads();  // the C tile is in LDS
+    // From here on plain barriers (no memory fence: a fence would wait for this wave's own stores
+    // to HBM); LDS traffic is ordered by explicit waits, and the empty statements keep the
+    // compiler from moving memory accesses across them.
+    __builtin_amdgcn_s_barrier();  // staging tile free (first group)
+    const bool vec_ok = (a.ldxh % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.Xh) & 15) == 0);
+    for (int g = 0; g < G; ++g) {
+      __builtin_amdgcn_s_barrier();  // staging tile holds group g
+      asm volatile("" ::: "memory");
+      u32x4 ro[16];
+#pragma unroll
+      for (int q = 0; q < 16; ++q)
+        ro[q] = *reinterpret_cast<const u32x4*>(smem_raw + RW_OUT + (crow + 8 * q) * RW_OLD + ccol * 2);
+      const int n = g * 256 + ccol;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int mrow = m0 + crow + 8 * q;
+        if (mrow < a.N && n < a.d) {
+          bf16_t* o = a.Xh + (int64_t)mrow * a.ldxh + n;
+          if (vec_ok && n + 8 <= a.d) {
+            *reinterpret_cast<u32x4*>(o) = ro[q];
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (n + e < a.d) o[e] = (bf16_t)((ro[q][e >> 1] >> (16 * (e & 1))) & 0xFFFFu);
+          }
+        }
+      }
+      // the stores above have read their registers, hence the LDS reads are complete
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      if (g + 1 < G) __builtin_amdgcn_s_barrier();  // staging tile free again
+    }
+    return;
+  }
+
+  // -------------------------------------------------------------- matrix waves
+  const int lane = tid & 63, li = lane & 31, lh = lane >> 5;
+  const char* pbase = reinterpret_cast<const char*>(a.Ptfrag);
+  const uint32_t boff = (uint32_t)(wave * 2 * 64 + lane) * 16u;  // this wave's two column blocks of a group
+  const int64_t brow = (int64_t)a.ncb * 1024;                    // bytes per k-block of fragments
+  f32x16 acc[8];
+  // ring as in the compress kernel; a "tile" is a column group, 8 blocks (8 KB) further along each k-block row
+  u32x4 rb[8][2];
+  auto group_base = [&](int g) { return pbase + (g < G ? (int64_t)g * 8192 : (int64_t)0); };  // uniform
+  const char* preq = group_base(0);
+  const char* next_base = group_base(1);
+#pragma unroll
+  for (int kk = 0; kk < 7; ++kk) {
+    ring_request<0>(rb[kk][0], boff, preq);
+    ring_request<1024>(rb[kk][1], boff, preq);
+    preq += brow;
+  }
+  constexpr int VM = 12;
+#define PRAC_IC(v) std::integral_constant<int, (v)> {}
+  auto kblock = [&](auto oc, const u32x4 (&fcur)[4], u32x4 (&fnext)[4], auto kkc, unsigned lds) {
+    constexpr int O = decltype(oc)::value, KK = decltype(kkc)::value;
+    kblock2t<O, VM, KK == 0>(acc, fcur, fnext, rb[KK & 7][0], rb[KK & 7][1], lds, rb[(KK + 7) & 7][0],
+                             rb[(KK + 7) & 7][1], boff, preq);
+    if constexpr (KK == 8) preq = next_base;
+    else preq += brow;
+  };
+  const unsigned lds0 =
+      (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw + (unsigned)(li * WS_LD * 2 + lh * 16);
+  u32x4 fa[4], fb[4];
+  __builtin_amdgcn_s_barrier();  // the C tile is in LDS
+  frag_read4(fa, lds0);
+  // staging address of this lane: token row li (+ 32 i), columns 64 wave (+ 32 j + 8 q) + 4 lh .. + 3
+  unsigned char* const orow = smem_raw + RW_OUT + li * RW_OLD + (wave * 64 + 4 * lh) * 2;
+  for (int g = 0; g < G; ++g) {
+    static_for<WS_KB>([&](auto jc) {
+      constexpr int J = decltype(jc)::value;
+      // the fragments read during k-block 15 are those of k-block 0 again: the next group's first
+      if constexpr (J % 2 == 0) kblock(PRAC_IC(32 * ((J + 1) % WS_KB)), fa, fb, jc, lds0);
+      else kblock(PRAC_IC(32 * ((J + 1) % WS_KB)), fb, fa, jc, lds0);
+    });
+    next_base = group_base(g + 2);
+    // The matrix pipeline and the ring are drained before compiler-scheduled code runs (see the
+    // compress kernel): the code below needs registers, and the compiler may only move or spill
+    // ring registers whose requests have landed.  The ring then holds the next group's first
+    // seven k-blocks, so the matrix pipeline restarts at once after the tile is staged.
+    drain_mfma<8, 2>(acc, rb);
+    __builtin_amdgcn_s_barrier();  // staging tile free
+    asm volatile("" ::: "memory");
+    // block (i, j) = acc[2 i + j]: register v of lane (li, lh) is token row 32 i + li, column
+    // 32 j + 8 (v / 4) + 4 lh + v % 4 of the wave's 64
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        // one block at a time leaves the accumulator registers (keeps the copies short-lived)
+        asm volatile("" : "+a"(acc[2 * i + j]) : : "memory");
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          uint2 w;
+          w.x = pack2_hw(acc[2 * i + j][4 * q], acc[2 * i + j][4 * q + 1]);
+          w.y = pack2_hw(acc[2 * i + j][4 * q + 2], acc[2 * i + j][4 * q + 3]);
+          *reinterpret_cast<uint2*>(orow + i * 32 * RW_OLD + (j * 32 + q * 8) * 2) = w;
+        }
+      }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();  // staging tile holds group g
+  }
+#undef PRAC_IC
+}
+
 // ----------------------------------------------------------------------- C^T dY
 // Token-split partial sums of T = C^T dY (Lemma 1, reassociated), same workgroup shape:
 //   loader waves   stream dY tiles (128 tokens x 128 columns), transpose each 8 x 8 patch in
@@ -474,14 +690,14 @@ __device__ __forceinline__ void kblock_ct(f32x16 (&acc)[8], const u32x4 (&fc)[4]
                                           uint32_t v1, const char* src) {
   asm volatile(
       "s_waitcnt vmcnt(%28)\n"
+      "global_load_dwordx4 %12, %21, %23\n"
+      "global_load_dwordx4 %13, %22, %23\n"
       "ds_read_b128 %8, %20 offset:%24\n"
       "v_mfma_f32_32x32x16_bf16 %0, %18, %14, %0\n"
       "ds_read_b128 %9, %20 offset:%25\n"
       "v_mfma_f32_32x32x16_bf16 %4, %19, %14, %4\n"
-      "global_load_dwordx4 %12, %21, %23\n"
       "ds_read_b128 %10, %20 offset:%26\n"
       "v_mfma_f32_32x32x16_bf16 %1, %18, %15, %1\n"
-      "global_load_dwordx4 %13, %22, %23\n"
       "ds_read_b128 %11, %20 offset:%27\n"
       "v_mfma_f32_32x32x16_bf16 %5, %19, %15, %5\n"
       "v_mfma_f32_32x32x16_bf16 %2, %18, %16, %2\n"
@@ -734,6 +950,21 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
     if (rc) return rc;
     PRAC_LAUNCH(ctx, kern2, grid, block, smem, a);
   }
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  return PRAC_OK;
+}
+
+int launch_reconstruct_ws(prac_ctx* ctx, const bf16_t* C, int64_t ldc, int N, int c, int d, const bf16_t* Ptfrag, int ncb,
+                          bf16_t* Xh, int64_t ldxh) {
+  if (c < 1 || c > WS_BK || ncb % 8 != 0 || (int64_t)ncb * 32 < d) return PRAC_EINVAL;
+  ReconWsArgs a;
+  a.C = C; a.ldc = ldc; a.N = N; a.c = c; a.d = d; a.Ptfrag = Ptfrag; a.ncb = ncb; a.Xh = Xh; a.ldxh = ldxh;
+  a.tiles_m = (N + WS_BM - 1) / WS_BM;
+  a.groups = (d + 255) / 256;
+  static bool s = false;
+  int rc = set_smem(ctx, reconstruct_ws_kernel, (size_t)RW_SMEM, s);
+  if (rc) return rc;
+  PRAC_LAUNCH(ctx, reconstruct_ws_kernel, dim3(((a.tiles_m + 7) / 8) * 8), dim3(512), (size_t)RW_SMEM, a);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }

@@ -2,10 +2,11 @@
 
 The matrix blocks of csrc/ws_kernels.hip issue MFMAs and ring loads inside inline assembly,
 so the compiler does not know that accumulators are still being written by the matrix pipeline
-or that ring registers have loads in flight.  That is safe only while, between the first
-matrix block and the drain (the assembly block holding `s_waitcnt vmcnt(0)`), no instruction
-outside the assembly blocks touches an accumulator register or a ring register (a destination
-of an in-assembly `global_load_dwordx4`).  This script compiles the file to ISA and checks it.
+or that ring registers have loads in flight.  That is safe only while no instruction outside
+the assembly blocks touches an accumulator register between a matrix block and the block that
+drains the matrix pipeline, or a ring register (a destination of an in-assembly
+`global_load_dwordx4`) between the first matrix block and the block holding `s_waitcnt vmcnt(0)`.
+This script compiles the file to ISA and checks it.
 
 Usage: python -m paper_2602_23111_amd.lint_isa      (exit status 0 = clean)
 """
@@ -50,19 +51,30 @@ def lint_text(isa: str) -> list[str]:
         if not ring:
             problems.append(f"{name}: no ring loads found inside assembly blocks")
             continue
-        inasm = started = done = False
+        # Walk the text in order.  Accumulators are busy from an assembly block with MFMAs until an
+        # assembly block that drains the matrix pipeline (four `s_nop 15` and no MFMA); ring registers
+        # from the first matrix block (before it the compiler may still use a slot's registers: the
+        # first fills do not touch every slot) until the assembly block with `s_waitcnt vmcnt(0)`.
+        # (A loop body is laid out once; its drain precedes the code that reads the accumulators.)
+        inasm = acc_busy = ring_busy = ring_done = False
+        block = []
         for line in body:
             if "ASMSTART" in line:
-                inasm = True
+                inasm, block = True, []
                 continue
             if "ASMEND" in line:
                 inasm = False
+                text = "\n".join(block)
+                if "v_mfma" in text:
+                    acc_busy = True
+                    ring_busy = ring_busy or not ring_done
+                elif text.count("s_nop 15") >= 4:
+                    acc_busy = False
+                if "s_waitcnt vmcnt(0)" in text:
+                    ring_busy, ring_done = False, True
                 continue
             if inasm:
-                started = started or "v_mfma" in line
-                done = done or (started and "s_waitcnt vmcnt(0)" in line)
-                continue
-            if not started or done:
+                block.append(line)
                 continue
             text = line.strip()
             if not text or text[0] in ".;" or text.startswith("s_"):
@@ -71,9 +83,9 @@ def lint_text(isa: str) -> list[str]:
             used = set()
             for o in ops[1:]:
                 used |= _regs(o)
-            if "accvgpr" in ops[0] or any(r.startswith("a") for r in used):
+            if acc_busy and ("accvgpr" in ops[0] or any(r.startswith("a") for r in used)):
                 problems.append(f"{name}: accumulator register touched outside assembly: {text}")
-            elif used & ring:
+            elif ring_busy and used & ring:
                 problems.append(f"{name}: ring register touched outside assembly: {text}")
     return problems
 
