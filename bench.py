@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 
 WORKLOAD = dict(name="llama1b_attn_proj", N=32768, d=2048, m=2048, k=128, r=128, alpha=0.8,
                 n_out=8, out_scale=30.0, dy_std=1e-3, refresh_every=500, n_sets=4, layer_seed=3000,
-                warm_iters=2, warm_oversample=16, row_stride=1)
+                warm_iters=2, warm_oversample=-1, row_stride=1)
 # The other layer shapes of the configurations (same protocol; `--workload NAME`).  The headline
 # above is what the driver's plain `python bench.py` measures.
 OTHER_WORKLOADS = {

@@ -328,6 +328,8 @@ __global__ __launch_bounds__(256) void copy_cols_kernel(const float* __restrict_
 
 struct FitWs {
   size_t G, V, Y, W64, X64, Rinv, lam, Z, S, T, slabs, gram, total;
+  size_t trk_pf, trk_c, trk_slabs;  // tracking refit: V in fragment order, packed X V, slabs of (X V)^T X
+  int trk_nkb, trk_ncb, trk_splits;
   int b;
   int splits_bb;  // split count of the b x b fp64 Gram products
   int splits_gv;  // split count of G V
@@ -342,10 +344,21 @@ int block_width(int64_t d, int k, const prac_fit_opts& o) {
   return (int)b;
 }
 
-FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool need_g, size_t gram_bytes) {
+// Tracking refit (warm start, block width k, bf16 X the streaming kernels accept): no Gram
+// matrix is formed.  One step is V <- orth(X^T (X V)): the compress kernel forms X V, the C^T dY
+// kernel with X in the place of dY forms (X V)^T X.
+bool can_track(const void* X, prac_dtype xdt, int64_t rows, int64_t d, int64_t ldx, int k, const prac_fit_opts& o) {
+  const int64_t ld = ldx * (o.row_stride > 0 ? o.row_stride : 1);
+  return o.warm_start && o.oversample < 0 && o.iters >= 1 && k > 0 && k <= 256 && xdt == PRAC_BF16 &&
+         (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 8 == 0 && rows >= 256 && rows < ((int64_t)1 << 31) &&
+         d >= 128;
+}
+
+FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool need_g, size_t gram_bytes, bool track,
+               int64_t rows) {
   FitWs w{};
   WsPlan p;
-  const int b = need_g ? block_width(d, k, o) : 0;
+  const int b = track ? k : (need_g ? block_width(d, k, o) : 0);
   const int bb = b > r ? b : r;  // widest panel that goes through orth()
   w.b = b;
   w.G = p.take(need_g ? (size_t)d * d * 4 : 0);
@@ -374,6 +387,19 @@ FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool n
   const size_t slab_bb = (size_t)s * bb * bb * 8, slab_gv = sg > 1 ? (size_t)sg * d * b * 4 : 0;
   w.slabs = p.take(slab_bb > slab_gv ? slab_bb : slab_gv);
   w.gram = p.take(gram_bytes);
+  if (track) {
+    w.trk_nkb = (int)(round_up64(d, 256) / 16);
+    w.trk_ncb = (int)round_up64((k + 31) / 32, 8);
+    const int tiles = (int)((d + 127) / 128);  // k <= 256: one row group of T
+    int sp = n_cu / tiles;
+    if (sp > rows / 256) sp = (int)(rows / 256);
+    if (sp < 1) sp = 1;
+    if (sp > 64) sp = 64;
+    w.trk_splits = sp;
+    w.trk_pf = p.take((size_t)w.trk_nkb * w.trk_ncb * 64 * 8 * sizeof(bf16_t));
+    w.trk_c = p.take((size_t)((rows + 127) / 128) * 8 * ((k + 31) / 32) * 64 * 8 * sizeof(bf16_t));
+    w.trk_slabs = p.take((size_t)sp * k * d * sizeof(float));
+  }
   w.total = p.off;
   return w;
 }
@@ -438,8 +464,11 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
   const bool do_q2 = (refresh & PRAC_REFRESH_RANDOM) && r > 0;
   if (!do_q1 && !do_q2) return PRAC_OK;
   if (k > 1024 || r > 1024) return PRAC_EUNSUPPORTED;  // single-workgroup panel kernels
-  const size_t gram_bytes = do_q1 ? gram_scratch_bytes(ctx, X, xdt, N, d, ldx, o.row_stride, d) : 0;
-  const FitWs L = plan_fit(d, k, r, o, ctx->n_cu, do_q1, gram_bytes);
+  const int64_t stride = o.row_stride > 0 ? o.row_stride : 1;
+  const int64_t rows = (N + stride - 1) / stride;
+  const bool track = do_q1 && can_track(X, xdt, rows, d, ldx, k, o);
+  const size_t gram_bytes = do_q1 && !track ? gram_scratch_bytes(ctx, X, xdt, N, d, ldx, o.row_stride, d) : 0;
+  const FitWs L = plan_fit(d, k, r, o, ctx->n_cu, do_q1 && !track, gram_bytes, track, rows);
   int rc = prac_ws_reserve(ctx, L.total);
   if (rc) return rc;
   float* G = reinterpret_cast<float*>(ctx->ws + L.G);
@@ -447,7 +476,31 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
   float* Y = reinterpret_cast<float*>(ctx->ws + L.Y);
   hipStream_t st = ctx->stream;
 
-  if (do_q1) {
+  if (track) {
+    // V starts as the previous Q1.  The span is what matters (compression and the estimator are
+    // invariant to a rotation inside Q1), so there is no Rayleigh-Ritz step: each iteration is one
+    // subspace-iteration step on X^T X, orthonormalised by Cholesky-QR (two passes on the last).
+    const bf16_t* Xb = reinterpret_cast<const bf16_t*>(X);
+    const int64_t ld = ldx * stride;
+    bf16_t* Pf = reinterpret_cast<bf16_t*>(ctx->ws + L.trk_pf);
+    bf16_t* Cpk = reinterpret_cast<bf16_t*>(ctx->ws + L.trk_c);
+    float* slabs = reinterpret_cast<float*>(ctx->ws + L.trk_slabs);
+    const int dm = (int)d;
+    for (int it = 0; it < o.iters; ++it) {
+      rc = launch_pack_pfrag(ctx, it == 0 ? P : V, d, it == 0 ? ldp : (int64_t)k, k, L.trk_nkb, L.trk_ncb, Pf);
+      if (rc) return rc;
+      rc = launch_compress_ws(ctx, Xb, ld, (int)rows, dm, Pf, L.trk_ncb, k, Cpk, 0, true, nullptr, 0, 0, nullptr, 0);
+      if (rc) return rc;
+      rc = launch_ctdy_ws(ctx, Cpk, k, (int)rows, 1, &Xb, &ld, &dm, &slabs, L.trk_splits);
+      if (rc) return rc;
+      rc = launch_reduce_transpose_f32(ctx, slabs, L.trk_splits, k, dm, Y, k);
+      if (rc) return rc;
+      rc = cholqr(ctx, L, Y, V, d, k, it == o.iters - 1 ? 2 : 1, 1e-11);
+      if (rc) return rc;
+    }
+    hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, V, (int64_t)k, P, ldp, d, k);
+    PRAC_HIP_TRY(ctx, hipGetLastError());
+  } else if (do_q1) {
     const int b = L.b;
     rc = gram_device(ctx, X, xdt, N, d, ldx, o.row_stride, G, d, ctx->ws + L.gram);
     if (rc) return rc;

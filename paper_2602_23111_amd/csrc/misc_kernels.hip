@@ -144,6 +144,29 @@ __global__ __launch_bounds__(256) void reduce_transpose_bf16_kernel(const float*
   }
 }
 
+// part: splits x M x N fp32.  out[n][j] = sum_z part[z][j][n] (N x M, ld = ldo)
+__global__ __launch_bounds__(256) void reduce_transpose_f32_kernel(const float* __restrict__ part, int splits, int M,
+                                                                   int N, float* __restrict__ out, int64_t ldo) {
+  __shared__ float tile[32][33];
+  const int j0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
+  const int64_t slab = (int64_t)M * N;
+  for (int r = ty; r < 32; r += 8) {
+    const int j = j0 + r, n = n0 + tx;
+    float s = 0.f;
+    if (j < M && n < N) {
+      const float* p = part + (int64_t)j * N + n;
+      for (int z = 0; z < splits; ++z) s += p[z * slab];
+    }
+    tile[r][tx] = s;
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) {
+    const int n = n0 + r, j = j0 + tx;
+    if (n < N && j < M) out[(int64_t)n * ldo + j] = tile[tx][r];
+  }
+}
+
 __global__ __launch_bounds__(256) void scale_rows_kernel(float* T, int rows, int cols, int64_t ld, int k_lo, float s) {
   const int64_t total = (int64_t)(rows - k_lo) * cols;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
@@ -220,6 +243,13 @@ int launch_reduce_transpose_bf16(prac_ctx* ctx, const float* part, int splits, i
   dim3 grid((N + 31) / 32, (unsigned)((ldt + 31) / 32));
   hipLaunchKernelGGL(reduce_transpose_bf16_kernel, grid, dim3(256), 0, ctx->stream, part, splits, M, N, k_lo,
                      scale_hi, Tt, ldt);
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  return PRAC_OK;
+}
+
+int launch_reduce_transpose_f32(prac_ctx* ctx, const float* part, int splits, int M, int N, float* out, int64_t ldo) {
+  dim3 grid((N + 31) / 32, (M + 31) / 32);
+  hipLaunchKernelGGL(reduce_transpose_f32_kernel, grid, dim3(256), 0, ctx->stream, part, splits, M, N, out, ldo);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }

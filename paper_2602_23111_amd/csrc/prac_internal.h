@@ -104,6 +104,8 @@ int launch_reduce_slabs(prac_ctx* ctx, const float* part, int splits, int64_t st
 // Tt (N x ldt bf16) = transpose of rowscale(j) * sum_s part[s][j][n], j < M; columns M..ldt-1 zeroed
 int launch_reduce_transpose_bf16(prac_ctx* ctx, const float* part, int splits, int M, int N, int k_lo,
                                  float scale_hi, bf16_t* Tt, int64_t ldt);
+// out (N x M fp32, ld = ldo) = transpose of sum_s part[s][j][n], j < M
+int launch_reduce_transpose_f32(prac_ctx* ctx, const float* part, int splits, int M, int N, float* out, int64_t ldo);
 // fp32 matrix (rows x cols, ld) rows >= k_lo multiplied by s
 int launch_scale_rows(prac_ctx* ctx, float* T, int rows, int cols, int64_t ld, int k_lo, float s);
 int launch_philox(prac_ctx* ctx, uint64_t seed, uint32_t draw, uint32_t stream, void* out, int64_t n,

@@ -54,9 +54,10 @@ def outlier_channels(d: int, n_out: int, rng: np.random.Generator) -> np.ndarray
 
 def activation(N: int, d: int, alpha: float, seed: int, n_out: int = 0,
                out_scale: float = 1.0, exact_spectrum: bool = False,
-               sigma: np.ndarray | None = None):
+               sigma: np.ndarray | None = None, batch: int = 0):
     """X = Z diag(sigma) R (fp64) with Z ~ N(0,1) (N x d), sigma_i = i^-alpha,
-    R Haar; then n_out channels (columns) multiplied by out_scale.
+    R Haar; then n_out channels (columns) multiplied by out_scale.  `batch` > 0
+    draws another Z for the same R and channels: the next batch of one layer.
 
     exact_spectrum=True replaces Z by an N x d matrix with orthonormal
     columns, so that (without outliers) the singular values of X are exactly
@@ -66,6 +67,8 @@ def activation(N: int, d: int, alpha: float, seed: int, n_out: int = 0,
     rng = np.random.default_rng(seed)
     sig = power_law_sigma(d, alpha) if sigma is None else np.asarray(sigma, dtype=np.float64)
     Z = rng.standard_normal((N, d))
+    if batch:
+        Z = np.random.default_rng([seed, batch]).standard_normal((N, d))
     if exact_spectrum:
         if N < d:
             raise ValueError("exact_spectrum needs N >= d")

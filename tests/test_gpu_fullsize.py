@@ -98,13 +98,13 @@ def test_fit_basis_full_size_invariants(ctx):
 
 
 def test_fit_basis_warm_start_as_benchmarked(ctx):
-    # the refits inside bench.py's timed region: next batch of the same layer, block started from the
-    # previous Q1 plus 16 fresh columns, 2 iterations
+    # the refits inside bench.py's timed region: next batch of the same layer, two Gram-free tracking
+    # steps from the previous Q1 (no oversampling)
     d, k, r = 2048, 128, 128
     X0 = si.activation_torch(N, d, 0.8, 3000, 8, 30.0, torch.bfloat16, DEV, batch=0)
     X1 = si.activation_torch(N, d, 0.8, 3000, 8, 30.0, torch.bfloat16, DEV, batch=1)
     P, _, _ = ctx.fit_basis(X0, k, r, seed=1234, draw=0)
-    P, _, scale = ctx.fit_basis(X1, k, r, seed=1234, draw=1, P=P, warm_start=True, iters=2, oversample=16)
+    P, _, scale = ctx.fit_basis(X1, k, r, seed=1234, draw=1, P=P, warm_start=True, iters=2, oversample=-1)
     ctx.sync_status()
     P64 = si.as_f64(P)
     assert np.abs(P64.T @ P64 - np.eye(k + r)).max() < 1e-5

@@ -431,6 +431,29 @@ def test_fit_basis_row_subsample_and_warm_start(ctx):
     assert not torch.equal(P2[:, k:], P[:, k:])          # a new draw gives a new random block
 
 
+@pytest.mark.parametrize("N,d,k,r,stride,iters", [(4096, 256, 16, 16, 4, 2), (3000, 328, 40, 24, 1, 1),
+                                                  (2048, 512, 160, 32, 2, 2)])
+def test_fit_basis_tracking_refit(ctx, N, d, k, r, stride, iters):
+    # warm start without oversampling on bf16 data: the Gram-free refit (Q1 <- orth(X^T (X Q1)) through the
+    # compress and C^T dY kernels).  Next batch of the same layer; what is unique is checked: orthonormality,
+    # Q1 _|_ Q2, the scale, and the energy Q1 captures of the (sub)sampled rows against the oracle's top-k sum.
+    X0 = si.round_to(si.activation(N, d, 0.8, seed=40 + k, n_out=4, out_scale=20.0)[0], "bf16")
+    X1 = si.round_to(si.activation(N, d, 0.8, seed=40 + k, n_out=4, out_scale=20.0, batch=1)[0], "bf16")
+    P, _, _ = ctx.fit_basis(X0.to(DEV), k, r, seed=3, draw=0, row_stride=stride, pack=False)
+    P2, _, scale = ctx.fit_basis(X1.to(DEV), k, r, seed=3, draw=1, row_stride=stride, P=P.clone(), iters=iters,
+                                 oversample=-1, warm_start=True, pack=False)
+    ctx.sync_status()
+    P64 = si.as_f64(P2)
+    assert np.abs(P64.T @ P64 - np.eye(k + r)).max() < 1e-5
+    assert scale == pytest.approx((d - k) / r)
+    Xs = si.as_f64(X1)[::stride]
+    _, lam = orc.principal_subspace(orc.gram(Xs), k)
+    captured = float(np.sum((Xs @ P64[:, :k]) ** 2))
+    assert (1 - 1e-3) * lam[:k].sum() <= captured <= (1 + 1e-6) * lam[:k].sum()
+    assert not torch.equal(P2[:, :k], P[:, :k])           # Q1 moved with the new batch
+    assert not torch.equal(P2[:, k:], P[:, k:])
+
+
 # ------------------------------------------------- estimator statistics on the GPU path
 def _gpu_monte_carlo(ctx, Xt, dYt, k, r, draws, scale_factor=1.0):
     """Mean of Xh and of dW, and the squared errors of Xh, over `draws` redraws of Q2 (Q1 fixed):
