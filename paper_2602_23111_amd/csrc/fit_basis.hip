@@ -419,32 +419,81 @@ int set_dyn_smem(prac_ctx* ctx) {
   return PRAC_OK;
 }
 
-// V (d x n, ld = n, fp32) <- orth(Y) by `passes` rounds of Cholesky-QR; ping-pongs
-// between Y and V, result always ends in `V`.  The first round shifts the Gram matrix.
-int cholqr(prac_ctx* ctx, const FitWs& w, float* Y, float* V, int64_t d, int n, int passes, double first_shift) {
+__global__ __launch_bounds__(256) void f32_to_f64_kernel(const float* __restrict__ src, double* __restrict__ dst, int n) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) dst[i] = (double)src[i];
+}
+
+// W (n x n) <- 1.5 I - 0.5 W
+__global__ __launch_bounds__(256) void newton_schulz_factor_kernel(float* W, int n) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n * n; i += gridDim.x * blockDim.x)
+    W[i] = (i / n == i % n ? 1.5f : 0.f) - 0.5f * W[i];
+}
+
+// M (n x n) = src^T src for a d x n block (ld = n): fp64 sums into W64, or fp32 sums on the matrix
+// cores into M32 (enough for a block whose condition number is small)
+int panel_gram(prac_ctx* ctx, const FitWs& w, const float* src, int64_t d, int n, double* W64, float* M32) {
+  GemmGenArgs g{};
+  g.A = src; g.B = src; g.adt = PRAC_F32; g.bdt = PRAC_F32;
+  g.a_rs = 1; g.a_cs = n; g.b_rs = n; g.b_cs = 1;
+  g.M = n; g.N = n; g.K = d; g.k_stride = 1;
+  g.ldo = n; g.alpha = 1.f; g.beta = 0.f;
+  g.splits = w.splits_bb; g.slabs = ctx->ws + w.slabs;
+  if (W64) { g.out = nullptr; g.out64 = W64; g.acc64 = true; }
+  else { g.out = M32; g.out64 = nullptr; g.acc64 = false; }
+  return launch_gemm_generic(ctx, g);
+}
+
+// dst = src R^-1 with R^T R = src^T src (+ shift): one Cholesky-QR pass
+int cholqr_pass(prac_ctx* ctx, const FitWs& w, const float* src, float* dst, int64_t d, int n, double shift, bool gram64) {
   double* W64 = reinterpret_cast<double*>(ctx->ws + w.W64);
+  int rc;
+  if (gram64) {
+    rc = panel_gram(ctx, w, src, d, n, W64, nullptr);
+    if (rc) return rc;
+  } else {
+    float* M32 = reinterpret_cast<float*>(ctx->ws + w.Rinv);
+    rc = panel_gram(ctx, w, src, d, n, nullptr, M32);
+    if (rc) return rc;
+    hipLaunchKernelGGL(f32_to_f64_kernel, dim3((n * n + 255) / 256), dim3(256), 0, ctx->stream, M32, W64, n * n);
+  }
+  rc = set_dyn_smem(ctx);
+  if (rc) return rc;
+  hipLaunchKernelGGL(chol_upper_kernel<1024>, dim3(1), dim3(1024), (size_t)CH_NB * n * sizeof(double), ctx->stream, W64,
+                     n, shift, ctx->d_flag);
+  hipLaunchKernelGGL(trsm_right_upper_kernel, dim3((unsigned)((d + TR_ROWS - 1) / TR_ROWS)), dim3(256),
+                     (size_t)(TR_ROWS + TR_CH) * n * sizeof(float), ctx->stream, src, W64, dst, d, n);
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  return PRAC_OK;
+}
+
+// dst = src (1.5 I - 0.5 src^T src): one Newton-Schulz step towards orthonormal columns.  For a block
+// with ||src^T src - I|| = e the result has 0.75 e^2: the cheap second pass after a Cholesky-QR pass,
+// made of two products and no factorisation.
+int polish_pass(prac_ctx* ctx, const FitWs& w, const float* src, float* dst, int64_t d, int n) {
+  float* M32 = reinterpret_cast<float*>(ctx->ws + w.Rinv);
+  int rc = panel_gram(ctx, w, src, d, n, nullptr, M32);
+  if (rc) return rc;
+  hipLaunchKernelGGL(newton_schulz_factor_kernel, dim3((n * n + 255) / 256), dim3(256), 0, ctx->stream, M32, n);
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  GemmGenArgs g{};
+  g.A = src; g.B = M32; g.adt = PRAC_F32; g.bdt = PRAC_F32;
+  g.a_rs = n; g.a_cs = 1; g.b_rs = n; g.b_cs = 1;
+  g.M = (int)d; g.N = n; g.K = n; g.k_stride = 1;
+  g.out = dst; g.ldo = n; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
+  return launch_gemm_generic(ctx, g);
+}
+
+// V (d x n, ld = n, fp32) <- orth(Y): `passes` rounds of Cholesky-QR (the first one shifted), then
+// `polish` Newton-Schulz steps; ping-pongs between Y and V, result always ends in `V`.
+// gram64_first = false: the first Gram matrix is summed in fp32 (well-conditioned blocks only).
+int cholqr(prac_ctx* ctx, const FitWs& w, float* Y, float* V, int64_t d, int n, int passes, double first_shift,
+           int polish = 0, bool gram64_first = true) {
   float* src = Y;
   float* dst = V;
-  for (int pass = 0; pass < passes; ++pass) {
-    GemmGenArgs g{};
-    g.A = src; g.B = src; g.adt = PRAC_F32; g.bdt = PRAC_F32;
-    g.a_rs = 1; g.a_cs = n; g.b_rs = n; g.b_cs = 1;
-    g.M = n; g.N = n; g.K = d; g.k_stride = 1;
-    g.out = nullptr; g.out64 = W64; g.ldo = n; g.alpha = 1.f; g.beta = 0.f; g.acc64 = true;
-    g.splits = w.splits_bb; g.slabs = ctx->ws + w.slabs;
-    int rc = launch_gemm_generic(ctx, g);
+  for (int pass = 0; pass < passes + polish; ++pass) {
+    int rc = pass < passes ? cholqr_pass(ctx, w, src, dst, d, n, pass == 0 ? first_shift : 1e-15, pass > 0 || gram64_first)
+                           : polish_pass(ctx, w, src, dst, d, n);
     if (rc) return rc;
-    rc = set_dyn_smem(ctx);
-    if (rc) return rc;
-    if (n <= 0)  // 256 threads measured slower at every panel width tried
-      hipLaunchKernelGGL(chol_upper_kernel<256>, dim3(1), dim3(256), (size_t)CH_NB * n * sizeof(double), ctx->stream,
-                         W64, n, pass == 0 ? first_shift : 1e-15, ctx->d_flag);
-    else
-      hipLaunchKernelGGL(chol_upper_kernel<1024>, dim3(1), dim3(1024), (size_t)CH_NB * n * sizeof(double), ctx->stream,
-                         W64, n, pass == 0 ? first_shift : 1e-15, ctx->d_flag);
-    hipLaunchKernelGGL(trsm_right_upper_kernel, dim3((unsigned)((d + TR_ROWS - 1) / TR_ROWS)), dim3(256),
-                       (size_t)(TR_ROWS + TR_CH) * n * sizeof(float), ctx->stream, src, W64, dst, d, n);
-    PRAC_HIP_TRY(ctx, hipGetLastError());
     float* t = src; src = dst; dst = t;
   }
   // result is in `src` after the swap
@@ -495,7 +544,10 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       if (rc) return rc;
       rc = launch_reduce_transpose_f32(ctx, slabs, L.trk_splits, k, dm, Y, k);
       if (rc) return rc;
-      rc = cholqr(ctx, L, Y, V, d, k, it == o.iters - 1 ? 2 : 1, 1e-11);
+      // One power step from an orthonormal block leaves a condition number of at most lambda_1 /
+      // lambda_k, within reach of an unshifted Cholesky factor of the fp64 Gram matrix; the last
+      // iteration then gets two Newton-Schulz steps in place of a second factorisation.
+      rc = cholqr(ctx, L, Y, V, d, k, 1, 1e-15, it == o.iters - 1 ? 2 : 0);
       if (rc) return rc;
     }
     hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, V, (int64_t)k, P, ldp, d, k);
@@ -614,7 +666,9 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
         g.A = P; g.B = S; g.adt = PRAC_F32; g.bdt = PRAC_F32;
         g.a_rs = 1; g.a_cs = ldp; g.b_rs = r; g.b_cs = 1;
         g.M = k; g.N = r; g.K = d; g.k_stride = 1;
-        g.out = T; g.ldo = r; g.alpha = 1.f; g.beta = 0.f; g.acc64 = true; g.out64 = nullptr;
+        // fp32 sums on the matrix cores: the second projection removes what rounding left of the first
+        g.out = T; g.ldo = r; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
+        g.splits = L.splits_bb; g.slabs = ctx->ws + L.slabs;
         rc = launch_gemm_generic(ctx, g);
         if (rc) return rc;
         GemmGenArgs h{};
@@ -626,7 +680,12 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
         if (rc) return rc;
       }
     }
-    rc = cholqr(ctx, L, S, V, d, r, 2, 1e-13);
+    // a narrow projected Gaussian block is well conditioned (singular values within 1 +- sqrt(r/d) of
+    // each other): fp32 sums are enough for its Gram matrix, and one Newton-Schulz step finishes it
+    // (up to r = d/4, where the ratio of the extreme singular values reaches 3; wider blocks keep two
+    // Cholesky-QR passes over fp64 Gram matrices)
+    if ((int64_t)4 * r <= d - k) rc = cholqr(ctx, L, S, V, d, r, 1, 1e-13, 1, false);
+    else rc = cholqr(ctx, L, S, V, d, r, 2, 1e-13);
     if (rc) return rc;
     hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, V, (int64_t)r, P + k, ldp, d, r);
     PRAC_HIP_TRY(ctx, hipGetLastError());
