@@ -1,6 +1,8 @@
 // Wave-specialised streaming contractions for gfx950.
 //
-//   compress   C = X P   (Alg. 1 compression step)            compress_ws_kernel
+//   compress        C = X P          (Alg. 1 compression step)          compress_ws_kernel
+//   reconstruction  X~ = C Ps^T      (Section 5.1; Alg. 2 backward)       reconstruct_ws_kernel
+//   weight gradient T = C^T dY       (Lemma 1, reassociated)              ctdy_ws_kernel
 //
 // A workgroup is 8 waves: 4 matrix waves and 4 loader waves, one of each per SIMD.
 //   loader waves   stream the big operand (X) HBM -> registers -> LDS in ordinary
@@ -73,8 +75,10 @@ constexpr int WS_NCH = 4, WS_NIF = 2;        // chunks per tile, chunks in fligh
 // One k-block of a 128 x 64 wave tile: acc[2 i + j] += fa[i] * b_j, while the four A fragments
 // at byte offsets O + i * WS_RB from `lds` are read into fn.  The block also issues the two
 // 1 KB requests that refill another slot of the P ring (n0, n1 <- fragments at `src` + lane
-// offset `voff`, and 1 KB further): the matrix pipeline runs while they are issued, and the
-// address is an SGPR pair plus one VGPR, so no vector arithmetic sits between the blocks.
+// offset `voff`, and 1 KB further); the address is an SGPR pair plus one VGPR, so no vector
+// arithmetic sits between the blocks.  The requests come first in the block, before the LDS
+// reads: a vector-memory request placed between two LDS reads stalls the wave's in-order issue
+// and with it the MFMAs behind it (measured: 29 against 20 us for the 128 k-blocks of a workgroup).
 // The compiler cannot see these loads.  The block therefore starts with its own wait: all
 // but the VM youngest requests of this wave have arrived (the ring's distance times the
 // requests per block; b0 / b1 were requested that long ago), and n0 / n1 may only be read
