@@ -181,12 +181,27 @@ __global__ __launch_bounds__(256) void reduce_scale_bf16_kernel(const float* __r
 // One workgroup per (k-block, pair of 32-column blocks): 256 threads sum a 16 x 64 patch of
 // the slabs with one float4 per thread and slab (coalesced 256-byte rows), exchange it through
 // LDS and 128 of them emit the two fragments.
-__global__ __launch_bounds__(256) void reduce_to_tfrag_kernel(const float* __restrict__ slabs, int splits, int c, int m,
-                                                              int k_lo, float scale_hi, int nkb, int nmb,
-                                                              bf16_t* __restrict__ Tf) {
+struct ReduceTfArgs {
+  int n_out, splits, c, k_lo, nkb;
+  float scale_hi;
+  const float* slabs[PRAC_CTDY_MAX_OUT];  // [splits][c][m_h]
+  bf16_t* Tf[PRAC_CTDY_MAX_OUT];          // [nkb][nmb_h][64][8]
+  int m[PRAC_CTDY_MAX_OUT];
+  int nmb[PRAC_CTDY_MAX_OUT];
+  int pair0[PRAC_CTDY_MAX_OUT + 1];       // first pair of column blocks of output h in the launch
+};
+
+__global__ __launch_bounds__(256) void reduce_to_tfrag_kernel(ReduceTfArgs a) {
   __shared__ float patch[16][68];
-  const int pairs = nmb / 2;
-  const int kb = blockIdx.x / pairs, np = blockIdx.x % pairs;
+  const int pairs = a.pair0[a.n_out];
+  const int kb = blockIdx.x / pairs, gp = blockIdx.x % pairs;
+  int h = 0;
+#pragma unroll
+  for (int q = 1; q < PRAC_CTDY_MAX_OUT; ++q)
+    if (q < a.n_out && gp >= a.pair0[q]) h = q;
+  const int np = gp - a.pair0[h];
+  const float* __restrict__ slabs = a.slabs[h];
+  const int m = a.m[h], nmb = a.nmb[h], c = a.c, splits = a.splits;
   const int tid = threadIdx.x;
   const int row = tid >> 4, col = (tid & 15) * 4;
   const int k = kb * 16 + row, n = np * 64 + col;
@@ -208,7 +223,7 @@ __global__ __launch_bounds__(256) void reduce_to_tfrag_kernel(const float* __res
         if (n + 3 < m) s.w += p[z * slab + 3];
       }
     }
-    const float w = k >= k_lo ? scale_hi : 1.f;
+    const float w = k >= a.k_lo ? a.scale_hi : 1.f;
     s.x *= w; s.y *= w; s.z *= w; s.w *= w;
   }
   patch[row][col + 0] = s.x;
@@ -217,13 +232,13 @@ __global__ __launch_bounds__(256) void reduce_to_tfrag_kernel(const float* __res
   patch[row][col + 3] = s.w;
   __syncthreads();
   if (tid < 128) {
-    const int nbl = tid >> 6, lane = tid & 63, j = lane & 31, h = lane >> 5;
+    const int nbl = tid >> 6, lane = tid & 63, j = lane & 31, hh = lane >> 5;
     u32x4 o;
-    o.x = pack2_hw(patch[8 * h + 0][nbl * 32 + j], patch[8 * h + 1][nbl * 32 + j]);
-    o.y = pack2_hw(patch[8 * h + 2][nbl * 32 + j], patch[8 * h + 3][nbl * 32 + j]);
-    o.z = pack2_hw(patch[8 * h + 4][nbl * 32 + j], patch[8 * h + 5][nbl * 32 + j]);
-    o.w = pack2_hw(patch[8 * h + 6][nbl * 32 + j], patch[8 * h + 7][nbl * 32 + j]);
-    reinterpret_cast<u32x4*>(Tf)[((int64_t)kb * nmb + np * 2 + nbl) * 64 + lane] = o;
+    o.x = pack2_hw(patch[8 * hh + 0][nbl * 32 + j], patch[8 * hh + 1][nbl * 32 + j]);
+    o.y = pack2_hw(patch[8 * hh + 2][nbl * 32 + j], patch[8 * hh + 3][nbl * 32 + j]);
+    o.z = pack2_hw(patch[8 * hh + 4][nbl * 32 + j], patch[8 * hh + 5][nbl * 32 + j]);
+    o.w = pack2_hw(patch[8 * hh + 6][nbl * 32 + j], patch[8 * hh + 7][nbl * 32 + j]);
+    reinterpret_cast<u32x4*>(a.Tf[h])[((int64_t)kb * nmb + np * 2 + nbl) * 64 + lane] = o;
   }
 }
 
@@ -254,15 +269,30 @@ __global__ __launch_bounds__(256) void pack_pafrag_kernel(const float* __restric
 
 struct PtArgs {
   const bf16_t* Pa;  // [nrb][nkb][64][8]
-  const bf16_t* Tf;  // [nkb][nmb][64][8]
-  void* dW;
-  int64_t lddw;
-  int d, m, nkb, nmb;
-  int tiles_m, tiles_n;
-  int tiles_m_rb;  // 32-row blocks held by Pa
+  int d, nkb;
+  int tiles_m, tiles_n;  // tiles_n: 128-column tiles over all outputs
+  int tiles_m_rb;        // 32-row blocks held by Pa
   float beta;
-  int vec_ok;  // dW rows allow aligned 16-byte accesses
+  // up to PRAC_CTDY_MAX_OUT products sharing P (layers reading the same input, Section 5.1):
+  // output h owns the column tiles tile0[h] .. tile0[h+1]-1 of the launch
+  int n_out;
+  const bf16_t* Tf[PRAC_CTDY_MAX_OUT];  // [nkb][nmb_h][64][8]
+  void* dW[PRAC_CTDY_MAX_OUT];
+  int64_t lddw[PRAC_CTDY_MAX_OUT];
+  int m[PRAC_CTDY_MAX_OUT];
+  int nmb[PRAC_CTDY_MAX_OUT];
+  int vec_ok[PRAC_CTDY_MAX_OUT];        // dW rows allow aligned 16-byte accesses
+  int tile0[PRAC_CTDY_MAX_OUT + 1];
 };
+
+// which output a column tile of the launch belongs to
+__device__ __forceinline__ int pt_output_of(const PtArgs& a, int tn) {
+  int h = 0;
+#pragma unroll
+  for (int q = 1; q < PRAC_CTDY_MAX_OUT; ++q)
+    if (q < a.n_out && tn >= a.tile0[q]) h = q;
+  return h;
+}
 
 // dW (d x m) = P T, K = c (a few hundred): both operands are read in fragment order
 // straight from L2, no LDS.  256 threads = 2 x 2 waves, a 128 x 128 tile per workgroup,
@@ -277,12 +307,16 @@ __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int logical = xcd * per_xcd + slot;
   if (slot >= per_xcd || logical >= total) return;
-  const int tn = logical % a.tiles_n, tm = logical / a.tiles_n;
+  const int tn_g = logical % a.tiles_n, tm = logical / a.tiles_n;
+  const int h = pt_output_of(a, tn_g), tn = tn_g - a.tile0[h];
+  const u32x4* __restrict__ Tf = reinterpret_cast<const u32x4*>(a.Tf[h]);
+  void* const odW = a.dW[h];
+  const int64_t olddw = a.lddw[h];
+  const int om = a.m[h], onmb = a.nmb[h], ovec = a.vec_ok[h];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 31, lh = lane >> 5;
   const int rb0 = tm * 4 + (wave >> 1) * 2, nb0 = tn * 4 + (wave & 1) * 2;
   const u32x4* __restrict__ Pa = reinterpret_cast<const u32x4*>(a.Pa);
-  const u32x4* __restrict__ Tf = reinterpret_cast<const u32x4*>(a.Tf);
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -297,8 +331,8 @@ __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
     const int k = min(kb, a.nkb - 1);
     r[0] = Pa[((int64_t)rb0 * a.nkb + k) * 64 + lane];
     r[1] = Pa[((int64_t)(rb0 + 1) * a.nkb + k) * 64 + lane];
-    r[2] = Tf[((int64_t)k * a.nmb + nb0) * 64 + lane];
-    r[3] = Tf[((int64_t)k * a.nmb + nb0 + 1) * 64 + lane];
+    r[2] = Tf[((int64_t)k * onmb + nb0) * 64 + lane];
+    r[3] = Tf[((int64_t)k * onmb + nb0 + 1) * 64 + lane];
   };
   auto mfma4 = [&](const u32x4 (&r)[4]) {
     acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(r[0]), as_frag(r[2]), acc[0][0], 0, 0, 0);
@@ -345,12 +379,12 @@ __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
     for (int p = 0; p < 8; ++p) {
       const int row = cr + 16 * p;
       const int grow = row0 + row, gcol = col0 + c8;
-      if (grow >= a.d || gcol >= a.m) continue;
+      if (grow >= a.d || gcol >= om) continue;
       const float4 lo = *reinterpret_cast<const float4*>(tile + row * PT_TLD + c8);
       const float4 hi = *reinterpret_cast<const float4*>(tile + row * PT_TLD + c8 + 4);
       float x[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-      bf16_t* q = reinterpret_cast<bf16_t*>(a.dW) + (int64_t)grow * a.lddw + gcol;
-      if (a.vec_ok && gcol + 8 <= a.m) {
+      bf16_t* q = reinterpret_cast<bf16_t*>(odW) + (int64_t)grow * olddw + gcol;
+      if (ovec && gcol + 8 <= om) {
         if (a.beta != 0.f) {
           const u32x4 old = *reinterpret_cast<const u32x4*>(q);
 #pragma unroll
@@ -364,7 +398,7 @@ __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
         o.w = pack2_hw(x[6], x[7]);
         *reinterpret_cast<u32x4*>(q) = o;
       } else {
-        for (int e = 0; e < 8 && gcol + e < a.m; ++e)
+        for (int e = 0; e < 8 && gcol + e < om; ++e)
           q[e] = f32_to_bf16(a.beta == 0.f ? x[e] : x[e] + a.beta * __uint_as_float(((uint32_t)q[e]) << 16));
       }
     }
@@ -375,10 +409,10 @@ __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
     for (int p = 0; p < 16; ++p) {
       const int row = cr + 8 * p;
       const int grow = row0 + row, gcol = col0 + c4;
-      if (grow >= a.d || gcol >= a.m) continue;
+      if (grow >= a.d || gcol >= om) continue;
       float4 x = *reinterpret_cast<const float4*>(tile + row * PT_TLD + c4);
-      float* q = reinterpret_cast<float*>(a.dW) + (int64_t)grow * a.lddw + gcol;
-      if (a.vec_ok && gcol + 4 <= a.m) {
+      float* q = reinterpret_cast<float*>(odW) + (int64_t)grow * olddw + gcol;
+      if (ovec && gcol + 4 <= om) {
         if (a.beta != 0.f) {
           const float4 old = *reinterpret_cast<const float4*>(q);
           x.x += a.beta * old.x; x.y += a.beta * old.y; x.z += a.beta * old.z; x.w += a.beta * old.w;
@@ -386,7 +420,7 @@ __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
         *reinterpret_cast<float4*>(q) = x;
       } else {
         const float xs[4] = {x.x, x.y, x.z, x.w};
-        for (int e = 0; e < 4 && gcol + e < a.m; ++e) q[e] = a.beta == 0.f ? xs[e] : xs[e] + a.beta * q[e];
+        for (int e = 0; e < 4 && gcol + e < om; ++e) q[e] = a.beta == 0.f ? xs[e] : xs[e] + a.beta * q[e];
       }
     }
   }
@@ -414,12 +448,16 @@ __global__ __launch_bounds__(256) void pt_tiled_kernel(PtArgs a) {
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int logical = xcd * per_xcd + slot;
   if (slot >= per_xcd || logical >= total) return;
-  const int tn = logical % a.tiles_n, tm = logical / a.tiles_n;
+  const int tn_g = logical % a.tiles_n, tm = logical / a.tiles_n;
+  const int h = pt_output_of(a, tn_g), tn = tn_g - a.tile0[h];
+  const u32x4* __restrict__ Tf = reinterpret_cast<const u32x4*>(a.Tf[h]);
+  void* const odW = a.dW[h];
+  const int64_t olddw = a.lddw[h];
+  const int om = a.m[h], onmb = a.nmb[h], ovec = a.vec_ok[h];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 31, lh = lane >> 5;
   const int wr = wave >> 1, wc = wave & 1;
   const u32x4* __restrict__ Pa = reinterpret_cast<const u32x4*>(a.Pa);
-  const u32x4* __restrict__ Tf = reinterpret_cast<const u32x4*>(a.Tf);
   const int nrb = a.tiles_m_rb;  // 32-row blocks Pa holds
 
   f32x16 acc[RI][2];
@@ -445,7 +483,7 @@ __global__ __launch_bounds__(256) void pt_tiled_kernel(PtArgs a) {
 #pragma unroll
     for (int s = 0; s < B_LD; ++s) {
       const int kb = min(kb0 + s, a.nkb - 1);
-      rb[s] = Tf[((int64_t)kb * a.nmb + tn * 4 + sub) * 64 + lane];
+      rb[s] = Tf[((int64_t)kb * onmb + tn * 4 + sub) * 64 + lane];
     }
   };
   auto sstore = [&](int stage) {
@@ -507,11 +545,11 @@ __global__ __launch_bounds__(256) void pt_tiled_kernel(PtArgs a) {
       const int grow = tm * TM + wr * (TM / 2) + p * 64 + row, gcol = tn * 128 + wc * 64 + ec;
       const float4 lo = *reinterpret_cast<const float4*>(tile + row * PT2_ELD + ec);
       const float4 hi = *reinterpret_cast<const float4*>(tile + row * PT2_ELD + ec + 4);
-      if (grow >= a.d || gcol >= a.m) continue;
+      if (grow >= a.d || gcol >= om) continue;
       float x[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
       if (OUT_BF16) {
-        bf16_t* o = reinterpret_cast<bf16_t*>(a.dW) + (int64_t)grow * a.lddw + gcol;
-        if (a.vec_ok && gcol + 8 <= a.m) {
+        bf16_t* o = reinterpret_cast<bf16_t*>(odW) + (int64_t)grow * olddw + gcol;
+        if (ovec && gcol + 8 <= om) {
           if (a.beta != 0.f) {
             const u32x4 old = *reinterpret_cast<const u32x4*>(o);
 #pragma unroll
@@ -525,12 +563,12 @@ __global__ __launch_bounds__(256) void pt_tiled_kernel(PtArgs a) {
           w.w = pack2_hw(x[6], x[7]);
           *reinterpret_cast<u32x4*>(o) = w;
         } else {
-          for (int e = 0; e < 8 && gcol + e < a.m; ++e)
+          for (int e = 0; e < 8 && gcol + e < om; ++e)
             o[e] = f32_to_bf16(a.beta == 0.f ? x[e] : x[e] + a.beta * __uint_as_float(((uint32_t)o[e]) << 16));
         }
       } else {
-        float* o = reinterpret_cast<float*>(a.dW) + (int64_t)grow * a.lddw + gcol;
-        if (a.vec_ok && gcol + 8 <= a.m) {
+        float* o = reinterpret_cast<float*>(odW) + (int64_t)grow * olddw + gcol;
+        if (ovec && gcol + 8 <= om) {
           if (a.beta != 0.f) {
             const float4 o0 = *reinterpret_cast<const float4*>(o), o1 = *reinterpret_cast<const float4*>(o + 4);
             x[0] += a.beta * o0.x; x[1] += a.beta * o0.y; x[2] += a.beta * o0.z; x[3] += a.beta * o0.w;
@@ -539,7 +577,7 @@ __global__ __launch_bounds__(256) void pt_tiled_kernel(PtArgs a) {
           *reinterpret_cast<float4*>(o) = make_float4(x[0], x[1], x[2], x[3]);
           *reinterpret_cast<float4*>(o + 4) = make_float4(x[4], x[5], x[6], x[7]);
         } else {
-          for (int e = 0; e < 8 && gcol + e < a.m; ++e) o[e] = a.beta == 0.f ? x[e] : x[e] + a.beta * o[e];
+          for (int e = 0; e < 8 && gcol + e < om; ++e) o[e] = a.beta == 0.f ? x[e] : x[e] + a.beta * o[e];
         }
       }
     }
@@ -612,10 +650,19 @@ int launch_reduce_scale_bf16(prac_ctx* ctx, const float* slabs, int splits, int 
   return PRAC_OK;
 }
 
-int launch_reduce_to_tfrag(prac_ctx* ctx, const float* slabs, int splits, int c, int m, int k_lo, float scale_hi,
-                           int nkb, int nmb, bf16_t* Tf) {
-  PRAC_LAUNCH(ctx, reduce_to_tfrag_kernel, dim3(nkb * (nmb / 2)), dim3(256), 0, slabs, splits, c, m, k_lo, scale_hi, nkb,
-              nmb, Tf);
+int launch_reduce_to_tfrag(prac_ctx* ctx, int n_out, const float* const* slabs, int splits, int c, const int* m, int k_lo,
+                           float scale_hi, int nkb, const int* nmb, bf16_t* const* Tf) {
+  if (n_out < 1 || n_out > PRAC_CTDY_MAX_OUT) return PRAC_EINVAL;
+  ReduceTfArgs a{};
+  a.n_out = n_out; a.splits = splits; a.c = c; a.k_lo = k_lo; a.nkb = nkb; a.scale_hi = scale_hi;
+  int pairs = 0;
+  for (int h = 0; h < n_out; ++h) {
+    a.slabs[h] = slabs[h]; a.Tf[h] = Tf[h]; a.m[h] = m[h]; a.nmb[h] = nmb[h];
+    a.pair0[h] = pairs;
+    pairs += nmb[h] / 2;
+  }
+  for (int h = n_out; h <= PRAC_CTDY_MAX_OUT; ++h) a.pair0[h] = pairs;
+  PRAC_LAUNCH(ctx, reduce_to_tfrag_kernel, dim3(nkb * pairs), dim3(256), 0, a);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }
@@ -627,13 +674,21 @@ int launch_pack_pafrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, in
   return PRAC_OK;
 }
 
-int launch_pt(prac_ctx* ctx, const bf16_t* Pa, const bf16_t* Tf, int d, int m, int nkb, int nmb, void* dW,
-              int64_t lddw, bool out_bf16, float beta) {
-  PtArgs a;
-  a.Pa = Pa; a.Tf = Tf; a.dW = dW; a.lddw = lddw; a.d = d; a.m = m; a.nkb = nkb; a.nmb = nmb;
-  a.tiles_n = (m + 127) / 128; a.beta = beta;
+int launch_pt(prac_ctx* ctx, const bf16_t* Pa, int n_out, const bf16_t* const* Tf, int d, const int* m, int nkb,
+              const int* nmb, void* const* dW, const int64_t* lddw, bool out_bf16, float beta) {
+  if (n_out < 1 || n_out > PRAC_CTDY_MAX_OUT) return PRAC_EINVAL;
+  PtArgs a{};
+  a.Pa = Pa; a.d = d; a.nkb = nkb; a.beta = beta; a.n_out = n_out;
   a.tiles_m_rb = ((d + 127) / 128) * 4;
-  a.vec_ok = (reinterpret_cast<uintptr_t>(dW) % 16 == 0 && lddw % (out_bf16 ? 8 : 4) == 0) ? 1 : 0;
+  int tiles = 0;
+  for (int h = 0; h < n_out; ++h) {
+    a.Tf[h] = Tf[h]; a.dW[h] = dW[h]; a.lddw[h] = lddw[h]; a.m[h] = m[h]; a.nmb[h] = nmb[h];
+    a.vec_ok[h] = (reinterpret_cast<uintptr_t>(dW[h]) % 16 == 0 && lddw[h] % (out_bf16 ? 8 : 4) == 0) ? 1 : 0;
+    a.tile0[h] = tiles;
+    tiles += (m[h] + 127) / 128;
+  }
+  for (int h = n_out; h <= PRAC_CTDY_MAX_OUT; ++h) a.tile0[h] = tiles;
+  a.tiles_n = tiles;
   // the direct kernel for a single round of short products, the LDS-staged one otherwise (measured:
   // 21 against 26 us at d = 2048, m = 5461, c = 256; 95 against 117 us at d = 4096, m = 11008, c = 512)
   a.tiles_m = (d + 127) / 128;

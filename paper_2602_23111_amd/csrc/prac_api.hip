@@ -568,18 +568,19 @@ int weight_grad_fast(prac_ctx* ctx, const void* C, int64_t N, int64_t ldc, bool 
     rc = launch_ctdy_ws(ctx, Cpk, c, (int)N, n_out, dYp, lddy, mi, part, splits);
   }
   if (rc) return rc;
-  for (int h = 0; h < n_out; ++h) {
-    bf16_t* Tf = reinterpret_cast<bf16_t*>(ctx->ws + o_t[h]);
-    {  // T in fragment order (bf16): slabs summed, random rows weighted by the scaling factor
-      ProfScope ps(ctx, PRAC_KERNEL_T_REDUCE);
-      rc = launch_reduce_to_tfrag(ctx, part[h], splits, c, mi[h], k, scale, l.nckb, nmb[h], Tf);
-    }
-    if (rc) return rc;
-    ProfScope ps(ctx, PRAC_KERNEL_P_T);  // dW = P T
-    rc = launch_pt(ctx, reinterpret_cast<const bf16_t*>(lp + l.off_pa), Tf, (int)d, mi[h], l.nckb, nmb[h], dW[h], lddw[h],
-                   odt == PRAC_BF16, beta);
-    if (rc) return rc;
+  bf16_t* Tf[PRAC_CTDY_MAX_OUT];
+  for (int h = 0; h < n_out; ++h) Tf[h] = reinterpret_cast<bf16_t*>(ctx->ws + o_t[h]);
+  {  // T_h in fragment order (bf16): slabs summed, random rows weighted by the scaling factor
+    ProfScope ps(ctx, PRAC_KERNEL_T_REDUCE);
+    rc = launch_reduce_to_tfrag(ctx, n_out, part, splits, c, mi, k, scale, l.nckb, nmb, Tf);
   }
+  if (rc) return rc;
+  {
+    ProfScope ps(ctx, PRAC_KERNEL_P_T);  // dW_h = P T_h, all outputs in one launch
+    rc = launch_pt(ctx, reinterpret_cast<const bf16_t*>(lp + l.off_pa), n_out, Tf, (int)d, mi, l.nckb, nmb, dW, lddw,
+                   odt == PRAC_BF16, beta);
+  }
+  if (rc) return rc;
   return PRAC_OK;
 }
 

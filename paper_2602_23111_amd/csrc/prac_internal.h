@@ -138,11 +138,12 @@ int launch_pack_c(prac_ctx* ctx, const bf16_t* C, int64_t ldc, int N, int c, bf1
 int launch_reduce_scale_bf16(prac_ctx* ctx, const float* slabs, int splits, int c, int m, int k_lo,
                              float scale_hi, bf16_t* T, int64_t ldt);
 
-int launch_reduce_to_tfrag(prac_ctx* ctx, const float* slabs, int splits, int c, int m, int k_lo, float scale_hi,
-                           int nkb, int nmb, bf16_t* Tf);
+int launch_reduce_to_tfrag(prac_ctx* ctx, int n_out, const float* const* slabs, int splits, int c, const int* m, int k_lo,
+                           float scale_hi, int nkb, const int* nmb, bf16_t* const* Tf);
 int launch_pack_pafrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nrb, int nkb, bf16_t* out);
-int launch_pt(prac_ctx* ctx, const bf16_t* Pa, const bf16_t* Tf, int d, int m, int nkb, int nmb, void* dW,
-              int64_t lddw, bool out_bf16, float beta);
+// dW_h (d x m_h) = P T_h (+ beta dW_h) for n_out <= PRAC_CTDY_MAX_OUT outputs in one launch
+int launch_pt(prac_ctx* ctx, const bf16_t* Pa, int n_out, const bf16_t* const* Tf, int d, const int* m, int nkb,
+              const int* nmb, void* const* dW, const int64_t* lddw, bool out_bf16, float beta);
 
 // P (d x c fp32, ldp) -> B operand of Xh = C Ps^T in fragment order [nkb][ncb][64][8] (bf16, zero padded):
 // element (k = column of P, n = row of P) = P[n][k] * (k >= k_lo ? scale_hi : 1)
