@@ -19,8 +19,7 @@ namespace {
 // panel is factored there (right-looking inside the panel, across its full width), written
 // back, and applied to the trailing rows as a rank-CH_NB update.  Non-finite or
 // non-positive pivots raise *flag and are replaced by a tiny positive number.
-// NT threads: 256 for small matrices, where the barriers between the pivot steps cost more than
-// the arithmetic they separate, 1024 otherwise.
+// NT threads (1024 is what is launched; 256 measured slower at every panel width tried).
 constexpr int CH_NB = 16;
 template <int NT>
 __global__ __launch_bounds__(NT) void chol_upper_kernel(double* W, int b, double shift_rel, int* flag) {
@@ -409,8 +408,6 @@ int set_dyn_smem(prac_ctx* ctx) {
   static bool done = false;
   if (!done) {
     PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_upper_kernel<1024>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, CH_NB * 1024 * 8));
-    PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_upper_kernel<256>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, CH_NB * 1024 * 8));
     PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(trsm_right_upper_kernel),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (TR_ROWS + TR_CH) * 1024 * 4));

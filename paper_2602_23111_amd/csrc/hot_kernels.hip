@@ -145,35 +145,6 @@ __global__ __launch_bounds__(256) void pack_c_kernel(const bf16_t* __restrict__ 
   }
 }
 
-// T (c x ldt bf16, row-major) = w_j * sum_z slab[z][j][n]; w_j = 1 (j < k_lo) or scale_hi.
-// Four columns per thread; columns m..ldt-1 are zeroed.
-__global__ __launch_bounds__(256) void reduce_scale_bf16_kernel(const float* __restrict__ slabs, int splits, int c,
-                                                                int m, int k_lo, float scale_hi,
-                                                                bf16_t* __restrict__ T, int64_t ldt) {
-  const int64_t quads = ldt / 4, total = (int64_t)c * quads, slab = (int64_t)c * m;
-  for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t j = g / quads, n = (g % quads) * 4;
-    float s[4] = {0.f, 0.f, 0.f, 0.f};
-    const float* p = slabs + j * m + n;
-    if (n + 3 < m && (m & 3) == 0) {
-#pragma unroll 4
-      for (int z = 0; z < splits; ++z) {
-        const float4 v = *reinterpret_cast<const float4*>(p + z * slab);
-        s[0] += v.x; s[1] += v.y; s[2] += v.z; s[3] += v.w;
-      }
-    } else {
-      for (int z = 0; z < splits; ++z)
-        for (int e = 0; e < 4; ++e)
-          if (n + e < m) s[e] += p[z * slab + e];
-    }
-    const float w = j >= k_lo ? scale_hi : 1.f;
-    uint2 o;
-    o.x = pack2(s[0] * w, s[1] * w);
-    o.y = pack2(s[2] * w, s[3] * w);
-    *reinterpret_cast<uint2*>(T + j * ldt + n) = o;
-  }
-}
-
 // ------------------------------------------------------------------- dW = P T
 // T in fragment order, built by the slab reducer: Tf[(kb * nmb + nb) * 64 + lane][e] =
 // bf16(w_k * sum_z slab[z][k][n]) with k = 16 kb + 8 h + e, n = 32 nb + j, lane = 32 h + j,
@@ -638,14 +609,6 @@ int launch_pack_c(prac_ctx* ctx, const bf16_t* C, int64_t ldc, int N, int c, bf1
   const int ccb = (c + 31) / 32;
   hipLaunchKernelGGL(pack_c_kernel, dim3(grid_for((int64_t)((N + 127) / 128) * 8 * ccb * 64, ctx->n_cu)), dim3(256), 0,
                      ctx->stream, C, ldc, N, c, ccb, Cpk);
-  PRAC_HIP_TRY(ctx, hipGetLastError());
-  return PRAC_OK;
-}
-
-int launch_reduce_scale_bf16(prac_ctx* ctx, const float* slabs, int splits, int c, int m, int k_lo, float scale_hi,
-                             bf16_t* T, int64_t ldt) {
-  hipLaunchKernelGGL(reduce_scale_bf16_kernel, dim3(grid_for((int64_t)c * (ldt / 4), ctx->n_cu)), dim3(256), 0,
-                     ctx->stream, slabs, splits, c, m, k_lo, scale_hi, T, ldt);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }

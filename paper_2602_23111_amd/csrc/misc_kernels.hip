@@ -118,32 +118,6 @@ __global__ __launch_bounds__(256) void reduce_slabs_kernel(const float* __restri
   }
 }
 
-// part: splits x M x N fp32.  Tt[n][j] = bf16(w_j * sum_z part[z][j][n]) with w_j = 1 for
-// j < k_lo and scale_hi above; Tt has ldt >= M columns, the excess is zeroed.
-__global__ __launch_bounds__(256) void reduce_transpose_bf16_kernel(const float* __restrict__ part, int splits, int M,
-                                                                    int N, int k_lo, float scale_hi,
-                                                                    bf16_t* __restrict__ Tt, int64_t ldt) {
-  __shared__ float tile[32][33];
-  const int j0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
-  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
-  const int64_t slab = (int64_t)M * N;
-  for (int r = ty; r < 32; r += 8) {
-    const int j = j0 + r, n = n0 + tx;
-    float s = 0.f;
-    if (j < M && n < N) {
-      const float* p = part + (int64_t)j * N + n;
-      for (int z = 0; z < splits; ++z) s += p[z * slab];
-      if (j >= k_lo) s *= scale_hi;
-    }
-    tile[r][tx] = s;
-  }
-  __syncthreads();
-  for (int r = ty; r < 32; r += 8) {
-    const int n = n0 + r, j = j0 + tx;
-    if (n < N && j < ldt) Tt[(int64_t)n * ldt + j] = f32_to_bf16(tile[tx][r]);
-  }
-}
-
 // part: splits x M x N fp32.  out[n][j] = sum_z part[z][j][n] (N x M, ld = ldo)
 __global__ __launch_bounds__(256) void reduce_transpose_f32_kernel(const float* __restrict__ part, int splits, int M,
                                                                    int N, float* __restrict__ out, int64_t ldo) {
@@ -192,14 +166,6 @@ __global__ __launch_bounds__(256) void cast_out_kernel(const float* __restrict__
   }
 }
 
-__global__ __launch_bounds__(256) void symmetrize_kernel(float* G, int d, int64_t ldg) {
-  const int64_t total = (int64_t)d * d;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t r = i / d, c = i % d;
-    if (r > c) G[r * ldg + c] = G[c * ldg + r];
-  }
-}
-
 inline int grid_for(int64_t n, int n_cu) {
   int64_t g = (n + 255) / 256;
   const int64_t cap = (int64_t)n_cu * 8;
@@ -238,15 +204,6 @@ int launch_reduce_slabs(prac_ctx* ctx, const float* part, int splits, int64_t st
   return PRAC_OK;
 }
 
-int launch_reduce_transpose_bf16(prac_ctx* ctx, const float* part, int splits, int M, int N, int k_lo, float scale_hi,
-                                 bf16_t* Tt, int64_t ldt) {
-  dim3 grid((N + 31) / 32, (unsigned)((ldt + 31) / 32));
-  hipLaunchKernelGGL(reduce_transpose_bf16_kernel, grid, dim3(256), 0, ctx->stream, part, splits, M, N, k_lo,
-                     scale_hi, Tt, ldt);
-  PRAC_HIP_TRY(ctx, hipGetLastError());
-  return PRAC_OK;
-}
-
 int launch_reduce_transpose_f32(prac_ctx* ctx, const float* part, int splits, int M, int N, float* out, int64_t ldo) {
   dim3 grid((N + 31) / 32, (M + 31) / 32);
   hipLaunchKernelGGL(reduce_transpose_f32_kernel, grid, dim3(256), 0, ctx->stream, part, splits, M, N, out, ldo);
@@ -273,8 +230,3 @@ int launch_cast_out(prac_ctx* ctx, const float* src, int64_t lds, void* dst, pra
   return PRAC_OK;
 }
 
-int launch_symmetrize(prac_ctx* ctx, float* G, int d, int64_t ldg) {
-  hipLaunchKernelGGL(symmetrize_kernel, dim3(grid_for((int64_t)d * d, ctx->n_cu)), dim3(256), 0, ctx->stream, G, d, ldg);
-  PRAC_HIP_TRY(ctx, hipGetLastError());
-  return PRAC_OK;
-}

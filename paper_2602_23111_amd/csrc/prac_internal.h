@@ -101,9 +101,6 @@ int launch_gemm_generic(prac_ctx* ctx, const GemmGenArgs& a);
 // out[i] = alpha * sum_s part[s*stride + i] + beta * out[i], i < n (fp32)
 int launch_reduce_slabs(prac_ctx* ctx, const float* part, int splits, int64_t stride, float* out,
                         int64_t n, float alpha, float beta);
-// Tt (N x ldt bf16) = transpose of rowscale(j) * sum_s part[s][j][n], j < M; columns M..ldt-1 zeroed
-int launch_reduce_transpose_bf16(prac_ctx* ctx, const float* part, int splits, int M, int N, int k_lo,
-                                 float scale_hi, bf16_t* Tt, int64_t ldt);
 // out (N x M fp32, ld = ldo) = transpose of sum_s part[s][j][n], j < M
 int launch_reduce_transpose_f32(prac_ctx* ctx, const float* part, int splits, int M, int N, float* out, int64_t ldo);
 // fp32 matrix (rows x cols, ld) rows >= k_lo multiplied by s
@@ -114,7 +111,6 @@ int launch_pack_basis(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int
                       int64_t ldpt, bf16_t* Pn, int64_t ldpn);
 int launch_cast_out(prac_ctx* ctx, const float* src, int64_t lds, void* dst, prac_dtype odt,
                     int64_t ldd, int rows, int cols, float beta);
-int launch_symmetrize(prac_ctx* ctx, float* G, int d, int64_t ldg);  // copy upper -> lower
 
 // ---- kernels of the per-step path (ws_kernels.hip, hot_kernels.hip) -----------------
 // Wfrag != nullptr: also Y (N x m, ldy) = X W, W in the fragment order of Pfrag with ncb_w column blocks
@@ -135,8 +131,6 @@ int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, int N, int n_out, co
 int launch_pack_pfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nkb, int ncb, bf16_t* out);
 int launch_unpack_c(prac_ctx* ctx, const bf16_t* Cpk, int N, int c, bf16_t* C, int64_t ldc);
 int launch_pack_c(prac_ctx* ctx, const bf16_t* C, int64_t ldc, int N, int c, bf16_t* Cpk);
-int launch_reduce_scale_bf16(prac_ctx* ctx, const float* slabs, int splits, int c, int m, int k_lo,
-                             float scale_hi, bf16_t* T, int64_t ldt);
 
 int launch_reduce_to_tfrag(prac_ctx* ctx, int n_out, const float* const* slabs, int splits, int c, const int* m, int k_lo,
                            float scale_hi, int nkb, const int* nmb, bf16_t* const* Tf);
