@@ -111,13 +111,119 @@ def cpu_baseline(X, dY, k, r, refresh_every):
                        f"steps), compress + weight-grad {t_cw:.2f} s (best of 2)")
 
 
+BLOCK_WORKLOAD = "llama1b_block"
+
+
+def run_block(args):
+    """All seven linear layers of one LLaMA-1B transformer block with subspace sharing (Section 5.1):
+    q/k/v share the compressed attention input, up/gate the compressed MLP input; o and down have
+    their own.  4 compressions + 7 weight gradients per step, each of the 4 bases refreshed (tracking
+    refit on the step's batch) every 500 steps."""
+    import torch
+
+    import synth_inputs as si
+    from paper_2602_23111_amd.prac import C_PACKED, Prac
+
+    N, k, r, refresh_every, n_sets = 32768, 128, 128, 500, 2
+    c = k + r
+    groups = [("attn_in:q,k,v", 2048, [2048, 2048, 2048]), ("attn_out:o", 2048, [2048]),
+              ("mlp_in:up,gate", 2048, [5461, 5461]), ("mlp_down:down", 5461, [2048])]
+    ld8 = lambda n: (n + 7) // 8 * 8
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+    ctx = Prac(0)
+    G = []
+    for gi, (name, d, ms) in enumerate(groups):
+        seed = 3000 + 10 * gi
+        g = dict(name=name, d=d, ms=ms, P=torch.zeros((d, c), dtype=torch.float32, device=dev), lp=None, scale=0.0,
+                 X=[si.activation_torch(N, d, 0.8, seed, 8, 30.0, torch.bfloat16, dev, ld=ld8(d), batch=i)
+                    for i in range(n_sets)],
+                 dY=[[si.grad_output_torch(N, m, 1e-3, seed + 100 + 10 * i + j, torch.bfloat16, dev, ld=ld8(m))
+                      for j, m in enumerate(ms)] for i in range(n_sets)],
+                 C=[torch.empty(ctx.compressed_bytes(N, c) // 2, dtype=torch.bfloat16, device=dev) for _ in range(n_sets)],
+                 dW=[torch.empty((d, ld8(m)), dtype=torch.bfloat16, device=dev)[:, :m] for m in ms])
+        G.append(g)
+    fits = [0]
+
+    def layer_compress(g, i):
+        ctx.compress(g["X"][i], g["P"], P_lp=g["lp"], out=g["C"][i], layout=C_PACKED)
+
+    def layer_wgrad(g, i):
+        if len(g["ms"]) == 1:
+            ctx.weight_grad(g["C"][i], g["dY"][i][0], g["P"], k, r, g["scale"], P_lp=g["lp"], out=g["dW"][0],
+                            layout=C_PACKED)
+        else:
+            ctx.weight_grad_shared(g["C"][i], g["dY"][i], g["P"], k, r, g["scale"], P_lp=g["lp"], outs=g["dW"],
+                                   layout=C_PACKED)
+
+    def step(t):
+        i = t % n_sets
+        for g in G:
+            if t % refresh_every == 0:
+                warm = g["lp"] is not None
+                _, g["lp"], g["scale"] = ctx.fit_basis(g["X"][i], k, r, seed=1234, draw=t // refresh_every, P=g["P"],
+                                                       warm_start=warm, iters=WORKLOAD["warm_iters"] if warm else 0,
+                                                       oversample=WORKLOAD["warm_oversample"] if warm else 0)
+                fits[0] += 1
+            layer_compress(g, i)
+            layer_wgrad(g, i)
+
+    for t in range(max(min(args.warmup, 5), 1)):
+        step(t)
+    torch.cuda.synchronize()
+
+    def wall(fn, reps=20):
+        for t in range(2):
+            fn(t % n_sets)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(reps):
+            fn(t % n_sets)
+        torch.cuda.synchronize()
+        return 1e6 * (time.perf_counter() - t0) / reps
+
+    layers_us = {}
+    for g in G:
+        layers_us[g["name"]] = {"compress": wall(lambda i: layer_compress(g, i)), "weight_grad": wall(lambda i: layer_wgrad(g, i))}
+    fits[0] = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.steps):
+        step(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ctx.sync_status()
+    ms_per_step = 1e3 * elapsed / args.steps
+    # algorithmic bytes of the block: every X, dY, C (written and read once per gradient launch), P and dW once
+    by = 0.0
+    for _, d, ms in groups:
+        by += 2.0 * (N * d + d * c + N * c) + 2.0 * (N * c + sum(N * m + d * m for m in ms) + d * c)
+    out = {
+        "metric": "PRAC compress+weight-grad tokens/s at LLaMA-1B shape",
+        "value": N / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{BLOCK_WORKLOAD}: the 7 linear layers of one LLaMA-1B block, N={N} k={k} r={r} bf16, dW bf16, "
+                               f"q/k/v and up/gate share their compressed input (4 compressions, 7 weight gradients per "
+                               f"step), 4 bases refreshed every {refresh_every} steps ({fits[0]} refits in the timed region), "
+                               f"{n_sets} rotating input sets"},
+        "roofline": {"kernel": "whole step", "bound": "hbm", "achieved": by / (ms_per_step * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": by / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None},
+        "cpu_baseline": None,
+        "layers_us": layers_us,
+    }
+    print(json.dumps(out))
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--cpu-sample", type=int, default=1, help="0: skip the oracle's timed run on the host")
-    ap.add_argument("--workload", default=WORKLOAD["name"], choices=[WORKLOAD["name"]] + sorted(OTHER_WORKLOADS),
+    ap.add_argument("--workload", default=WORKLOAD["name"], choices=[WORKLOAD["name"], BLOCK_WORKLOAD] + sorted(OTHER_WORKLOADS),
                     help="layer shape to run (default: the headline attention projection of the LLaMA-1B configuration)")
     ap.add_argument("--others", type=int, default=1,
                     help="0: skip timing the fused forward and the reconstruction (outside the timed region)")
@@ -138,6 +244,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.workload == BLOCK_WORKLOAD:
+        return run_block(args)
     w = WORKLOAD if args.workload == WORKLOAD["name"] else OTHER_WORKLOADS[args.workload]
     if w is not WORKLOAD:
         args.others = 0          # the extra entry points are timed at the headline shape only
