@@ -127,6 +127,108 @@ __global__ __launch_bounds__(256) void trsm_right_upper_kernel(const float* __re
     for (int c = cl; c < n; c += 16) dst[row * n + c] = y[r * n + c];
 }
 
+// value of x in lane U of each row of 16 lanes
+template <int U>
+__device__ __forceinline__ float row_share(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x150 + U, 0xf, 0xf, false));
+}
+
+// steps U .. 15 of chunk JC (columns 16 JC .. 16 JC + 15) of the register-resident triangular solve
+// (see the kernel below)
+template <int U, int JC, int NPT>
+__device__ __forceinline__ void trsm_steps(float (&y)[NPT], const float* __restrict__ rch, int n, int nt, int cl) {
+  if constexpr (U < 16) {
+    if (U < nt) {  // uniform
+      const float* ru = rch + U * n;
+      const float vt = row_share<U>(y[JC]) * ru[16 * JC + U];
+      if (cl == U) y[JC] = vt;
+      if (cl > U) y[JC] -= vt * ru[16 * JC + cl];
+#pragma unroll
+      for (int j = JC + 1; j < NPT; ++j) {
+        const int c = cl + 16 * j;
+        if (c < n) y[j] -= vt * ru[c];
+      }
+      trsm_steps<U + 1, JC, NPT>(y, rch, n, nt, cl);
+    }
+  }
+}
+
+// row t0 + r of R, columns cl, cl + 16, ... into registers (thread (r, cl) of the workgroup)
+template <int NPT>
+__device__ __forceinline__ void trsm_fetch(double (&nx)[NPT], const double* __restrict__ R, int n, int t0, int r, int cl) {
+#pragma unroll
+  for (int j = 0; j < NPT; ++j) {
+    const int c = cl + 16 * j, t = t0 + r;
+    nx[j] = (t < n && c < n && c >= t) ? R[(int64_t)t * n + c] : 0.0;
+  }
+}
+
+// ... and from there into LDS as fp32, the diagonal inverted
+template <int NPT>
+__device__ __forceinline__ void trsm_stage(const double (&nx)[NPT], float* rch, int n, int t0, int r, int cl) {
+#pragma unroll
+  for (int j = 0; j < NPT; ++j) {
+    const int c = cl + 16 * j;
+    if (c < n) {
+      double v = nx[j];
+      if (c == t0 + r) v = 1.0 / v;
+      rch[r * n + c] = (float)v;
+    }
+  }
+}
+
+// chunks JC .. NPT-1: the 16 steps of chunk JC run while the rows of R for chunk JC + 1 are in flight
+template <int JC, int NPT>
+__device__ __forceinline__ void trsm_chunks(float (&y)[NPT], double (&nx)[NPT], float* rch, const double* __restrict__ R,
+                                            int n, int r, int cl) {
+  if constexpr (JC < NPT) {
+    constexpr int t0 = 16 * JC;
+    if (t0 < n) {  // uniform
+      const int nt = min(16, n - t0);
+      __syncthreads();  // previous chunk fully used
+      trsm_stage<NPT>(nx, rch, n, t0, r, cl);
+      __syncthreads();
+      if (t0 + 16 < n) trsm_fetch<NPT>(nx, R, n, t0 + 16, r, cl);
+      trsm_steps<0, JC, NPT>(y, rch, n, nt, cl);
+      trsm_chunks<JC + 1, NPT>(y, nx, rch, R, n, r, cl);
+    }
+  }
+}
+
+// dst (rows x n, fp32) = src * R^-1 as above for n <= 16 NPT, with the rows of y in registers: 16
+// threads per row, thread cl holds columns cl, cl + 16, ...  Step t multiplies column t by
+// 1 / R[t][t] (a DPP row share broadcasts it to the row's 16 lanes) and subtracts it, times row t of
+// R, from the columns to its right.  No barrier and no LDS round trip per step.  Chunks and steps
+// are unrolled, so every register index and every broadcast lane is a constant.  R is staged
+// through LDS 16 rows at a time as fp32 with the diagonal inverted (two barriers per chunk), the
+// next chunk's rows being fetched while the current chunk's steps run.
+template <int NPT>
+__global__ __launch_bounds__(256) void trsm_right_upper_reg_kernel(const float* __restrict__ src,
+                                                                   const double* __restrict__ R, float* __restrict__ dst,
+                                                                   int64_t rows, int n) {
+  extern __shared__ __align__(16) unsigned char trsm_smem[];
+  float* rch = reinterpret_cast<float*>(trsm_smem);  // [TR_CH][n]: rows t0 .. t0+15 of R, diagonal inverted
+  const int tid = threadIdx.x, r = tid >> 4, cl = tid & 15;
+  const int64_t row = (int64_t)blockIdx.x * TR_ROWS + r;
+  const bool ok = row < rows;
+  float y[NPT];
+#pragma unroll
+  for (int j = 0; j < NPT; ++j) {
+    const int c = cl + 16 * j;
+    y[j] = (ok && c < n) ? src[row * n + c] : 0.f;
+  }
+  double nx[NPT];
+  trsm_fetch<NPT>(nx, R, n, 0, r, cl);
+  trsm_chunks<0, NPT>(y, nx, rch, R, n, r, cl);
+  if (ok) {
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) {
+      const int c = cl + 16 * j;
+      if (c < n) dst[row * n + c] = y[j];
+    }
+  }
+}
+
 // ------------------------------------------------------- symmetric eigen (Jacobi)
 // One-sided (Hestenes) Jacobi on the columns of the symmetric PSD matrix H, held
 // row-major so that "column" p is the contiguous row p (H is symmetric).  Rotating
@@ -457,8 +559,16 @@ int cholqr_pass(prac_ctx* ctx, const FitWs& w, const float* src, float* dst, int
   if (rc) return rc;
   hipLaunchKernelGGL(chol_upper_kernel<1024>, dim3(1), dim3(1024), (size_t)CH_NB * n * sizeof(double), ctx->stream, W64,
                      n, shift, ctx->d_flag);
-  hipLaunchKernelGGL(trsm_right_upper_kernel, dim3((unsigned)((d + TR_ROWS - 1) / TR_ROWS)), dim3(256),
-                     (size_t)(TR_ROWS + TR_CH) * n * sizeof(float), ctx->stream, src, W64, dst, d, n);
+  const dim3 tgrid((unsigned)((d + TR_ROWS - 1) / TR_ROWS));
+  if (n <= 128)
+    hipLaunchKernelGGL(trsm_right_upper_reg_kernel<8>, tgrid, dim3(256), (size_t)TR_CH * n * sizeof(float), ctx->stream,
+                       src, W64, dst, d, n);
+  else if (n <= 256)
+    hipLaunchKernelGGL(trsm_right_upper_reg_kernel<16>, tgrid, dim3(256), (size_t)TR_CH * n * sizeof(float), ctx->stream,
+                       src, W64, dst, d, n);
+  else
+    hipLaunchKernelGGL(trsm_right_upper_kernel, tgrid, dim3(256), (size_t)(TR_ROWS + TR_CH) * n * sizeof(float),
+                       ctx->stream, src, W64, dst, d, n);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }
