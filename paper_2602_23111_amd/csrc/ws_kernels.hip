@@ -656,9 +656,11 @@ __global__ __launch_bounds__(512) void reconstruct_ws_kernel(ReconWsArgs a) {
 //                  A fragments (packed C, L2-resident) straight into registers, issue MFMAs.
 // LDS stage: [k-block 0..7][column block 0..3][64 lanes][16 bytes].  Column block nb holds the
 // tile's columns 4 j + nb (j = 0..31), so that a lane's four accumulators of one row are four
-// consecutive columns of T.  Lane slot (j, h) sits at 16-byte slot h*32 + ((j & 16) | ((j & 15) ^ (j >> 4)))
-// of its 1 KB block: with this swizzle both the loaders' stores (16 lanes write slots 2 cc + u of
-// four different blocks) and the fragment reads are free of bank conflicts.
+// consecutive columns of T.  Lane slot (j, h) sits at 16-byte slot h*32 + (j ^ ((j >> 3) & 1)) of its
+// 1 KB block.  A 16-byte LDS access is served eight lanes at a time (8 x 16 bytes = the 32 banks):
+// eight consecutive lanes of a fragment read (j = 8 g .. 8 g + 7) get the eight slots of one
+// 128-byte line, and eight consecutive loader lanes, which write every other column slot
+// (j = 2 cc + u), get eight slots that differ modulo 8 - neither has a bank conflict.
 // Element e of lane half h is token 16 kb + (e < 4 ? 4 h + e : 8 + 4 h + e - 4), the slot order of
 // packed C, so both operands list the tokens of a k-block in the same order.
 struct CtdyWsArgs {
@@ -729,7 +731,7 @@ __device__ __forceinline__ void frag_read4_ct(u32x4 (&f)[4], unsigned lds) {
 }
 
 __device__ __forceinline__ int c_slot_tok(int h, int e) { return e < 4 ? 4 * h + e : 8 + 4 * h + (e - 4); }
-__device__ __forceinline__ int frag_slot(int j, int h) { return h * 32 + ((j & 16) | ((j & 15) ^ (j >> 4))); }
+__device__ __forceinline__ int frag_slot(int j, int h) { return h * 32 + (j ^ ((j >> 3) & 1)); }
 
 __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
