@@ -554,8 +554,11 @@ __global__ __launch_bounds__(512) void reconstruct_ws_kernel(ReconWsArgs a) {
       asm volatile("" ::: "memory");
       u32x4 ro[16];
 #pragma unroll
-      for (int q = 0; q < 16; ++q)
+      for (int q = 0; q < 16; ++q) {
         ro[q] = *reinterpret_cast<const u32x4*>(smem_raw + RW_OUT + (crow + 8 * q) * RW_OLD + ccol * 2);
+        // rows 8 .. 15 (mod 16) are staged with the 8-byte halves of every 16 bytes swapped (see the writers)
+        if (q & 1) ro[q] = u32x4{ro[q].z, ro[q].w, ro[q].x, ro[q].y};
+      }
       const int n = g * 256 + ccol;
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
@@ -610,7 +613,9 @@ __global__ __launch_bounds__(512) void reconstruct_ws_kernel(ReconWsArgs a) {
   __builtin_amdgcn_s_barrier();  // the C tile is in LDS
   frag_read4(fa, lds0);
   // staging address of this lane: token row li (+ 32 i), columns 64 wave (+ 32 j + 8 q) + 4 lh .. + 3
-  unsigned char* const orow = smem_raw + RW_OUT + li * RW_OLD + (wave * 64 + 4 * lh) * 2;
+  // (a row is 528 bytes: lanes li and li + 8 of an 8-byte store would meet in the same banks, so
+  // rows 8 .. 15 of every 16 swap the two 8-byte halves of each 16 bytes)
+  unsigned char* const orow = smem_raw + RW_OUT + li * RW_OLD + (((wave * 64 + 4 * lh) * 2) ^ (((li >> 3) & 1) << 3));
   for (int g = 0; g < G; ++g) {
     static_for<WS_KB>([&](auto jc) {
       constexpr int J = decltype(jc)::value;
