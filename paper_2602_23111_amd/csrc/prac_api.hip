@@ -639,15 +639,21 @@ int prac_reconstruct(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int
     // (its "feature" dimension is c) and Ps^T in the role of W.
     const int nkb = (int)(round_up64(c, 256) / 16);
     const int ncb = (int)round_up64((d + 31) / 32, 8);
+    const bool direct = c <= 256;  // the dedicated kernel reads packed C itself
     const int64_t ldcrm = packed ? round_up64(c, 8) : ldc;
     WsPlan plan;
     const size_t o_pt = plan.take((size_t)nkb * ncb * 64 * 8 * sizeof(bf16_t));
-    const size_t o_c = plan.take(packed ? (size_t)N * ldcrm * sizeof(bf16_t) : 0);
+    const size_t o_c = plan.take(packed && !direct ? (size_t)N * ldcrm * sizeof(bf16_t) : 0);
     int rc = prac_ws_reserve(ctx, plan.off);
     if (rc) return rc;
     bf16_t* Pt = reinterpret_cast<bf16_t*>(ctx->ws + o_pt);
     rc = launch_pack_ptfrag(ctx, P, d, ldp, c, k, scale, nkb, ncb, Pt);
     if (rc) return rc;
+    if (direct) {
+      ProfScope ps(ctx, PRAC_KERNEL_RECONSTRUCT);
+      return launch_reconstruct_ws(ctx, reinterpret_cast<const bf16_t*>(C), ldc, packed, (int)N, c, (int)d, Pt, ncb,
+                                   reinterpret_cast<bf16_t*>(Xh), ldxh);
+    }
     const bf16_t* Crm = reinterpret_cast<const bf16_t*>(C);
     if (packed) {
       rc = launch_unpack_c(ctx, reinterpret_cast<const bf16_t*>(C), (int)N, c, reinterpret_cast<bf16_t*>(ctx->ws + o_c),
@@ -656,8 +662,6 @@ int prac_reconstruct(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int
       Crm = reinterpret_cast<const bf16_t*>(ctx->ws + o_c);
     }
     ProfScope ps(ctx, PRAC_KERNEL_RECONSTRUCT);
-    if (c <= 256)
-      return launch_reconstruct_ws(ctx, Crm, ldcrm, (int)N, c, (int)d, Pt, ncb, reinterpret_cast<bf16_t*>(Xh), ldxh);
     return launch_compress_ws(ctx, Crm, ldcrm, (int)N, c, nullptr, 0, 0, nullptr, 0, false, Pt, ncb, (int)d,
                               reinterpret_cast<bf16_t*>(Xh), ldxh);
   }

@@ -117,10 +117,10 @@ int launch_cast_out(prac_ctx* ctx, const float* src, int64_t lds, void* dst, pra
 int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d, const bf16_t* Pfrag, int ncb,
                        int c, bf16_t* C, int64_t ldc, bool packed, const bf16_t* Wfrag, int ncb_w, int m,
                        bf16_t* Y, int64_t ldy);
-// Xh (N x d, bf16) = C (N x c, row-major bf16, c <= 256) Ps^T with Ps^T in fragment order
-// [16][ncb][64][8] (pack_ptfrag_kernel); ncb a multiple of 8 covering d.
-int launch_reconstruct_ws(prac_ctx* ctx, const bf16_t* C, int64_t ldc, int N, int c, int d, const bf16_t* Ptfrag, int ncb,
-                          bf16_t* Xh, int64_t ldxh);
+// Xh (N x d, bf16) = C (N x c bf16, row-major with ldc or packed; c <= 256) Ps^T with Ps^T in fragment
+// order [16][ncb][64][8] (pack_ptfrag_kernel); ncb a multiple of 8 covering d.
+int launch_reconstruct_ws(prac_ctx* ctx, const bf16_t* C, int64_t ldc, bool packed, int N, int c, int d,
+                          const bf16_t* Ptfrag, int ncb, bf16_t* Xh, int64_t ldxh);
 // W (bf16; w_layout 0: d x m, 1: m x d; ldw) -> [nkb][ncb_w][64][8] fragment order, zero padded
 int launch_pack_wfrag(prac_ctx* ctx, const bf16_t* W, int64_t ldw, int w_layout, int64_t d, int m, int nkb,
                       int ncb_w, bf16_t* out);

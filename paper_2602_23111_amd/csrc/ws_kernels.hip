@@ -443,8 +443,9 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
 // four waves - idle once C is in LDS - read it back along rows and store 16 bytes per lane to
 // HBM, with their own memory counter, while the matrix waves multiply the next group.
 struct ReconWsArgs {
-  const bf16_t* C;       // row-major N x c
+  const bf16_t* C;       // row-major N x c, or packed [ceil(N/128)*8][ccb][64][8] (see CtdyWsArgs)
   int64_t ldc;
+  int packed, ccb;
   int N, c, d;
   const bf16_t* Ptfrag;  // [16][ncb][64][8]: fragments of Ps^T (k-block over c, 32-column block over d)
   int ncb;               // multiple of 8
@@ -528,7 +529,37 @@ __global__ __launch_bounds__(512) void reconstruct_ws_kernel(ReconWsArgs a) {
     // ------------------------------------------------ loader, then store waves
     const int lt = tid - 256;
     const int crow = lt >> 5, ccol = (lt & 31) * 8;  // row crow + 8 q, 16-byte chunk at column ccol
-    {
+    if (a.packed) {
+      // Packed C holds, per lane slot, 8 tokens of one column; the tile needs 8 columns of one token per
+      // 16 bytes.  A thread takes 8 x 8 patches: 8 consecutive column slots (128 contiguous bytes),
+      // transposed in registers as the C^T dY loader does for dY.  Patch p of the tile's 512:
+      // column octet o = p & 3, token half h = (p >> 2) & 1, column block cb = (p >> 3) & 7, token block tb = p >> 6.
+      const u32x4* Cp = reinterpret_cast<const u32x4*>(a.C);
+#pragma unroll
+      for (int pp = 0; pp < 2; ++pp) {
+        const int p = lt + 256 * pp;
+        const int o = p & 3, h = (p >> 2) & 1, cb = (p >> 3) & 7, tb = p >> 6;
+        u32x4 rr[8];
+        const bool live = cb < a.ccb;  // column blocks past c are zero in the tile
+        const int64_t base = ((int64_t)((m0 >> 4) + tb) * a.ccb + (live ? cb : 0)) * 64 + h * 32 + 8 * o;
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) rr[jj] = Cp[base + jj];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          // token slot e of the patch: 16-bit element e of each of the 8 column slots
+          uint32_t w[4];
+#pragma unroll
+          for (int e2 = 0; e2 < 4; ++e2) {
+            const uint32_t lo = rr[2 * e2][e >> 1], hi = rr[2 * e2 + 1][e >> 1];
+            w[e2] = __builtin_amdgcn_perm(hi, lo, (e & 1) ? 0x07060302u : 0x05040100u);
+          }
+          const int row = 16 * tb + (e < 4 ? 4 * h + e : 8 + 4 * h + (e - 4));
+          u32x4 v = {w[0], w[1], w[2], w[3]};
+          if (!live) v = u32x4{0u, 0u, 0u, 0u};
+          *reinterpret_cast<u32x4*>(smem_raw + (row * WS_LD + 32 * cb + 8 * o) * 2) = v;
+        }
+      }
+    } else {
       const char* cbase = reinterpret_cast<const char*>(a.C + (int64_t)m0 * a.ldc);
       const int last_chunk = ((a.c - 1) / 8) * 8;
       const int nv = a.c - ccol;  // valid columns of this thread's chunk (<= 0: none)
@@ -965,11 +996,11 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
   return PRAC_OK;
 }
 
-int launch_reconstruct_ws(prac_ctx* ctx, const bf16_t* C, int64_t ldc, int N, int c, int d, const bf16_t* Ptfrag, int ncb,
-                          bf16_t* Xh, int64_t ldxh) {
+int launch_reconstruct_ws(prac_ctx* ctx, const bf16_t* C, int64_t ldc, bool packed, int N, int c, int d,
+                          const bf16_t* Ptfrag, int ncb, bf16_t* Xh, int64_t ldxh) {
   if (c < 1 || c > WS_BK || ncb % 8 != 0 || (int64_t)ncb * 32 < d) return PRAC_EINVAL;
   ReconWsArgs a;
-  a.C = C; a.ldc = ldc; a.N = N; a.c = c; a.d = d; a.Ptfrag = Ptfrag; a.ncb = ncb; a.Xh = Xh; a.ldxh = ldxh;
+  a.C = C; a.ldc = ldc; a.packed = packed ? 1 : 0; a.ccb = (c + 31) / 32; a.N = N; a.c = c; a.d = d; a.Ptfrag = Ptfrag; a.ncb = ncb; a.Xh = Xh; a.ldxh = ldxh;
   a.tiles_m = (N + WS_BM - 1) / WS_BM;
   a.groups = (d + 255) / 256;
   static bool s = false;
