@@ -275,7 +275,21 @@ __device__ __forceinline__ void tournament_pair(int step, int i, int players_eve
   }
 }
 
-__global__ __launch_bounds__(1024) void symmetrize64_kernel(double* H, int b) {
+// H <- (H + H^T) / 2; block 0 also leaves the largest diagonal entry in *hmax (the scale against
+// which the eigen-iteration decides that a column is numerically zero)
+__global__ __launch_bounds__(1024) void symmetrize64_kernel(double* H, int b, double* hmax) {
+  if (blockIdx.x == 0) {
+    __shared__ double s_mx[16];
+    double mx = 0.0;
+    for (int i = threadIdx.x; i < b; i += 1024) mx = fmax(mx, fabs(H[(int64_t)i * b + i]));
+    for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o));
+    if ((threadIdx.x & 63) == 0) s_mx[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int w = 1; w < 16; ++w) mx = fmax(mx, s_mx[w]);
+      *hmax = mx;
+    }
+  }
   for (int e = blockIdx.x * 1024 + threadIdx.x; e < b * b; e += gridDim.x * 1024) {
     const int i = e / b, j = e % b;
     if (i < j) {
@@ -287,13 +301,15 @@ __global__ __launch_bounds__(1024) void symmetrize64_kernel(double* H, int b) {
 }
 
 __global__ __launch_bounds__(1024) void jacobi_block_kernel(double* H, int b, int nbk, int nblk_even, int step, int sweep,
-                                                            int inner_sweeps, double tol, unsigned* counts) {
+                                                            int inner_sweeps, double tol, unsigned* counts,
+                                                            const double* hmax) {
   extern __shared__ __align__(16) unsigned char jac_smem[];
   double* cols = reinterpret_cast<double*>(jac_smem);  // [2 nbk][b]
   __shared__ int s_rows[64];
   __shared__ double s_n2[64];
   __shared__ int s_rot;
   if (sweep > 0 && counts[sweep - 1] == 0) return;  // converged in the previous sweep
+  const double floor2 = 1e-26 * *hmax * *hmax;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int bp, bq;
   tournament_pair(step, blockIdx.x, nblk_even, bp, bq);
@@ -338,9 +354,12 @@ __global__ __launch_bounds__(1024) void jacobi_block_kernel(double* H, int b, in
         for (int t = lane; t < b; t += 64) ga += hp[t] * hq[t];
         ga = wave_sum_f64(ga);
         const double al = s_n2[p], be2 = s_n2[q];
-        // rotate when |ga| > tol sqrt(al be2), compared as squares
+        // rotate when |ga| > tol sqrt(al be2), compared as squares.  A rotation that involves a
+        // numerically zero column (an eigenvalue below 1e-13 of the largest: rank-deficient input)
+        // is applied but does not count towards convergence: such a column is rounding noise and
+        // its cosines never settle.
         if (ga * ga > tol * tol * al * be2 && fabs(ga) > 1e-300) {
-          rotated = 1;
+          if (fmin(al, be2) > floor2) rotated = 1;
           // The angle may be approximate (the iteration corrects it), so tan comes from the
           // hardware reciprocal / square root estimates; (cs, sn) must be a rotation to full
           // precision, so cs = (1 + tt^2)^-1/2 gets Newton steps on top of its estimate.
@@ -598,7 +617,10 @@ int cholqr(prac_ctx* ctx, const FitWs& w, float* Y, float* V, int64_t d, int n, 
   float* src = Y;
   float* dst = V;
   for (int pass = 0; pass < passes + polish; ++pass) {
-    int rc = pass < passes ? cholqr_pass(ctx, w, src, dst, d, n, pass == 0 ? first_shift : 1e-15, pass > 0 || gram64_first)
+    // Later passes work on a block that is orthonormal up to the first pass's error, except in
+    // directions where the input was rank deficient: there the Gram matrix is zero up to rounding
+    // (a few 1e-16), and the shift has to be safely above that for the pivot to stay positive.
+    int rc = pass < passes ? cholqr_pass(ctx, w, src, dst, d, n, pass == 0 ? first_shift : 1e-13, pass > 0 || gram64_first)
                            : polish_pass(ctx, w, src, dst, d, n);
     if (rc) return rc;
     float* t = src; src = dst; dst = t;
@@ -652,9 +674,10 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       rc = launch_reduce_transpose_f32(ctx, slabs, L.trk_splits, k, dm, Y, k);
       if (rc) return rc;
       // One power step from an orthonormal block leaves a condition number of at most lambda_1 /
-      // lambda_k, within reach of an unshifted Cholesky factor of the fp64 Gram matrix; the last
+      // lambda_k, within reach of a Cholesky factor of the fp64 Gram matrix with a shift just above its
+      // rounding (so that a rank-deficient batch still factors); the last
       // iteration then gets two Newton-Schulz steps in place of a second factorisation.
-      rc = cholqr(ctx, L, Y, V, d, k, 1, 1e-15, it == o.iters - 1 ? 2 : 0);
+      rc = cholqr(ctx, L, Y, V, d, k, 1, 1e-14, it == o.iters - 1 ? 2 : 0);
       if (rc) return rc;
     }
     hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, V, (int64_t)k, P, ldp, d, k);
@@ -727,18 +750,19 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
         smem_set = true;
       }
       hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(64), 0, st, counts, MAX_SWEEPS);
-      hipLaunchKernelGGL(symmetrize64_kernel, dim3(16), dim3(1024), 0, st, H, b);
+      double* hmax = reinterpret_cast<double*>(counts + 16);
+      hipLaunchKernelGGL(symmetrize64_kernel, dim3(16), dim3(1024), 0, st, H, b, hmax);
       const size_t smem = (size_t)2 * nbk * b * sizeof(double);
       if (nblk == 1) {
         // a single block: one workgroup orthogonalises everything in LDS
-        hipLaunchKernelGGL(jacobi_block_kernel, dim3(1), dim3(1024), smem, st, H, b, nbk, 2, 0, 0, 30, JACOBI_TOL, counts);
+        hipLaunchKernelGGL(jacobi_block_kernel, dim3(1), dim3(1024), smem, st, H, b, nbk, 2, 0, 0, 30, JACOBI_TOL, counts, hmax);
         hipLaunchKernelGGL(jacobi_finish_kernel, dim3(16), dim3(1024), 0, st, H, b, lam, counts, MAX_SWEEPS - 1,
                            ctx->d_flag);
       } else {
         for (int sweep = 0; sweep < MAX_SWEEPS; ++sweep)
           for (int step = 0; step < nblk_even - 1; ++step)
             hipLaunchKernelGGL(jacobi_block_kernel, dim3(nblk_even / 2), dim3(1024), smem, st, H, b, nbk, nblk_even,
-                               step, sweep, 1, JACOBI_TOL, counts);
+                               step, sweep, 1, JACOBI_TOL, counts, hmax);
         hipLaunchKernelGGL(jacobi_finish_kernel, dim3(16), dim3(1024), 0, st, H, b, lam, counts, MAX_SWEEPS - 1,
                            ctx->d_flag);
       }
@@ -754,8 +778,10 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       rc = launch_gemm_generic(ctx, g);
       if (rc) return rc;
     }
-    // tidy the rounding of the last product, then store Q1 into P[:, :k]
-    rc = cholqr(ctx, L, Y, V, d, k, 1, 0.0);
+    // tidy the rounding of the last product (one Cholesky-QR pass and a Newton-Schulz step: with more
+    // Ritz vectors asked for than the data has rank, the surplus ones are rounding noise, far from
+    // orthogonal to each other, and one fp32 pass leaves 1e-4), then store Q1 into P[:, :k]
+    rc = cholqr(ctx, L, Y, V, d, k, 1, 0.0, 1);
     if (rc) return rc;
     hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, V, (int64_t)k, P, ldp, d, k);
     PRAC_HIP_TRY(ctx, hipGetLastError());
