@@ -23,6 +23,8 @@
  *   - Return value: PRAC_OK (0) or a negative prac_status.  Shape and argument
  *     errors are detected on the host BEFORE anything is enqueued and before
  *     the ctx is looked at, so they can be exercised without a GPU.
+ *   - Size limits (PRAC_EINVAL beyond them): 1 <= N < 2^31 tokens,
+ *     1 <= d, m <= 2^20 features.
  *   - bf16 fast paths need 16-byte aligned base pointers and leading
  *     dimensions that are multiples of 8 elements; otherwise a slower generic
  *     kernel runs (same results to rounding).

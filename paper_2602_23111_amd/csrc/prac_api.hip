@@ -9,6 +9,8 @@ namespace {
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 inline size_t esize(prac_dtype t) { return t == PRAC_BF16 ? 2 : 4; }
 inline bool valid_dtype(int t) { return t == PRAC_F32 || t == PRAC_BF16; }
+// token counts are 32-bit inside the kernels' launch arguments
+inline bool bad_tokens(int64_t N) { return N < 1 || N >= ((int64_t)1 << 31); }
 
 struct LpLayout {
   int64_t ldpt, ldpn;
@@ -297,7 +299,7 @@ int prac_philox_normal(prac_ctx* ctx, uint64_t seed, uint64_t draw, uint32_t str
 // ------------------------------------------------------------------------- Gram
 int prac_gram(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, int64_t row_stride,
               float* G, int64_t ldg) {
-  if (!X || !G || !valid_dtype(xdt) || N < 1 || d < 1 || d > (1 << 20) || ldx < d || ldg < d || row_stride < 1)
+  if (!X || !G || !valid_dtype(xdt) || bad_tokens(N) || d < 1 || d > (1 << 20) || ldx < d || ldg < d || row_stride < 1)
     return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
   const size_t need = gram_scratch_bytes(ctx, X, xdt, N, d, ldx, row_stride, ldg);
@@ -332,7 +334,7 @@ int prac_fit_basis(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int6
       draw > 0xFFFFFFFFull || (refresh & ~3) != 0)
     return PRAC_EINVAL;
   const bool need_x = (refresh & PRAC_REFRESH_PRINCIPAL) && k > 0;
-  if (need_x && (!X || !valid_dtype(xdt) || N < 1 || ldx < d)) return PRAC_EINVAL;
+  if (need_x && (!X || !valid_dtype(xdt) || bad_tokens(N) || ldx < d)) return PRAC_EINVAL;
   prac_fit_opts o{};
   if (opts) o = *opts;
   if (o.iters < 0 || o.row_stride < 0 || (o.warm_start != 0 && o.warm_start != 1)) return PRAC_EINVAL;
@@ -356,7 +358,7 @@ size_t prac_compressed_bytes(int64_t N, int c, prac_dtype dt, int c_layout, int6
 }
 
 int prac_unpack_compressed(prac_ctx* ctx, const void* Cpk, int64_t N, int c, void* C, int64_t ldc) {
-  if (!Cpk || !C || N < 1 || N >= ((int64_t)1 << 31) || c < 1 || ldc < c || !aligned16(Cpk)) return PRAC_EINVAL;
+  if (!Cpk || !C || bad_tokens(N) || c < 1 || ldc < c || !aligned16(Cpk)) return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
   return launch_unpack_c(ctx, reinterpret_cast<const bf16_t*>(Cpk), (int)N, c, reinterpret_cast<bf16_t*>(C), ldc);
 }
@@ -446,7 +448,7 @@ static bool bad_c_layout(int c_layout, int64_t ldc, int c) {
 
 int prac_compress(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, const float* P,
                   const void* P_lp, int64_t ldp, int c, void* C, int64_t ldc, int c_layout) {
-  if (!X || !P || !C || !valid_dtype(xdt) || N < 1 || d < 1 || d > (1 << 20) || c < 1 || c > d || ldx < d ||
+  if (!X || !P || !C || !valid_dtype(xdt) || bad_tokens(N) || d < 1 || d > (1 << 20) || c < 1 || c > d || ldx < d ||
       ldp < c || bad_c_layout(c_layout, ldc, c) || (P_lp && !aligned16(P_lp)))
     return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
@@ -456,7 +458,7 @@ int prac_compress(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64
 int prac_compress_fused_fwd(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
                             const void* W, int64_t m, int64_t ldw, int w_layout, const float* P, const void* P_lp,
                             int64_t ldp, int c, void* Y, int64_t ldy, void* C, int64_t ldc, int c_layout) {
-  if (!X || !P || !C || !W || !Y || !valid_dtype(xdt) || N < 1 || d < 1 || d > (1 << 20) || c < 1 || c > d ||
+  if (!X || !P || !C || !W || !Y || !valid_dtype(xdt) || bad_tokens(N) || d < 1 || d > (1 << 20) || c < 1 || c > d ||
       m < 1 || m > (1 << 20) || ldx < d || ldp < c || bad_c_layout(c_layout, ldc, c) || ldy < m ||
       (w_layout != 0 && w_layout != 1) || ldw < (w_layout == 1 ? d : m) || (P_lp && !aligned16(P_lp)))
     return PRAC_EINVAL;
@@ -600,7 +602,7 @@ int prac_weight_grad_shared(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t
                             const void* P_lp, int64_t d, int64_t ldp, int k, int r, float scale, void* const* dW,
                             prac_dtype odt, const int64_t* lddw, float beta) {
   if (!C || !dY || !m || !lddy || !dW || !lddw || !P || n_out < 1 || n_out > PRAC_MAX_SHARED || !valid_dtype(dt) ||
-      !valid_dtype(odt) || N < 1 || d < 1 || d > (1 << 20) || k < 0 || r < 0 || k + r < 1 || (int64_t)k + r > d ||
+      !valid_dtype(odt) || bad_tokens(N) || d < 1 || d > (1 << 20) || k < 0 || r < 0 || k + r < 1 || (int64_t)k + r > d ||
       bad_c_layout(c_layout, ldc, k + r) || ldp < k + r || (P_lp && !aligned16(P_lp)))
     return PRAC_EINVAL;
   for (int h = 0; h < n_out; ++h)
@@ -625,7 +627,7 @@ int prac_weight_grad_shared(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t
 // ------------------------------------------------------------------ reconstruction
 int prac_reconstruct(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int64_t ldc, int c_layout, const float* P,
                      int64_t d, int64_t ldp, int k, int r, float scale, void* Xh, int64_t ldxh) {
-  if (!C || !P || !Xh || !valid_dtype(dt) || N < 1 || d < 1 || d > (1 << 20) || k < 0 || r < 0 || k + r < 1 ||
+  if (!C || !P || !Xh || !valid_dtype(dt) || bad_tokens(N) || d < 1 || d > (1 << 20) || k < 0 || r < 0 || k + r < 1 ||
       (int64_t)k + r > d || bad_c_layout(c_layout, ldc, k + r) || ldp < k + r || ldxh < d)
     return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;

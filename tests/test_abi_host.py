@@ -52,6 +52,8 @@ def test_compress_argument_checks(lib):
     assert _compress(lib, Cp=None) == -1
     assert _compress(lib, dt=7) == -1
     assert _compress(lib, N=0) == -1
+    assert _compress(lib, N=1 << 31) == -1         # token counts are below 2^31
+    assert _compress(lib, N=(1 << 31) - 1) == -6
     assert _compress(lib, ldx=15) == -1            # ldx < d
     assert _compress(lib, c=17, ldp=17, ldc=17) == -1  # c > d
     assert _compress(lib, ldp=3) == -1
@@ -71,6 +73,7 @@ def test_weight_grad_argument_checks(lib):
     assert _wgrad(lib) == -6
     assert _wgrad(lib, dY=None) == -1
     assert _wgrad(lib, k=-1) == -1
+    assert _wgrad(lib, N=1 << 31) == -1
     assert _wgrad(lib, k=0, r=0) == -1
     assert _wgrad(lib, k=10, r=7, ldc=17, ldp=17) == -1   # k + r > d
     assert _wgrad(lib, ldc=3) == -1
