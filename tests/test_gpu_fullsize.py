@@ -163,3 +163,55 @@ def test_reconstruct_full_size_sampled_rows(ctx):
     ref = orc.reconstruct(si.as_f64(Cm[rows_t]), si.as_f64(P32), k, s)
     assert rel_fro(si.as_f64(Xh[rows_t]), ref) < 1e-2
     assert torch.isfinite(Xh.float()).all()
+
+
+# ---- LLaMA-7B-shaped layer (N = 16384, d = 4096 -> m = 11008, k = r = 256; spectrum i^-0.8 with 16
+# outlier channels x50; the basis refitted every step from every fourth token)
+N7, D7, M7, K7, R7 = 16384, 4096, 11008, 256, 256
+
+
+def test_llama7b_layer_compress_and_weight_grad_sampled(ctx):
+    from paper_2602_23111_amd.prac import C_PACKED
+    c = K7 + R7
+    s = orc.scaling_factor(D7, K7, R7)
+    X = si.activation_torch(N7, D7, 0.8, 5000, 16, 50.0, torch.bfloat16, DEV)
+    P32 = si.round_to(si.orthonormal_basis(D7, c, seed=11), "f32")
+    Pd = P32.to(DEV)
+    lp = ctx.pack_basis(Pd)
+    flat = ctx.compress(X, Pd, P_lp=lp, layout=C_PACKED)
+    Cm = ctx.unpack_compressed(flat, N7, c)
+    torch.cuda.synchronize()
+    rows_t = torch.from_numpy(sample_rows(N7, 136, seed=12)).to(DEV)
+    assert rel_fro(si.as_f64(Cm[rows_t]), orc.compress(si.as_f64(X[rows_t]), si.as_f64(P32))) < 1e-2
+    assert torch.isfinite(Cm.float()).all()
+    del X
+    # the weight gradient from the library's own packed C, against the oracle's on the same (rounded) C
+    dY = si.grad_output_torch(N7, M7, 1e-3, 5100, torch.bfloat16, DEV)
+    dW = ctx.weight_grad(flat, dY, Pd, K7, R7, s, P_lp=lp, out_dtype=torch.bfloat16, layout=C_PACKED)
+    torch.cuda.synchronize()
+    cols = np.sort(np.concatenate([np.random.default_rng(13).choice(M7 - 2, size=14, replace=False), [M7 - 2, M7 - 1]]))
+    cols_t = torch.from_numpy(cols).to(DEV)
+    ref = orc.weight_grad(si.as_f64(Cm), si.as_f64(dY[:, cols_t]), si.as_f64(P32), K7, s)
+    assert rel_fro(si.as_f64(dW[:, cols_t]), ref) < 1e-2
+    assert torch.isfinite(dW.float()).all()
+
+
+def test_llama7b_per_step_refit_from_token_subsample(ctx):
+    # cold fit on batch 0, then the per-step refit as that workload runs it: two tracking steps from
+    # the previous Q1 on every fourth token of the next batch
+    stride = 4
+    X0 = si.activation_torch(N7, D7, 0.8, 5000, 16, 50.0, torch.bfloat16, DEV, batch=0)
+    X1 = si.activation_torch(N7, D7, 0.8, 5000, 16, 50.0, torch.bfloat16, DEV, batch=1)
+    P, _, _ = ctx.fit_basis(X0, K7, R7, seed=77, draw=0, row_stride=stride)
+    P, _, scale = ctx.fit_basis(X1, K7, R7, seed=77, draw=1, P=P, warm_start=True, iters=2, oversample=-1,
+                                row_stride=stride)
+    ctx.sync_status()
+    assert scale == pytest.approx((D7 - K7) / R7)
+    P64 = si.as_f64(P)
+    assert np.abs(P64.T @ P64 - np.eye(K7 + R7)).max() < 1e-5
+    Xs = si.as_f64(X1[::stride])
+    _, lam = orc.principal_subspace(orc.gram(Xs), K7)
+    captured = float(np.sum((Xs @ P64[:, :K7]) ** 2))
+    assert (1 - 1e-3) * lam[:K7].sum() <= captured <= (1 + 1e-6) * lam[:K7].sum()
+    total = float(np.sum(Xs ** 2))
+    assert total - captured <= 1.02 * (total - lam[:K7].sum())
