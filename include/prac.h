@@ -67,7 +67,7 @@ typedef struct {
 } prac_fit_opts;
 /* Tracking refit: with warm_start = 1 and oversample < 0 (block width k), bf16 X that is
  * 16-byte aligned with row pitch (ldx * row_stride) a multiple of 8, at least 256 rows in
- * the (sub)sample, d >= 128 and k <= 256, no Gram matrix is formed: each of the `iters`
+ * the (sub)sample, d >= 128 and k <= 1024, no Gram matrix is formed: each of the `iters`
  * iterations is one subspace-iteration step Q1 <- orth(X^T (X Q1)) through the compress and
  * C^T dY kernels, without the Rayleigh-Ritz step (Q1 spans the tracked subspace; its columns
  * are not ordered by eigenvalue).  The lazy-update premise of Alg. 1 - the subspace drifts

@@ -469,7 +469,7 @@ int block_width(int64_t d, int k, const prac_fit_opts& o) {
 // kernel with X in the place of dY forms (X V)^T X.
 bool can_track(const void* X, prac_dtype xdt, int64_t rows, int64_t d, int64_t ldx, int k, const prac_fit_opts& o) {
   const int64_t ld = ldx * (o.row_stride > 0 ? o.row_stride : 1);
-  return o.warm_start && o.oversample < 0 && o.iters >= 1 && k > 0 && k <= 256 && xdt == PRAC_BF16 &&
+  return o.warm_start && o.oversample < 0 && o.iters >= 1 && k > 0 && k <= 1024 && xdt == PRAC_BF16 &&
          (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 8 == 0 && rows >= 256 && rows < ((int64_t)1 << 31) &&
          d >= 128;
 }
@@ -510,7 +510,7 @@ FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool n
   if (track) {
     w.trk_nkb = (int)(round_up64(d, 256) / 16);
     w.trk_ncb = (int)round_up64((k + 31) / 32, 8);
-    const int tiles = (int)((d + 127) / 128);  // k <= 256: one row group of T
+    const int tiles = (int)((d + 127) / 128) * ((k + 255) / 256);  // 256 x 128 tiles of (X Q1)^T X
     int sp = n_cu / tiles;
     if (sp > rows / 256) sp = (int)(rows / 256);
     if (sp < 1) sp = 1;

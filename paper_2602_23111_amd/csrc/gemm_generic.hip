@@ -1,7 +1,8 @@
 // Strided GEMM on the vector ALUs: fp32 or bf16 operands with arbitrary element
 // strides, fp32 or fp64 accumulation.  It serves the fp32 data path (where bf16 MFMA
 // rounding is not allowed), unaligned bf16 inputs, and the small dense products of
-// the basis fit (G V, V^T Y with fp64 sums, Y R^-1, V Z, Q1 (Q1^T S)).
+// the basis fit (G V, Y R^-1, V Z, Q1 (Q1^T S)); products whose unit strides allow it run on
+// the matrix cores instead (fp32 sums, or fp64 sums for the fit's Gram matrices).
 #include "prac_internal.h"
 
 namespace {
@@ -178,6 +179,73 @@ __global__ __launch_bounds__(256) void gemm_f32_mfma_kernel(GArgs a) {
   }
 }
 
+// ---- fp64 sums on the matrix cores --------------------------------------------------
+// Same contract again for fp32 operands with fp64 sums (the fit's n x n Gram matrices Y^T Y and
+// V^T Y over panels of d rows): products of fp32 values are exact in fp64, the sums run on
+// v_mfma_f64_16x16x4_f64.  64 x 64 tile per workgroup, a 32 x 32 block (2 x 2 MFMA blocks) per wave;
+// operands go from global memory straight to registers, since a workgroup's share of k is a few
+// dozen rows and all of its requests are in flight at once.  Lane l holds A(m = l % 16, k = l / 16)
+// and B(k = l / 16, n = l % 16); register v of lane l is D(m = 4 v + l / 16, n = l % 16).
+typedef double f64x4_t __attribute__((ext_vector_type(4)));
+constexpr int DK = 32;  // k values per step: 8 MFMA steps of 4
+
+__global__ __launch_bounds__(256) void gemm_f64_mfma_kernel(GArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int fi = lane & 15, fk = lane >> 4;
+  const int m0 = blockIdx.y * 64 + (wave >> 1) * 32, n0 = blockIdx.x * 64 + (wave & 1) * 32;
+  const int64_t kbeg = (int64_t)blockIdx.z * a.steps_per_split;
+  const int64_t kend = min(a.K, kbeg + a.steps_per_split);
+  const bool am[2] = {m0 + fi < a.M, m0 + 16 + fi < a.M}, bn[2] = {n0 + fi < a.N, n0 + 16 + fi < a.N};
+  const float* __restrict__ Ap = reinterpret_cast<const float*>(a.A) + (m0 + fi);
+  const float* __restrict__ Bp = reinterpret_cast<const float*>(a.B) + (n0 + fi);
+  f64x4_t acc[2][2];
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[s][t][v] = 0.0;
+  for (int64_t k0 = kbeg; k0 < kend; k0 += DK) {
+    float ra[DK / 4][2], rb[DK / 4][2];
+#pragma unroll
+    for (int u = 0; u < DK / 4; ++u) {
+      const int64_t k = k0 + 4 * u + fk;
+      const bool kin = k < kend;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        ra[u][t] = (kin && am[t]) ? Ap[k * a.a_cs + 16 * t] : 0.f;
+        rb[u][t] = (kin && bn[t]) ? Bp[k * a.b_rs + 16 * t] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < DK / 4; ++u)
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+          acc[s][t] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)ra[u][s], (double)rb[u][t], acc[s][t], 0, 0, 0);
+  }
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int m = m0 + 16 * s + 4 * v + fk, n = n0 + 16 * t + fi;
+        if (m < a.M && n < a.N) {
+          const int64_t o = (int64_t)m * a.ldo + n;
+          if (a.splits > 1) {
+            reinterpret_cast<double*>(a.slabs)[((int64_t)blockIdx.z * a.M + m) * a.N + n] = acc[s][t][v];
+          } else if (a.out64) {
+            a.out64[o] = (double)a.alpha * acc[s][t][v] + (a.beta == 0.f ? 0.0 : (double)a.beta * a.out64[o]);
+          } else {
+            const float x = a.alpha * (float)acc[s][t][v];
+            a.out[o] = a.beta == 0.f ? x : x + a.beta * a.out[o];
+          }
+        }
+      }
+}
+
 template <typename TA, typename TB, typename ACC>
 void launch3(const GArgs& a, hipStream_t st) {
   dim3 grid((a.N + TN - 1) / TN, (a.M + TM - 1) / TM, a.splits), block(256);
@@ -226,9 +294,14 @@ int launch_gemm_generic(prac_ctx* ctx, const GemmGenArgs& g) {
   const bool abf = g.adt == PRAC_BF16, bbf = g.bdt == PRAC_BF16;
   const bool mfma = !abf && !bbf && !g.acc64 && !g.out64 && a.a_rs == 1 && a.b_cs == 1 && a.k_stride == 1 &&
                     (int64_t)a.M * a.N >= 64 * 64 && a.K >= 64;
+  const bool mfma64 = !abf && !bbf && g.acc64 && a.a_rs == 1 && a.b_cs == 1 && a.k_stride == 1;
   if (mfma) {
     a.steps_per_split = ((a.K + a.splits - 1) / a.splits + FK - 1) / FK * FK;
     hipLaunchKernelGGL(gemm_f32_mfma_kernel, dim3((a.N + 63) / 64, (a.M + 63) / 64, a.splits), dim3(256), 0, ctx->stream,
+                       a);
+  } else if (mfma64) {
+    a.steps_per_split = ((a.K + a.splits - 1) / a.splits + 3) / 4 * 4;
+    hipLaunchKernelGGL(gemm_f64_mfma_kernel, dim3((a.N + 63) / 64, (a.M + 63) / 64, a.splits), dim3(256), 0, ctx->stream,
                        a);
   } else if (abf && bbf) launch2<bf16_t, bf16_t>(a, g.acc64, ctx->stream);
   else if (abf) launch2<bf16_t, float>(a, g.acc64, ctx->stream);

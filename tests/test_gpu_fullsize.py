@@ -97,10 +97,11 @@ def test_fit_basis_full_size_invariants(ctx):
     assert captured <= (1 + 1e-6) * lam[:k].sum()
 
 
-def test_fit_basis_warm_start_as_benchmarked(ctx):
+@pytest.mark.parametrize("k,r", [(128, 128), (512, 512)])      # headline ranks; the rank sweep's widest basis
+def test_fit_basis_warm_start_as_benchmarked(ctx, k, r):
     # the refits inside bench.py's timed region: next batch of the same layer, two Gram-free tracking
     # steps from the previous Q1 (no oversampling)
-    d, k, r = 2048, 128, 128
+    d = 2048
     X0 = si.activation_torch(N, d, 0.8, 3000, 8, 30.0, torch.bfloat16, DEV, batch=0)
     X1 = si.activation_torch(N, d, 0.8, 3000, 8, 30.0, torch.bfloat16, DEV, batch=1)
     P, _, _ = ctx.fit_basis(X0, k, r, seed=1234, draw=0)
