@@ -13,78 +13,160 @@
 namespace {
 
 // ---------------------------------------------------------------- Cholesky (upper)
-// In place on the row-major b x b fp64 matrix W (only the upper triangle is read and
-// written): W = R^T R.  `shift_rel` * max diag(W) is added to the diagonal first.
-// One workgroup of 1024 threads, blocked by panels of CH_NB rows that live in LDS: the
-// panel is factored there (right-looking inside the panel, across its full width), written
-// back, and applied to the trailing rows as a rank-CH_NB update.  Non-finite or
-// non-positive pivots raise *flag and are replaced by a tiny positive number.
-// NT threads (1024 is what is launched; 256 measured slower at every panel width tried).
-constexpr int CH_NB = 16;
-template <int NT>
-__global__ __launch_bounds__(NT) void chol_upper_kernel(double* W, int b, double shift_rel, int* flag) {
-  constexpr int NW = NT / 64;
+// value of x in lane U of each row of 16 lanes
+template <int U>
+__device__ __forceinline__ double row_share64(double x) {
+  const uint64_t b = (uint64_t)__double_as_longlong(x);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, 0x150 + U, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), 0x150 + U, 0xf, 0xf, false);
+  return __longlong_as_double((long long)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo));
+}
+
+template <int N, typename F>
+__device__ __forceinline__ void chol_static_for(F&& f) {
+  if constexpr (N > 0) {
+    chol_static_for<N - 1>(f);
+    f(std::integral_constant<int, N - 1>{});
+  }
+}
+
+// In place on the row-major b x b fp64 matrix W (b <= 1024; the upper triangle is read, rows of R
+// are written to it): W = R^T R.  `shift_rel` * max diag(W) is added to the diagonal first.
+// Non-finite or non-positive pivots raise *flag and are replaced by a tiny positive number.
+// One workgroup of 1024 threads.  Per panel of 16 rows: the rows go to LDS (columns padded to a
+// multiple of 16 with the identity); one wave factors the 16 x 16 diagonal block in registers (a
+// column per lane, pivots and multipliers broadcast with DPP, 1 / sqrt(pivot) by two Newton steps
+// from v_rsq_f64); every thread then solves one column of the rest of the panel against that block;
+// the finished rows go back to memory and the trailing matrix takes its rank-16 update as 16 x 16
+// tiles on v_mfma_f64_16x16x4_f64, dealt to the 16 waves four at a time so that their loads overlap.
+// 67 / 177 us at b = 128 / 256 (107 / 355 us for the vector-ALU version this replaces); per panel
+// 2.8 us for the diagonal block, 2.3 us for the solve, 0.5 - 13 us for the update.
+typedef double f64x4_t __attribute__((ext_vector_type(4)));
+constexpr int CH_NB = 16;  // panel height = block size of the fp64 matrix instruction
+constexpr int CH_TB = 4;   // trailing tiles a wave has in flight
+constexpr int CH_MAX = 1024;
+__global__ __launch_bounds__(1024) void chol_upper_kernel(double* W, int b, double shift_rel, int* flag) {
   extern __shared__ __align__(16) unsigned char chol_smem[];
-  double* panel = reinterpret_cast<double*>(chol_smem);  // [CH_NB][b]
+  const int bpad = (b + CH_NB - 1) / CH_NB * CH_NB, ldp = bpad + 2;
+  double* panel = reinterpret_cast<double*>(chol_smem);  // [CH_NB][ldp]
   __shared__ double s_red[16];
-  __shared__ double s_piv[CH_NB];
+  __shared__ double s_dinv[CH_NB];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   double mx = 0.0;
-  for (int i = tid; i < b; i += NT) mx = fmax(mx, W[(int64_t)i * b + i]);
+  for (int i = tid; i < b; i += 1024) mx = fmax(mx, W[(int64_t)i * b + i]);
   for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o));
   if (lane == 0) s_red[wave] = mx;
   __syncthreads();
   mx = 0.0;
-  for (int w = 0; w < NW; ++w) mx = fmax(mx, s_red[w]);
+  for (int w = 0; w < 16; ++w) mx = fmax(mx, s_red[w]);
   const double shift = shift_rel * mx;
   const double tiny = 1e-300 + 1e-30 * mx;
-  for (int j0 = 0; j0 < b; j0 += CH_NB) {
-    const int nb = min(CH_NB, b - j0), width = b - j0;
-    // panel rows j0 .. j0+nb-1, columns j0 .. b-1 (column index relative to j0)
-    // one wave per panel row, lanes along the columns (no index division in these loops)
-    for (int u = wave; u < nb; u += NW)
-      for (int c = lane; c < width; c += 64) {
-        double v = c >= u ? W[(int64_t)(j0 + u) * b + j0 + c] : 0.0;
-        if (c == u) v += shift;
-        panel[u * b + c] = v;
+  const int fi = lane & 15, fk = lane >> 4;
+
+  for (int j0 = 0; j0 < bpad; j0 += CH_NB) {
+    const int wpad = bpad - j0;  // panel width, padded columns included
+    // panel rows j0 .. j0+15, columns j0 .. bpad-1 (relative index c)
+    for (int u = wave; u < CH_NB; u += 16)
+      for (int c = lane; c < wpad; c += 64) {
+        const bool real = j0 + u < b && j0 + c < b;
+        double v = real ? (c >= u ? W[(int64_t)(j0 + u) * b + j0 + c] : 0.0) : (c == u ? 1.0 : 0.0);
+        if (real && c == u) v += shift;
+        panel[u * ldp + c] = v;
       }
     __syncthreads();
-    // Pivot steps with one barrier each: the rows below the pivot row are updated from the
-    // unscaled pivot row (R[t][u] R[t][c] = a[t][u] a[t][c] / pivot); the pivot rows themselves are
-    // scaled by 1 / sqrt(pivot) in one pass after the last step.
-    for (int t = 0; t < nb; ++t) {
-      double p = panel[t * b + t];
-      const bool bad = !(p > tiny) || !isfinite(p);
-      if (bad) p = tiny;
-      if (tid == 0) {
-        s_piv[t] = p;
+    // diagonal block: col[u] of lane c is element (u, c); the four rows of 16 lanes work alike
+    if (wave == 0) {
+      double col[CH_NB], dinv[CH_NB];
+#pragma unroll
+      for (int u = 0; u < CH_NB; ++u) col[u] = panel[u * ldp + fi];
+      bool bad = false;
+      chol_static_for<CH_NB>([&](auto tc) {
+        constexpr int T = decltype(tc)::value;
+        double p = row_share64<T>(col[T]);
+        if (!(p > tiny) || !isfinite(p)) {
+          bad = true;
+          p = tiny;
+        }
+        double rs = __builtin_amdgcn_rsq(p);
+        rs = rs * (1.5 - 0.5 * p * rs * rs);
+        rs = rs * (1.5 - 0.5 * p * rs * rs);
+        dinv[T] = rs;
+        col[T] = fi == T ? p * rs : (fi > T ? col[T] * rs : 0.0);  // row T of R; the pivot becomes sqrt(p)
+        chol_static_for<CH_NB - 1 - T>([&](auto uc) {
+          constexpr int U = T + 1 + decltype(uc)::value;
+          col[U] -= row_share64<U>(col[T]) * col[T];
+        });
+      });
+      if (lane < CH_NB) {
+#pragma unroll
+        for (int u = 0; u < CH_NB; ++u) panel[u * ldp + fi] = fi >= u ? col[u] : 0.0;
+      }
+      if (lane == 0) {
+#pragma unroll
+        for (int u = 0; u < CH_NB; ++u) s_dinv[u] = dinv[u];
         if (bad) atomicOr(flag, 1);
       }
-      const double invp = 1.0 / p;
-      for (int u = t + 1 + wave; u < nb; u += NW) {
-        const double f = panel[t * b + u] * invp;
-        for (int c = u + lane; c < width; c += 64) panel[u * b + c] -= f * panel[t * b + c];
-      }
-      __syncthreads();
-    }
-    for (int u = wave; u < nb; u += NW) {
-      const double sq = sqrt(s_piv[u]), inv = 1.0 / sq;
-      for (int c = u + lane; c < width; c += 64) panel[u * b + c] = c == u ? sq : panel[u * b + c] * inv;
     }
     __syncthreads();
-    for (int u = wave; u < nb; u += NW)
-      for (int c = u + lane; c < width; c += 64) W[(int64_t)(j0 + u) * b + j0 + c] = panel[u * b + c];
-    // trailing rows i >= j0 + nb: W[i][c] -= sum_t R[t][i] R[t][c], c >= i
-    for (int i = j0 + nb + wave; i < b; i += NW) {
-      double ri[CH_NB];
+    // the rest of the panel: column c solves R11^T x = a by forward substitution
+    for (int c = CH_NB + tid; c < wpad; c += 1024) {
+      double x[CH_NB];
 #pragma unroll
-      for (int t = 0; t < CH_NB; ++t) ri[t] = t < nb ? panel[t * b + (i - j0)] : 0.0;
-      double* wi = W + (int64_t)i * b;
-      for (int c = i + lane; c < b; c += 64) {
-        double acc = wi[c];
+      for (int u = 0; u < CH_NB; ++u) {
+        double s = panel[u * ldp + c];
 #pragma unroll
-        for (int t = 0; t < CH_NB; ++t) acc -= ri[t] * (t < nb ? panel[t * b + (c - j0)] : 0.0);
-        wi[c] = acc;
+        for (int t = 0; t < u; ++t) s -= panel[t * ldp + u] * x[t];
+        x[u] = s * s_dinv[u];
+      }
+#pragma unroll
+      for (int u = 0; u < CH_NB; ++u) panel[u * ldp + c] = x[u];
+    }
+    __syncthreads();
+    // finished rows of R
+    for (int u = wave; u < CH_NB; u += 16)
+      if (j0 + u < b)
+        for (int c = u + lane; c < wpad; c += 64)
+          if (j0 + c < b) W[(int64_t)(j0 + u) * b + j0 + c] = panel[u * ldp + c];
+    // trailing update, tile (I, J), I <= J, of the 16 x 16 blocks behind the panel:
+    // W[i][c] -= sum_t R[t][i] R[t][c].  Lane (fi, fk) holds A(m = fi, k = fk), B(k = fk, n = fi);
+    // its register v is D(m = 4 v + fk, n = fi).
+    const int nb = wpad / CH_NB - 1;
+    const int ntiles = nb * (nb + 1) / 2;
+    for (int q0 = wave * CH_TB; q0 < ntiles; q0 += 16 * CH_TB) {
+      f64x4_t acc[CH_TB];
+      int ti[CH_TB], tj[CH_TB];
+#pragma unroll
+      for (int e = 0; e < CH_TB; ++e) {
+        // tile number q -> (I, J): block row I holds nb - I tiles
+        int q = q0 + e, I = 0;
+        const bool live = q < ntiles;
+        if (!live) q = 0;
+        while (q >= nb - I) {
+          q -= nb - I;
+          ++I;
+        }
+        ti[e] = live ? I : -1;
+        tj[e] = I + q;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int row = j0 + CH_NB * (I + 1) + 4 * v + fk, colg = j0 + CH_NB * (tj[e] + 1) + fi;
+          acc[e][v] = (live && row < b && colg < b) ? W[(int64_t)row * b + colg] : 0.0;
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < CH_TB; ++e) {
+        if (ti[e] < 0) continue;  // uniform
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const double a = -panel[(4 * s + fk) * ldp + CH_NB * (ti[e] + 1) + fi];
+          const double bb = panel[(4 * s + fk) * ldp + CH_NB * (tj[e] + 1) + fi];
+          acc[e] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bb, acc[e], 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int row = j0 + CH_NB * (ti[e] + 1) + 4 * v + fk, colg = j0 + CH_NB * (tj[e] + 1) + fi;
+          if (row < b && colg < b) W[(int64_t)row * b + colg] = acc[e][v];
+        }
       }
     }
     __syncthreads();
@@ -528,8 +610,8 @@ FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool n
 int set_dyn_smem(prac_ctx* ctx) {
   static bool done = false;
   if (!done) {
-    PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_upper_kernel<1024>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, CH_NB * 1024 * 8));
+    PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_upper_kernel),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, CH_NB * (CH_MAX + 2) * 8));
     PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(trsm_right_upper_kernel),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (TR_ROWS + TR_CH) * 1024 * 4));
     done = true;
@@ -576,8 +658,9 @@ int cholqr_pass(prac_ctx* ctx, const FitWs& w, const float* src, float* dst, int
   }
   rc = set_dyn_smem(ctx);
   if (rc) return rc;
-  hipLaunchKernelGGL(chol_upper_kernel<1024>, dim3(1), dim3(1024), (size_t)CH_NB * n * sizeof(double), ctx->stream, W64,
-                     n, shift, ctx->d_flag);
+  if (n > CH_MAX) return PRAC_EUNSUPPORTED;
+  hipLaunchKernelGGL(chol_upper_kernel, dim3(1), dim3(1024),
+                     (size_t)CH_NB * (round_up64(n, CH_NB) + 2) * sizeof(double), ctx->stream, W64, n, shift, ctx->d_flag);
   const dim3 tgrid((unsigned)((d + TR_ROWS - 1) / TR_ROWS));
   if (n <= 128)
     hipLaunchKernelGGL(trsm_right_upper_reg_kernel<8>, tgrid, dim3(256), (size_t)TR_CH * n * sizeof(float), ctx->stream,
