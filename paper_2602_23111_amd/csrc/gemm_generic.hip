@@ -114,6 +114,9 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GArgs a) {
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 constexpr int FK = 32, FLD = 64 + 32;
 
+// A_KFAST: A's k stride is one element instead (a tall row-major block times a small matrix: V M, V Z,
+// Q1 T); a thread then fetches 8 consecutive k of one row, lanes along m as they are stored to LDS.
+template <bool A_KFAST>
 __global__ __launch_bounds__(256) void gemm_f32_mfma_kernel(GArgs a) {
   __shared__ float As[2][FK][FLD];
   __shared__ float Bs[2][FK][FLD];
@@ -132,14 +135,19 @@ __global__ __launch_bounds__(256) void gemm_f32_mfma_kernel(GArgs a) {
     for (int p = 0; p < 8; ++p) {
       const int64_t k = k0 + lr + 4 * p;
       const bool kin = k < kend;
-      ra[p] = (kin && m0 + lc < a.M) ? A[k * a.a_cs + (m0 + lc)] : 0.f;
+      if constexpr (A_KFAST) {
+        const int64_t ka = k0 + 8 * lr + p;
+        ra[p] = (ka < kend && m0 + lc < a.M) ? A[(int64_t)(m0 + lc) * a.a_rs + ka] : 0.f;
+      } else {
+        ra[p] = (kin && m0 + lc < a.M) ? A[k * a.a_cs + (m0 + lc)] : 0.f;
+      }
       rb[p] = (kin && n0 + lc < a.N) ? B[k * a.b_rs + (n0 + lc)] : 0.f;
     }
   };
   auto sstore = [&](int buf) {
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-      As[buf][lr + 4 * p][lc] = ra[p];
+      As[buf][A_KFAST ? 8 * lr + p : lr + 4 * p][lc] = ra[p];
       Bs[buf][lr + 4 * p][lc] = rb[p];
     }
   };
@@ -292,13 +300,14 @@ int launch_gemm_generic(prac_ctx* ctx, const GemmGenArgs& g) {
   if (a.steps_per_split < TK) a.steps_per_split = TK;
   a.slabs = g.slabs;
   const bool abf = g.adt == PRAC_BF16, bbf = g.bdt == PRAC_BF16;
-  const bool mfma = !abf && !bbf && !g.acc64 && !g.out64 && a.a_rs == 1 && a.b_cs == 1 && a.k_stride == 1 &&
-                    (int64_t)a.M * a.N >= 64 * 64 && a.K >= 64;
+  const bool mfma = !abf && !bbf && !g.acc64 && !g.out64 && (a.a_rs == 1 || a.a_cs == 1) && a.b_cs == 1 &&
+                    a.k_stride == 1 && (int64_t)a.M * a.N >= 64 * 64 && a.K >= 64;
   const bool mfma64 = !abf && !bbf && g.acc64 && a.a_rs == 1 && a.b_cs == 1 && a.k_stride == 1;
   if (mfma) {
     a.steps_per_split = ((a.K + a.splits - 1) / a.splits + FK - 1) / FK * FK;
-    hipLaunchKernelGGL(gemm_f32_mfma_kernel, dim3((a.N + 63) / 64, (a.M + 63) / 64, a.splits), dim3(256), 0, ctx->stream,
-                       a);
+    const dim3 grid((a.N + 63) / 64, (a.M + 63) / 64, a.splits);
+    if (a.a_rs == 1) hipLaunchKernelGGL(gemm_f32_mfma_kernel<false>, grid, dim3(256), 0, ctx->stream, a);
+    else hipLaunchKernelGGL(gemm_f32_mfma_kernel<true>, grid, dim3(256), 0, ctx->stream, a);
   } else if (mfma64) {
     a.steps_per_split = ((a.K + a.splits - 1) / a.splits + 3) / 4 * 4;
     hipLaunchKernelGGL(gemm_f64_mfma_kernel, dim3((a.N + 63) / 64, (a.M + 63) / 64, a.splits), dim3(256), 0, ctx->stream,
