@@ -218,19 +218,18 @@ __device__ __forceinline__ float row_share(float x) {
 // steps U .. 15 of chunk JC (columns 16 JC .. 16 JC + 15) of the register-resident triangular solve
 // (see the kernel below)
 template <int U, int JC, int NPT>
-__device__ __forceinline__ void trsm_steps(float (&y)[NPT], const float* __restrict__ rch, int n, int nt, int cl) {
+__device__ __forceinline__ void trsm_steps(float (&y)[NPT], const float* __restrict__ rch, int nt, int cl) {
   if constexpr (U < 16) {
     if (U < nt) {  // uniform
-      const float* ru = rch + U * n;
+      // no per-element conditions: the staged rows are zero past column n, so every read and
+      // multiply-add below is unconditional and the reads of a step are issued together
+      const float* ru = rch + U * (16 * NPT);
       const float vt = row_share<U>(y[JC]) * ru[16 * JC + U];
-      if (cl == U) y[JC] = vt;
-      if (cl > U) y[JC] -= vt * ru[16 * JC + cl];
+      const float upd = y[JC] - vt * ru[16 * JC + cl];
+      y[JC] = cl == U ? vt : (cl > U ? upd : y[JC]);
 #pragma unroll
-      for (int j = JC + 1; j < NPT; ++j) {
-        const int c = cl + 16 * j;
-        if (c < n) y[j] -= vt * ru[c];
-      }
-      trsm_steps<U + 1, JC, NPT>(y, rch, n, nt, cl);
+      for (int j = JC + 1; j < NPT; ++j) y[j] -= vt * ru[cl + 16 * j];
+      trsm_steps<U + 1, JC, NPT>(y, rch, nt, cl);
     }
   }
 }
@@ -251,11 +250,9 @@ __device__ __forceinline__ void trsm_stage(const double (&nx)[NPT], float* rch, 
 #pragma unroll
   for (int j = 0; j < NPT; ++j) {
     const int c = cl + 16 * j;
-    if (c < n) {
-      double v = nx[j];
-      if (c == t0 + r) v = 1.0 / v;
-      rch[r * n + c] = (float)v;
-    }
+    double v = nx[j];  // zero below the diagonal and past row / column n
+    if (c == t0 + r) v = c < n ? 1.0 / v : 0.0;
+    rch[r * (16 * NPT) + c] = (float)v;
   }
 }
 
@@ -271,7 +268,7 @@ __device__ __forceinline__ void trsm_chunks(float (&y)[NPT], double (&nx)[NPT], 
       trsm_stage<NPT>(nx, rch, n, t0, r, cl);
       __syncthreads();
       if (t0 + 16 < n) trsm_fetch<NPT>(nx, R, n, t0 + 16, r, cl);
-      trsm_steps<0, JC, NPT>(y, rch, n, nt, cl);
+      trsm_steps<0, JC, NPT>(y, rch, nt, cl);
       trsm_chunks<JC + 1, NPT>(y, nx, rch, R, n, r, cl);
     }
   }
@@ -289,7 +286,7 @@ __global__ __launch_bounds__(256) void trsm_right_upper_reg_kernel(const float* 
                                                                    const double* __restrict__ R, float* __restrict__ dst,
                                                                    int64_t rows, int n) {
   extern __shared__ __align__(16) unsigned char trsm_smem[];
-  float* rch = reinterpret_cast<float*>(trsm_smem);  // [TR_CH][n]: rows t0 .. t0+15 of R, diagonal inverted
+  float* rch = reinterpret_cast<float*>(trsm_smem);  // [TR_CH][16 NPT]: rows t0 .. t0+15 of R, diagonal inverted, zero padded
   const int tid = threadIdx.x, r = tid >> 4, cl = tid & 15;
   const int64_t row = (int64_t)blockIdx.x * TR_ROWS + r;
   const bool ok = row < rows;
@@ -663,10 +660,10 @@ int cholqr_pass(prac_ctx* ctx, const FitWs& w, const float* src, float* dst, int
                      (size_t)CH_NB * (round_up64(n, CH_NB) + 2) * sizeof(double), ctx->stream, W64, n, shift, ctx->d_flag);
   const dim3 tgrid((unsigned)((d + TR_ROWS - 1) / TR_ROWS));
   if (n <= 128)
-    hipLaunchKernelGGL(trsm_right_upper_reg_kernel<8>, tgrid, dim3(256), (size_t)TR_CH * n * sizeof(float), ctx->stream,
+    hipLaunchKernelGGL(trsm_right_upper_reg_kernel<8>, tgrid, dim3(256), (size_t)TR_CH * 128 * sizeof(float), ctx->stream,
                        src, W64, dst, d, n);
   else if (n <= 256)
-    hipLaunchKernelGGL(trsm_right_upper_reg_kernel<16>, tgrid, dim3(256), (size_t)TR_CH * n * sizeof(float), ctx->stream,
+    hipLaunchKernelGGL(trsm_right_upper_reg_kernel<16>, tgrid, dim3(256), (size_t)TR_CH * 256 * sizeof(float), ctx->stream,
                        src, W64, dst, d, n);
   else
     hipLaunchKernelGGL(trsm_right_upper_kernel, tgrid, dim3(256), (size_t)(TR_ROWS + TR_CH) * n * sizeof(float),
