@@ -367,7 +367,8 @@ def main():
         step(t)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    dom_ms, dom_n = ctx.profile_read()
+    dom_each = ctx.profile_read_each()
+    dom_ms, dom_n = sum(dom_each), len(dom_each)
     ctx.profile_select(0)
     ctx.sync_status()
 
@@ -383,7 +384,8 @@ def main():
                     unit="GB/s" if hbm_bound else "TFLOP/s",
                     frac=ach_gbs / HBM_PEAK_GBS if hbm_bound else ach_tf / MFMA_BF16_PEAK_TFLOPS,
                     traffic=read_traffic(dominant, w["name"]),
-                    avg_us=dom_us, launches=dom_n, hbm_gbs=ach_gbs, hbm_frac=ach_gbs / HBM_PEAK_GBS,
+                    avg_us=dom_us, median_us=1e3 * sorted(dom_each)[len(dom_each) // 2] if dom_each else None,
+                    min_us=1e3 * min(dom_each) if dom_each else None, launches=dom_n, hbm_gbs=ach_gbs, hbm_frac=ach_gbs / HBM_PEAK_GBS,
                     mfma_tflops=ach_tf, mfma_frac=ach_tf / MFMA_BF16_PEAK_TFLOPS)
 
     cpu = None

@@ -102,6 +102,9 @@ enum {
 };
 int prac_profile_select(prac_ctx* ctx, int kind);
 int prac_profile_read(prac_ctx* ctx, double* total_ms, int64_t* launches);
+/* Same, launch by launch: the first min(cap, *launches) durations [host, milliseconds], in
+ * launch order, go to each_ms (may be NULL when cap is 0). */
+int prac_profile_read_each(prac_ctx* ctx, float* each_ms, int64_t cap, int64_t* launches);
 /* Launch-shape override for sweeps: PRAC_TUNE_CTDY_SPLITS = number of token ranges
  * the C^T dY reduction is split into (1..64; 0 restores the built-in choice). */
 enum { PRAC_TUNE_CTDY_SPLITS = 1 };

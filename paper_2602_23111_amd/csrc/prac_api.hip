@@ -260,26 +260,36 @@ int prac_set_tuning(prac_ctx* ctx, int key, int value) {
   return PRAC_OK;
 }
 
-int prac_profile_read(prac_ctx* ctx, double* total_ms, int64_t* launches) {
-  if (!total_ms || !launches) return PRAC_EINVAL;
+int prac_profile_read_each(prac_ctx* ctx, float* each_ms, int64_t cap, int64_t* launches) {
+  if (!launches || cap < 0 || (cap > 0 && !each_ms)) return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
   PRAC_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-  double sum = 0.0;
   int64_t n = 0;
   for (auto& pr : ctx->prof_pairs) {
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) {
-      sum += ms;
+      if (n < cap) each_ms[n] = ms;
       ++n;
     } else {
-      (void)hipGetLastError();
+      (void)hipGetLastError();  // a pair no launch took: its events were never recorded
     }
     ctx->prof_pool.push_back(pr.first);
     ctx->prof_pool.push_back(pr.second);
   }
   ctx->prof_pairs.clear();
-  *total_ms = sum;
   *launches = n;
+  return PRAC_OK;
+}
+
+int prac_profile_read(prac_ctx* ctx, double* total_ms, int64_t* launches) {
+  if (!total_ms || !launches) return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  std::vector<float> each(ctx->prof_pairs.size());
+  int rc = prac_profile_read_each(ctx, each.data(), (int64_t)each.size(), launches);
+  if (rc) return rc;
+  double sum = 0.0;
+  for (int64_t i = 0; i < *launches; ++i) sum += each[(size_t)i];
+  *total_ms = sum;
   return PRAC_OK;
 }
 

@@ -23,7 +23,7 @@ STATUS = {0: "PRAC_OK", -1: "PRAC_EINVAL", -2: "PRAC_ENOMEM", -3: "PRAC_EHIP",
           -4: "PRAC_ENUMERIC", -5: "PRAC_EUNSUPPORTED", -6: "PRAC_ENOCTX"}
 
 EXPORTS = ["prac_create", "prac_destroy", "prac_set_stream", "prac_sync_status", "prac_strerror",
-           "prac_last_hip_error", "prac_profile_select", "prac_profile_read", "prac_set_tuning",
+           "prac_last_hip_error", "prac_profile_select", "prac_profile_read", "prac_profile_read_each", "prac_set_tuning",
            "prac_compressed_bytes", "prac_unpack_compressed", "prac_philox_words", "prac_philox_normal", "prac_gram",
            "prac_basis_lp_bytes", "prac_pack_basis", "prac_fit_basis", "prac_compress",
            "prac_compress_fused_fwd", "prac_weight_grad", "prac_weight_grad_shared", "prac_reconstruct"]
@@ -61,6 +61,7 @@ def load_library() -> C.CDLL:
         "prac_last_hip_error": (i32, [vp]),
         "prac_profile_select": (i32, [vp, i32]),
         "prac_profile_read": (i32, [vp, C.POINTER(C.c_double), C.POINTER(i64)]),
+        "prac_profile_read_each": (i32, [vp, C.POINTER(C.c_float), i64, C.POINTER(i64)]),
         "prac_set_tuning": (i32, [vp, i32, i32]),
         "prac_compressed_bytes": (C.c_size_t, [i64, i32, i32, i32, i64]),
         "prac_unpack_compressed": (i32, [vp, vp, i64, i32, vp, i64]),
@@ -148,6 +149,12 @@ class Prac:
         ms, n = C.c_double(0.0), C.c_int64(0)
         _check(self.lib.prac_profile_read(self._h, C.byref(ms), C.byref(n)), "prac_profile_read")
         return float(ms.value), int(n.value)
+
+    def profile_read_each(self, cap: int = 1 << 16):
+        """Per-launch milliseconds (a list, launch order) of the selected kernel since the last read."""
+        buf, n = (C.c_float * cap)(), C.c_int64(0)
+        _check(self.lib.prac_profile_read_each(self._h, buf, cap, C.byref(n)), "prac_profile_read_each")
+        return [float(buf[i]) for i in range(min(cap, int(n.value)))]
 
     # ---- Gaussian draw
     def philox_words(self, seed: int, draw: int, stream: int, n: int) -> torch.Tensor:

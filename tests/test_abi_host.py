@@ -123,6 +123,9 @@ def test_other_entry_points_reject_bad_arguments(lib):
     assert lib.prac_unpack_compressed(None, DUMMY, 8, 4, DUMMY, 3) == -1
     assert lib.prac_set_tuning(None, 1, 8) == -6 and lib.prac_set_tuning(None, 2, 8) == -1
     assert lib.prac_profile_select(None, 9) == -1 and lib.prac_profile_select(None, 1) == -6
+    n64 = C.c_int64(0)
+    assert lib.prac_profile_read_each(None, None, 4, C.byref(n64)) == -1       # cap > 0 needs a buffer
+    assert lib.prac_profile_read_each(None, None, 0, C.byref(n64)) == -6
     # packed C: 8 * ceil(N/128) x ceil(c/32) blocks of 64 lanes x 8 bf16
     assert lib.prac_compressed_bytes(100, 40, 1, 1, 0) == 8 * 2 * 64 * 8 * 2
     assert lib.prac_compressed_bytes(100, 40, 1, 0, 48) == 100 * 48 * 2
