@@ -317,7 +317,7 @@ def test_weight_grad_exact_gradient_when_complement_is_full(ctx):
 @pytest.mark.parametrize("dt,N,d,ldx,stride", [
     ("f32", 2048, 512, 512, 1), ("f32", 700, 130, 136, 3),
     ("bf16", 2048, 512, 512, 1), ("bf16", 4100, 264, 264, 1), ("bf16", 3001, 200, 200, 4),
-    ("bf16", 500, 77, 77, 2),
+    ("bf16", 500, 77, 77, 2), ("bf16", 4500, 328, 336, 2),    # the last: streaming path, ragged in rows and columns
 ])
 def test_gram_matches_oracle(ctx, dt, N, d, ldx, stride):
     Xt = si.round_to(si.activation(N, d, 1.0, seed=d, n_out=2, out_scale=20.0)[0], dt)
