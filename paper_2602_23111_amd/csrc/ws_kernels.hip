@@ -968,8 +968,11 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
   a.X = X; a.ldx = ldx; a.N = N; a.d = d; a.Pfrag = Pfrag; a.ncb = ncb; a.c = c;
   a.C = C; a.ldc = ldc; a.ccb = (c + 31) / 32; a.packed = packed ? 1 : 0;
   a.tiles_m = (N + WS_BM - 1) / WS_BM;
-  // with a forward output the wide (64-column) wave tile is used throughout
-  const int FN = (c <= 128 && !Wfrag) ? 1 : 2;
+  // with a forward output the wide (64-column) wave tile is used throughout; without one the narrow
+  // tile also serves launches whose wide tiles would leave half of the CUs idle (few token rows):
+  // twice the workgroups, each with half the multiplications, X reaching the second of a pair from L2
+  const int wide_groups = (a.ccb + 7) / 8;
+  const int FN = (!Wfrag && (c <= 128 || (int64_t)a.tiles_m * wide_groups * 2 <= ctx->n_cu)) ? 1 : 2;
   // Pfrag == nullptr (only with a forward output): no C part, the launch is a plain Y = X W
   const int p_groups = Pfrag ? (a.ccb + 4 * FN - 1) / (4 * FN) : 0;
   if (p_groups * 4 * FN > ncb || (!Pfrag && !Wfrag)) return PRAC_EINVAL;  // packed basis narrower than assumed
