@@ -509,3 +509,26 @@ def test_gpu_path_wrong_scale_is_biased_as_predicted(ctx):
     se = np.sqrt(f * f * (s - 1.0) * np.sum(tailX ** 2) / draws)
     assert np.linalg.norm(mean_x - predicted) < 4.0 * se
     assert np.linalg.norm(mean_x - X) > 10.0 * se
+
+
+# ------------------------------------------------- per-kernel timing hook
+def test_profile_hook_counts_selected_launches_only(ctx):
+    N, d, c = 1024, 256, 64
+    X = torch.randn(N, d, device=DEV).to(torch.bfloat16)
+    P = si.round_to(si.orthonormal_basis(d, c, seed=9), "f32").to(DEV)
+    dY = torch.randn(N, 128, device=DEV).to(torch.bfloat16)
+    ctx.profile_select(1)                                   # the compress kernel
+    Cm = None
+    for _ in range(3):
+        Cm = ctx.compress(X, P)
+    ctx.weight_grad(Cm, dY, P, 32, 32, 7.0)                 # other kernels are not counted
+    each = ctx.profile_read_each()
+    assert len(each) == 3 and all(0.0 < ms < 100.0 for ms in each)
+    assert ctx.profile_read() == (0.0, 0)                   # a read clears
+    Cm = ctx.compress(X, P)
+    ms, n = ctx.profile_read()
+    assert n == 1 and ms > 0.0
+    ctx.profile_select(0)
+    ctx.compress(X, P)
+    assert ctx.profile_read_each() == []
+    ctx.sync_status()
