@@ -278,7 +278,8 @@ __global__ __launch_bounds__(256) void reduce_gen_kernel(const ACC* __restrict__
   const int64_t total = (int64_t)M * N;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
     ACC s = (ACC)0;
-    for (int z = 0; z < splits; ++z) s += slabs[z * total + i];
+#pragma unroll 8
+    for (int z = 0; z < splits; ++z) s += slabs[z * total + i];  // eight slabs in flight
     const int64_t o = (i / N) * ldo + i % N;
     const OUT v = (OUT)alpha * (OUT)s;
     out[o] = beta == 0.f ? v : v + (OUT)beta * out[o];

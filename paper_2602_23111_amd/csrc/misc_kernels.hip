@@ -112,32 +112,64 @@ __global__ __launch_bounds__(256) void reduce_slabs_kernel(const float* __restri
                                                            float beta) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
     float s = 0.f;
-    for (int z = 0; z < splits; ++z) s += part[z * stride + i];
+#pragma unroll 8
+    for (int z = 0; z < splits; ++z) s += part[z * stride + i];  // eight slabs in flight
     s *= alpha;
     out[i] = beta == 0.f ? s : s + beta * out[i];
   }
 }
 
-// part: splits x M x N fp32.  out[n][j] = sum_z part[z][j][n] (N x M, ld = ldo)
+// part: splits x M x N fp32.  out[n][j] = sum_z part[z][j][n] (N x M, ld = ldo).  One workgroup per
+// 16 (j) x 64 (n) patch: a thread sums four consecutive n of one row j over the slabs (16-byte loads,
+// 256-byte runs per row and slab, eight slabs in flight), the patch is transposed through LDS and
+// stored four consecutive j at a time.
 __global__ __launch_bounds__(256) void reduce_transpose_f32_kernel(const float* __restrict__ part, int splits, int M,
                                                                    int N, float* __restrict__ out, int64_t ldo) {
-  __shared__ float tile[32][33];
-  const int j0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
-  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
+  __shared__ float patch[16][65];
+  const int j0 = blockIdx.y * 16, n0 = blockIdx.x * 64;
+  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
   const int64_t slab = (int64_t)M * N;
-  for (int r = ty; r < 32; r += 8) {
-    const int j = j0 + r, n = n0 + tx;
-    float s = 0.f;
+  const bool vec_in = (N & 3) == 0 && (reinterpret_cast<uintptr_t>(part) & 15) == 0;
+  {
+    const int j = j0 + ty, n = n0 + 4 * tx;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     if (j < M && n < N) {
       const float* p = part + (int64_t)j * N + n;
-      for (int z = 0; z < splits; ++z) s += p[z * slab];
+      if (vec_in && n + 3 < N) {
+#pragma unroll 8
+        for (int z = 0; z < splits; ++z) {
+          const float4 v = *reinterpret_cast<const float4*>(p + z * slab);
+          s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+      } else {
+        for (int z = 0; z < splits; ++z) {
+          s.x += p[z * slab];
+          if (n + 1 < N) s.y += p[z * slab + 1];
+          if (n + 2 < N) s.z += p[z * slab + 2];
+          if (n + 3 < N) s.w += p[z * slab + 3];
+        }
+      }
     }
-    tile[r][tx] = s;
+    patch[ty][4 * tx + 0] = s.x;
+    patch[ty][4 * tx + 1] = s.y;
+    patch[ty][4 * tx + 2] = s.z;
+    patch[ty][4 * tx + 3] = s.w;
   }
   __syncthreads();
-  for (int r = ty; r < 32; r += 8) {
-    const int n = n0 + r, j = j0 + tx;
-    if (n < N && j < M) out[(int64_t)n * ldo + j] = tile[tx][r];
+  const bool vec_out = (ldo & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
+  const int nl = threadIdx.x / 4, jq = (threadIdx.x % 4) * 4;  // output row n0 + nl, columns j0 + jq .. + 3
+  const int n = n0 + nl, j = j0 + jq;
+  if (n < N && j < M) {
+    float* o = out + (int64_t)n * ldo + j;
+    const float x0 = patch[jq + 0][nl], x1 = patch[jq + 1][nl], x2 = patch[jq + 2][nl], x3 = patch[jq + 3][nl];
+    if (vec_out && j + 3 < M) {
+      *reinterpret_cast<float4*>(o) = make_float4(x0, x1, x2, x3);
+    } else {
+      o[0] = x0;
+      if (j + 1 < M) o[1] = x1;
+      if (j + 2 < M) o[2] = x2;
+      if (j + 3 < M) o[3] = x3;
+    }
   }
 }
 
@@ -205,7 +237,7 @@ int launch_reduce_slabs(prac_ctx* ctx, const float* part, int splits, int64_t st
 }
 
 int launch_reduce_transpose_f32(prac_ctx* ctx, const float* part, int splits, int M, int N, float* out, int64_t ldo) {
-  dim3 grid((N + 31) / 32, (M + 31) / 32);
+  dim3 grid((N + 63) / 64, (M + 15) / 16);
   hipLaunchKernelGGL(reduce_transpose_f32_kernel, grid, dim3(256), 0, ctx->stream, part, splits, M, N, out, ldo);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
