@@ -106,8 +106,11 @@ int prac_profile_read(prac_ctx* ctx, double* total_ms, int64_t* launches);
  * launch order, go to each_ms (may be NULL when cap is 0). */
 int prac_profile_read_each(prac_ctx* ctx, float* each_ms, int64_t cap, int64_t* launches);
 /* Launch-shape override for sweeps: PRAC_TUNE_CTDY_SPLITS = number of token ranges
- * the C^T dY reduction is split into (1..64; 0 restores the built-in choice). */
-enum { PRAC_TUNE_CTDY_SPLITS = 1 };
+ * the C^T dY reduction is split into (1..64; 0 restores the built-in choice).
+ * PRAC_TUNE_PROFILE_STRIDE = n (1..1024; 0 means 1): only every n-th launch of the selected
+ * kernel kind, counted from the selection, carries the event pair (an event pair costs a few
+ * microseconds of stream time, which a benchmark loop may not want on every step). */
+enum { PRAC_TUNE_CTDY_SPLITS = 1, PRAC_TUNE_PROFILE_STRIDE = 2 };
 int prac_set_tuning(prac_ctx* ctx, int key, int value);
 
 /* ---- Gaussian draw (Eq. (S_o): S_ij ~ N(0,1) i.i.d.) -------------------- */

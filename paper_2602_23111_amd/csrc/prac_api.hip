@@ -78,6 +78,7 @@ ProfScope::ProfScope(prac_ctx* c, int kind) : ctx(c) {
   c->ev_start = nullptr;
   c->ev_stop = nullptr;
   if (c->prof_kind != kind || kind == 0) return;
+  if (c->prof_seen++ % c->prof_stride != 0) return;
   hipEvent_t ev[2] = {nullptr, nullptr};
   for (int i = 0; i < 2; ++i) {
     if (!c->prof_pool.empty()) {
@@ -237,6 +238,8 @@ int prac_create(prac_ctx** out, int device, void* hip_stream) {
   c->d_flag = nullptr;
   c->last_hip = 0;
   c->prof_kind = 0;
+  c->prof_stride = 1;
+  c->prof_seen = 0;
   c->ev_start = nullptr;
   c->ev_stop = nullptr;
   c->tune_splits = 0;
@@ -289,10 +292,17 @@ int prac_profile_select(prac_ctx* ctx, int kind) {
   if (kind < PRAC_KERNEL_NONE || kind > PRAC_KERNEL_RECONSTRUCT) return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
   ctx->prof_kind = kind;
+  ctx->prof_seen = 0;
   return PRAC_OK;
 }
 
 int prac_set_tuning(prac_ctx* ctx, int key, int value) {
+  if (key == PRAC_TUNE_PROFILE_STRIDE) {
+    if (value < 0 || value > 1024) return PRAC_EINVAL;
+    if (!ctx) return PRAC_ENOCTX;
+    ctx->prof_stride = value < 1 ? 1 : value;
+    return PRAC_OK;
+  }
   if (key != PRAC_TUNE_CTDY_SPLITS || value < 0 || value > 127) return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
   ctx->tune_splits = value;

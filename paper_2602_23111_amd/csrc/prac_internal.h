@@ -24,6 +24,8 @@ struct prac_ctx {
   int n_cu;
   int tune_splits;    // > 0: override the token-split count of C^T dY (tuning hook)
   int prof_kind;      // kernel kind bracketed by events (0: none), see prac_profile_select
+  int prof_stride;    // every prof_stride-th launch of that kind carries the event pair
+  int64_t prof_seen;  // launches of that kind since the selection
   hipEvent_t ev_start, ev_stop;  // set by ProfScope: the next PRAC_LAUNCH attaches them to its kernel
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_pairs;  // recorded, not yet read
   std::vector<hipEvent_t> prof_pool;                          // idle events

@@ -528,6 +528,12 @@ def test_profile_hook_counts_selected_launches_only(ctx):
     Cm = ctx.compress(X, P)
     ms, n = ctx.profile_read()
     assert n == 1 and ms > 0.0
+    ctx.set_tuning(2, 2)                                    # every second launch of the selected kind
+    ctx.profile_select(1)
+    for _ in range(5):
+        ctx.compress(X, P)
+    assert len(ctx.profile_read_each()) == 3                # launches 0, 2 and 4
+    ctx.set_tuning(2, 1)
     ctx.profile_select(0)
     ctx.compress(X, P)
     assert ctx.profile_read_each() == []
