@@ -665,6 +665,9 @@ int cholqr_pass(prac_ctx* ctx, const FitWs& w, const float* src, float* dst, int
   else if (n <= 256)
     hipLaunchKernelGGL(trsm_right_upper_reg_kernel<16>, tgrid, dim3(256), (size_t)TR_CH * 256 * sizeof(float), ctx->stream,
                        src, W64, dst, d, n);
+  else if (n <= 512)
+    hipLaunchKernelGGL(trsm_right_upper_reg_kernel<32>, tgrid, dim3(256), (size_t)TR_CH * 512 * sizeof(float), ctx->stream,
+                       src, W64, dst, d, n);
   else
     hipLaunchKernelGGL(trsm_right_upper_kernel, tgrid, dim3(256), (size_t)(TR_ROWS + TR_CH) * n * sizeof(float),
                        ctx->stream, src, W64, dst, d, n);
