@@ -7,7 +7,7 @@
  * Q1 (d x k) spans the top-k right singular vectors of X, Q2 (d x r) is an
  * orthonormal basis of (I - Q1 Q1^T) S for a Gaussian S, and the random block
  * is weighted by the scaling factor s = (d - k) / r so that the reconstruction
- * X~ = C_1 Q1^T + s C_2 Q2^T is unbiased (Section 4.2, Eq. (S_o), Eq. (R),
+ * X~ = C_1 Q1^T + s C_2 Q2^T is unbiased (Section 4.3, Eq. (S_o), Eq. (R),
  * Theorem 1).  The weight gradient is then X~^T dY (Lemma 1; Alg. 2).
  *
  * Symbols: the paper's n, r_1, r_2 and scaling factor k are d, k, r and
@@ -17,9 +17,14 @@
  *   - Matrices are row-major with an explicit leading dimension (elements).
  *   - Unless marked [host], a pointer is a caller-owned DEVICE pointer valid on
  *     the ctx device.  The library never frees or keeps user buffers.
- *   - Work is enqueued on the ctx stream and the call returns without waiting.
- *     Scratch memory lives in the ctx and grows (hipMalloc) on demand; a ctx
- *     must not be used from two host threads at once.
+ *   - Work is enqueued on the ctx stream and the call returns without waiting,
+ *     PROVIDED the ctx scratch block is large enough.  Scratch memory lives in
+ *     the ctx; a call that needs more than the ctx holds waits for the device,
+ *     frees the block and allocates a larger one (hipMalloc).  Callers that
+ *     must not wait or allocate inside a hot call size the block up front:
+ *     prac_workspace_bytes for every call shape they will issue, then one
+ *     prac_reserve_workspace with the largest answer.  A ctx must not be used
+ *     from two host threads at once.
  *   - Return value: PRAC_OK (0) or a negative prac_status.  Shape and argument
  *     errors are detected on the host BEFORE anything is enqueued and before
  *     the ctx is looked at, so they can be exercised without a GPU.
@@ -85,6 +90,48 @@ int prac_sync_status(prac_ctx* ctx);
 const char* prac_strerror(int status);          /* [host] static string */
 int prac_last_hip_error(const prac_ctx* ctx);   /* last hipError_t seen */
 
+/* ---- scratch sizing ------------------------------------------------------ */
+/* The shape of one call, for prac_workspace_bytes.  Fields an entry point does not
+ * take are ignored.  `generic` = 1 says that the call will run the strided kernels
+ * (a base pointer that is not 16-byte aligned or a leading dimension that is not a
+ * multiple of 8 elements; fp32 data always does). */
+typedef enum {
+  PRAC_OP_GRAM = 1,        /* prac_gram: dt, N, d, fit.row_stride */
+  PRAC_OP_FIT_BASIS = 2,   /* prac_fit_basis: dt, N, d, k, r, refresh, fit */
+  PRAC_OP_COMPRESS = 3,    /* prac_compress: dt, N, d, k + r, c_layout, have_p_lp */
+  PRAC_OP_FUSED_FWD = 4,   /* prac_compress_fused_fwd: as compress, n_out = 1, m[0] */
+  PRAC_OP_WEIGHT_GRAD = 5, /* prac_weight_grad(_shared): dt, odt, N, d, k, r, n_out, m[], c_layout, have_p_lp */
+  PRAC_OP_RECONSTRUCT = 6  /* prac_reconstruct: dt, N, d, k, r, c_layout */
+} prac_op;
+#define PRAC_MAX_SHARED 4
+typedef struct {
+  int op;                      /* prac_op */
+  int dt;                      /* prac_dtype of X / C / dY */
+  int odt;                     /* prac_dtype of dW (weight gradient) */
+  int64_t N, d;
+  int k, r;
+  int n_out;                   /* outputs that share C (weight gradient), 1 for the fused forward */
+  int64_t m[PRAC_MAX_SHARED];  /* their widths */
+  int c_layout;                /* prac_c_layout */
+  int have_p_lp;               /* 1: the call hands over a packed basis P_lp */
+  int generic;                 /* 1: unaligned operands, the strided kernels run */
+  int refresh;                 /* fit: PRAC_REFRESH_* bits */
+  prac_fit_opts fit;           /* fit / Gram: options as passed to the call */
+} prac_call_shape;
+/* Bytes of ctx scratch one call of that shape needs (0: none); (size_t)-1 for a shape
+ * the entry point would reject.  [host]; ctx may be NULL (then the split counts are
+ * planned for the 256 compute units of an MI355X).  The answer depends on the ctx's
+ * tuning overrides (prac_set_tuning): query after setting them. */
+size_t prac_workspace_bytes(const prac_ctx* ctx, const prac_call_shape* shape /* [host] */);
+/* Grow the ctx scratch block to at least `bytes` now (waits for the device and
+ * reallocates if it is smaller; never shrinks).  After it, no call whose
+ * prac_workspace_bytes is <= bytes waits, frees or allocates. */
+int prac_reserve_workspace(prac_ctx* ctx, size_t bytes);
+/* Test hook [host]: bytes by which the fit's split-sum block exceeds the largest split
+ * product prac_fit_basis issues for that shape (negative: the plan would be too small;
+ * the launchers refuse such a product instead of writing past the block). */
+int64_t prac_debug_fit_slab_margin(const prac_call_shape* shape /* [host] */);
+
 /* ---- per-kernel timing hook (for benchmarks) ---------------------------- */
 /* While a kind other than PRAC_KERNEL_NONE is selected, every launch of that
  * kernel is bracketed by a HIP event pair on the ctx stream.  prac_profile_read
@@ -131,7 +178,7 @@ int prac_philox_normal(prac_ctx* ctx, uint64_t seed, uint64_t draw, uint32_t str
 int prac_gram(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d,
               int64_t ldx, int64_t row_stride, float* G, int64_t ldg);
 
-/* ---- basis fit (Section 4.2 construction; Alg. 1 lines 1-14) ------------ */
+/* ---- basis fit (Section 4.3 construction; Alg. 1, both update branches) -- */
 /* Bytes of the packed low-precision copy of a d x c basis (see below). */
 size_t prac_basis_lp_bytes(int64_t d, int c);
 /* Build the packed bf16 copy P_lp of P (d x c fp32, ldp >= c) that the bf16
@@ -204,7 +251,6 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
  * be coarser than for one output alone.  dY, m, lddy, dW, lddw are [host] arrays
  * of n_out entries (dY[h], dW[h] device pointers; dW_h is d x m[h]); everything
  * else as in prac_weight_grad, which is this call with n_out = 1. */
-#define PRAC_MAX_SHARED 4
 int prac_weight_grad_shared(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int64_t ldc,
                             int c_layout, int n_out, const void* const* dY, const int64_t* m,
                             const int64_t* lddy, const float* P, const void* P_lp, int64_t d,

@@ -28,7 +28,7 @@ _U32 = np.uint64(0xFFFFFFFF)
 
 # --------------------------------------------------------------------------
 # Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): the counter-based
-# generator behind "S_ij ~ i.i.d. N(0,1)" (Section 4.2, Eq. S_o; Alg. 1).
+# generator behind "S_ij ~ i.i.d. N(0,1)" (Section 4.3, Eq. S_o; Alg. 1).
 # The paper fixes only the distribution; the stream layout is this build's.
 # --------------------------------------------------------------------------
 _PHILOX_M0 = np.uint64(0xD2511F53)
@@ -109,7 +109,7 @@ def gaussian_matrix(seed: int, draw: int, rows: int, cols: int,
 
 
 # --------------------------------------------------------------------------
-# Principal subspace (Section 4.1 PAC; Alg. 1, principal-subspace update)
+# Principal subspace (Section 4.2 PAC; Alg. 1, principal-subspace update)
 # --------------------------------------------------------------------------
 def gram(X: np.ndarray, row_stride: int = 1) -> np.ndarray:
     """G = Xs^T Xs over rows 0, stride, 2*stride, ... of X.  The right
@@ -128,7 +128,7 @@ def principal_subspace(G: np.ndarray, k: int):
 
 
 # --------------------------------------------------------------------------
-# Random complement basis (Section 4.2, Eq. (S_o); Lemma 4)
+# Random complement basis (Section 4.3, Eq. (S_o); Lemma 4)
 # --------------------------------------------------------------------------
 def thin_qr_positive(A: np.ndarray):
     """Thin QR with diag(R) > 0 (the unique factorisation that Lemma 1 and

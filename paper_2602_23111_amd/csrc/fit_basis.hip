@@ -1,4 +1,4 @@
-// Basis fit: P = [Q1 | Q2] (Section 4.2; Alg. 1, both refresh branches).
+// Basis fit: P = [Q1 | Q2] (Section 4.3 construction; Alg. 1, both refresh branches).
 //
 // Q1: the paper takes the top-r_1 right singular vectors of X "via SVD".  They are
 // the dominant eigenvectors of G = X^T X, found here by block power iteration
@@ -8,6 +8,8 @@
 // complement of Q1 and orthonormalised.  orth() is Cholesky-QR with an fp64 Gram
 // matrix, which yields the thin-QR factor with a positive-diagonal R, i.e. the
 // same Q2 that Householder QR with sign normalisation gives.
+#include <algorithm>
+
 #include "prac_internal.h"
 
 namespace {
@@ -526,7 +528,7 @@ __global__ __launch_bounds__(256) void copy_cols_kernel(const float* __restrict_
 }
 
 struct FitWs {
-  size_t G, V, Y, W64, X64, Rinv, lam, Z, S, T, slabs, gram, total;
+  size_t G, V, Y, W64, X64, Rinv, lam, Z, S, T, slabs, slab_bytes, gram, total;
   size_t trk_pf, trk_c, trk_slabs;  // tracking refit: V in fragment order, packed X V, slabs of (X V)^T X
   int trk_nkb, trk_ncb, trk_splits;
   int b;
@@ -583,8 +585,12 @@ FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool n
   if (sg < 1) sg = 1;
   if (sg > 16) sg = 16;
   w.splits_gv = sg;
+  // the slab block serves every split product of the fit: the bb x bb panel Gram matrices (fp64), G V
+  // (d x b, fp32) and Q1^T S (k x r, fp32; wider than a panel Gram when k > 2 r and Q1 is not refreshed)
   const size_t slab_bb = (size_t)s * bb * bb * 8, slab_gv = sg > 1 ? (size_t)sg * d * b * 4 : 0;
-  w.slabs = p.take(slab_bb > slab_gv ? slab_bb : slab_gv);
+  const size_t slab_kr = (size_t)s * k * r * 4;
+  w.slab_bytes = std::max(slab_bb, std::max(slab_gv, slab_kr));
+  w.slabs = p.take(w.slab_bytes);
   w.gram = p.take(gram_bytes);
   if (track) {
     w.trk_nkb = (int)(round_up64(d, 256) / 16);
@@ -634,7 +640,7 @@ int panel_gram(prac_ctx* ctx, const FitWs& w, const float* src, int64_t d, int n
   g.a_rs = 1; g.a_cs = n; g.b_rs = n; g.b_cs = 1;
   g.M = n; g.N = n; g.K = d; g.k_stride = 1;
   g.ldo = n; g.alpha = 1.f; g.beta = 0.f;
-  g.splits = w.splits_bb; g.slabs = ctx->ws + w.slabs;
+  g.splits = w.splits_bb; g.slabs = ctx->ws + w.slabs; g.slab_bytes = w.slab_bytes;
   if (W64) { g.out = nullptr; g.out64 = W64; g.acc64 = true; }
   else { g.out = M32; g.out64 = nullptr; g.acc64 = false; }
   return launch_gemm_generic(ctx, g);
@@ -717,19 +723,69 @@ int cholqr(prac_ctx* ctx, const FitWs& w, float* Y, float* V, int64_t d, int n, 
   return PRAC_OK;
 }
 
+
+
+// The scratch plan of one fit: which path runs (tracking / Gram-based) and where everything lives.
+struct FitPlan {
+  bool do_q1, do_q2, track;
+  int64_t rows;
+  FitWs L;
+};
+FitPlan make_fit_plan(int n_cu, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, int k, int r,
+                      int refresh, const prac_fit_opts& o) {
+  FitPlan f{};
+  f.do_q1 = (refresh & PRAC_REFRESH_PRINCIPAL) && k > 0;
+  f.do_q2 = (refresh & PRAC_REFRESH_RANDOM) && r > 0;
+  const int64_t stride = o.row_stride > 0 ? o.row_stride : 1;
+  f.rows = (N + stride - 1) / stride;
+  if (!f.do_q1 && !f.do_q2) return f;  // nothing to refresh: no scratch
+  f.track = f.do_q1 && can_track(X, xdt, f.rows, d, ldx, k, o);
+  const size_t gram_bytes = f.do_q1 && !f.track ? gram_scratch_bytes(n_cu, X, xdt, N, d, ldx, stride, d) : 0;
+  f.L = plan_fit(d, k, r, o, n_cu, f.do_q1 && !f.track, gram_bytes, f.track, f.rows);
+  return f;
+}
+
 }  // namespace
+
+size_t fit_scratch_bytes(int n_cu, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, int k, int r,
+                         int refresh, const prac_fit_opts& o) {
+  const FitPlan f = make_fit_plan(n_cu, X, xdt, N, d, ldx, k, r, refresh, o);
+  return (f.do_q1 || f.do_q2) ? f.L.total : 0;
+}
+
+// Bytes by which the slab block of the plan exceeds the largest split product of the fit (negative:
+// a product would not fit).  The products are listed here as fit_basis_device issues them.
+int64_t fit_slab_margin(int n_cu, prac_dtype xdt, int64_t N, int64_t d, int k, int r, int refresh,
+                        const prac_fit_opts& o) {
+  const FitPlan f = make_fit_plan(n_cu, nullptr, xdt, N, d, d, k, r, refresh, o);
+  const FitWs& L = f.L;
+  if (!f.do_q1 && !f.do_q2) return 0;
+  size_t need = 0;
+  auto product = [&](int splits, int64_t M, int64_t Nn, size_t esz) {
+    if (splits > 1) need = std::max(need, (size_t)splits * M * Nn * esz);
+  };
+  if (f.do_q1) {
+    const int n = L.b;  // block width of the iteration (k when tracking)
+    product(L.splits_bb, n, n, 8);                    // panel Gram matrices of orth(), Rayleigh-Ritz
+    if (!f.track) product(L.splits_gv, d, n, 4);      // G V
+    product(L.splits_bb, k, k, 8);                    // tidy pass on Q1
+  }
+  if (f.do_q2) {
+    if (k > 0) product(L.splits_bb, k, r, 4);         // Q1^T S
+    product(L.splits_bb, r, r, 8);                    // panel Gram matrices of orth(S_o)
+  }
+  return (int64_t)L.slab_bytes - (int64_t)need;
+}
 
 int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, int k, int r,
                      uint64_t seed, uint32_t draw, int refresh, const prac_fit_opts& o, float* P, int64_t ldp) {
-  const bool do_q1 = (refresh & PRAC_REFRESH_PRINCIPAL) && k > 0;
-  const bool do_q2 = (refresh & PRAC_REFRESH_RANDOM) && r > 0;
+  const FitPlan plan = make_fit_plan(ctx->n_cu, X, xdt, N, d, ldx, k, r, refresh, o);
+  const bool do_q1 = plan.do_q1, do_q2 = plan.do_q2, track = plan.track;
   if (!do_q1 && !do_q2) return PRAC_OK;
   if (k > 1024 || r > 1024) return PRAC_EUNSUPPORTED;  // single-workgroup panel kernels
   const int64_t stride = o.row_stride > 0 ? o.row_stride : 1;
-  const int64_t rows = (N + stride - 1) / stride;
-  const bool track = do_q1 && can_track(X, xdt, rows, d, ldx, k, o);
-  const size_t gram_bytes = do_q1 && !track ? gram_scratch_bytes(ctx, X, xdt, N, d, ldx, o.row_stride, d) : 0;
-  const FitWs L = plan_fit(d, k, r, o, ctx->n_cu, do_q1 && !track, gram_bytes, track, rows);
+  const int64_t rows = plan.rows;
+  const FitWs& L = plan.L;
   int rc = prac_ws_reserve(ctx, L.total);
   if (rc) return rc;
   float* G = reinterpret_cast<float*>(ctx->ws + L.G);
@@ -785,7 +841,7 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       g.A = G; g.B = it == 0 ? Y : V; g.adt = PRAC_F32; g.bdt = PRAC_F32;
       g.a_rs = 1; g.a_cs = d; g.b_rs = b; g.b_cs = 1;  // G(m, k) read as G[k][m]: G is symmetric
       g.M = (int)d; g.N = b; g.K = d; g.k_stride = 1;
-      g.splits = L.splits_gv; g.slabs = ctx->ws + L.slabs;
+      g.splits = L.splits_gv; g.slabs = ctx->ws + L.slabs; g.slab_bytes = L.slab_bytes;
       g.out = it == 0 ? V : Y; g.ldo = b; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
       rc = launch_gemm_generic(ctx, g);
       if (rc) return rc;
@@ -810,7 +866,7 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       g.a_rs = 1; g.a_cs = b; g.b_rs = b; g.b_cs = 1;
       g.M = b; g.N = b; g.K = d; g.k_stride = 1;
       g.out = nullptr; g.out64 = H; g.ldo = b; g.alpha = 1.f; g.beta = 0.f; g.acc64 = true;
-      g.splits = L.splits_bb; g.slabs = ctx->ws + L.slabs;
+      g.splits = L.splits_bb; g.slabs = ctx->ws + L.slabs; g.slab_bytes = L.slab_bytes;
       rc = launch_gemm_generic(ctx, g);
       if (rc) return rc;
     }
@@ -884,7 +940,7 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
         g.M = k; g.N = r; g.K = d; g.k_stride = 1;
         // fp32 sums on the matrix cores: the second projection removes what rounding left of the first
         g.out = T; g.ldo = r; g.alpha = 1.f; g.beta = 0.f; g.acc64 = false; g.out64 = nullptr;
-        g.splits = L.splits_bb; g.slabs = ctx->ws + L.slabs;
+        g.splits = L.splits_bb; g.slabs = ctx->ws + L.slabs; g.slab_bytes = L.slab_bytes;
         rc = launch_gemm_generic(ctx, g);
         if (rc) return rc;
         GemmGenArgs h{};

@@ -297,6 +297,8 @@ int launch_gemm_generic(prac_ctx* ctx, const GemmGenArgs& g) {
   a.out = g.out; a.out64 = g.out64; a.ldo = g.ldo; a.alpha = g.alpha; a.beta = g.beta;
   const int64_t nsteps = (a.K + a.k_stride - 1) / a.k_stride;
   a.splits = (g.splits > 1 && g.slabs) ? g.splits : 1;
+  if (a.splits > 1 && (size_t)a.splits * a.M * a.N * (g.acc64 ? sizeof(double) : sizeof(float)) > g.slab_bytes)
+    return PRAC_EINVAL;  // the caller's plan is too small for this product: never write past it
   a.steps_per_split = ((nsteps + a.splits - 1) / a.splits + TK - 1) / TK * TK;
   if (a.steps_per_split < TK) a.steps_per_split = TK;
   a.slabs = g.slabs;

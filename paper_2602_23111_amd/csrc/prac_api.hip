@@ -1,5 +1,6 @@
 // C ABI of libprac (see include/prac.h): argument checks, scratch planning and the
 // sequence of kernel launches behind each entry point.
+#include <algorithm>
 #include <new>
 
 #include "prac_internal.h"
@@ -50,8 +51,10 @@ inline int pick_splits(int tiles, int64_t K, int n_cu, int min_k) {
 
 int prac_ws_reserve(prac_ctx* ctx, size_t bytes) {
   if (bytes <= ctx->ws_bytes) return PRAC_OK;
-  // Work already enqueued may still read the old block: wait before replacing it.
-  PRAC_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  // Work already enqueued may still read the old block (on the ctx stream, or on a stream the ctx
+  // was bound to earlier): wait for the device before replacing it.  Callers that must not wait
+  // size the block up front (prac_workspace_bytes, prac_reserve_workspace).
+  PRAC_HIP_TRY(ctx, hipDeviceSynchronize());
   if (ctx->ws) PRAC_HIP_TRY(ctx, hipFree(ctx->ws));
   ctx->ws = nullptr;
   ctx->ws_bytes = 0;
@@ -104,9 +107,9 @@ namespace {
 inline bool gram_fast(const void* X, prac_dtype xdt, int64_t rows, int64_t ldx, int64_t row_stride) {
   return xdt == PRAC_BF16 && aligned16(X) && ldx % 8 == 0 && rows < ((int64_t)1 << 31);
 }
-inline int gram_splits(const prac_ctx* ctx, int64_t d, int64_t rows) {
+inline int gram_splits(int n_cu, int64_t d, int64_t rows) {
   const int tiles = (int)(((d + 127) / 128) * ((d + 127) / 128));
-  return pick_splits(tiles, rows, ctx->n_cu, 512);
+  return pick_splits(tiles, rows, n_cu, 512);
 }
 }  // namespace
 
@@ -115,9 +118,9 @@ namespace {
 // d = 2048 is 2.5 times that of the tiled GEMM): X is first copied into the packed layout the
 // kernel reads its C operand from.
 inline bool gram_streaming(int64_t rows, int64_t d) { return rows >= 2048 && d >= 256; }
-inline int gram_stream_splits(const prac_ctx* ctx, int64_t d, int64_t rows) {
+inline int gram_stream_splits(int n_cu, int64_t d, int64_t rows) {
   const int64_t tiles = ((d + 127) / 128) * ((d + 255) / 256);
-  int64_t s = ctx->n_cu / tiles;
+  int64_t s = n_cu / tiles;
   if (s > rows / 256) s = rows / 256;
   if (s > 64) s = 64;
   return s < 1 ? 1 : (int)s;
@@ -127,10 +130,10 @@ struct GramPlan {
   int splits;
   size_t o_part, o_g, o_pack, bytes;
 };
-inline GramPlan plan_gram(const prac_ctx* ctx, int64_t rows, int64_t d, int64_t ldg) {
+inline GramPlan plan_gram(int n_cu, int64_t rows, int64_t d, int64_t ldg) {
   GramPlan g{};
   g.streaming = gram_streaming(rows, d);
-  g.splits = g.streaming ? gram_stream_splits(ctx, d, rows) : gram_splits(ctx, d, rows);
+  g.splits = g.streaming ? gram_stream_splits(n_cu, d, rows) : gram_splits(n_cu, d, rows);
   WsPlan plan;
   g.o_part = plan.take(g.splits > 1 ? (size_t)g.splits * d * d * sizeof(float) : 0);
   g.o_g = plan.take(ldg == d ? 0 : (size_t)d * d * sizeof(float));
@@ -140,11 +143,11 @@ inline GramPlan plan_gram(const prac_ctx* ctx, int64_t rows, int64_t d, int64_t 
 }
 }  // namespace
 
-size_t gram_scratch_bytes(const prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
+size_t gram_scratch_bytes(int n_cu, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
                           int64_t row_stride, int64_t ldg) {
   const int64_t rows = (N + row_stride - 1) / row_stride;
   if (!gram_fast(X, xdt, rows, ldx, row_stride)) return 0;
-  return plan_gram(ctx, rows, d, ldg).bytes;
+  return plan_gram(n_cu, rows, d, ldg).bytes;
 }
 
 // G = Xs^T Xs with all scratch taken from `scratch` (gram_scratch_bytes of it).
@@ -152,7 +155,7 @@ int gram_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t
                 float* G, int64_t ldg, char* scratch) {
   const int64_t rows = (N + row_stride - 1) / row_stride;
   if (gram_fast(X, xdt, rows, ldx, row_stride)) {
-    const GramPlan gp = plan_gram(ctx, rows, d, ldg);
+    const GramPlan gp = plan_gram(ctx->n_cu, rows, d, ldg);
     const int splits = gp.splits;
     const size_t o_part = gp.o_part, o_g = gp.o_g;
     float* dense = ldg == d ? G : reinterpret_cast<float*>(scratch + o_g);
@@ -245,8 +248,14 @@ int prac_create(prac_ctx** out, int device, void* hip_stream) {
   c->tune_splits = 0;
   hipDeviceProp_t prop;
   c->n_cu = (hipGetDeviceProperties(&prop, device) == hipSuccess) ? prop.multiProcessorCount : 256;
-  if (hipMalloc(reinterpret_cast<void**>(&c->d_flag), 256) != hipSuccess ||
-      hipMemset(c->d_flag, 0, 256) != hipSuccess) {
+  if (hipMalloc(reinterpret_cast<void**>(&c->d_flag), 256) != hipSuccess) {
+    (void)hipGetLastError();
+    delete c;
+    return PRAC_EHIP;
+  }
+  if (hipMemset(c->d_flag, 0, 256) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(c->d_flag);
     delete c;
     return PRAC_EHIP;
   }
@@ -303,7 +312,7 @@ int prac_set_tuning(prac_ctx* ctx, int key, int value) {
     ctx->prof_stride = value < 1 ? 1 : value;
     return PRAC_OK;
   }
-  if (key != PRAC_TUNE_CTDY_SPLITS || value < 0 || value > 127) return PRAC_EINVAL;
+  if (key != PRAC_TUNE_CTDY_SPLITS || value < 0 || value > 64) return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
   ctx->tune_splits = value;
   return PRAC_OK;
@@ -361,7 +370,7 @@ int prac_gram(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d
   if (!X || !G || !valid_dtype(xdt) || bad_tokens(N) || d < 1 || d > (1 << 20) || ldx < d || ldg < d || row_stride < 1)
     return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
-  const size_t need = gram_scratch_bytes(ctx, X, xdt, N, d, ldx, row_stride, ldg);
+  const size_t need = gram_scratch_bytes(ctx->n_cu, X, xdt, N, d, ldx, row_stride, ldg);
   int rc = prac_ws_reserve(ctx, need);
   if (rc) return rc;
   return gram_device(ctx, X, xdt, N, d, ldx, row_stride, G, ldg, ctx->ws);
@@ -422,6 +431,31 @@ int prac_unpack_compressed(prac_ctx* ctx, const void* Cpk, int64_t N, int c, voi
   return launch_unpack_c(ctx, reinterpret_cast<const bf16_t*>(Cpk), (int)N, c, reinterpret_cast<bf16_t*>(C), ldc);
 }
 
+namespace {
+// Scratch of one compress / fused-forward call.  fast: the bf16 kernels run (aligned bf16 X).
+struct CompressPlan {
+  size_t o_lp, o_w, o_tmp, o_c, bytes;
+  int ncb_w;
+};
+CompressPlan plan_compress(bool fast, bool fused, bool packed, bool has_lp, prac_dtype xdt, int64_t N, int64_t d, int c,
+                           int64_t m) {
+  CompressPlan q{};
+  WsPlan plan;
+  if (fast) {
+    const LpLayout l = lp_layout(d, c);
+    q.o_lp = plan.take(has_lp ? 0 : l.bytes);
+    q.ncb_w = fused ? (int)round_up64((m + 31) / 32, 8) : 0;  // whole 256-column groups
+    q.o_w = plan.take(fused ? (size_t)l.nkb * q.ncb_w * 64 * 8 * sizeof(bf16_t) : 0);
+  } else {
+    const bool need_tmp = xdt == PRAC_BF16;
+    q.o_tmp = plan.take(need_tmp ? (size_t)N * (c > m ? c : (size_t)m) * sizeof(float) : 0);
+    q.o_c = plan.take(packed ? (size_t)N * round_up64(c, 8) * sizeof(bf16_t) : 0);
+  }
+  q.bytes = plan.off;
+  return q;
+}
+}  // namespace
+
 static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
                          const void* W, int64_t m, int64_t ldw, int w_layout, const float* P, const void* P_lp,
                          int64_t ldp, int c, void* Y, int64_t ldy, void* C, int64_t ldc, int c_layout) {
@@ -429,14 +463,16 @@ static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N
   const bool packed = c_layout == PRAC_C_PACKED;
   const bool fast = xdt == PRAC_BF16 && aligned16(X) && ldx % 8 == 0 && N < ((int64_t)1 << 31);
   if (packed && (xdt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
+  const CompressPlan q = plan_compress(fast, fused, packed, P_lp != nullptr, xdt, N, d, c, m);
+  if (q.bytes) {
+    int rc = prac_ws_reserve(ctx, q.bytes);
+    if (rc) return rc;
+  }
   if (fast) {
     const LpLayout l = lp_layout(d, c);
-    WsPlan plan;
-    const size_t o_lp = plan.take(P_lp ? 0 : l.bytes);
-    const int ncb_w = fused ? (int)round_up64((m + 31) / 32, 8) : 0;  // whole 256-column groups
-    const size_t o_w = plan.take(fused ? (size_t)l.nkb * ncb_w * 64 * 8 * sizeof(bf16_t) : 0);
-    int rc = prac_ws_reserve(ctx, plan.off);
-    if (rc) return rc;
+    const size_t o_lp = q.o_lp, o_w = q.o_w;
+    const int ncb_w = q.ncb_w;
+    int rc;
     const char* lp = reinterpret_cast<const char*>(P_lp);
     if (!lp) {
       rc = prac_pack_basis(ctx, P, d, ldp, c, ctx->ws + o_lp);
@@ -460,14 +496,8 @@ static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N
                               reinterpret_cast<bf16_t*>(Y), ldy);
   }
   // generic path: fp32 data (P used in fp32) or unaligned bf16
-  WsPlan plan;
   const bool need_tmp = xdt == PRAC_BF16;
-  const size_t o_tmp = plan.take(need_tmp ? (size_t)N * (c > m ? c : (size_t)m) * sizeof(float) : 0);
-  const size_t o_c = plan.take(packed ? (size_t)N * round_up64(c, 8) * sizeof(bf16_t) : 0);
-  if (plan.off) {
-    int rc = prac_ws_reserve(ctx, plan.off);
-    if (rc) return rc;
-  }
+  const size_t o_tmp = q.o_tmp, o_c = q.o_c;
   float* tmp = need_tmp ? reinterpret_cast<float*>(ctx->ws + o_tmp) : nullptr;
   void* Crm = packed ? static_cast<void*>(ctx->ws + o_c) : C;
   const int64_t ldcrm = packed ? round_up64(c, 8) : ldc;
@@ -532,25 +562,35 @@ namespace {
 
 // One gradient through the strided kernels (fp32 data, unaligned bf16): T = C^T dY (fp32), scale
 // the random rows, dW = P T.
-int weight_grad_generic(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt, int64_t N, int64_t m, int64_t ldc,
-                        bool packed, int64_t lddy, const float* P, int64_t d, int64_t ldp, int k, int r, float scale,
-                        void* dW, prac_dtype odt, int64_t lddw, float beta) {
-  const int c = k + r;
+struct WgradGenPlan {
+  size_t o_t, o_dw, o_crm, bytes;
+};
+WgradGenPlan plan_wgrad_generic(int64_t N, int64_t d, int64_t m, int c, bool packed, prac_dtype odt) {
+  WgradGenPlan q{};
   WsPlan plan;
-  const size_t o_t = plan.take((size_t)c * m * sizeof(float));
-  const size_t o_dw = plan.take(odt == PRAC_BF16 ? (size_t)d * m * sizeof(float) : 0);
-  const size_t o_crm = plan.take(packed ? (size_t)N * c * sizeof(bf16_t) : 0);
-  int rc = prac_ws_reserve(ctx, plan.off);
-  if (rc) return rc;
+  q.o_t = plan.take((size_t)c * m * sizeof(float));
+  q.o_dw = plan.take(odt == PRAC_BF16 ? (size_t)d * m * sizeof(float) : 0);
+  q.o_crm = plan.take(packed ? (size_t)N * c * sizeof(bf16_t) : 0);
+  q.bytes = plan.off;
+  return q;
+}
+
+int weight_grad_generic(prac_ctx* ctx, char* ws, const void* C, const void* dY, prac_dtype dt, int64_t N, int64_t m,
+                        int64_t ldc, bool packed, int64_t lddy, const float* P, int64_t d, int64_t ldp, int k, int r,
+                        float scale, void* dW, prac_dtype odt, int64_t lddw, float beta) {
+  const int c = k + r;
+  const WgradGenPlan q = plan_wgrad_generic(N, d, m, c, packed, odt);
+  const size_t o_t = q.o_t, o_dw = q.o_dw, o_crm = q.o_crm;
+  int rc;
   const void* Crm = C;
   int64_t ldcrm = ldc;
   if (packed) {
-    rc = launch_unpack_c(ctx, reinterpret_cast<const bf16_t*>(C), (int)N, c, reinterpret_cast<bf16_t*>(ctx->ws + o_crm), c);
+    rc = launch_unpack_c(ctx, reinterpret_cast<const bf16_t*>(C), (int)N, c, reinterpret_cast<bf16_t*>(ws + o_crm), c);
     if (rc) return rc;
-    Crm = ctx->ws + o_crm;
+    Crm = ws + o_crm;
     ldcrm = c;
   }
-  float* T = reinterpret_cast<float*>(ctx->ws + o_t);
+  float* T = reinterpret_cast<float*>(ws + o_t);
   GemmGenArgs g{};
   g.A = Crm; g.adt = dt; g.a_rs = 1; g.a_cs = ldcrm;
   g.B = dY; g.bdt = dt; g.b_rs = lddy; g.b_cs = 1;
@@ -569,7 +609,7 @@ int weight_grad_generic(prac_ctx* ctx, const void* C, const void* dY, prac_dtype
     h.out = reinterpret_cast<float*>(dW); h.ldo = lddw; h.beta = beta;
     return launch_gemm_generic(ctx, h);
   }
-  float* tmp = reinterpret_cast<float*>(ctx->ws + o_dw);
+  float* tmp = reinterpret_cast<float*>(ws + o_dw);
   h.out = tmp; h.ldo = m; h.beta = 0.f;
   rc = launch_gemm_generic(ctx, h);
   if (rc) return rc;
@@ -578,50 +618,62 @@ int weight_grad_generic(prac_ctx* ctx, const void* C, const void* dY, prac_dtype
 
 // n_out gradients from one C on the bf16 kernels: one launch forms the token-split slabs of every
 // C^T dY_h, then each output gets its slab reduction and its dW_h = P T_h.
-int weight_grad_fast(prac_ctx* ctx, const void* C, int64_t N, int64_t ldc, bool packed, int n_out,
-                     const void* const* dY, const int64_t* m, const int64_t* lddy, const float* P, const void* P_lp,
-                     int64_t d, int64_t ldp, int k, int r, float scale, void* const* dW, prac_dtype odt,
-                     const int64_t* lddw, float beta) {
-  const int c = k + r;
+struct WgradPlan {
+  int splits;
+  int nmb[PRAC_CTDY_MAX_OUT];
+  size_t o_part[PRAC_CTDY_MAX_OUT], o_t[PRAC_CTDY_MAX_OUT], o_lp, o_cpk, bytes;
+};
+WgradPlan plan_wgrad_fast(int n_cu, int tune_splits, int64_t N, int64_t d, int c, int n_out, const int64_t* m,
+                          bool packed, bool has_lp) {
+  WgradPlan q{};
   const LpLayout l = lp_layout(d, c);
   int tiles = 0;
   for (int h = 0; h < n_out; ++h) tiles += ((c + 255) / 256) * (int)((m[h] + 127) / 128);
   // one workgroup per CU at most: a second, partly filled round would cost a whole workgroup time
-  int splits = ctx->n_cu / tiles;
+  int splits = n_cu / tiles;
   if (splits > N / 256) splits = (int)(N / 256);
   if (splits < 1) splits = 1;
   if (splits > 64) splits = 64;
-  if (ctx->tune_splits > 0) splits = ctx->tune_splits;
+  if (tune_splits > 0) splits = tune_splits;
+  q.splits = splits;
   WsPlan plan;
-  size_t o_part[PRAC_CTDY_MAX_OUT], o_t[PRAC_CTDY_MAX_OUT];
-  int nmb[PRAC_CTDY_MAX_OUT];
   for (int h = 0; h < n_out; ++h) {
-    nmb[h] = (int)round_up64((m[h] + 31) / 32, 4);  // 32-column blocks of T, whole 128-column tiles
-    o_part[h] = plan.take((size_t)splits * c * m[h] * sizeof(float));
-    o_t[h] = plan.take((size_t)l.nckb * nmb[h] * 64 * 8 * sizeof(bf16_t));
+    q.nmb[h] = (int)round_up64((m[h] + 31) / 32, 4);  // 32-column blocks of T, whole 128-column tiles
+    q.o_part[h] = plan.take((size_t)splits * c * m[h] * sizeof(float));
+    q.o_t[h] = plan.take((size_t)l.nckb * q.nmb[h] * 64 * 8 * sizeof(bf16_t));
   }
-  const size_t o_lp = plan.take(P_lp ? 0 : l.bytes);
-  const size_t o_cpk = plan.take(packed ? 0 : packed_c_bytes(N, c));
-  int rc = prac_ws_reserve(ctx, plan.off);
-  if (rc) return rc;
+  q.o_lp = plan.take(has_lp ? 0 : l.bytes);
+  q.o_cpk = plan.take(packed ? 0 : packed_c_bytes(N, c));
+  q.bytes = plan.off;
+  return q;
+}
+
+int weight_grad_fast(prac_ctx* ctx, char* ws, const WgradPlan& q, const void* C, int64_t N, int64_t ldc, bool packed,
+                     int n_out, const void* const* dY, const int64_t* m, const int64_t* lddy, const float* P,
+                     const void* P_lp, int64_t d, int64_t ldp, int k, int r, float scale, void* const* dW,
+                     prac_dtype odt, const int64_t* lddw, float beta) {
+  const int c = k + r;
+  const LpLayout l = lp_layout(d, c);
+  const int splits = q.splits;
+  int rc;
   const char* lp = reinterpret_cast<const char*>(P_lp);
   if (!lp) {
-    rc = prac_pack_basis(ctx, P, d, ldp, c, ctx->ws + o_lp);
+    rc = prac_pack_basis(ctx, P, d, ldp, c, ws + q.o_lp);
     if (rc) return rc;
-    lp = ctx->ws + o_lp;
+    lp = ws + q.o_lp;
   }
   const bf16_t* Cpk = reinterpret_cast<const bf16_t*>(C);
   if (!packed) {
-    rc = launch_pack_c(ctx, reinterpret_cast<const bf16_t*>(C), ldc, (int)N, c, reinterpret_cast<bf16_t*>(ctx->ws + o_cpk));
+    rc = launch_pack_c(ctx, reinterpret_cast<const bf16_t*>(C), ldc, (int)N, c, reinterpret_cast<bf16_t*>(ws + q.o_cpk));
     if (rc) return rc;
-    Cpk = reinterpret_cast<const bf16_t*>(ctx->ws + o_cpk);
+    Cpk = reinterpret_cast<const bf16_t*>(ws + q.o_cpk);
   }
   const bf16_t* dYp[PRAC_CTDY_MAX_OUT];
   float* part[PRAC_CTDY_MAX_OUT];
   int mi[PRAC_CTDY_MAX_OUT];
   for (int h = 0; h < n_out; ++h) {
     dYp[h] = reinterpret_cast<const bf16_t*>(dY[h]);
-    part[h] = reinterpret_cast<float*>(ctx->ws + o_part[h]);
+    part[h] = reinterpret_cast<float*>(ws + q.o_part[h]);
     mi[h] = (int)m[h];
   }
   {  // T_h = C^T dY_h as `splits` partial slabs over the token range
@@ -630,19 +682,38 @@ int weight_grad_fast(prac_ctx* ctx, const void* C, int64_t N, int64_t ldc, bool 
   }
   if (rc) return rc;
   bf16_t* Tf[PRAC_CTDY_MAX_OUT];
-  for (int h = 0; h < n_out; ++h) Tf[h] = reinterpret_cast<bf16_t*>(ctx->ws + o_t[h]);
+  for (int h = 0; h < n_out; ++h) Tf[h] = reinterpret_cast<bf16_t*>(ws + q.o_t[h]);
   {  // T_h in fragment order (bf16): slabs summed, random rows weighted by the scaling factor
     ProfScope ps(ctx, PRAC_KERNEL_T_REDUCE);
-    rc = launch_reduce_to_tfrag(ctx, n_out, part, splits, c, mi, k, scale, l.nckb, nmb, Tf);
+    rc = launch_reduce_to_tfrag(ctx, n_out, part, splits, c, mi, k, scale, l.nckb, q.nmb, Tf);
   }
   if (rc) return rc;
   {
     ProfScope ps(ctx, PRAC_KERNEL_P_T);  // dW_h = P T_h, all outputs in one launch
-    rc = launch_pt(ctx, reinterpret_cast<const bf16_t*>(lp + l.off_pa), n_out, Tf, (int)d, mi, l.nckb, nmb, dW, lddw,
+    rc = launch_pt(ctx, reinterpret_cast<const bf16_t*>(lp + l.off_pa), n_out, Tf, (int)d, mi, l.nckb, q.nmb, dW, lddw,
                    odt == PRAC_BF16, beta);
   }
   if (rc) return rc;
   return PRAC_OK;
+}
+
+// Argument checks of the weight-gradient entry points (no ctx needed).
+int wgrad_check(const void* C, prac_dtype dt, int64_t N, int64_t ldc, int c_layout, int n_out, const void* const* dY,
+                const int64_t* m, const int64_t* lddy, const float* P, const void* P_lp, int64_t d, int64_t ldp, int k,
+                int r, void* const* dW, prac_dtype odt, const int64_t* lddw) {
+  if (!C || !dY || !m || !lddy || !dW || !lddw || !P || n_out < 1 || n_out > PRAC_MAX_SHARED || !valid_dtype(dt) ||
+      !valid_dtype(odt) || bad_tokens(N) || d < 1 || d > (1 << 20) || k < 0 || r < 0 || k + r < 1 || (int64_t)k + r > d ||
+      (c_layout != PRAC_C_PACKED && (c_layout != PRAC_C_ROWMAJOR || ldc < k + r)) || ldp < k + r ||
+      (P_lp && !aligned16(P_lp)))
+    return PRAC_EINVAL;
+  for (int h = 0; h < n_out; ++h)
+    if (!dY[h] || !dW[h] || m[h] < 1 || m[h] > (1 << 20) || lddy[h] < m[h] || lddw[h] < m[h]) return PRAC_EINVAL;
+  return PRAC_OK;
+}
+bool wgrad_is_fast(prac_dtype dt, int64_t N, int n_out, const void* const* dY, const int64_t* lddy) {
+  bool fast = dt == PRAC_BF16 && N < ((int64_t)1 << 31);
+  for (int h = 0; h < n_out; ++h) fast = fast && aligned16(dY[h]) && lddy[h] % 8 == 0;
+  return fast;
 }
 
 }  // namespace
@@ -660,22 +731,25 @@ int prac_weight_grad_shared(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t
                             const void* const* dY, const int64_t* m, const int64_t* lddy, const float* P,
                             const void* P_lp, int64_t d, int64_t ldp, int k, int r, float scale, void* const* dW,
                             prac_dtype odt, const int64_t* lddw, float beta) {
-  if (!C || !dY || !m || !lddy || !dW || !lddw || !P || n_out < 1 || n_out > PRAC_MAX_SHARED || !valid_dtype(dt) ||
-      !valid_dtype(odt) || bad_tokens(N) || d < 1 || d > (1 << 20) || k < 0 || r < 0 || k + r < 1 || (int64_t)k + r > d ||
-      bad_c_layout(c_layout, ldc, k + r) || ldp < k + r || (P_lp && !aligned16(P_lp)))
-    return PRAC_EINVAL;
-  for (int h = 0; h < n_out; ++h)
-    if (!dY[h] || !dW[h] || m[h] < 1 || m[h] > (1 << 20) || lddy[h] < m[h] || lddw[h] < m[h]) return PRAC_EINVAL;
+  int rc = wgrad_check(C, dt, N, ldc, c_layout, n_out, dY, m, lddy, P, P_lp, d, ldp, k, r, dW, odt, lddw);
+  if (rc) return rc;
   if (!ctx) return PRAC_ENOCTX;
   const bool packed = c_layout == PRAC_C_PACKED;
   if (packed && (dt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
-  bool fast = dt == PRAC_BF16 && N < ((int64_t)1 << 31);
-  for (int h = 0; h < n_out; ++h) fast = fast && aligned16(dY[h]) && lddy[h] % 8 == 0;
-  if (fast)
-    return weight_grad_fast(ctx, C, N, ldc, packed, n_out, dY, m, lddy, P, P_lp, d, ldp, k, r, scale, dW, odt, lddw, beta);
+  if (wgrad_is_fast(dt, N, n_out, dY, lddy)) {
+    const WgradPlan q = plan_wgrad_fast(ctx->n_cu, ctx->tune_splits, N, d, k + r, n_out, m, packed, P_lp != nullptr);
+    rc = prac_ws_reserve(ctx, q.bytes);
+    if (rc) return rc;
+    return weight_grad_fast(ctx, ctx->ws, q, C, N, ldc, packed, n_out, dY, m, lddy, P, P_lp, d, ldp, k, r, scale, dW, odt,
+                            lddw, beta);
+  }
+  size_t need = 0;
+  for (int h = 0; h < n_out; ++h) need = std::max(need, plan_wgrad_generic(N, d, m[h], k + r, packed, odt).bytes);
+  rc = prac_ws_reserve(ctx, need);
+  if (rc) return rc;
   for (int h = 0; h < n_out; ++h) {
-    int rc = weight_grad_generic(ctx, C, dY[h], dt, N, m[h], ldc, packed, lddy[h], P, d, ldp, k, r, scale, dW[h], odt,
-                                 lddw[h], beta);
+    rc = weight_grad_generic(ctx, ctx->ws, C, dY[h], dt, N, m[h], ldc, packed, lddy[h], P, d, ldp, k, r, scale, dW[h], odt,
+                             lddw[h], beta);
     if (rc) return rc;
   }
   return PRAC_OK;
@@ -684,6 +758,33 @@ int prac_weight_grad_shared(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t
 }  // extern "C"
 
 // ------------------------------------------------------------------ reconstruction
+namespace {
+struct ReconPlan {
+  bool fast, direct;
+  int nkb, ncb;
+  int64_t ldcrm;
+  size_t o_pt, o_c, o_tmp, o_crm, bytes;
+};
+ReconPlan plan_reconstruct(bool fast, prac_dtype dt, int64_t N, int64_t d, int c, bool packed, int64_t ldc) {
+  ReconPlan q{};
+  q.fast = fast;
+  WsPlan plan;
+  if (fast) {
+    q.nkb = (int)(round_up64(c, 256) / 16);
+    q.ncb = (int)round_up64((d + 31) / 32, 8);
+    q.direct = c <= 256;  // the dedicated kernel reads packed C itself
+    q.ldcrm = packed ? round_up64(c, 8) : ldc;
+    q.o_pt = plan.take((size_t)q.nkb * q.ncb * 64 * 8 * sizeof(bf16_t));
+    q.o_c = plan.take(packed && !q.direct ? (size_t)N * q.ldcrm * sizeof(bf16_t) : 0);
+  } else {
+    q.o_tmp = plan.take(dt == PRAC_BF16 ? (size_t)N * d * sizeof(float) : 0);
+    q.o_crm = plan.take(packed ? (size_t)N * c * sizeof(bf16_t) : 0);
+  }
+  q.bytes = plan.off;
+  return q;
+}
+}  // namespace
+
 int prac_reconstruct(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int64_t ldc, int c_layout, const float* P,
                      int64_t d, int64_t ldp, int k, int r, float scale, void* Xh, int64_t ldxh) {
   if (!C || !P || !Xh || !valid_dtype(dt) || bad_tokens(N) || d < 1 || d > (1 << 20) || k < 0 || r < 0 || k + r < 1 ||
@@ -695,56 +796,47 @@ int prac_reconstruct(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int
   if (packed && (dt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
   const bool rm_ok = !packed && aligned16(C) && ldc % 8 == 0;
   const bool fast = dt == PRAC_BF16 && (packed || rm_ok) && N < ((int64_t)1 << 31);
+  const ReconPlan q = plan_reconstruct(fast, dt, N, d, c, packed, ldc);
+  if (q.bytes) {
+    int rc = prac_ws_reserve(ctx, q.bytes);
+    if (rc) return rc;
+  }
   if (fast) {
     // Xh = C Ps^T is the forward-output launch of the compress kernel with C in the role of X
     // (its "feature" dimension is c) and Ps^T in the role of W.
-    const int nkb = (int)(round_up64(c, 256) / 16);
-    const int ncb = (int)round_up64((d + 31) / 32, 8);
-    const bool direct = c <= 256;  // the dedicated kernel reads packed C itself
-    const int64_t ldcrm = packed ? round_up64(c, 8) : ldc;
-    WsPlan plan;
-    const size_t o_pt = plan.take((size_t)nkb * ncb * 64 * 8 * sizeof(bf16_t));
-    const size_t o_c = plan.take(packed && !direct ? (size_t)N * ldcrm * sizeof(bf16_t) : 0);
-    int rc = prac_ws_reserve(ctx, plan.off);
+    const int nkb = q.nkb, ncb = q.ncb;
+    const int64_t ldcrm = q.ldcrm;
+    bf16_t* Pt = reinterpret_cast<bf16_t*>(ctx->ws + q.o_pt);
+    int rc = launch_pack_ptfrag(ctx, P, d, ldp, c, k, scale, nkb, ncb, Pt);
     if (rc) return rc;
-    bf16_t* Pt = reinterpret_cast<bf16_t*>(ctx->ws + o_pt);
-    rc = launch_pack_ptfrag(ctx, P, d, ldp, c, k, scale, nkb, ncb, Pt);
-    if (rc) return rc;
-    if (direct) {
+    if (q.direct) {
       ProfScope ps(ctx, PRAC_KERNEL_RECONSTRUCT);
       return launch_reconstruct_ws(ctx, reinterpret_cast<const bf16_t*>(C), ldc, packed, (int)N, c, (int)d, Pt, ncb,
                                    reinterpret_cast<bf16_t*>(Xh), ldxh);
     }
     const bf16_t* Crm = reinterpret_cast<const bf16_t*>(C);
     if (packed) {
-      rc = launch_unpack_c(ctx, reinterpret_cast<const bf16_t*>(C), (int)N, c, reinterpret_cast<bf16_t*>(ctx->ws + o_c),
+      rc = launch_unpack_c(ctx, reinterpret_cast<const bf16_t*>(C), (int)N, c, reinterpret_cast<bf16_t*>(ctx->ws + q.o_c),
                            ldcrm);
       if (rc) return rc;
-      Crm = reinterpret_cast<const bf16_t*>(ctx->ws + o_c);
+      Crm = reinterpret_cast<const bf16_t*>(ctx->ws + q.o_c);
     }
     ProfScope ps(ctx, PRAC_KERNEL_RECONSTRUCT);
     return launch_compress_ws(ctx, Crm, ldcrm, (int)N, c, nullptr, 0, 0, nullptr, 0, false, Pt, ncb, (int)d,
                               reinterpret_cast<bf16_t*>(Xh), ldxh);
   }
   // generic path: Xh = C1 Q1^T, then Xh += scale * C2 Q2^T (fp32 sums)
-  WsPlan plan;
   const bool need_tmp = dt == PRAC_BF16;
-  const size_t o_tmp = plan.take(need_tmp ? (size_t)N * d * sizeof(float) : 0);
-  const size_t o_crm = plan.take(packed ? (size_t)N * c * sizeof(bf16_t) : 0);
-  if (plan.off) {
-    int rc = prac_ws_reserve(ctx, plan.off);
-    if (rc) return rc;
-  }
   const void* Crm = C;
   int64_t ldcrm = ldc;
   if (packed) {
     int rc = launch_unpack_c(ctx, reinterpret_cast<const bf16_t*>(C), (int)N, c,
-                             reinterpret_cast<bf16_t*>(ctx->ws + o_crm), c);
+                             reinterpret_cast<bf16_t*>(ctx->ws + q.o_crm), c);
     if (rc) return rc;
-    Crm = ctx->ws + o_crm;
+    Crm = ctx->ws + q.o_crm;
     ldcrm = c;
   }
-  float* out = need_tmp ? reinterpret_cast<float*>(ctx->ws + o_tmp) : reinterpret_cast<float*>(Xh);
+  float* out = need_tmp ? reinterpret_cast<float*>(ctx->ws + q.o_tmp) : reinterpret_cast<float*>(Xh);
   const int64_t ldo = need_tmp ? d : ldxh;
   const size_t es = esize(dt);
   bool first = true;
@@ -765,3 +857,73 @@ int prac_reconstruct(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int
   if (need_tmp) return launch_cast_out(ctx, out, d, Xh, PRAC_BF16, ldxh, (int)N, (int)d, 0.f);
   return PRAC_OK;
 }
+
+// ------------------------------------------------------------------ scratch sizing
+extern "C" {
+
+size_t prac_workspace_bytes(const prac_ctx* ctx, const prac_call_shape* sh) {
+  const size_t bad = ~(size_t)0;
+  if (!sh || !valid_dtype(sh->dt) || sh->N < 1 || sh->N >= ((int64_t)1 << 31) || sh->d < 1 || sh->d > (1 << 20) ||
+      sh->k < 0 || sh->r < 0 || (int64_t)sh->k + sh->r > sh->d)
+    return bad;
+  const int n_cu = ctx ? ctx->n_cu : 256;
+  const int tune = ctx ? ctx->tune_splits : 0;
+  const prac_dtype dt = (prac_dtype)sh->dt;
+  const int c = sh->k + sh->r;
+  const bool fast = dt == PRAC_BF16 && !sh->generic;
+  const bool packed = sh->c_layout == PRAC_C_PACKED;
+  // an unaligned pointer stands for "the strided kernels will run" where a plan looks at alignment
+  const void* xptr = sh->generic ? reinterpret_cast<const void*>(uintptr_t(2)) : nullptr;
+  const int64_t ldq = sh->generic ? sh->d : round_up64(sh->d, 8);  // row pitch the plan assumes for X
+  switch (sh->op) {
+    case PRAC_OP_GRAM:
+      return gram_scratch_bytes(n_cu, xptr, dt, sh->N, sh->d, ldq, sh->fit.row_stride > 0 ? sh->fit.row_stride : 1, sh->d);
+    case PRAC_OP_FIT_BASIS: {
+      if (c < 1) return bad;
+      prac_fit_opts o = sh->fit;
+      if (o.iters == 0) o.iters = 8;
+      if (o.row_stride == 0) o.row_stride = 1;
+      size_t b = fit_scratch_bytes(n_cu, xptr, dt, sh->N, sh->d, ldq, sh->k, sh->r, sh->refresh, o);
+      return b;  // the packed copy goes to the caller's P_lp, not to scratch
+    }
+    case PRAC_OP_COMPRESS:
+    case PRAC_OP_FUSED_FWD: {
+      if (c < 1) return bad;
+      const bool fused = sh->op == PRAC_OP_FUSED_FWD;
+      if (fused && (sh->n_out != 1 || sh->m[0] < 1)) return bad;
+      return plan_compress(fast, fused, packed, sh->have_p_lp != 0, dt, sh->N, sh->d, c, fused ? sh->m[0] : 0).bytes;
+    }
+    case PRAC_OP_WEIGHT_GRAD: {
+      if (c < 1 || sh->n_out < 1 || sh->n_out > PRAC_MAX_SHARED) return bad;
+      for (int h = 0; h < sh->n_out; ++h)
+        if (sh->m[h] < 1 || sh->m[h] > (1 << 20)) return bad;
+      if (fast) return plan_wgrad_fast(n_cu, tune, sh->N, sh->d, c, sh->n_out, sh->m, packed, sh->have_p_lp != 0).bytes;
+      size_t need = 0;
+      for (int h = 0; h < sh->n_out; ++h)
+        need = std::max(need, plan_wgrad_generic(sh->N, sh->d, sh->m[h], c, packed,
+                                                 sh->odt == PRAC_BF16 ? PRAC_BF16 : PRAC_F32).bytes);
+      return need;
+    }
+    case PRAC_OP_RECONSTRUCT:
+      if (c < 1) return bad;
+      return plan_reconstruct(fast, dt, sh->N, sh->d, c, packed, c).bytes;
+    default:
+      return bad;
+  }
+}
+
+int prac_reserve_workspace(prac_ctx* ctx, size_t bytes) {
+  if (bytes == ~(size_t)0) return PRAC_EINVAL;
+  if (!ctx) return PRAC_ENOCTX;
+  return prac_ws_reserve(ctx, bytes);
+}
+
+int64_t prac_debug_fit_slab_margin(const prac_call_shape* sh) {
+  if (!sh) return -1;
+  prac_fit_opts o = sh->fit;
+  if (o.iters == 0) o.iters = 8;
+  if (o.row_stride == 0) o.row_stride = 1;
+  return fit_slab_margin(256, (prac_dtype)sh->dt, sh->N, sh->d, sh->k, sh->r, sh->refresh, o);
+}
+
+}  // extern "C"

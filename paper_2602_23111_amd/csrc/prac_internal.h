@@ -96,6 +96,7 @@ struct GemmGenArgs {
   double* out64;  // when non-null the fp64 result is written here instead (ldo applies)
   int splits;     // > 1 with slabs != nullptr: split the reduction, then sum the slabs
   void* slabs;    // splits * M * N accumulators (fp64 if acc64 else fp32)
+  size_t slab_bytes;  // size of `slabs`; a launch whose slabs would not fit is refused (PRAC_EINVAL)
 };
 int launch_gemm_generic(prac_ctx* ctx, const GemmGenArgs& a);
 
@@ -150,8 +151,13 @@ int launch_pack_ptfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, in
 int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
                      int k, int r, uint64_t seed, uint32_t draw, int refresh, const prac_fit_opts& o,
                      float* P, int64_t ldp);
-size_t gram_scratch_bytes(const prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d,
+size_t gram_scratch_bytes(int n_cu, const void* X, prac_dtype xdt, int64_t N, int64_t d,
                           int64_t ldx, int64_t row_stride, int64_t ldg);
+// scratch of one prac_fit_basis call (X is only looked at for its alignment)
+size_t fit_scratch_bytes(int n_cu, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx, int k, int r,
+                         int refresh, const prac_fit_opts& o);
+int64_t fit_slab_margin(int n_cu, prac_dtype xdt, int64_t N, int64_t d, int k, int r, int refresh,
+                        const prac_fit_opts& o);
 int gram_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d, int64_t ldx,
                 int64_t row_stride, float* G, int64_t ldg, char* scratch);
 

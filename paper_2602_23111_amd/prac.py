@@ -26,7 +26,9 @@ EXPORTS = ["prac_create", "prac_destroy", "prac_set_stream", "prac_sync_status",
            "prac_last_hip_error", "prac_profile_select", "prac_profile_read", "prac_profile_read_each", "prac_set_tuning",
            "prac_compressed_bytes", "prac_unpack_compressed", "prac_philox_words", "prac_philox_normal", "prac_gram",
            "prac_basis_lp_bytes", "prac_pack_basis", "prac_fit_basis", "prac_compress",
-           "prac_compress_fused_fwd", "prac_weight_grad", "prac_weight_grad_shared", "prac_reconstruct"]
+           "prac_compress_fused_fwd", "prac_weight_grad", "prac_weight_grad_shared", "prac_reconstruct",
+           "prac_workspace_bytes", "prac_reserve_workspace", "prac_debug_fit_slab_margin"]
+OPS = {"gram": 1, "fit_basis": 2, "compress": 3, "fused_fwd": 4, "weight_grad": 5, "reconstruct": 6}
 
 
 class PracError(RuntimeError):
@@ -38,6 +40,26 @@ class PracError(RuntimeError):
 class FitOpts(C.Structure):
     _fields_ = [("iters", C.c_int), ("oversample", C.c_int), ("row_stride", C.c_int64),
                 ("warm_start", C.c_int)]
+
+
+class CallShape(C.Structure):
+    """prac_call_shape of include/prac.h."""
+    _fields_ = [("op", C.c_int), ("dt", C.c_int), ("odt", C.c_int), ("N", C.c_int64), ("d", C.c_int64),
+                ("k", C.c_int), ("r", C.c_int), ("n_out", C.c_int), ("m", C.c_int64 * 4), ("c_layout", C.c_int),
+                ("have_p_lp", C.c_int), ("generic", C.c_int), ("refresh", C.c_int), ("fit", FitOpts)]
+
+
+def call_shape(op: str, N: int, d: int, k: int, r: int, m=(), dt: int = PRAC_BF16, odt: int = PRAC_BF16,
+               c_layout: int = C_PACKED, have_p_lp: bool = True, generic: bool = False, refresh: int = 3,
+               iters: int = 0, oversample: int = 0, row_stride: int = 0, warm_start: bool = False) -> CallShape:
+    sh = CallShape()
+    sh.op, sh.dt, sh.odt, sh.N, sh.d, sh.k, sh.r = OPS[op], dt, odt, N, d, k, r
+    sh.n_out = len(m)
+    for i, v in enumerate(m):
+        sh.m[i] = v
+    sh.c_layout, sh.have_p_lp, sh.generic, sh.refresh = c_layout, int(have_p_lp), int(generic), refresh
+    sh.fit = FitOpts(iters, oversample, row_stride, 1 if warm_start else 0)
+    return sh
 
 
 _lib = None
@@ -78,6 +100,9 @@ def load_library() -> C.CDLL:
         "prac_weight_grad": (i32, [vp, vp, vp, i32, i64, i64, i64, i32, i64, vp, vp, i64, i64, i32, i32,
                                    f32, vp, i32, i64, f32]),
         "prac_reconstruct": (i32, [vp, vp, i32, i64, i64, i32, vp, i64, i64, i32, i32, f32, vp, i64]),
+        "prac_workspace_bytes": (C.c_size_t, [vp, C.POINTER(CallShape)]),
+        "prac_reserve_workspace": (i32, [vp, C.c_size_t]),
+        "prac_debug_fit_slab_margin": (i64, [C.POINTER(CallShape)]),
         "prac_weight_grad_shared": (i32, [vp, vp, i32, i64, i64, i32, i32, C.POINTER(vp), C.POINTER(i64),
                                           C.POINTER(i64), vp, vp, i64, i64, i32, i32, f32, C.POINTER(vp), i32,
                                           C.POINTER(i64), f32]),
@@ -139,6 +164,13 @@ class Prac:
 
     def sync_status(self):
         _check(self.lib.prac_sync_status(self._h), "prac_sync_status")
+
+    # ---- scratch sizing
+    def workspace_bytes(self, shape: CallShape) -> int:
+        return int(self.lib.prac_workspace_bytes(self._h, C.byref(shape)))
+
+    def reserve_workspace(self, nbytes: int):
+        _check(self.lib.prac_reserve_workspace(self._h, nbytes), "prac_reserve_workspace")
 
     # ---- per-kernel timing hook
     def profile_select(self, kind: int):

@@ -184,3 +184,59 @@ s_waitcnt vmcnt(0)
                                                                 "\t;;#ASMEND\n\tv_accvgpr_read_b32 v30, a3\n")
     found = lint_isa.lint_text(drained)
     assert len(found) == 1 and "ring register" in found[0]
+
+
+# ---- scratch sizing (prac_workspace_bytes / prac_reserve_workspace) ----------------------------
+def test_workspace_bytes_matches_the_documented_scratch_of_each_call(lib):
+    BAD = (1 << 64) - 1
+    ws = lambda sh: int(lib.prac_workspace_bytes(None, C.byref(sh)))
+    up = lambda b: (b + 255) // 256 * 256
+    N, d, m, k, r = 32768, 2048, 2048, 128, 128
+    c = k + r
+    lp = int(lib.prac_basis_lp_bytes(d, c))
+    # compress with a packed basis handed in needs nothing; without one, room for the packed copy
+    assert ws(prac.call_shape("compress", N, d, k, r)) == 0
+    assert ws(prac.call_shape("compress", N, d, k, r, have_p_lp=False)) == up(lp)
+    # fused forward: W in fragment order, d padded to 256 rows, m to 256 columns
+    assert ws(prac.call_shape("fused_fwd", N, d, k, r, m=[m])) == 2048 * 2048 * 2
+    # weight gradient at the headline shape: 16 token ranges of fp32 partial sums + T in fragment order (bf16)
+    assert ws(prac.call_shape("weight_grad", N, d, k, r, m=[m])) == 16 * c * m * 4 + c * m * 2
+    # three outputs sharing C: 5 token ranges (256 CUs / 48 tiles)
+    assert ws(prac.call_shape("weight_grad", N, d, k, r, m=[m, m, m])) == 3 * (5 * c * m * 4 + c * m * 2)
+    # row-major C has to be packed first
+    extra = int(lib.prac_compressed_bytes(N, c, 1, 1, 0))
+    assert ws(prac.call_shape("weight_grad", N, d, k, r, m=[m], c_layout=0)) == 16 * c * m * 4 + c * m * 2 + extra
+    # strided kernels (fp32 data): T, and nothing else for an fp32 dW
+    assert ws(prac.call_shape("weight_grad", 2048, 512, 32, 32, m=[1376], dt=0, odt=0, c_layout=0)) == up(64 * 1376 * 4)
+    # reconstruction: Ps^T in fragment order (k-blocks over 256, column blocks over d)
+    assert ws(prac.call_shape("reconstruct", N, d, k, r)) == 16 * 64 * 1024
+    # the tracking refit is cheaper than the Gram-based fit, and a random-only refresh cheaper still
+    cold = ws(prac.call_shape("fit_basis", N, d, k, r))
+    track = ws(prac.call_shape("fit_basis", N, d, k, r, warm_start=True, oversample=-1, iters=2))
+    rnd = ws(prac.call_shape("fit_basis", N, d, k, r, refresh=2))
+    assert cold > d * d * 4 and 0 < rnd < track < cold
+    assert ws(prac.call_shape("gram", N, d, 0, 0)) > 0
+    # shapes the entry points would reject
+    assert ws(prac.call_shape("compress", N, d, 0, 0)) == BAD
+    assert ws(prac.call_shape("weight_grad", N, d, k, r, m=[])) == BAD
+    assert ws(prac.call_shape("weight_grad", N, 100, 64, 64, m=[m])) == BAD      # k + r > d
+    bad_op = prac.call_shape("compress", N, d, k, r)
+    bad_op.op = 99
+    assert ws(bad_op) == BAD
+    assert int(lib.prac_workspace_bytes(None, None)) == BAD
+    assert lib.prac_reserve_workspace(None, 1 << 20) == -6
+    assert lib.prac_reserve_workspace(None, BAD) == -1
+
+
+def test_fit_plan_holds_every_split_product():
+    """The split-sum block of the fit's scratch plan is at least as large as every split product the fit
+    issues, for every rank split and refresh branch (a random-only refresh with k > 2 r once was not)."""
+    lib = prac.load_library()
+    for d in (384, 768, 2048, 4096):
+        for k, r in ((0, 64), (64, 0), (16, 16), (96, 16), (256, 32), (32, 256), (128, 128), (512, 64), (1024, 8)):
+            if k + r > d:
+                continue
+            for refresh in (1, 2, 3):
+                for opts in (dict(), dict(warm_start=True, oversample=-1, iters=2), dict(oversample=8)):
+                    sh = prac.call_shape("fit_basis", 32768, d, k, r, refresh=refresh, **opts)
+                    assert lib.prac_debug_fit_slab_margin(C.byref(sh)) >= 0, (d, k, r, refresh, opts)

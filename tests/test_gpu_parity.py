@@ -354,10 +354,10 @@ def test_fit_basis_principal_projector(ctx, dt):
     assert torch.equal(lp, ctx.pack_basis(P))
 
 
-def test_fit_basis_random_block_matches_oracle_draw(ctx):
+@pytest.mark.parametrize("d,k,r", [(384, 24, 40), (384, 96, 16), (768, 256, 32)])   # also k > 2 r
+def test_fit_basis_random_block_matches_oracle_draw(ctx, d, k, r):
     # Q2 alone (Alg. 1, random-subspace branch): Q1 is handed in, so Q2 is a
     # deterministic function of (Q1, seed, draw) and can be compared column by column
-    d, k, r = 384, 24, 40
     P32, P64 = basis32(d, k, seed=31)
     for draw in (0, 5):
         P = torch.zeros((d, k + r), dtype=torch.float32, device=DEV)
@@ -452,6 +452,47 @@ def test_fit_basis_tracking_refit(ctx, N, d, k, r, stride, iters):
     assert (1 - 1e-3) * lam[:k].sum() <= captured <= (1 + 1e-6) * lam[:k].sum()
     assert not torch.equal(P2[:, :k], P[:, :k])           # Q1 moved with the new batch
     assert not torch.equal(P2[:, k:], P[:, k:])
+
+
+def batch_pair_with_gap(N, d, k, alpha, shrink, seed):
+    """Two batches of one layer (same mixing matrix, fresh Gaussian tokens) whose spectrum drops by
+    `shrink` after the k-th singular value: the top-k subspace is well defined in both, and differs
+    between them by sampling noise only (what a lazily refreshed basis meets at a refresh)."""
+    sig = si.power_law_sigma(d, alpha)
+    sig[k:] *= shrink
+    X0 = si.round_to(si.activation(N, d, alpha, seed, sigma=sig)[0], "bf16")
+    X1 = si.round_to(si.activation(N, d, alpha, seed, sigma=sig, batch=1)[0], "bf16")
+    return X0, X1
+
+
+@pytest.mark.parametrize("shrink,iters,must_meet", [(0.9, 2, False), (0.9, 10, True), (0.5, 2, True)])
+def test_fit_basis_tracking_refit_projector(ctx, shrink, iters, must_meet):
+    """The Gram-free tracking refit (what bench.py's refreshes run) against the exact top-k projector of
+    the new batch.  Each tracking step contracts the distance to that subspace by lambda_{k+1} / lambda_k:
+    from the previous batch's basis (a few 1e-3 away in max-abs) two steps reach the 1e-3 tolerance where
+    the eigenvalue ratio at k is large (4.5 here), ten where it is 1.4; at ratios near the 1.05 threshold
+    two steps do NOT reach it - there the refit is held to the energy criterion instead, and that is what
+    is asserted for such a case."""
+    N, d, k, r = 4096, 256, 16, 16
+    X0, X1 = batch_pair_with_gap(N, d, k, 1.0, shrink, seed=6)
+    Q1, lam = orc.principal_subspace(orc.gram(si.as_f64(X1)), k)
+    assert lam[k - 1] / lam[k] >= 1.05
+    P, _, _ = ctx.fit_basis(X0.to(DEV), k, r, seed=2, draw=0, pack=False)
+    P2, _, _ = ctx.fit_basis(X1.to(DEV), k, r, seed=2, draw=1, P=P.clone(), iters=iters, oversample=-1,
+                             warm_start=True, pack=False)
+    ctx.sync_status()
+    U0, U2 = si.as_f64(P)[:, :k], si.as_f64(P2)[:, :k]
+    before = np.abs(U0 @ U0.T - Q1 @ Q1.T).max()
+    after = np.abs(U2 @ U2.T - Q1 @ Q1.T).max()
+    print(f"eigenvalue ratio {lam[k - 1] / lam[k]:.3f}, {iters} tracking steps: projector max-abs {before:.2e} -> {after:.2e}")
+    assert after < before                                   # the refit moved towards the new batch's subspace
+    if must_meet:
+        assert after < 1e-3
+    # always: the energy criterion (what the variance of the estimator depends on, Theorem 2)
+    X64 = si.as_f64(X1)
+    captured, total = float(np.sum((X64 @ U2) ** 2)), float(np.sum(X64 ** 2))
+    assert (1 - 1e-3) * lam[:k].sum() <= captured <= (1 + 1e-6) * lam[:k].sum()
+    assert total - captured <= 1.01 * (total - lam[:k].sum())
 
 
 # ------------------------------------------------- estimator statistics on the GPU path

@@ -4,7 +4,7 @@ the paper or the mathematics fixes, never against the oracle itself.
   Philox words      published known-answer vectors (tests/golden)
   Gaussian          moments + Kolmogorov-Smirnov against the normal CDF
   Gram + eigen      closed-form spectrum X = Q diag(sigma) R; PAC bias
-                    = tail energy (Section 4.1); rank-<=k exactness
+                    = tail energy (Section 4.2); rank-<=k exactness
   thin QR           hand-rolled Gram-Schmidt written here
   complement        Lemma 4 by Monte Carlo; Q1^T Q2 = 0
   basis             P^T P = I
@@ -96,7 +96,7 @@ def test_gram_eigen_closed_form_spectrum():
     # top-k right singular vectors are the first k rows of R (X = Z diag(sigma) R)
     proj_true = R[:k].T @ R[:k]
     assert np.abs(Q1 @ Q1.T - proj_true).max() < 1e-10
-    # PAC bias equals the tail energy (Section 4.1)
+    # PAC bias equals the tail energy (Section 4.2)
     assert np.isclose(np.linalg.norm(X - X @ Q1 @ Q1.T) ** 2, np.sum(sig[k:] ** 2), rtol=1e-10)
     # third opinion from a library SVD, called here and not in the oracle
     Vt = np.linalg.svd(X, full_matrices=False)[2]
