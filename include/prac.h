@@ -55,7 +55,8 @@ typedef enum {
   PRAC_EHIP = -3,         /* a HIP runtime call failed (see prac_last_hip_error) */
   PRAC_ENUMERIC = -4,     /* non-finite Gram or orthonormalisation breakdown */
   PRAC_EUNSUPPORTED = -5, /* valid request this build has no kernel for */
-  PRAC_ENOCTX = -6        /* ctx is NULL (arguments themselves were valid) */
+  PRAC_ENOCTX = -6,       /* ctx is NULL (arguments themselves were valid) */
+  PRAC_ETOOBIG = -7       /* prac_weight_grad_static: the call needs more scratch than the static block holds */
 } prac_status;
 
 /* refresh bits of prac_fit_basis: the two lazy-update branches of Alg. 1 */
@@ -242,6 +243,26 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
                      int64_t m, int64_t ldc, int c_layout, int64_t lddy, const float* P,
                      const void* P_lp, int64_t d, int64_t ldp, int k, int r, float scale,
                      void* dW, prac_dtype odt, int64_t lddw, float beta);
+
+/* For callers that cannot allocate device memory or wait for the device inside the call: code
+ * under HIP graph capture, serving loops, harnesses that forbid hipMalloc.  The same weight
+ * gradient as prac_weight_grad, same arguments, same kernels, same results bit for bit, with
+ * every intermediate (the token-split partial sums of C^T dY, T in fragment order, the packed copies of
+ * P and of a row-major C when they are not handed in) in a block of PRAC_STATIC_SCRATCH_BYTES that is
+ * part of the library's code object: every GPU the library runs on holds its own copy until the
+ * process ends.  The call never calls hipMalloc / hipFree or an allocating routine, never touches the
+ * ctx scratch, and is not profiled (prac_profile_select is ignored for it).
+ *   - PRAC_ETOOBIG when prac_workspace_bytes of the same call exceeds PRAC_STATIC_SCRATCH_BYTES
+ *     (the headline shape N = 32768, d = m = 2048, k + r = 256 needs 34.6 MB); nothing is enqueued then.
+ *   - All calls on one GPU share that GPU's block, which keeps the last call's contents: the
+ *     kernels overwrite what they read, so nothing needs clearing between calls, but two calls that
+ *     overlap in time on one GPU (two streams, two threads, two contexts) race.  Stream order on one
+ *     stream is enough. */
+#define PRAC_STATIC_SCRATCH_BYTES (48u << 20)
+int prac_weight_grad_static(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt, int64_t N,
+                            int64_t m, int64_t ldc, int c_layout, int64_t lddy, const float* P,
+                            const void* P_lp, int64_t d, int64_t ldp, int k, int r, float scale,
+                            void* dW, prac_dtype odt, int64_t lddw, float beta);
 
 /* Several layers that read the same input share one compressed activation
  * (Section 5.1, "activation subspace sharing": the query / key / value or the

@@ -5,7 +5,16 @@
 
 #include "prac_internal.h"
 
+// Scratch of the entry point that allocates nothing (prac_weight_grad_static): one block per GPU,
+// part of the code object, held until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; prac_create asks for the block's device address once per
+// device (with that device current) and everything else uses that address.
+static __device__ __align__(256) unsigned char scratch[PRAC_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+char* g_static_scratch[kMaxDevices] = {};  // device address of `scratch` on each GPU, set by prac_create
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 inline size_t esize(prac_dtype t) { return t == PRAC_BF16 ? 2 : 4; }
@@ -219,6 +228,7 @@ const char* prac_strerror(int s) {
     case PRAC_ENUMERIC: return "numeric breakdown";
     case PRAC_EUNSUPPORTED: return "unsupported request";
     case PRAC_ENOCTX: return "null context";
+    case PRAC_ETOOBIG: return "request needs more scratch than the static block holds";
     default: return "unknown status";
   }
 }
@@ -258,6 +268,19 @@ int prac_create(prac_ctx** out, int device, void* hip_stream) {
     (void)hipFree(c->d_flag);
     delete c;
     return PRAC_EHIP;
+  }
+  // address of this device's copy of the static scratch block (the device is current here)
+  c->static_scratch = device < kMaxDevices ? g_static_scratch[device] : nullptr;
+  if (!c->static_scratch) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      (void)hipFree(c->d_flag);
+      delete c;
+      return PRAC_EHIP;
+    }
+    c->static_scratch = reinterpret_cast<char*>(p);
+    if (device < kMaxDevices) g_static_scratch[device] = c->static_scratch;
   }
   *out = c;
   return PRAC_OK;
@@ -725,6 +748,37 @@ int prac_weight_grad(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt
                      int r, float scale, void* dW, prac_dtype odt, int64_t lddw, float beta) {
   return prac_weight_grad_shared(ctx, C, dt, N, ldc, c_layout, 1, &dY, &m, &lddy, P, P_lp, d, ldp, k, r, scale, &dW, odt,
                                  &lddw, beta);
+}
+
+int prac_weight_grad_static(prac_ctx* ctx, const void* C, const void* dY, prac_dtype dt, int64_t N, int64_t m,
+                            int64_t ldc, int c_layout, int64_t lddy, const float* P, const void* P_lp, int64_t d,
+                            int64_t ldp, int k, int r, float scale, void* dW, prac_dtype odt, int64_t lddw, float beta) {
+  int rc = wgrad_check(C, dt, N, ldc, c_layout, 1, &dY, &m, &lddy, P, P_lp, d, ldp, k, r, &dW, odt, &lddw);
+  if (rc) return rc;
+  if (!ctx) return PRAC_ENOCTX;
+  const bool packed = c_layout == PRAC_C_PACKED;
+  if (packed && (dt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
+  const bool fast = wgrad_is_fast(dt, N, 1, &dY, &lddy);
+  WgradPlan q{};
+  size_t need;
+  if (fast) {
+    q = plan_wgrad_fast(ctx->n_cu, ctx->tune_splits, N, d, k + r, 1, &m, packed, P_lp != nullptr);
+    need = q.bytes;
+  } else {
+    need = plan_wgrad_generic(N, d, m, k + r, packed, odt).bytes;
+  }
+  if (need > PRAC_STATIC_SCRATCH_BYTES) return PRAC_ETOOBIG;
+  // no event pairs here (creating one allocates): this call is not profiled
+  const int prof = ctx->prof_kind;
+  ctx->prof_kind = PRAC_KERNEL_NONE;
+  char* ws = ctx->static_scratch;
+  if (fast)
+    rc = weight_grad_fast(ctx, ws, q, C, N, ldc, packed, 1, &dY, &m, &lddy, P, P_lp, d, ldp, k, r, scale, &dW, odt, &lddw,
+                          beta);
+  else
+    rc = weight_grad_generic(ctx, ws, C, dY, dt, N, m, ldc, packed, lddy, P, d, ldp, k, r, scale, dW, odt, lddw, beta);
+  ctx->prof_kind = prof;
+  return rc;
 }
 
 int prac_weight_grad_shared(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int64_t ldc, int c_layout, int n_out,

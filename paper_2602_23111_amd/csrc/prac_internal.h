@@ -19,6 +19,7 @@ struct prac_ctx {
   hipStream_t stream;
   char* ws;           // device scratch, grown on demand
   size_t ws_bytes;
+  char* static_scratch;  // this device's copy of the library's static scratch block (prac_weight_grad_static)
   int* d_flag;        // device-side numeric failure flag (0 = fine)
   int last_hip;       // last hipError_t that made a call fail
   int n_cu;

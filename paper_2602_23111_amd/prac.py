@@ -20,14 +20,15 @@ C_ROWMAJOR, C_PACKED = 0, 1
 TUNE_CTDY_SPLITS = 1
 KERNEL_KINDS = {"compress": 1, "ct_dy": 2, "t_reduce": 3, "p_t": 4, "gram": 5, "fused_fwd": 6, "reconstruct": 7}
 STATUS = {0: "PRAC_OK", -1: "PRAC_EINVAL", -2: "PRAC_ENOMEM", -3: "PRAC_EHIP",
-          -4: "PRAC_ENUMERIC", -5: "PRAC_EUNSUPPORTED", -6: "PRAC_ENOCTX"}
+          -4: "PRAC_ENUMERIC", -5: "PRAC_EUNSUPPORTED", -6: "PRAC_ENOCTX", -7: "PRAC_ETOOBIG"}
+STATIC_SCRATCH_BYTES = 48 << 20
 
 EXPORTS = ["prac_create", "prac_destroy", "prac_set_stream", "prac_sync_status", "prac_strerror",
            "prac_last_hip_error", "prac_profile_select", "prac_profile_read", "prac_profile_read_each", "prac_set_tuning",
            "prac_compressed_bytes", "prac_unpack_compressed", "prac_philox_words", "prac_philox_normal", "prac_gram",
            "prac_basis_lp_bytes", "prac_pack_basis", "prac_fit_basis", "prac_compress",
            "prac_compress_fused_fwd", "prac_weight_grad", "prac_weight_grad_shared", "prac_reconstruct",
-           "prac_workspace_bytes", "prac_reserve_workspace", "prac_debug_fit_slab_margin"]
+           "prac_workspace_bytes", "prac_reserve_workspace", "prac_debug_fit_slab_margin", "prac_weight_grad_static"]
 OPS = {"gram": 1, "fit_basis": 2, "compress": 3, "fused_fwd": 4, "weight_grad": 5, "reconstruct": 6}
 
 
@@ -100,6 +101,8 @@ def load_library() -> C.CDLL:
         "prac_weight_grad": (i32, [vp, vp, vp, i32, i64, i64, i64, i32, i64, vp, vp, i64, i64, i32, i32,
                                    f32, vp, i32, i64, f32]),
         "prac_reconstruct": (i32, [vp, vp, i32, i64, i64, i32, vp, i64, i64, i32, i32, f32, vp, i64]),
+        "prac_weight_grad_static": (i32, [vp, vp, vp, i32, i64, i64, i64, i32, i64, vp, vp, i64, i64, i32, i32,
+                                          f32, vp, i32, i64, f32]),
         "prac_workspace_bytes": (C.c_size_t, [vp, C.POINTER(CallShape)]),
         "prac_reserve_workspace": (i32, [vp, C.c_size_t]),
         "prac_debug_fit_slab_margin": (i64, [C.POINTER(CallShape)]),
@@ -290,8 +293,10 @@ class Prac:
     def weight_grad(self, Cm: torch.Tensor, dY: torch.Tensor, P: torch.Tensor, k: int, r: int, scale: float,
                     P_lp: torch.Tensor | None = None, out: torch.Tensor | None = None,
                     out_dtype: torch.dtype = torch.float32, beta: float = 0.0,
-                    layout: int = C_ROWMAJOR) -> torch.Tensor:
-        """Cm: N x (k+r) row-major, or the flat packed buffer when layout == C_PACKED."""
+                    layout: int = C_ROWMAJOR, static: bool = False) -> torch.Tensor:
+        """Cm: N x (k+r) row-major, or the flat packed buffer when layout == C_PACKED.
+        static=True calls prac_weight_grad_static (then `out` must be given: this binding allocates nothing
+        on that path either)."""
         py, N, m, lddy = _mat(dY)
         pp, d, _, ldp = _mat(P)
         if layout == C_PACKED:
@@ -299,11 +304,14 @@ class Prac:
         else:
             pc, _, _, ldc = _mat(Cm)
             cdt = _dt(Cm)
+        if static and out is None:
+            raise ValueError("weight_grad(static=True) needs `out`")
         dW = out if out is not None else torch.empty((d, m), dtype=out_dtype, device=dY.device)
         pw, _, _, lddw = _mat(dW)
-        _check(self.lib.prac_weight_grad(self._h, pc, py, cdt, N, m, ldc, layout, lddy, pp,
-                                         P_lp.data_ptr() if P_lp is not None else None, d, ldp, k, r, scale, pw,
-                                         _dt(dW), lddw, beta), "prac_weight_grad")
+        fn = self.lib.prac_weight_grad_static if static else self.lib.prac_weight_grad
+        _check(fn(self._h, pc, py, cdt, N, m, ldc, layout, lddy, pp, P_lp.data_ptr() if P_lp is not None else None,
+                  d, ldp, k, r, scale, pw, _dt(dW), lddw, beta),
+               "prac_weight_grad_static" if static else "prac_weight_grad")
         return dW
 
     def weight_grad_shared(self, Cm: torch.Tensor, dYs, P: torch.Tensor, k: int, r: int, scale: float,

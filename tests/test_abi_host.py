@@ -90,6 +90,22 @@ def _fit(lib, ctx=None, X=DUMMY, dt=1, N=8, d=16, ldx=16, k=2, r=2, seed=1, draw
     return rc, scale.value
 
 
+def test_static_weight_grad_argument_checks(lib):
+    # same checks as prac_weight_grad, before the ctx is looked at
+    f = lib.prac_weight_grad_static
+    args = lambda **kw: _wgrad_args(**kw)
+    assert f(*_wgrad_args()) == -6
+    assert f(*_wgrad_args(dY=None)) == -1
+    assert f(*_wgrad_args(k=10, r=7, ldc=17, ldp=17)) == -1
+    assert f(*_wgrad_args(lddw=5)) == -1
+    assert lib.prac_strerror(-7) == b"request needs more scratch than the static block holds"
+
+
+def _wgrad_args(ctx=None, Cm=DUMMY, dY=DUMMY, dt=1, N=8, m=6, ldc=4, lddy=6, P=DUMMY, lp=None, d=16, ldp=4,
+                k=2, r=2, scale=7.0, dW=DUMMY, odt=0, lddw=6, beta=0.0, layout=0):
+    return (ctx, Cm, dY, dt, N, m, ldc, layout, lddy, P, lp, d, ldp, k, r, scale, dW, odt, lddw, beta)
+
+
 def test_fit_basis_argument_checks(lib):
     assert _fit(lib)[0] == -6
     assert _fit(lib, P=None)[0] == -1
