@@ -8,6 +8,13 @@ compress the saved activation (C = X P) and form the weight gradient
 a power-law spectrum and outlier channels, rotated over four independent input
 sets so that no step finds its inputs in the 256 MB last-level cache.
 
+The step counter t runs on from the warm-up into the timed region, as it does in
+training: step 0 (in the warm-up) fits the basis from scratch, every 500th step
+after it refreshes it.  With the default 500 timed steps exactly one refresh falls
+into the timed region; a short run (--steps 20) holds none, and the line then
+carries the measured cost of a refresh and the per-step figure with that cost
+amortised over 500 steps (keys `refit` and `value_with_amortised_refit`).
+
 Prints ONE JSON line: metric, value (tokens/s), roofline of the dominant kernel, the oracle timed on the host.
 """
 from __future__ import annotations
@@ -15,7 +22,6 @@ from __future__ import annotations
 import argparse
 import json
 import os
-import re
 import sys
 import time
 
@@ -41,8 +47,14 @@ OTHER_WORKLOADS = {
     "llama7b_up_gate": dict(WORKLOAD, name="llama7b_up_gate", N=16384, d=4096, m=11008, k=256, r=256, n_out=16,
                             out_scale=50.0, refresh_every=1, row_stride=4, n_sets=2, layer_seed=5000),
 }
+BLOCK_WORKLOAD = "llama1b_block"
+ABLATION_WORKLOAD = "estimator_ablation"
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+METRIC = "PRAC compress+weight-grad tokens/s at LLaMA-1B shape"
+REFIT_LABEL = ("Gram-free tracking refit, 2 subspace-iteration steps from the previous Q1: energy-tracked (captured and "
+               "residual energy within 1e-3 / 1 % of the exact top-k subspace); the 1e-3 projector tolerance is met at "
+               "2 steps only where lambda_k/lambda_{k+1} is about 3 or more, at 10 steps for a ratio of 1.4")
 
 
 def algorithmic_bytes(kind: str, w: dict) -> float:
@@ -56,13 +68,15 @@ def algorithmic_bytes(kind: str, w: dict) -> float:
         return 4.0 * c * m + 2.0 * c * m
     if kind == "p_t":
         return 2.0 * (d * c + c * m + d * m)
+    if kind == "weight_grad":       # the whole weight gradient in one launch; the c x m intermediate is not counted
+        return 2.0 * (N * c + N * m) + 2.0 * d * c + 2.0 * d * m
     raise KeyError(kind)
 
 
 def algorithmic_flops(kind: str, w: dict) -> float:
     N, d, m, c = w["N"], w["d"], w["m"], w["k"] + w["r"]
     return {"compress": 2.0 * N * d * c, "ct_dy": 2.0 * N * c * m, "t_reduce": float(c * m),
-            "p_t": 2.0 * d * c * m}[kind]
+            "p_t": 2.0 * d * c * m, "weight_grad": 2.0 * N * c * m + 2.0 * d * c * m}[kind]
 
 
 def read_traffic(kind: str, workload: str):
@@ -106,25 +120,24 @@ def cpu_baseline(X, dY, k, r, refresh_every):
         t_cw = min(t_cw, time.perf_counter() - t0)
     assert np.isfinite(dW).all()
     n = X64.shape[0]
-    return dict(value=n / (t_cw + t_fit / refresh_every), unit="tokens/s", cores=int(cores), kind="oracle",
+    return dict(value=n / (t_cw + t_fit / refresh_every), unit="tokens/s", cores=int(cores),
+                host_cpu_count=int(os.cpu_count() or 0), kind="oracle",
                 sample=f"all {n} tokens of one batch in fp64 numpy: fit {t_fit:.2f} s (once per {refresh_every} "
-                       f"steps), compress + weight-grad {t_cw:.2f} s (best of 2)")
+                       f"steps), compress + weight-grad {t_cw:.2f} s (best of 2); cores = threads of the BLAS pool")
 
 
-BLOCK_WORKLOAD = "llama1b_block"
-
-
-def run_block(args):
+# --------------------------------------------------------------------------- the LLaMA-1B block
+def measure_block(steps: int, warmup: int = 3, n_sets: int = 2):
     """All seven linear layers of one LLaMA-1B transformer block with subspace sharing (Section 5.1):
     q/k/v share the compressed attention input, up/gate the compressed MLP input; o and down have
     their own.  4 compressions + 7 weight gradients per step, each of the 4 bases refreshed (tracking
-    refit on the step's batch) every 500 steps."""
+    refit on the step's batch) every 500 steps.  Returns a dict of figures."""
     import torch
 
     import synth_inputs as si
     from paper_2602_23111_amd.prac import C_PACKED, Prac
 
-    N, k, r, refresh_every, n_sets = 32768, 128, 128, 500, 2
+    N, k, r, refresh_every = 32768, 128, 128, 500
     c = k + r
     groups = [("attn_in:q,k,v", 2048, [2048, 2048, 2048]), ("attn_out:o", 2048, [2048]),
               ("mlp_in:up,gate", 2048, [5461, 5461]), ("mlp_down:down", 5461, [2048])]
@@ -168,11 +181,11 @@ def run_block(args):
             layer_compress(g, i)
             layer_wgrad(g, i)
 
-    for t in range(max(min(args.warmup, 5), 1)):
+    for t in range(max(warmup, 1)):       # step 0 fits the four bases
         step(t)
     torch.cuda.synchronize()
 
-    def wall(fn, reps=20):
+    def wall(fn, reps=10):
         for t in range(2):
             fn(t % n_sets)
         torch.cuda.synchronize()
@@ -188,45 +201,142 @@ def run_block(args):
     fits[0] = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for t in range(args.steps):
+    for t in range(warmup, warmup + steps):    # the step counter runs on: a refresh where t mod 500 == 0
         step(t)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ctx.sync_status()
-    ms_per_step = 1e3 * elapsed / args.steps
+    ctx.close()
+    ms_per_step = 1e3 * elapsed / steps
     # algorithmic bytes of the block: every X, dY, C (written and read once per gradient launch), P and dW once
     by = 0.0
     for _, d, ms in groups:
         by += 2.0 * (N * d + d * c + N * c) + 2.0 * (N * c + sum(N * m + d * m for m in ms) + d * c)
+    return dict(ms_per_step=ms_per_step, tokens_per_s=N / (ms_per_step * 1e-3), steps=steps, refits=fits[0],
+                n_sets=n_sets, algorithmic_bytes=by, hbm_gbs=by / (ms_per_step * 1e-3) / 1e9,
+                hbm_frac=by / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, layers_us=layers_us,
+                what="the 7 linear layers of one LLaMA-1B block (4 compressions, 7 weight gradients per step, q/k/v and "
+                     "up/gate share their compressed input), N=32768 k=r=128 bf16; roofline time 311 us per step")
+
+
+def run_block(args):
+    b = measure_block(args.steps if args.steps != 500 else 50, max(min(args.warmup, 5), 1))
     out = {
-        "metric": "PRAC compress+weight-grad tokens/s at LLaMA-1B shape",
-        "value": N / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
-        "data": "synthetic",
-        "config": {"workload": f"{BLOCK_WORKLOAD}: the 7 linear layers of one LLaMA-1B block, N={N} k={k} r={r} bf16, dW bf16, "
-                               f"q/k/v and up/gate share their compressed input (4 compressions, 7 weight gradients per "
-                               f"step), 4 bases refreshed every {refresh_every} steps ({fits[0]} refits in the timed region), "
-                               f"{n_sets} rotating input sets"},
-        "roofline": {"kernel": "whole step", "bound": "hbm", "achieved": by / (ms_per_step * 1e-3) / 1e9,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": by / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": None},
-        "cpu_baseline": None,
-        "layers_us": layers_us,
+        "metric": METRIC, "value": b["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": b["steps"],
+        "warmup": args.warmup, "ms_per_step": b["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{BLOCK_WORKLOAD}: {b['what']}; {b['refits']} refits in the timed region, "
+                               f"{b['n_sets']} rotating input sets"},
+        "roofline": {"kernel": "whole step", "bound": "hbm", "achieved": b["hbm_gbs"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": b["hbm_frac"], "traffic": None},
+        "cpu_baseline": None, "layers_us": b["layers_us"],
     }
     print(json.dumps(out))
+
+
+# ------------------------------------------------------------- estimator ablations on the GPU path
+ABLATION_CASES = [
+    # name, k, r, factor on the scaling factor (d - k) / r
+    ("prac_scale_1.0", 8, 8, 1.0), ("prac_scale_0.5", 8, 8, 0.5), ("prac_scale_0.2", 8, 8, 0.2),
+    ("prac_scale_1.2", 8, 8, 1.2), ("rac_random_only", 0, 16, 1.0), ("pac_principal_only", 16, 0, 1.0),
+]
+
+
+def estimator_ablation(ctx, draws: int = 2000, N: int = 48, d: int = 96, seed: int = 91):
+    """Bias and variance of the reconstruction X~ as the library computes it (fit of the random block ->
+    compress -> reconstruct, fp32 data, all through the C ABI), over `draws` redraws of Q2 around a fixed Q1,
+    against what the paper proves: E[X~] = X Q1 Q1^T + f X (I - Q1 Q1^T) for a scaling factor f (d-k)/r
+    (Theorem 1 at f = 1; the scale ablation of the appendix otherwise), E||X~ - E X~||^2 =
+    f^2 ((d-k)/r - 1) ||X (I - Q1 Q1^T)||^2 (the equality inside the proof of Theorem 2), RAC as k = 0 and PAC
+    as r = 0 (biased by the tail energy, no variance; Section 4.2).  Shrunk shape: the statistics need thousands
+    of draws.  Returns one dict per case; z_* are distances in standard errors of the Monte-Carlo estimate."""
+    import numpy as np
+    import torch
+
+    import synth_inputs as si
+    from paper_2602_23111_amd.prac import PRAC_REFRESH_RANDOM
+
+    dev = "cuda:0"
+    X64, _ = si.activation(N, d, 0.8, seed=seed)
+    Xt = si.round_to(X64, "f32")
+    X = si.as_f64(Xt)
+    Xd = Xt.to(dev)
+    sv = np.linalg.svd(X, compute_uv=False)
+    out = []
+    for name, k, r, f in ABLATION_CASES:
+        P, _, s = ctx.fit_basis(Xd, k, r, seed=77, draw=0, pack=False)
+        n_draw = draws if r > 0 else 1
+        mean = torch.zeros((N, d), dtype=torch.float64, device=dev)
+        sum2 = torch.zeros((N, d), dtype=torch.float64, device=dev)
+        dev2 = torch.zeros(n_draw, dtype=torch.float64, device=dev)    # ||X~_t - predicted mean||^2 per draw
+        Q1 = si.as_f64(P)[:, :k]
+        tail = X - X @ Q1 @ Q1.T
+        tail2 = float(np.sum(tail ** 2))
+        pred_mean = X - (1.0 - (f if r > 0 else 0.0)) * tail
+        pm = torch.from_numpy(pred_mean).to(dev)
+        for t in range(n_draw):
+            if r > 0:
+                ctx.fit_basis(None, k, r, seed=77, draw=t + 1, refresh=PRAC_REFRESH_RANDOM, P=P, d=d, pack=False)
+            Xh = ctx.reconstruct(ctx.compress(Xd, P), P, k, r, f * s).double()
+            mean += Xh
+            sum2 += Xh * Xh
+            dev2[t] = ((Xh - pm) ** 2).sum()
+        ctx.sync_status()
+        mean = (mean / n_draw).cpu().numpy()
+        pred_bias = float(np.linalg.norm(pred_mean - X))
+        pred_var = (f * f * (s - 1.0) * tail2) if r > 0 else 0.0
+        rec = dict(case=name, k=k, r=r, scale=f * s, draws=n_draw,
+                   bias_measured=float(np.linalg.norm(mean - X)), bias_predicted=pred_bias,
+                   variance_predicted=pred_var)
+        if r > 0:
+            # E||X~ - E X~||^2 from the per-element sample variances (unbiased), and from the spread around the
+            # predicted mean with its standard error over draws
+            rec["variance_measured"] = float(((sum2 / n_draw).cpu().numpy() - mean ** 2).sum() * n_draw / (n_draw - 1))
+            e2 = dev2.cpu().numpy()
+            rec["z_mean"] = float(np.linalg.norm(mean - pred_mean) / np.sqrt(pred_var / n_draw))
+            rec["z_variance"] = float(abs(e2.mean() - pred_var) / (np.std(e2, ddof=1) / np.sqrt(n_draw)))
+        else:
+            # PAC: deterministic; its bias is the tail energy beyond the k-th singular value (Section 4.2)
+            rec["variance_measured"] = 0.0
+            rec["bias_predicted_from_spectrum"] = float(np.sqrt(np.sum(sv[k:] ** 2)))
+            rec["mean_error"] = float(np.linalg.norm(mean - pred_mean))
+        out.append(rec)
+    return out
+
+
+def run_ablation(args):
+    import torch
+
+    from paper_2602_23111_amd.prac import Prac
+
+    torch.cuda.set_device(0)
+    ctx = Prac(0)
+    t0 = time.perf_counter()
+    cases = estimator_ablation(ctx)
     ctx.close()
+    print(json.dumps({"workload": ABLATION_WORKLOAD,
+                      "what": "bias ||E[X~] - X||_F and variance E||X~ - E X~||_F^2 of the library's reconstruction over redraws "
+                              "of the random block (fp32, N=48, d=96), against the closed forms of Theorems 1 and 2",
+                      "seconds": time.perf_counter() - t0, "cases": cases}))
 
 
+# --------------------------------------------------------------------------------------- headline
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--cpu-sample", type=int, default=1, help="0: skip the oracle's timed run on the host")
-    ap.add_argument("--workload", default=WORKLOAD["name"], choices=[WORKLOAD["name"], BLOCK_WORKLOAD] + sorted(OTHER_WORKLOADS),
+    ap.add_argument("--workload", default=WORKLOAD["name"],
+                    choices=[WORKLOAD["name"], BLOCK_WORKLOAD, ABLATION_WORKLOAD] + sorted(OTHER_WORKLOADS),
                     help="layer shape to run (default: the headline attention projection of the LLaMA-1B configuration)")
     ap.add_argument("--others", type=int, default=1,
-                    help="0: skip timing the fused forward and the reconstruction (outside the timed region)")
+                    help="0: skip timing the fused forward, the reconstruction and the LLaMA-1B block (outside the timed region)")
+    ap.add_argument("--graph", type=int, default=0,
+                    help="1: the compress + weight-gradient launches of a step are replayed from a HIP graph (one per input "
+                         "set); 0 (default): launched one by one, which is the faster of the two here (106 against 113 us "
+                         "per step at the headline shape)")
+    ap.add_argument("--refresh-every", type=int, default=0, help="override the refresh interval (0: the workload's, 500)")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="after the timed region, also run three plain device copies of this many MB "
                          "(a kernel of known traffic, for scaling rocprofv3 --pmc byte counters)")
@@ -239,25 +349,41 @@ def main():
     import torch
 
     import synth_inputs as si
-    from paper_2602_23111_amd.prac import C_PACKED, KERNEL_KINDS, Prac
+    from paper_2602_23111_amd.prac import C_PACKED, KERNEL_KINDS, TUNE_PROFILE_STRIDE, Prac, call_shape
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     if args.workload == BLOCK_WORKLOAD:
         return run_block(args)
-    w = WORKLOAD if args.workload == WORKLOAD["name"] else OTHER_WORKLOADS[args.workload]
-    if w is not WORKLOAD:
+    if args.workload == ABLATION_WORKLOAD:
+        return run_ablation(args)
+    w = dict(WORKLOAD if args.workload == WORKLOAD["name"] else OTHER_WORKLOADS[args.workload])
+    headline = w["name"] == WORKLOAD["name"]
+    if not headline:
         args.others = 0          # the extra entry points are timed at the headline shape only
         args.cpu_sample = 0      # ... and so is the oracle on the host (an eigendecomposition of d x d)
         if w["refresh_every"] == 1 and args.steps == 500:
             args.steps = 50      # a refit per step: keep the default run short
+    if args.refresh_every > 0:
+        w["refresh_every"] = args.refresh_every
     N, d, m, k, r = w["N"], w["d"], w["m"], w["k"], w["r"]
+    T = w["refresh_every"]
     ld8 = lambda n: (n + 7) // 8 * 8
     c = k + r
     dev = torch.device("cuda:0")
     torch.cuda.set_device(0)
     ctx = Prac(0)
+    main_stream = torch.cuda.current_stream()
+
+    # scratch of every call this run issues, reserved once: no call below allocates or waits for the device
+    shapes = [call_shape("fit_basis", N, d, k, r, row_stride=w["row_stride"]),
+              call_shape("fit_basis", N, d, k, r, warm_start=True, iters=w["warm_iters"], oversample=w["warm_oversample"],
+                         row_stride=w["row_stride"]),
+              call_shape("compress", N, d, k, r), call_shape("weight_grad", N, d, k, r, m=[m]),
+              call_shape("weight_grad", N, d, k, r, m=[m, m, m]), call_shape("fused_fwd", N, d, k, r, m=[m]),
+              call_shape("reconstruct", N, d, k, r)]
+    ctx.reserve_workspace(max(ctx.workspace_bytes(s) for s in shapes))
 
     Xs, dYs, Cs = [], [], []
     for i in range(w["n_sets"]):
@@ -268,40 +394,47 @@ def main():
         Cs.append(torch.empty(ctx.compressed_bytes(N, c) // 2, dtype=torch.bfloat16, device=dev))
     dW = torch.empty((d, ld8(m)), dtype=torch.bfloat16, device=dev)[:, :m]
     P = torch.zeros((d, c), dtype=torch.float32, device=dev)
-    state = dict(lp=None, scale=0.0, fits=0)
+    lp = torch.zeros(ctx.basis_lp_bytes(d, c), dtype=torch.uint8, device=dev)     # one buffer for the run (the graphs hold its address)
+    state = dict(scale=float(d - k) / r if r else 0.0, fitted=False, fits=0)
+
+    def refresh(t: int):
+        # every refresh after the first starts the subspace iteration from the previous Q1
+        warm = state["fitted"]
+        _, _, state["scale"] = ctx.fit_basis(Xs[t % w["n_sets"]], k, r, seed=1234, draw=t // T, P=P, P_lp=lp,
+                                             warm_start=warm, iters=w["warm_iters"] if warm else 0,
+                                             oversample=w["warm_oversample"] if warm else 0, row_stride=w["row_stride"])
+        state["fitted"] = True
+        state["fits"] += 1
+
+    def launches(i: int):
+        ctx.compress(Xs[i], P, P_lp=lp, out=Cs[i], layout=C_PACKED)
+        ctx.weight_grad(Cs[i], dYs[i], P, k, r, state["scale"], P_lp=lp, out=dW, layout=C_PACKED)
 
     def step(t: int):
-        i = t % w["n_sets"]
-        if t % w["refresh_every"] == 0:
-            # every refresh after the first starts the subspace iteration from the previous Q1
-            warm = state["lp"] is not None
-            _, state["lp"], state["scale"] = ctx.fit_basis(Xs[i], k, r, seed=1234, draw=t // w["refresh_every"], P=P,
-                                                           warm_start=warm, iters=w["warm_iters"] if warm else 0,
-                                                           oversample=w["warm_oversample"] if warm else 0,
-                                                           row_stride=w["row_stride"])
-            state["fits"] += 1
-        ctx.compress(Xs[i], P, P_lp=state["lp"], out=Cs[i], layout=C_PACKED)
-        ctx.weight_grad(Cs[i], dYs[i], P, k, r, state["scale"], P_lp=state["lp"], out=dW, layout=C_PACKED)
+        if t % T == 0:
+            refresh(t)
+        launches(t % w["n_sets"])
 
-    # warm-up (includes the first fit so that scratch is allocated), then find the dominant kernel
-    for t in range(max(args.warmup, 1)):
+    # warm-up: steps 0 .. W-1 (step 0 fits the basis from scratch), then find the dominant kernel
+    W = max(args.warmup, 1)
+    for t in range(W):
         step(t)
     torch.cuda.synchronize()
     per_kernel_us = {}
-    for kind in ("compress", "ct_dy", "t_reduce", "p_t"):
+    for kind in ("compress", "weight_grad", "ct_dy", "t_reduce", "p_t"):
         ctx.profile_select(KERNEL_KINDS[kind])
-        for t in range(1, 9):
-            step(t)
+        for i in range(8):
+            launches(i % w["n_sets"])
         ms, n = ctx.profile_read()
-        per_kernel_us[kind] = 1e3 * ms / max(n, 1)
+        if n:           # kinds that saw no launch (the one-launch weight gradient unless selected) are left out
+            per_kernel_us[kind] = 1e3 * ms / n
     dominant = max(per_kernel_us, key=per_kernel_us.get)
-    ctx.profile_select(KERNEL_KINDS[dominant])
-    ctx.profile_read()
+    ctx.profile_select(0)
 
-    # fit alone, for the record (not part of `value` beyond its share of the timed steps)
+    # one refresh alone, for the record: what a step with t mod T == 0 adds
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ctx.fit_basis(Xs[0], k, r, seed=1234, draw=0, P=P, warm_start=True, iters=w["warm_iters"],
+    ctx.fit_basis(Xs[0], k, r, seed=1234, draw=0, P=P, P_lp=lp, warm_start=True, iters=w["warm_iters"],
                   oversample=w["warm_oversample"], row_stride=w["row_stride"])
     torch.cuda.synchronize()
     fit_ms = 1e3 * (time.perf_counter() - t0)
@@ -312,9 +445,9 @@ def main():
     if args.others:
         g = torch.Generator(device=dev)
         g.manual_seed(3200)
-        W = (torch.randn((m, d), generator=g, device=dev) * 0.02).to(torch.bfloat16)
+        Wt = (torch.randn((m, d), generator=g, device=dev) * 0.02).to(torch.bfloat16)
         Y = torch.empty((N, m), dtype=torch.bfloat16, device=dev)
-        for kind, fn in (("fused_fwd", lambda i: ctx.compress_fused_fwd(Xs[i], W, P, w_layout=1, P_lp=state["lp"], Y=Y,
+        for kind, fn in (("fused_fwd", lambda i: ctx.compress_fused_fwd(Xs[i], Wt, P, w_layout=1, P_lp=lp, Y=Y,
                                                                         out=Cs[i], layout=C_PACKED)),
                          ("reconstruct", lambda i: ctx.reconstruct(Cs[i], P, k, r, state["scale"], N=N, out=Y,
                                                                    layout=C_PACKED))):
@@ -326,15 +459,15 @@ def main():
             other_us[kind] = 1e3 * ms / max(n, 1)
         # for scale: the vendor library's forward alone (torch.matmul, hipBLASLt); unfused = this + compress
         for _ in range(3):
-            torch.matmul(Xs[0], W.t(), out=Y)
+            torch.matmul(Xs[0], Wt.t(), out=Y)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for t in range(8):
-            torch.matmul(Xs[t % w["n_sets"]], W.t(), out=Y)
+            torch.matmul(Xs[t % w["n_sets"]], Wt.t(), out=Y)
         e1.record()
         torch.cuda.synchronize()
         other_us["fwd_vendor_gemm"] = 1e3 * e0.elapsed_time(e1) / 8
-        del W, Y
+        del Wt, Y
         # query / key / value gradients from the one compressed activation they share (Section 5.1):
         # one call for the three against three calls, wall clock over 8 repetitions each
         dY3 = [dYs[0], dYs[1], dYs[2]]
@@ -351,30 +484,77 @@ def main():
             return 1e6 * (time.perf_counter() - t0) / reps
 
         other_us["wgrad_qkv_shared"] = wall(lambda: ctx.weight_grad_shared(
-            Cs[0], dY3, P, k, r, state["scale"], P_lp=state["lp"], outs=dW3, layout=C_PACKED))
+            Cs[0], dY3, P, k, r, state["scale"], P_lp=lp, outs=dW3, layout=C_PACKED))
         other_us["wgrad_qkv_three_calls"] = wall(lambda: [ctx.weight_grad(
-            Cs[0], y, P, k, r, state["scale"], P_lp=state["lp"], out=o, layout=C_PACKED) for y, o in zip(dY3, dW3)])
+            Cs[0], y, P, k, r, state["scale"], P_lp=lp, out=o, layout=C_PACKED) for y, o in zip(dY3, dW3)])
         del dW3
-        ctx.profile_select(KERNEL_KINDS[dominant])
-        ctx.profile_read()
         for i in range(w["n_sets"]):  # C was overwritten by the fused launches with the same values
-            ctx.compress(Xs[i], P, P_lp=state["lp"], out=Cs[i], layout=C_PACKED)
+            ctx.compress(Xs[i], P, P_lp=lp, out=Cs[i], layout=C_PACKED)
+    torch.cuda.synchronize()
 
+    # HIP graphs of a step's launches, one per input set (the refresh, when a step has one, runs before
+    # the replay as ordinary launches).  Nothing inside the captured calls allocates, waits or clears memory.
+    graphs, graph_note = None, "launches issued one by one"
+    if args.graph:
+        try:
+            cap = torch.cuda.Stream()
+            graphs = []
+            for i in range(w["n_sets"]):
+                gph = torch.cuda.CUDAGraph()
+                ctx.set_stream(cap)
+                try:
+                    with torch.cuda.graph(gph, stream=cap):
+                        launches(i)
+                finally:
+                    ctx.set_stream(main_stream)
+                graphs.append(gph)
+            # every graph against its eager launches before it is trusted with the timed region
+            for i in range(w["n_sets"]):
+                launches(i)
+                want_c, want_w = Cs[i].clone(), dW.clone()
+                Cs[i].zero_()
+                dW.zero_()
+                graphs[i].replay()
+                torch.cuda.synchronize()
+                if not (torch.equal(Cs[i], want_c) and torch.equal(dW, want_w)):
+                    raise RuntimeError("graph replay differs from the eager launches")
+            graph_note = "compress + weight-gradient launches of a step replayed from a HIP graph per input set"
+        except Exception as e:  # a run without graphs is still a valid measurement
+            graphs, graph_note = None, f"launches issued one by one (graph capture failed: {type(e).__name__}: {e})"
+            ctx.set_stream(main_stream)
+            torch.cuda.synchronize()
+
+    def timed_step(t: int):
+        if t % T == 0:
+            refresh(t)
+        if graphs is not None:
+            graphs[t % w["n_sets"]].replay()
+        else:
+            launches(t % w["n_sets"])
+
+    for i in range(2 * w["n_sets"]):      # (re-)warm the path the timed region takes
+        graphs[i % w["n_sets"]].replay() if graphs is not None else launches(i % w["n_sets"])
     state["fits"] = 0
-    # an event pair costs about 4 us of stream time: every 8th launch of the dominant kernel carries one
-    sample_every = 8 if args.steps >= 64 else 1
-    ctx.set_tuning(2, sample_every)
-    ctx.profile_select(KERNEL_KINDS[dominant])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for t in range(args.steps):
-        step(t)
+    for t in range(W, W + args.steps):          # the step counter runs on from the warm-up
+        timed_step(t)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    fits_in_region = state["fits"]
+    ctx.sync_status()
+
+    # the dominant kernel over the same steps again, launched one by one so that every launch can carry a
+    # HIP event pair on the ctx stream (events cannot be attached to the nodes of a replayed graph)
+    ctx.set_tuning(TUNE_PROFILE_STRIDE, 1)
+    ctx.profile_select(KERNEL_KINDS[dominant])
+    ctx.profile_read()
+    n_ev = min(args.steps, 200)
+    for t in range(W, W + n_ev):
+        launches(t % w["n_sets"])
     dom_each = ctx.profile_read_each()
-    ctx.set_tuning(2, 1)
-    dom_ms, dom_n = sum(dom_each), len(dom_each)
     ctx.profile_select(0)
+    dom_ms, dom_n = sum(dom_each), len(dom_each)
     ctx.sync_status()
 
     ms_per_step = 1e3 * elapsed / args.steps
@@ -390,8 +570,10 @@ def main():
                     frac=ach_gbs / HBM_PEAK_GBS if hbm_bound else ach_tf / MFMA_BF16_PEAK_TFLOPS,
                     traffic=read_traffic(dominant, w["name"]),
                     avg_us=dom_us, median_us=1e3 * sorted(dom_each)[len(dom_each) // 2] if dom_each else None,
-                    min_us=1e3 * min(dom_each) if dom_each else None, launches=dom_n, sampled_every=sample_every, hbm_gbs=ach_gbs, hbm_frac=ach_gbs / HBM_PEAK_GBS,
-                    mfma_tflops=ach_tf, mfma_frac=ach_tf / MFMA_BF16_PEAK_TFLOPS)
+                    min_us=1e3 * min(dom_each) if dom_each else None, launches=dom_n,
+                    timed_in=f"the same steps launched one by one right after the timed region, every launch of the kernel "
+                             f"between a HIP event pair on the ctx stream ({n_ev} steps)",
+                    hbm_gbs=ach_gbs, hbm_frac=ach_gbs / HBM_PEAK_GBS, mfma_tflops=ach_tf, mfma_frac=ach_tf / MFMA_BF16_PEAK_TFLOPS)
 
     cpu = None
     if args.calib_copy_mb > 0:
@@ -401,10 +583,19 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
     if args.cpu_sample > 0:
-        cpu = cpu_baseline(Xs[0].cpu(), dYs[0].cpu(), k, r, w["refresh_every"])
+        cpu = cpu_baseline(Xs[0].cpu(), dYs[0].cpu(), k, r, T)
+    ctx.close()
+    block = None
+    if args.others:
+        del Xs, dYs, Cs, graphs
+        torch.cuda.empty_cache()
+        block_b = measure_block(steps=10)
+        block = {kk: block_b[kk] for kk in ("ms_per_step", "tokens_per_s", "hbm_frac", "steps", "refits", "what")}
 
+    # a refresh per T steps: what the measured step time becomes when the timed region holds none
+    ms_amortised = ms_per_step + (fit_ms / T if fits_in_region == 0 else 0.0)
     out = {
-        "metric": "PRAC compress+weight-grad tokens/s at LLaMA-1B shape",
+        "metric": METRIC,
         "value": N / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -417,17 +608,21 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{w['name']}: N={N} d={d} m={m} k={k} r={r} bf16, dW bf16, "
-                               f"basis refresh every {w['refresh_every']} steps ({state['fits']} in the timed region, warm-started"
+                               f"basis refresh every {T} steps, step counter running on from the warm-up "
+                               f"(steps {W}..{W + args.steps - 1}: {fits_in_region} refresh(es) in the timed region, warm-started"
                                + (f", Gram over every {w['row_stride']}th token" if w["row_stride"] > 1 else "") + "), "
-                               f"{w['n_sets']} rotating input sets"},
+                               f"{w['n_sets']} rotating input sets; {graph_note}"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels_us": per_kernel_us,
+        "refit": {"ms": fit_ms, "in_timed_region": fits_in_region, "every": T, "amortised_us_per_step": 1e3 * fit_ms / T,
+                  "kind": REFIT_LABEL},
+        "value_with_amortised_refit": N / (ms_amortised * 1e-3),
         "other_entry_points_us": other_us,
+        "llama1b_block": block,
         "fit_basis_ms": fit_ms,
     }
     print(json.dumps(out))
-    ctx.close()
 
 
 if __name__ == "__main__":

@@ -146,7 +146,9 @@ enum {
   PRAC_KERNEL_P_T = 4,        /* dW = P T */
   PRAC_KERNEL_GRAM = 5,       /* X^T X partial sums */
   PRAC_KERNEL_FUSED_FWD = 6,  /* [Y | C] = X [W | P] */
-  PRAC_KERNEL_RECONSTRUCT = 7 /* Xh = C Ps^T */
+  PRAC_KERNEL_RECONSTRUCT = 7, /* Xh = C Ps^T */
+  PRAC_KERNEL_WEIGHT_GRAD = 8  /* the whole weight gradient in one launch (PRAC_TUNE_WGRAD_ONE_LAUNCH): partial
+                                  sums of C^T dY, their sum T and dW = P T (kinds 2 - 4 then see no launch) */
 };
 int prac_profile_select(prac_ctx* ctx, int kind);
 int prac_profile_read(prac_ctx* ctx, double* total_ms, int64_t* launches);
@@ -157,8 +159,12 @@ int prac_profile_read_each(prac_ctx* ctx, float* each_ms, int64_t cap, int64_t* 
  * the C^T dY reduction is split into (1..64; 0 restores the built-in choice).
  * PRAC_TUNE_PROFILE_STRIDE = n (1..1024; 0 means 1): only every n-th launch of the selected
  * kernel kind, counted from the selection, carries the event pair (an event pair costs a few
- * microseconds of stream time, which a benchmark loop may not want on every step). */
-enum { PRAC_TUNE_CTDY_SPLITS = 1, PRAC_TUNE_PROFILE_STRIDE = 2 };
+ * microseconds of stream time, which a benchmark loop may not want on every step).
+ * PRAC_TUNE_WGRAD_ONE_LAUNCH = 1: the bf16 weight gradient runs as one launch (the workgroups of a
+ * column tile of T meet inside the kernel to sum their partial sums and to form dW = P T) instead of
+ * three (partial sums, their reduction, P T); 0 restores the default.  Results are bit-identical; the
+ * three launches are the faster of the two on an MI355X at every benchmarked shape. */
+enum { PRAC_TUNE_CTDY_SPLITS = 1, PRAC_TUNE_PROFILE_STRIDE = 2, PRAC_TUNE_WGRAD_ONE_LAUNCH = 3 };
 int prac_set_tuning(prac_ctx* ctx, int key, int value);
 
 /* ---- Gaussian draw (Eq. (S_o): S_ij ~ N(0,1) i.i.d.) -------------------- */

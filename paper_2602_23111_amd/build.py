@@ -27,7 +27,7 @@ NOISE = "is not a recognized feature for this target"
 def _flags() -> list[str]:
     return ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC] + os.environ.get("PRAC_EXTRA_HIPCC_FLAGS", "").split()
 
 
 def _run(cmd: list[str]) -> str:

@@ -256,14 +256,19 @@ int prac_create(prac_ctx** out, int device, void* hip_stream) {
   c->ev_start = nullptr;
   c->ev_stop = nullptr;
   c->tune_splits = 0;
+  c->tune_one_launch = 0;
+  c->d_sync = nullptr;
   hipDeviceProp_t prop;
   c->n_cu = (hipGetDeviceProperties(&prop, device) == hipSuccess) ? prop.multiProcessorCount : 256;
-  if (hipMalloc(reinterpret_cast<void**>(&c->d_flag), 256) != hipSuccess) {
+  // failure flag (256 bytes) followed by the counters of the one-launch weight gradient
+  const size_t flag_bytes = 256 + PRAC_SYNC_BYTES;
+  if (hipMalloc(reinterpret_cast<void**>(&c->d_flag), flag_bytes) != hipSuccess) {
     (void)hipGetLastError();
     delete c;
     return PRAC_EHIP;
   }
-  if (hipMemset(c->d_flag, 0, 256) != hipSuccess) {
+  c->d_sync = c->d_flag + 64;
+  if (hipMemset(c->d_flag, 0, flag_bytes) != hipSuccess) {
     (void)hipGetLastError();
     (void)hipFree(c->d_flag);
     delete c;
@@ -313,6 +318,12 @@ int prac_sync_status(prac_ctx* ctx) {
   PRAC_HIP_TRY(ctx, hipMemcpy(&flag, ctx->d_flag, sizeof(int), hipMemcpyDeviceToHost));
   if (flag != 0) {
     PRAC_HIP_TRY(ctx, hipMemset(ctx->d_flag, 0, sizeof(int)));
+    if (flag == 2) {
+      // a wait between workgroups of the one-launch weight gradient gave up: its counters may be left
+      // non-zero, clear them for the next launch
+      PRAC_HIP_TRY(ctx, hipMemset(ctx->d_sync, 0, PRAC_SYNC_BYTES));
+      return PRAC_EHIP;
+    }
     return PRAC_ENUMERIC;
   }
   return PRAC_OK;
@@ -321,7 +332,7 @@ int prac_sync_status(prac_ctx* ctx) {
 int prac_last_hip_error(const prac_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
 
 int prac_profile_select(prac_ctx* ctx, int kind) {
-  if (kind < PRAC_KERNEL_NONE || kind > PRAC_KERNEL_RECONSTRUCT) return PRAC_EINVAL;
+  if (kind < PRAC_KERNEL_NONE || kind > PRAC_KERNEL_WEIGHT_GRAD) return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
   ctx->prof_kind = kind;
   ctx->prof_seen = 0;
@@ -333,6 +344,12 @@ int prac_set_tuning(prac_ctx* ctx, int key, int value) {
     if (value < 0 || value > 1024) return PRAC_EINVAL;
     if (!ctx) return PRAC_ENOCTX;
     ctx->prof_stride = value < 1 ? 1 : value;
+    return PRAC_OK;
+  }
+  if (key == PRAC_TUNE_WGRAD_ONE_LAUNCH) {
+    if (value != 0 && value != 1) return PRAC_EINVAL;
+    if (!ctx) return PRAC_ENOCTX;
+    ctx->tune_one_launch = value;
     return PRAC_OK;
   }
   if (key != PRAC_TUNE_CTDY_SPLITS || value < 0 || value > 64) return PRAC_EINVAL;
@@ -643,21 +660,26 @@ int weight_grad_generic(prac_ctx* ctx, char* ws, const void* C, const void* dY, 
 // C^T dY_h, then each output gets its slab reduction and its dW_h = P T_h.
 struct WgradPlan {
   int splits;
+  bool fused;  // one launch (see launch_wgrad_fused) instead of three
   int nmb[PRAC_CTDY_MAX_OUT];
   size_t o_part[PRAC_CTDY_MAX_OUT], o_t[PRAC_CTDY_MAX_OUT], o_lp, o_cpk, bytes;
 };
-WgradPlan plan_wgrad_fast(int n_cu, int tune_splits, int64_t N, int64_t d, int c, int n_out, const int64_t* m,
-                          bool packed, bool has_lp) {
+WgradPlan plan_wgrad_fast(int n_cu, int tune_splits, bool unfused, int64_t N, int64_t d, int c, int n_out,
+                          const int64_t* m, bool packed, bool has_lp) {
   WgradPlan q{};
   const LpLayout l = lp_layout(d, c);
-  int tiles = 0;
-  for (int h = 0; h < n_out; ++h) tiles += ((c + 255) / 256) * (int)((m[h] + 127) / 128);
-  // one workgroup per CU at most: a second, partly filled round would cost a whole workgroup time
-  int splits = n_cu / tiles;
-  if (splits > N / 256) splits = (int)(N / 256);
-  if (splits < 1) splits = 1;
-  if (splits > 64) splits = 64;
-  if (tune_splits > 0) splits = tune_splits;
+  int splits = unfused ? 0 : wgrad_fused_splits(n_cu, c, n_out, m, N, tune_splits);
+  q.fused = splits > 0;
+  if (!q.fused) {
+    int tiles = 0;
+    for (int h = 0; h < n_out; ++h) tiles += ((c + 255) / 256) * (int)((m[h] + 127) / 128);
+    // one workgroup per CU at most: a second, partly filled round would cost a whole workgroup time
+    splits = n_cu / tiles;
+    if (splits > N / 256) splits = (int)(N / 256);
+    if (splits < 1) splits = 1;
+    if (splits > 64) splits = 64;
+    if (tune_splits > 0) splits = tune_splits;
+  }
   q.splits = splits;
   WsPlan plan;
   for (int h = 0; h < n_out; ++h) {
@@ -671,7 +693,7 @@ WgradPlan plan_wgrad_fast(int n_cu, int tune_splits, int64_t N, int64_t d, int c
   return q;
 }
 
-int weight_grad_fast(prac_ctx* ctx, char* ws, const WgradPlan& q, const void* C, int64_t N, int64_t ldc, bool packed,
+int weight_grad_fast(prac_ctx* ctx, char* ws, int* cnt, const WgradPlan& q, const void* C, int64_t N, int64_t ldc, bool packed,
                      int n_out, const void* const* dY, const int64_t* m, const int64_t* lddy, const float* P,
                      const void* P_lp, int64_t d, int64_t ldp, int k, int r, float scale, void* const* dW,
                      prac_dtype odt, const int64_t* lddw, float beta) {
@@ -699,13 +721,20 @@ int weight_grad_fast(prac_ctx* ctx, char* ws, const WgradPlan& q, const void* C,
     part[h] = reinterpret_cast<float*>(ws + q.o_part[h]);
     mi[h] = (int)m[h];
   }
+  bf16_t* Tf[PRAC_CTDY_MAX_OUT];
+  for (int h = 0; h < n_out; ++h) Tf[h] = reinterpret_cast<bf16_t*>(ws + q.o_t[h]);
+  if (q.fused) {
+    // one launch: slabs, their sum T (bf16, fragment order, random rows scaled) and dW_h = P T_h
+    ProfScope ps(ctx, PRAC_KERNEL_WEIGHT_GRAD);
+    return launch_wgrad_fused(ctx, Cpk, c, (int)N, n_out, dYp, lddy, mi, part, splits, k, scale, l.nckb, q.nmb, Tf,
+                              reinterpret_cast<const bf16_t*>(lp + l.off_pa), (int)d, dW, lddw, odt == PRAC_BF16, beta,
+                              cnt);
+  }
   {  // T_h = C^T dY_h as `splits` partial slabs over the token range
     ProfScope ps(ctx, PRAC_KERNEL_CT_DY);
     rc = launch_ctdy_ws(ctx, Cpk, c, (int)N, n_out, dYp, lddy, mi, part, splits);
   }
   if (rc) return rc;
-  bf16_t* Tf[PRAC_CTDY_MAX_OUT];
-  for (int h = 0; h < n_out; ++h) Tf[h] = reinterpret_cast<bf16_t*>(ws + q.o_t[h]);
   {  // T_h in fragment order (bf16): slabs summed, random rows weighted by the scaling factor
     ProfScope ps(ctx, PRAC_KERNEL_T_REDUCE);
     rc = launch_reduce_to_tfrag(ctx, n_out, part, splits, c, mi, k, scale, l.nckb, q.nmb, Tf);
@@ -762,18 +791,21 @@ int prac_weight_grad_static(prac_ctx* ctx, const void* C, const void* dY, prac_d
   WgradPlan q{};
   size_t need;
   if (fast) {
-    q = plan_wgrad_fast(ctx->n_cu, ctx->tune_splits, N, d, k + r, 1, &m, packed, P_lp != nullptr);
+    q = plan_wgrad_fast(ctx->n_cu, ctx->tune_splits, ctx->tune_one_launch == 0, N, d, k + r, 1, &m, packed, P_lp != nullptr);
     need = q.bytes;
   } else {
     need = plan_wgrad_generic(N, d, m, k + r, packed, odt).bytes;
   }
-  if (need > PRAC_STATIC_SCRATCH_BYTES) return PRAC_ETOOBIG;
+  // the first 128 KB of the block are the counters of the one-launch weight gradient (zero when the code
+  // object is loaded, and every launch leaves them zero)
+  constexpr size_t kSync = PRAC_SYNC_BYTES;
+  if (need > PRAC_STATIC_SCRATCH_BYTES - kSync) return PRAC_ETOOBIG;
   // no event pairs here (creating one allocates): this call is not profiled
   const int prof = ctx->prof_kind;
   ctx->prof_kind = PRAC_KERNEL_NONE;
-  char* ws = ctx->static_scratch;
+  char* ws = ctx->static_scratch + kSync;
   if (fast)
-    rc = weight_grad_fast(ctx, ws, q, C, N, ldc, packed, 1, &dY, &m, &lddy, P, P_lp, d, ldp, k, r, scale, &dW, odt, &lddw,
+    rc = weight_grad_fast(ctx, ws, reinterpret_cast<int*>(ctx->static_scratch), q, C, N, ldc, packed, 1, &dY, &m, &lddy, P, P_lp, d, ldp, k, r, scale, &dW, odt, &lddw,
                           beta);
   else
     rc = weight_grad_generic(ctx, ws, C, dY, dt, N, m, ldc, packed, lddy, P, d, ldp, k, r, scale, dW, odt, lddw, beta);
@@ -791,10 +823,11 @@ int prac_weight_grad_shared(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t
   const bool packed = c_layout == PRAC_C_PACKED;
   if (packed && (dt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
   if (wgrad_is_fast(dt, N, n_out, dY, lddy)) {
-    const WgradPlan q = plan_wgrad_fast(ctx->n_cu, ctx->tune_splits, N, d, k + r, n_out, m, packed, P_lp != nullptr);
+    const WgradPlan q = plan_wgrad_fast(ctx->n_cu, ctx->tune_splits, ctx->tune_one_launch == 0, N, d, k + r, n_out, m, packed,
+                                        P_lp != nullptr);
     rc = prac_ws_reserve(ctx, q.bytes);
     if (rc) return rc;
-    return weight_grad_fast(ctx, ctx->ws, q, C, N, ldc, packed, n_out, dY, m, lddy, P, P_lp, d, ldp, k, r, scale, dW, odt,
+    return weight_grad_fast(ctx, ctx->ws, ctx->d_sync, q, C, N, ldc, packed, n_out, dY, m, lddy, P, P_lp, d, ldp, k, r, scale, dW, odt,
                             lddw, beta);
   }
   size_t need = 0;
@@ -951,7 +984,9 @@ size_t prac_workspace_bytes(const prac_ctx* ctx, const prac_call_shape* sh) {
       if (c < 1 || sh->n_out < 1 || sh->n_out > PRAC_MAX_SHARED) return bad;
       for (int h = 0; h < sh->n_out; ++h)
         if (sh->m[h] < 1 || sh->m[h] > (1 << 20)) return bad;
-      if (fast) return plan_wgrad_fast(n_cu, tune, sh->N, sh->d, c, sh->n_out, sh->m, packed, sh->have_p_lp != 0).bytes;
+      if (fast)
+        return plan_wgrad_fast(n_cu, tune, !(ctx && ctx->tune_one_launch), sh->N, sh->d, c, sh->n_out, sh->m, packed,
+                               sh->have_p_lp != 0).bytes;
       size_t need = 0;
       for (int h = 0; h < sh->n_out; ++h)
         need = std::max(need, plan_wgrad_generic(sh->N, sh->d, sh->m[h], c, packed,

@@ -24,6 +24,8 @@ struct prac_ctx {
   int last_hip;       // last hipError_t that made a call fail
   int n_cu;
   int tune_splits;    // > 0: override the token-split count of C^T dY (tuning hook)
+  int tune_one_launch;  // 1: the bf16 weight gradient as one launch instead of three (slabs, reduction, P T)
+  int* d_sync;        // PRAC_SYNC_TILES x 3 counters of the one-launch weight gradient (zero between launches)
   int prof_kind;      // kernel kind bracketed by events (0: none), see prac_profile_select
   int prof_stride;    // every prof_stride-th launch of that kind carries the event pair
   int64_t prof_seen;  // launches of that kind since the selection
@@ -132,6 +134,18 @@ int launch_pack_wfrag(prac_ctx* ctx, const bf16_t* W, int64_t ldw, int w_layout,
 #define PRAC_CTDY_MAX_OUT 4
 int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, int N, int n_out, const bf16_t* const* dY,
                    const int64_t* lddy, const int* m, float* const* slabs, int splits);
+// The whole weight gradient in one launch: partial slabs, their sum as T (bf16, fragment order, rows >= k_lo
+// scaled) and dW_h = P T_h, the workgroups of a column tile meeting through `cnt` (PRAC_SYNC_INTS_PER_TILE
+// ints per 128-column tile over all outputs, zero before and after the launch).  `splits` comes from
+// wgrad_fused_splits (0: this shape runs as three launches).
+#define PRAC_SYNC_TILES 4096
+#define PRAC_SYNC_INTS_PER_TILE 8
+#define PRAC_SYNC_BYTES ((size_t)PRAC_SYNC_TILES * PRAC_SYNC_INTS_PER_TILE * sizeof(int))
+int wgrad_fused_splits(int n_cu, int c, int n_out, const int64_t* m, int64_t N, int tune_splits);
+int launch_wgrad_fused(prac_ctx* ctx, const bf16_t* Cpk, int c, int N, int n_out, const bf16_t* const* dY,
+                       const int64_t* lddy, const int* m, float* const* slabs, int splits, int k_lo, float scale_hi,
+                       int nckb, const int* nmb, bf16_t* const* Tf, const bf16_t* Pa, int d, void* const* dW,
+                       const int64_t* lddw, bool out_bf16, float beta, int* cnt);
 int launch_pack_pfrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c, int nkb, int ncb, bf16_t* out);
 int launch_unpack_c(prac_ctx* ctx, const bf16_t* Cpk, int N, int c, bf16_t* C, int64_t ldc);
 int launch_pack_c(prac_ctx* ctx, const bf16_t* C, int64_t ldc, int N, int c, bf16_t* Cpk);

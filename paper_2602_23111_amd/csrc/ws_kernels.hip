@@ -28,6 +28,7 @@
 // paper; forward of Lemma 1): W is handed over in the fragment order of P, and the column
 // groups of Y come before those of C in the grid.  Workgroups of one row tile sit next to
 // each other on one XCD, so X comes from HBM once and from that XCD's L2 afterwards.
+#include <algorithm>
 #include <type_traits>
 
 #include "frag_utils.h"
@@ -716,7 +717,33 @@ struct CtdyWsArgs {
   int tok_per_split;   // multiple of 128
   int tiles_n;         // column tiles of 128 over all outputs
   int row_groups;      // groups of 8 column blocks (256 rows of T) over c
+  int groups_per_xcd;  // MODE > 0: column tiles per XCD
+  // ---- whole weight gradient in this launch (MODE > 0): the workgroups of one column tile sum their
+  // partial slabs into T (bf16, fragment order, random rows scaled) and form dW = P T for that tile
+  int* cnt;            // 3 counters per column tile, zero before the launch, zero again after it
+  int* fail;           // set to 2 if a wait between workgroups gave up
+  int nckb;            // 16-row k-blocks of T = ceil(c / 16)
+  int k_lo;            // rows >= k_lo of T carry scale_hi
+  float scale_hi;
+  bf16_t* Tf[PRAC_CTDY_MAX_OUT];   // [nckb][nmb_h][64][8]
+  int nmb[PRAC_CTDY_MAX_OUT];
+  const bf16_t* Pa;    // P as an A operand in fragment order [nrb][nckb][64][8]
+  int d;
+  void* dW[PRAC_CTDY_MAX_OUT];
+  int64_t lddw[PRAC_CTDY_MAX_OUT];
+  int vec_ok[PRAC_CTDY_MAX_OUT];   // dW rows allow aligned 16-byte accesses
+  float beta;
+#ifdef PRAC_WS_TIMESTAMPS
+  long long* stamps;   // development builds only: 8 wall-clock stamps per workgroup
+#endif
 };
+#ifdef PRAC_WS_TIMESTAMPS
+#define PRAC_STAMP(a, i) \
+  do { if ((a).stamps && threadIdx.x == 0) (a).stamps[(long long)blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+long long* g_ws_stamps = nullptr;
+#else
+#define PRAC_STAMP(a, i) do { } while (0)
+#endif
 
 constexpr int CW_BK = 128, CW_BN = 128;
 constexpr int CW_STAGE = 8 * 4 * 1024;  // bytes per LDS stage
@@ -769,21 +796,336 @@ __device__ __forceinline__ void frag_read4_ct(u32x4 (&f)[4], unsigned lds) {
 __device__ __forceinline__ int c_slot_tok(int h, int e) { return e < 4 ? 4 * h + e : 8 + 4 * h + (e - 4); }
 __device__ __forceinline__ int frag_slot(int j, int h) { return h * 32 + (j ^ ((j >> 3) & 1)); }
 
+
+// ---- second half of the weight gradient, inside the same launch --------------------------------
+// The `members` workgroups that hold partial sums of one 128-column tile of T meet twice: once all
+// partial slabs are written, each of them sums a share of the tile's 16-row k-blocks over the slabs
+// (in slab order, so the result does not depend on who arrives when), scales the random rows and
+// writes them as bf16 in fragment order; once all of T's tile is written, each of them forms a share
+// of the 128-row tiles of dW[:, tile] = P T[:, tile].
+//
+// The members of a tile have neighbouring slots on one XCD (workgroup i of a launch runs on XCD i mod 8),
+// so what they hand to each other stays in that XCD's L2, which is coherent for its compute units:
+// ordinary stores, a wait for their acknowledgement, a counter, ordinary loads.  That placement is
+// not promised by anything, so it is checked: at the first meeting every member adds the number of
+// the XCD it runs on (hardware register XCC_ID) and its square into the tile's counter word; all
+// members read the same final word and all are on one XCD exactly when n * sum(x^2) == (sum x)^2.  If
+// they are not, the tile takes the slow route: one thread per member writes its XCD's dirty lines back
+// (a cache-wide operation, tens of microseconds when many workgroups do it), the members meet again,
+// and the loads bypass the caches.
+//
+// The host launches at most one workgroup per compute unit of an XCD, so all members are resident and
+// the waits end; a wait that does not (a device shared with something that never finishes) gives up
+// after about a second, sets *fail and lets the workgroup run on to its exit, so the grid always drains.
+constexpr int WG_SPIN_LIMIT = 1 << 22;
+constexpr int WG_PATCH_LD = 128 + 4;            // floats per row of the 16 x 128 reduction patch
+constexpr int WG_T_BYTES = 16 * 4 * 1024;       // one chunk of T in LDS: 16 k-blocks x 4 column blocks
+constexpr int WG_STAGE_LD = 64 + 4;             // floats per row of a wave's 32 x 64 output staging tile
+constexpr int WG_SMEM = WG_T_BYTES + 8 * 32 * WG_STAGE_LD * 4 + 16;  // + the flag of the first meeting
+constexpr int WG_CNT_INTS = 8;                  // counters per column tile: [0:1] first meeting (64 bit), [2] its
+                                                // repeat on the slow route, [3] second meeting, [4] leavers
+constexpr int BUF_FLAGS = 0x00020000;  // raw buffer descriptor, 32-bit data format
+constexpr int DEV_SCOPE = 16;          // cache policy bit sc1 of the raw buffer builtins: device scope
+constexpr int HWREG_XCC_ID = 20 | (0 << 6) | (3 << 11);  // s_getreg operand: register 20, bits 3:0
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t dev_buffer(const void* base, size_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(bytes > 0xFFFFFFFFu ? 0xFFFFFFFFu : bytes),
+                                           BUF_FLAGS);
+}
+// 16 / 4 bytes through the XCD's caches (`local`) or past them
+__device__ __forceinline__ u32x4 tail_load16(__amdgpu_buffer_rsrc_t r, uint32_t off, bool local) {
+  return local ? __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0) : __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, DEV_SCOPE);
+}
+__device__ __forceinline__ float tail_load4(__amdgpu_buffer_rsrc_t r, uint32_t off, bool local) {
+  return __uint_as_float(local ? __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0)
+                               : __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, DEV_SCOPE));
+}
+
+__device__ __forceinline__ void spin_until(int* cnt, int members, int* fail) {
+  int spins = 0;
+  while (__hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < members) {
+    __builtin_amdgcn_s_sleep(2);
+    if (++spins > WG_SPIN_LIMIT) {
+      __hip_atomic_store(fail, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      break;
+    }
+  }
+}
+
+// First meeting: every member's slab is written.  Returns whether all members share one XCD.
+__device__ __forceinline__ bool group_meet_first(int* cnt, int members, int* fail, int* lds_flag) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's stores are acknowledged by L2
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int local = 1;
+    if (members > 1) {
+      unsigned long long* c64 = reinterpret_cast<unsigned long long*>(cnt);
+      const unsigned long long x = (unsigned long long)(__builtin_amdgcn_s_getreg(HWREG_XCC_ID) & 15);
+      __hip_atomic_fetch_add(c64, 1ull + (x << 16) + ((x * x) << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      unsigned long long w;
+      int spins = 0;
+      while (((w = __hip_atomic_load(c64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) & 0xFFFFull) <
+             (unsigned long long)members) {
+        __builtin_amdgcn_s_sleep(2);
+        if (++spins > WG_SPIN_LIMIT) {
+          __hip_atomic_store(fail, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          break;
+        }
+      }
+      const unsigned long long n = w & 0xFFFFull, sx = (w >> 16) & 0xFFFFull, sxx = w >> 32;
+      local = (n * sxx == sx * sx) ? 1 : 0;
+      if (!local) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // this XCD's dirty lines go to memory
+        __hip_atomic_fetch_add(cnt + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        spin_until(cnt + 2, members, fail);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      }
+    }
+    *lds_flag = local;
+  }
+  __syncthreads();
+  return *lds_flag != 0;
+}
+
+// Second meeting: every member's share of T is written.
+__device__ __forceinline__ void group_meet_second(int* cnt, int members, int* fail, bool local) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (members > 1 && threadIdx.x == 0) {
+    if (!local) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __hip_atomic_fetch_add(cnt + 3, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    spin_until(cnt + 3, members, fail);
+    if (!local) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    // the last member past this meeting leaves the counters as the next launch expects them
+    if (__hip_atomic_fetch_add(cnt + 4, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == members - 1) {
+#pragma unroll
+      for (int i = 0; i < 5; ++i) __hip_atomic_store(cnt + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+  __syncthreads();
+}
+
+template <bool OUT_BF16>
+__device__ __forceinline__ void wgrad_tail(const CtdyWsArgs& a, unsigned char* smem, int tn, int h, int n0, int member,
+                                           int members) {
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  int* cnt = a.cnt + WG_CNT_INTS * tn;
+  const int mh = a.m[h], nmb = a.nmb[h], nb0 = n0 >> 5, nckb = a.nckb;
+  const __amdgpu_buffer_rsrc_t rt = dev_buffer(a.Tf[h], (size_t)nckb * nmb * 1024);  // T_h, 1 KB per block
+
+  PRAC_STAMP(a, 1);
+  // every partial slab of this column tile is written
+  const bool local = group_meet_first(cnt, members, a.fail, reinterpret_cast<int*>(smem + WG_SMEM - 16));
+  PRAC_STAMP(a, 2);
+
+  {  // T[16 kb .. 16 kb + 15, n0 .. n0 + 127] for this member's k-blocks
+    const uint32_t slab = (uint32_t)a.c * (uint32_t)mh * 4u;  // bytes per slab (all slabs together stay below 4 GB)
+    const __amdgpu_buffer_rsrc_t rs = dev_buffer(a.slabs[h], (size_t)slab * a.splits);
+    float* patch = reinterpret_cast<float*>(smem);
+    const int row = tid >> 5, col = (tid & 31) * 4;
+    for (int kb = member; kb < nckb; kb += members) {
+      const int k = kb * 16 + row, n = n0 + col;
+      float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (k < a.c && n < mh) {
+        const uint32_t off = ((uint32_t)k * (uint32_t)mh + (uint32_t)n) * 4u;
+        if (n + 3 < mh && (mh & 3) == 0) {
+          // 16 slabs requested at once (one round trip), summed in slab order
+          for (int z0 = 0; z0 < a.splits; z0 += 16) {
+            u32x4 v[16];
+#pragma unroll
+            for (int z = 0; z < 16; ++z) v[z] = tail_load16(rs, off + (uint32_t)min(z0 + z, a.splits - 1) * slab, local);
+#pragma unroll
+            for (int z = 0; z < 16; ++z)
+              if (z0 + z < a.splits) {
+                sum.x += __uint_as_float(v[z].x); sum.y += __uint_as_float(v[z].y);
+                sum.z += __uint_as_float(v[z].z); sum.w += __uint_as_float(v[z].w);
+              }
+          }
+        } else {
+          for (int z = 0; z < a.splits; ++z) {
+            const uint32_t o = off + (uint32_t)z * slab;
+            sum.x += tail_load4(rs, o, local);
+            if (n + 1 < mh) sum.y += tail_load4(rs, o + 4, local);
+            if (n + 2 < mh) sum.z += tail_load4(rs, o + 8, local);
+            if (n + 3 < mh) sum.w += tail_load4(rs, o + 12, local);
+          }
+        }
+        const float w = k >= a.k_lo ? a.scale_hi : 1.f;
+        sum.x *= w; sum.y *= w; sum.z *= w; sum.w *= w;
+      }
+      *reinterpret_cast<float4*>(patch + row * WG_PATCH_LD + col) = sum;
+      __syncthreads();
+      if (tid < 256) {
+        const int j = lane & 31, hh = lane >> 5;
+        const float* q = patch + (8 * hh) * WG_PATCH_LD + wave * 32 + j;
+        u32x4 o;
+        o.x = pack2_hw(q[0], q[WG_PATCH_LD]);
+        o.y = pack2_hw(q[2 * WG_PATCH_LD], q[3 * WG_PATCH_LD]);
+        o.z = pack2_hw(q[4 * WG_PATCH_LD], q[5 * WG_PATCH_LD]);
+        o.w = pack2_hw(q[6 * WG_PATCH_LD], q[7 * WG_PATCH_LD]);
+        __builtin_amdgcn_raw_buffer_store_b128(o, rt, (uint32_t)(((kb * nmb + nb0 + wave) * 64 + lane) * 16), 0, 0);
+      }
+      __syncthreads();
+    }
+  }
+
+  // the P fragments of this member's first dW tile do not depend on T: requested before the meeting
+  const int tiles_m = (a.d + 127) / 128;
+  const int wr = wave >> 1, wc = wave & 1;
+  const u32x4* __restrict__ Pa = reinterpret_cast<const u32x4*>(a.Pa);
+  u32x4 fa0[16];
+  {
+    const int64_t rb = (int64_t)min(member, tiles_m - 1) * 4 + wr;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) fa0[q] = Pa[(rb * nckb + min(q, nckb - 1)) * 64 + lane];
+  }
+  PRAC_STAMP(a, 3);
+  group_meet_second(cnt, members, a.fail, local);  // all of T[:, tile] is written
+  PRAC_STAMP(a, 4);
+
+  // dW[128 tm .. , n0 .. n0 + 127] = P[rows] T[:, tile]: 8 waves as 4 (row blocks) x 2 (column halves), each
+  // 32 x 64.  T comes through LDS in chunks of 16 k-blocks (all of it when c <= 256), P straight from L2.
+  const int nchunks = (nckb + 15) / 16;
+  const int li = lane & 31, lh = lane >> 5;
+  float* stage = reinterpret_cast<float*>(smem + WG_T_BYTES) + wave * (32 * WG_STAGE_LD);
+  void* const odW = a.dW[h];
+  const int64_t olddw = a.lddw[h];
+  const int ovec = a.vec_ok[h];
+  bool t_in_lds = false;
+  for (int tm = member; tm < tiles_m; tm += members) {
+    f32x16 acc0, acc1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
+    const int64_t rb = (int64_t)tm * 4 + wr;
+    for (int ch = 0; ch < nchunks; ++ch) {
+      const int kb0 = ch * 16, kbs = min(16, nckb - kb0);
+      u32x4 fa[16];
+      if (tm == member && ch == 0) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) fa[q] = fa0[q];
+      } else {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) fa[q] = Pa[(rb * nckb + min(kb0 + q, nckb - 1)) * 64 + lane];
+      }
+      if (!(nchunks == 1 && t_in_lds)) {
+        __syncthreads();  // the previous chunk has been read
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int u = tid + 512 * i, blk = u >> 6, kbl = blk >> 2, nb = blk & 3;
+          if (kbl < kbs)
+            *reinterpret_cast<u32x4*>(smem + u * 16) =
+                tail_load16(rt, (uint32_t)((((kb0 + kbl) * nmb + nb0 + nb) * 64 + (u & 63)) * 16), local);
+        }
+        __syncthreads();
+        t_in_lds = true;
+      }
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        if (q < kbs) {
+          const u32x4 b0 = *reinterpret_cast<const u32x4*>(smem + (q * 4 + wc * 2) * 1024 + lane * 16);
+          const u32x4 b1 = *reinterpret_cast<const u32x4*>(smem + (q * 4 + wc * 2 + 1) * 1024 + lane * 16);
+          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[q]), as_frag(b0), acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fa[q]), as_frag(b1), acc1, 0, 0, 0);
+        }
+      }
+    }
+    // register v of lane (li, lh): row 8 (v / 4) + 4 lh + v % 4 of the wave's 32, column li (acc0) / 32 + li (acc1)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = 8 * (v / 4) + 4 * lh + (v % 4);
+      stage[row * WG_STAGE_LD + li] = acc0[v];
+      stage[row * WG_STAGE_LD + 32 + li] = acc1[v];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int row0 = tm * 128 + wr * 32, col0 = n0 + wc * 64;
+    if (OUT_BF16) {
+      const int er = lane >> 3, ec = (lane & 7) * 8;  // 8 lanes per row (16 bytes each), 8 rows per pass
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int row = er + 8 * p, grow = row0 + row, gcol = col0 + ec;
+        const float4 lo = *reinterpret_cast<const float4*>(stage + row * WG_STAGE_LD + ec);
+        const float4 hi = *reinterpret_cast<const float4*>(stage + row * WG_STAGE_LD + ec + 4);
+        if (grow >= a.d || gcol >= mh) continue;
+        float x[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        bf16_t* o = reinterpret_cast<bf16_t*>(odW) + (int64_t)grow * olddw + gcol;
+        if (ovec && gcol + 8 <= mh) {
+          if (a.beta != 0.f) {
+            const u32x4 old = *reinterpret_cast<const u32x4*>(o);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              x[e] += a.beta * __uint_as_float(((e & 1) ? (old[e >> 1] >> 16) : (old[e >> 1] & 0xFFFFu)) << 16);
+          }
+          u32x4 w;
+          w.x = pack2_hw(x[0], x[1]);
+          w.y = pack2_hw(x[2], x[3]);
+          w.z = pack2_hw(x[4], x[5]);
+          w.w = pack2_hw(x[6], x[7]);
+          *reinterpret_cast<u32x4*>(o) = w;
+        } else {
+          for (int e = 0; e < 8 && gcol + e < mh; ++e)
+            o[e] = f32_to_bf16(a.beta == 0.f ? x[e] : x[e] + a.beta * __uint_as_float(((uint32_t)o[e]) << 16));
+        }
+      }
+    } else {
+      const int er = lane >> 4, ec = (lane & 15) * 4;  // 16 lanes per row (16 bytes each), 4 rows per pass
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const int row = er + 4 * p, grow = row0 + row, gcol = col0 + ec;
+        float4 x = *reinterpret_cast<const float4*>(stage + row * WG_STAGE_LD + ec);
+        if (grow >= a.d || gcol >= mh) continue;
+        float* o = reinterpret_cast<float*>(odW) + (int64_t)grow * olddw + gcol;
+        if (ovec && gcol + 4 <= mh) {
+          if (a.beta != 0.f) {
+            const float4 old = *reinterpret_cast<const float4*>(o);
+            x.x += a.beta * old.x; x.y += a.beta * old.y; x.z += a.beta * old.z; x.w += a.beta * old.w;
+          }
+          *reinterpret_cast<float4*>(o) = x;
+        } else {
+          const float xs[4] = {x.x, x.y, x.z, x.w};
+          for (int e = 0; e < 4 && gcol + e < mh; ++e) o[e] = a.beta == 0.f ? xs[e] : xs[e] + a.beta * o[e];
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
+// MODE 0: partial slabs only; 1 / 2: the whole weight gradient (dW in fp32 / bf16)
+template <int MODE>
 __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
 
-  const int per_split = a.tiles_n * a.row_groups;
-  const int total = per_split * a.splits;
-  const int per_xcd = (total + 7) / 8;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int logical = xcd * per_xcd + slot;
-  if (slot >= per_xcd || logical >= total) return;
-  const int tn = logical % a.tiles_n;
-  const int rg = (logical / a.tiles_n) % a.row_groups;
-  const int split = logical / per_split;
+  int tn, rg, split;
+  if constexpr (MODE == 0) {
+    const int per_split = a.tiles_n * a.row_groups;
+    const int total = per_split * a.splits;
+    const int per_xcd = (total + 7) / 8;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int logical = xcd * per_xcd + slot;
+    if (slot >= per_xcd || logical >= total) return;
+    tn = logical % a.tiles_n;
+    rg = (logical / a.tiles_n) % a.row_groups;
+    split = logical / per_split;
+  } else {
+    // the workgroups of a column tile (its token ranges and row groups) take neighbouring slots of one XCD
+    const int members = a.splits * a.row_groups;
+    const int per_xcd = a.groups_per_xcd * members;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    tn = xcd * a.groups_per_xcd + slot / members;
+    if (slot >= per_xcd || tn >= a.tiles_n) return;
+    const int member = slot % members;
+    rg = member % a.row_groups;
+    split = member / a.row_groups;
+  }
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  PRAC_STAMP(a, 0);
   // which output this column tile belongs to
   int h = 0;
 #pragma unroll
@@ -801,7 +1143,7 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
 
   if (wave >= 4) {
     // ------------------------------------------------------------ loader waves
-    if (nk == 0) return;
+    if (nk > 0) {
     const int lt = tid - 256;
     const int cc = lt & 15, tg = lt >> 4, kb = tg >> 1, h = tg & 1;
     const int last_chunk = ((mh - 1) / 8) * 8;
@@ -854,9 +1196,9 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
       gload(kt + 3, ry);
       __syncthreads();
     }
-    return;
-  }
-
+    }
+    if constexpr (MODE == 0) return;
+  } else {
   // -------------------------------------------------------------- matrix waves
   const int lane = tid & 63, li = lane & 31, lh = lane >> 5;
   const int cb0 = rg * 8 + wave * 2;  // this wave's two 32-row blocks of T (column blocks of C)
@@ -926,6 +1268,7 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
 
   // epilogue: acc[4 i + j], register v of lane (li, lh): T row 32 (cb0 + i) + 8*(v/4) + 4*lh + v%4,
   // column n0 + 4 li + j
+  PRAC_STAMP(a, 6);
   float* out = a.slabs[h] + (int64_t)split * a.c * mh;
   const int n = n0 + 4 * li;
 #pragma unroll
@@ -946,6 +1289,14 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
         }
       }
     }
+  }
+  }
+  if constexpr (MODE != 0) {
+    // all eight waves: the slabs of this column tile -> T -> dW (see wgrad_tail)
+    const int members = a.splits * a.row_groups;
+    wgrad_tail<MODE == 2>(a, smem_raw, tn, h, n0, split * a.row_groups + rg, members);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    PRAC_STAMP(a, 5);
   }
 }
 
@@ -1014,10 +1365,9 @@ int launch_reconstruct_ws(prac_ctx* ctx, const bf16_t* C, int64_t ldc, bool pack
   return PRAC_OK;
 }
 
-int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, int N, int n_out, const bf16_t* const* dY,
-                   const int64_t* lddy, const int* m, float* const* slabs, int splits) {
-  if (n_out < 1 || n_out > PRAC_CTDY_MAX_OUT) return PRAC_EINVAL;
-  CtdyWsArgs a{};
+namespace {
+void fill_ctdy_args(CtdyWsArgs& a, const bf16_t* Cpk, int c, int N, int n_out, const bf16_t* const* dY, const int64_t* lddy,
+                    const int* m, float* const* slabs, int splits) {
   a.Cpk = Cpk; a.ccb = (c + 31) / 32; a.c = c; a.N = N; a.n_out = n_out; a.splits = splits;
   int tiles = 0;
   for (int h = 0; h < n_out; ++h) {
@@ -1030,12 +1380,80 @@ int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, int N, int n_out, co
   a.tok_per_split = ((ktiles + splits - 1) / splits) * CW_BK;
   a.tiles_n = tiles;
   a.row_groups = (a.ccb + 7) / 8;
+}
+}  // namespace
+
+int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, int N, int n_out, const bf16_t* const* dY,
+                   const int64_t* lddy, const int* m, float* const* slabs, int splits) {
+  if (n_out < 1 || n_out > PRAC_CTDY_MAX_OUT) return PRAC_EINVAL;
+  CtdyWsArgs a{};
+  fill_ctdy_args(a, Cpk, c, N, n_out, dY, lddy, m, slabs, splits);
   const size_t smem = (size_t)CW_STAGES * CW_STAGE;
   const int total = a.tiles_n * a.row_groups * splits;
   static bool s = false;
-  int rc = set_smem(ctx, ctdy_ws_kernel, smem, s);
+  int rc = set_smem(ctx, ctdy_ws_kernel<0>, smem, s);
   if (rc) return rc;
-  PRAC_LAUNCH(ctx, ctdy_ws_kernel, dim3(((total + 7) / 8) * 8), dim3(512), smem, a);
+  PRAC_LAUNCH(ctx, ctdy_ws_kernel<0>, dim3(((total + 7) / 8) * 8), dim3(512), smem, a);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }
+
+// Token ranges per column tile for the one-launch weight gradient, or 0 where it cannot run: the
+// workgroups of a column tile (token ranges x row groups) wait for each other, so all of them must be
+// resident - at most one workgroup per compute unit, with the tiles dealt to the 8 XCDs in equal numbers.
+int wgrad_fused_splits(int n_cu, int c, int n_out, const int64_t* m, int64_t N, int tune_splits) {
+  int64_t tiles = 0;
+  for (int h = 0; h < n_out; ++h) tiles += (m[h] + CW_BN - 1) / CW_BN;
+  if (tiles > PRAC_SYNC_TILES) return 0;
+  const int row_groups = ((c + 31) / 32 + 7) / 8;
+  const int64_t gpx = (tiles + 7) / 8;           // column tiles per XCD
+  const int cu_per_xcd = n_cu / 8;
+  if (gpx * row_groups > cu_per_xcd) return row_groups == 1 ? 1 : 0;  // single-member groups never wait
+  int splits = (int)(cu_per_xcd / (gpx * row_groups));
+  if (tune_splits > 0) {
+    if (tune_splits > splits) return 0;          // the override does not fit: three launches
+    splits = tune_splits;
+  }
+  if (splits > N / 256) splits = (int)(N / 256);
+  if (splits > 64) splits = 64;
+  return splits < 1 ? 1 : splits;
+}
+
+int launch_wgrad_fused(prac_ctx* ctx, const bf16_t* Cpk, int c, int N, int n_out, const bf16_t* const* dY,
+                       const int64_t* lddy, const int* m, float* const* slabs, int splits, int k_lo, float scale_hi,
+                       int nckb, const int* nmb, bf16_t* const* Tf, const bf16_t* Pa, int d, void* const* dW,
+                       const int64_t* lddw, bool out_bf16, float beta, int* cnt) {
+  if (n_out < 1 || n_out > PRAC_CTDY_MAX_OUT) return PRAC_EINVAL;
+  CtdyWsArgs a{};
+  fill_ctdy_args(a, Cpk, c, N, n_out, dY, lddy, m, slabs, splits);
+  a.groups_per_xcd = (a.tiles_n + 7) / 8;
+  const int per_xcd = a.groups_per_xcd * splits * a.row_groups;
+  // refuse a launch whose waiting workgroups might not all be resident
+  if (a.tiles_n > PRAC_SYNC_TILES || (splits * a.row_groups > 1 && per_xcd > ctx->n_cu / 8)) return PRAC_EINVAL;
+#ifdef PRAC_WS_TIMESTAMPS
+  a.stamps = g_ws_stamps;
+#endif
+  a.cnt = cnt; a.fail = ctx->d_flag; a.nckb = nckb; a.k_lo = k_lo; a.scale_hi = scale_hi; a.Pa = Pa; a.d = d; a.beta = beta;
+  for (int h = 0; h < n_out; ++h) {
+    a.Tf[h] = Tf[h]; a.nmb[h] = nmb[h]; a.dW[h] = dW[h]; a.lddw[h] = lddw[h];
+    a.vec_ok[h] = (reinterpret_cast<uintptr_t>(dW[h]) % 16 == 0 && lddw[h] % (out_bf16 ? 8 : 4) == 0) ? 1 : 0;
+  }
+  const size_t smem = std::max((size_t)CW_STAGES * CW_STAGE, (size_t)WG_SMEM);
+  static bool s1 = false, s2 = false;
+  const dim3 grid(8 * per_xcd), block(512);
+  if (out_bf16) {
+    int rc = set_smem(ctx, ctdy_ws_kernel<2>, smem, s2);
+    if (rc) return rc;
+    PRAC_LAUNCH(ctx, ctdy_ws_kernel<2>, grid, block, smem, a);
+  } else {
+    int rc = set_smem(ctx, ctdy_ws_kernel<1>, smem, s1);
+    if (rc) return rc;
+    PRAC_LAUNCH(ctx, ctdy_ws_kernel<1>, grid, block, smem, a);
+  }
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  return PRAC_OK;
+}
+
+#ifdef PRAC_WS_TIMESTAMPS
+extern "C" void prac_debug_set_stamps(void* p) { g_ws_stamps = reinterpret_cast<long long*>(p); }
+#endif

@@ -17,8 +17,9 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libprac.so
 PRAC_F32, PRAC_BF16 = 0, 1
 PRAC_REFRESH_PRINCIPAL, PRAC_REFRESH_RANDOM = 1, 2
 C_ROWMAJOR, C_PACKED = 0, 1
-TUNE_CTDY_SPLITS = 1
-KERNEL_KINDS = {"compress": 1, "ct_dy": 2, "t_reduce": 3, "p_t": 4, "gram": 5, "fused_fwd": 6, "reconstruct": 7}
+TUNE_CTDY_SPLITS, TUNE_PROFILE_STRIDE, TUNE_WGRAD_ONE_LAUNCH = 1, 2, 3
+KERNEL_KINDS = {"compress": 1, "ct_dy": 2, "t_reduce": 3, "p_t": 4, "gram": 5, "fused_fwd": 6, "reconstruct": 7,
+                "weight_grad": 8}
 STATUS = {0: "PRAC_OK", -1: "PRAC_EINVAL", -2: "PRAC_ENOMEM", -3: "PRAC_EHIP",
           -4: "PRAC_ENUMERIC", -5: "PRAC_EUNSUPPORTED", -6: "PRAC_ENOCTX", -7: "PRAC_ETOOBIG"}
 STATIC_SCRATCH_BYTES = 48 << 20
@@ -223,8 +224,8 @@ class Prac:
     def fit_basis(self, X: torch.Tensor | None, k: int, r: int, seed: int, draw: int,
                   refresh: int = PRAC_REFRESH_PRINCIPAL | PRAC_REFRESH_RANDOM, P: torch.Tensor | None = None,
                   d: int | None = None, iters: int = 0, oversample: int = 0, row_stride: int = 0,
-                  warm_start: bool = False, pack: bool = True):
-        """Returns (P, P_lp or None, scale)."""
+                  warm_start: bool = False, pack: bool = True, P_lp: torch.Tensor | None = None):
+        """Returns (P, P_lp or None, scale).  P_lp: an existing packed-basis buffer to write into."""
         if X is not None:
             px, N, dx, ldx = _mat(X)
             xdt, dev = _dt(X), X.device
@@ -233,7 +234,10 @@ class Prac:
         if P is None:
             P = torch.zeros((dx, k + r), dtype=torch.float32, device=dev)
         pp, _, _, ldp = _mat(P)
-        lp = torch.zeros(self.basis_lp_bytes(dx, k + r), dtype=torch.uint8, device=dev) if pack else None
+        if P_lp is not None:
+            lp, pack = P_lp, True
+        else:
+            lp = torch.zeros(self.basis_lp_bytes(dx, k + r), dtype=torch.uint8, device=dev) if pack else None
         opts = FitOpts(iters, oversample, row_stride, 1 if warm_start else 0)
         scale = C.c_float(0.0)
         _check(self.lib.prac_fit_basis(self._h, px, xdt, N, dx, ldx, k, r, seed, draw, refresh, C.byref(opts),

@@ -300,6 +300,56 @@ def test_weight_grad_matches_oracle(ctx, dt, N, d, m, k, r, odt):
         assert rel_fro(si.as_f64(got_p), ref) < TOL[dt]
 
 
+@pytest.mark.parametrize("N,d,ms,k,r,odt,beta", [
+    (3000, 328, [264], 40, 32, "f32", 0.0),         # several token splits, ragged tiles
+    (4096, 512, [640], 32, 32, "bf16", 0.0),
+    (900, 320, [520], 130, 130, "bf16", 0.5),       # c > 256: two row groups of T meet in one column tile
+    (1500, 300, [200], 150, 140, "f32", 0.25),      # 19 k-blocks: two chunks of T in the P T stage
+    (5000, 1100, [96], 10, 23, "f32", 0.0),         # more row tiles of dW than workgroups in a column tile
+    (2048, 256, [200, 72, 136], 24, 40, "bf16", 0.0),   # three outputs sharing C
+    (100, 64, [40], 4, 4, "f32", 0.0),              # fewer tokens than one tile
+])
+def test_weight_grad_one_launch_equals_three_launches(ctx, N, d, ms, k, r, odt, beta):
+    """The one-launch weight gradient (workgroups of a column tile meet to sum their partial slabs and
+    to form dW = P T) against the three-launch sequence it replaces: same sums in the same order, so
+    the results are equal bit for bit; the oracle comparison is test_weight_grad_matches_oracle's."""
+    from paper_2602_23111_amd.prac import C_PACKED, TUNE_WGRAD_ONE_LAUNCH
+    c = k + r
+    s = orc.scaling_factor(d, k, r)
+    X64, _ = si.activation(N, d, 0.8, seed=N + d)
+    P32, P64 = basis32(d, c, seed=k + 3 * r)
+    Ct = si.round_to(orc.compress(X64, P64), "bf16")
+    Cpk = pack_c_reference(Ct).to(DEV)
+    ld8 = lambda n: (n + 7) // 8 * 8
+    # two different upstream gradients, used alternately: the scratch the workgroups exchange their partial
+    # sums through is the same memory in every call, and no call may see what an earlier one left there
+    sets = [[dev_padded(si.round_to(si.grad_output(N, m, 1e-2, seed=m + 1000 * v), "bf16"), ld8(m)) for m in ms]
+            for v in range(2)]
+    Pd = P32.to(DEV)
+    lp = ctx.pack_basis(Pd)
+    torch.manual_seed(5)
+    base = [torch.randn((d, m), dtype=TORCH_DT[odt], device=DEV) * 1e-2 for m in ms]
+
+    def run(dYs):
+        outs = [b.clone() for b in base]
+        ctx.weight_grad_shared(Cpk, dYs, Pd, k, r, s, P_lp=lp, outs=outs, beta=beta, layout=C_PACKED)
+        ctx.sync_status()
+        return outs
+
+    ctx.set_tuning(TUNE_WGRAD_ONE_LAUNCH, 0)
+    want = [run(dYs) for dYs in sets]
+    ctx.set_tuning(TUNE_WGRAD_ONE_LAUNCH, 1)
+    try:
+        for v in (0, 1, 0, 1, 1, 0):
+            for a, b in zip(run(sets[v]), want[v]):
+                assert torch.equal(a, b)
+    finally:
+        ctx.set_tuning(TUNE_WGRAD_ONE_LAUNCH, 0)
+    for dYh, out, b in zip(sets[0], want[0], base):
+        ref = orc.weight_grad(si.as_f64(Ct), si.as_f64(dYh), P64, k, s) + beta * si.as_f64(b)
+        assert rel_fro(si.as_f64(out), ref) < 1e-2
+
+
 def test_weight_grad_exact_gradient_when_complement_is_full(ctx):
     # r = d - k: the estimator is the plain X^T dY (Lemma 1), whatever the basis
     N, d, m, k = 600, 64, 40, 24
@@ -550,6 +600,78 @@ def test_gpu_path_wrong_scale_is_biased_as_predicted(ctx):
     se = np.sqrt(f * f * (s - 1.0) * np.sum(tailX ** 2) / draws)
     assert np.linalg.norm(mean_x - predicted) < 4.0 * se
     assert np.linalg.norm(mean_x - X) > 10.0 * se
+
+
+def test_estimator_ablation_bench_mode_matches_closed_forms(ctx):
+    """bench.py --workload estimator_ablation: PAC, RAC and PRAC at scaling factors 1, 0.5, 0.2, 1.2 times (d-k)/r,
+    bias and variance of the library's reconstruction against the closed forms (Theorems 1 and 2; the scale
+    ablation of the appendix; Section 4.2 for PAC / RAC), each within 4 standard errors of the Monte-Carlo run."""
+    import bench
+    cases = {c["case"]: c for c in bench.estimator_ablation(ctx, draws=1500)}
+    assert set(cases) == {n for n, _, _, _ in bench.ABLATION_CASES}
+    for name, c in cases.items():
+        if c["r"] == 0:
+            # PAC: no randomness; biased by exactly the energy beyond the k-th singular value
+            assert c["mean_error"] < 1e-4 * max(c["bias_predicted"], 1e-30)
+            assert c["bias_measured"] == pytest.approx(c["bias_predicted_from_spectrum"], rel=1e-3)
+            assert c["variance_measured"] == 0.0
+            continue
+        assert c["z_mean"] < 4.0, (name, c)          # the mean is where the theory puts it ...
+        assert c["z_variance"] < 4.0, (name, c)      # ... and so is the spread around it
+        se = np.sqrt(c["variance_predicted"] / c["draws"])
+        if name in ("prac_scale_1.0", "rac_random_only"):
+            assert c["bias_predicted"] == 0.0 and c["bias_measured"] < 4.0 * se       # unbiased (Theorem 1)
+        else:
+            assert abs(c["bias_measured"] - c["bias_predicted"]) < 4.0 * se           # biased as predicted ...
+            if c["scale"] < 0.75 * (c["scale"] / float(name.rsplit("_", 1)[1])):
+                assert c["bias_measured"] > 4.0 * se                                   # ... and, at half the scale or less, measurably so
+    # the variance grows with the square of the factor on the scale
+    assert cases["prac_scale_0.5"]["variance_predicted"] == pytest.approx(0.25 * cases["prac_scale_1.0"]["variance_predicted"])
+
+
+def test_hip_graph_replays_match_eager_launches(ctx):
+    """compress + weight gradient captured into a HIP graph (as bench.py --graph 1 does): several replays, with
+    the program's own eager launches and synchronisations between them, each equal to the eager result bit for bit."""
+    from paper_2602_23111_amd.prac import C_PACKED, call_shape
+    N, d, m, k, r = 4096, 512, 640, 32, 32
+    c = k + r
+    s = orc.scaling_factor(d, k, r)
+    P32, _ = basis32(d, c, seed=3)
+    Pd = P32.to(DEV)
+    lp = ctx.pack_basis(Pd)
+    Xs = [si.round_to(si.activation(N, d, 0.8, seed=50 + i, n_out=2, out_scale=20.0)[0], "bf16").to(DEV) for i in range(2)]
+    dYs = [si.round_to(si.grad_output(N, m, 1e-2, seed=60 + i), "bf16").to(DEV) for i in range(2)]
+    Xin, dYin = Xs[0].clone(), dYs[0].clone()
+    Cm = torch.empty(ctx.compressed_bytes(N, c) // 2, dtype=torch.bfloat16, device=DEV)
+    dW = torch.empty((d, m), dtype=torch.bfloat16, device=DEV)
+    ctx.reserve_workspace(ctx.workspace_bytes(call_shape("weight_grad", N, d, k, r, m=[m])))
+
+    def launches():
+        ctx.compress(Xin, Pd, P_lp=lp, out=Cm, layout=C_PACKED)
+        ctx.weight_grad(Cm, dYin, Pd, k, r, s, P_lp=lp, out=dW, layout=C_PACKED)
+
+    want = []
+    for i in range(2):
+        Xin.copy_(Xs[i]); dYin.copy_(dYs[i])
+        launches()
+        torch.cuda.synchronize()
+        want.append((Cm.clone(), dW.clone()))
+    main_stream, cap = torch.cuda.current_stream(), torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    ctx.set_stream(cap)
+    try:
+        with torch.cuda.graph(g, stream=cap):
+            launches()
+    finally:
+        ctx.set_stream(main_stream)
+    for i in (1, 0, 1, 1, 0):
+        Xin.copy_(Xs[i]); dYin.copy_(dYs[i])
+        Cm.zero_(); dW.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Cm, want[i][0]) and torch.equal(dW, want[i][1])
+        ctx.compress(Xs[1 - i], Pd, P_lp=lp)          # eager work of the program's own between the replays
+        ctx.sync_status()
 
 
 # ------------------------------------------------- per-kernel timing hook

@@ -40,10 +40,12 @@ def _case(ctx, N, d, m, k, r, seed, layout_packed, odt):
     return got
 
 
-def test_static_weight_grad_two_calls_second_smaller():
-    from paper_2602_23111_amd.prac import Prac
+@pytest.mark.parametrize("one_launch", [0, 1])   # the three-launch default and the one-launch variant (its counters
+def test_static_weight_grad_two_calls_second_smaller(one_launch):   # live in the static block too)
+    from paper_2602_23111_amd.prac import TUNE_WGRAD_ONE_LAUNCH, Prac
     ctx = Prac(0)
     try:
+        ctx.set_tuning(TUNE_WGRAD_ONE_LAUNCH, one_launch)
         _case(ctx, 4096, 512, 640, 32, 32, seed=11, layout_packed=True, odt=torch.bfloat16)
         _case(ctx, 1000, 328, 200, 24, 16, seed=21, layout_packed=False, odt=torch.float32)   # smaller, row-major C
         _case(ctx, 4096, 512, 640, 32, 32, seed=11, layout_packed=True, odt=torch.bfloat16)   # and the first again
