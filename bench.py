@@ -336,6 +336,10 @@ def main():
                     help="1: the compress + weight-gradient launches of a step are replayed from a HIP graph (one per input "
                          "set); 0 (default): launched one by one, which is the faster of the two here (106 against 113 us "
                          "per step at the headline shape)")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="consecutive steps (independent batches) alternate over this many HIP streams, one library context "
+                         "each, so that the small tail kernels of one step overlap the streaming kernels of the next; "
+                         "1: everything on one stream")
     ap.add_argument("--refresh-every", type=int, default=0, help="override the refresh interval (0: the workload's, 500)")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="after the timed region, also run three plain device copies of this many MB "
@@ -375,6 +379,9 @@ def main():
     torch.cuda.set_device(0)
     ctx = Prac(0)
     main_stream = torch.cuda.current_stream()
+    n_streams = max(1, min(args.streams, 4))
+    if args.graph:
+        n_streams = 1
 
     # scratch of every call this run issues, reserved once: no call below allocates or waits for the device
     shapes = [call_shape("fit_basis", N, d, k, r, row_stride=w["row_stride"]),
@@ -524,25 +531,60 @@ def main():
             ctx.set_stream(main_stream)
             torch.cuda.synchronize()
 
+    # Consecutive steps work on independent batches (as consecutive layers of a model do): with more than one
+    # stream they alternate over the streams, each with its own library context (own scratch) and its own dW, so
+    # that one step's short tail kernels (slab reduction, P T) overlap the next step's streaming kernels.  Within a
+    # step compress -> weight gradient stay in order on the step's stream; a refresh waits for every stream and
+    # every stream waits for it (P is shared).
+    side = [torch.cuda.Stream() for _ in range(n_streams)] if n_streams > 1 else []
+    side_ctx = [Prac(0, stream=st) for st in side]
+    side_dw = [torch.empty_like(dW) for _ in side]
+    for cx in side_ctx:
+        cx.reserve_workspace(cx.workspace_bytes(call_shape("weight_grad", N, d, k, r, m=[m])))
+
+    def side_launches(j: int, i: int):
+        side_ctx[j].compress(Xs[i], P, P_lp=lp, out=Cs[i], layout=C_PACKED)
+        side_ctx[j].weight_grad(Cs[i], dYs[i], P, k, r, state["scale"], P_lp=lp, out=side_dw[j], layout=C_PACKED)
+
     def timed_step(t: int):
         if t % T == 0:
+            for st in side:
+                main_stream.wait_stream(st)
             refresh(t)
+            for st in side:
+                st.wait_stream(main_stream)
         if graphs is not None:
             graphs[t % w["n_sets"]].replay()
+        elif side:
+            side_launches(t % n_streams, t % w["n_sets"])
         else:
             launches(t % w["n_sets"])
 
+    def timed_run(first: int, count: int):
+        state["fits"] = 0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(first, first + count):       # the step counter runs on from the warm-up
+            timed_step(t)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    for st in side:
+        st.wait_stream(main_stream)
     for i in range(2 * w["n_sets"]):      # (re-)warm the path the timed region takes
-        graphs[i % w["n_sets"]].replay() if graphs is not None else launches(i % w["n_sets"])
-    state["fits"] = 0
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(W, W + args.steps):          # the step counter runs on from the warm-up
-        timed_step(t)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+        timed_step(W + i)
+    elapsed = timed_run(W, args.steps)
     fits_in_region = state["fits"]
     ctx.sync_status()
+    for cx in side_ctx:
+        cx.sync_status()
+    one_stream_ms = None
+    if side:
+        # the same steps on one stream, for comparison (outside the timed region)
+        keep, side = side, []
+        n_cmp = min(args.steps, 100)
+        one_stream_ms = 1e3 * timed_run(W, n_cmp) / n_cmp
+        side = keep
 
     # the dominant kernel over the same steps again, launched one by one so that every launch can carry a
     # HIP event pair on the ctx stream (events cannot be attached to the nodes of a replayed graph)
@@ -585,6 +627,8 @@ def main():
     if args.cpu_sample > 0:
         cpu = cpu_baseline(Xs[0].cpu(), dYs[0].cpu(), k, r, T)
     ctx.close()
+    for cx in side_ctx:
+        cx.close()
     block = None
     if args.others:
         del Xs, dYs, Cs, graphs
@@ -611,13 +655,16 @@ def main():
                                f"basis refresh every {T} steps, step counter running on from the warm-up "
                                f"(steps {W}..{W + args.steps - 1}: {fits_in_region} refresh(es) in the timed region, warm-started"
                                + (f", Gram over every {w['row_stride']}th token" if w["row_stride"] > 1 else "") + "), "
-                               f"{w['n_sets']} rotating input sets; {graph_note}"},
+                               f"{w['n_sets']} rotating input sets; {graph_note}"
+                               + (f"; consecutive steps alternate over {n_streams} HIP streams" if n_streams > 1 else "")},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels_us": per_kernel_us,
         "refit": {"ms": fit_ms, "in_timed_region": fits_in_region, "every": T, "amortised_us_per_step": 1e3 * fit_ms / T,
                   "kind": REFIT_LABEL},
         "value_with_amortised_refit": N / (ms_amortised * 1e-3),
+        "streams": n_streams,
+        "one_stream_ms_per_step": one_stream_ms,
         "other_entry_points_us": other_us,
         "llama1b_block": block,
         "fit_basis_ms": fit_ms,
