@@ -43,9 +43,12 @@ OTHER_WORKLOADS = {
                            out_scale=20.0, layer_seed=2001),
     "rank_sweep_0_256": dict(WORKLOAD, name="rank_sweep_0_256", k=0, r=256, n_out=0, layer_seed=4000),
     "rank_sweep_512_512": dict(WORKLOAD, name="rank_sweep_512_512", k=512, r=512, n_out=0, layer_seed=4001),
-    # basis refitted on every step from the Gram matrix of a 4096-token subsample
+    # basis refitted on every step from a 4096-token subsample: one tracking step per refit (with a refit on
+    # every step the basis never falls more than one batch behind)
     "llama7b_up_gate": dict(WORKLOAD, name="llama7b_up_gate", N=16384, d=4096, m=11008, k=256, r=256, n_out=16,
-                            out_scale=50.0, refresh_every=1, row_stride=4, n_sets=2, layer_seed=5000),
+                            out_scale=50.0, refresh_every=1, row_stride=4, n_sets=2, layer_seed=5000, warm_iters=1),
+    "llama7b_down": dict(WORKLOAD, name="llama7b_down", N=16384, d=11008, m=4096, k=256, r=256, n_out=16,
+                         out_scale=50.0, refresh_every=1, row_stride=4, n_sets=2, layer_seed=5001, warm_iters=1),
 }
 BLOCK_WORKLOAD = "llama1b_block"
 ABLATION_WORKLOAD = "estimator_ablation"
@@ -336,10 +339,11 @@ def main():
                     help="1: the compress + weight-gradient launches of a step are replayed from a HIP graph (one per input "
                          "set); 0 (default): launched one by one, which is the faster of the two here (106 against 113 us "
                          "per step at the headline shape)")
-    ap.add_argument("--streams", type=int, default=2,
+    ap.add_argument("--streams", type=int, default=0,
                     help="consecutive steps (independent batches) alternate over this many HIP streams, one library context "
                          "each, so that the small tail kernels of one step overlap the streaming kernels of the next; "
-                         "1: everything on one stream")
+                         "1: everything on one stream; 0 (default): one or two, whichever a short trial after the warm-up "
+                         "finds faster for the workload")
     ap.add_argument("--refresh-every", type=int, default=0, help="override the refresh interval (0: the workload's, 500)")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="after the timed region, also run three plain device copies of this many MB "
@@ -379,9 +383,9 @@ def main():
     torch.cuda.set_device(0)
     ctx = Prac(0)
     main_stream = torch.cuda.current_stream()
-    n_streams = max(1, min(args.streams, 4))
+    max_streams = 2 if args.streams == 0 else max(1, min(args.streams, 4))
     if args.graph:
-        n_streams = 1
+        max_streams = 1
 
     # scratch of every call this run issues, reserved once: no call below allocates or waits for the device
     shapes = [call_shape("fit_basis", N, d, k, r, row_stride=w["row_stride"]),
@@ -389,6 +393,7 @@ def main():
                          row_stride=w["row_stride"]),
               call_shape("compress", N, d, k, r), call_shape("weight_grad", N, d, k, r, m=[m]),
               call_shape("weight_grad", N, d, k, r, m=[m, m, m]), call_shape("fused_fwd", N, d, k, r, m=[m]),
+              call_shape("fused_fwd", N, d, k, r, m=[3 * m]),
               call_shape("reconstruct", N, d, k, r)]
     ctx.reserve_workspace(max(ctx.workspace_bytes(s) for s in shapes))
 
@@ -475,6 +480,25 @@ def main():
         torch.cuda.synchronize()
         other_us["fwd_vendor_gemm"] = 1e3 * e0.elapsed_time(e1) / 8
         del Wt, Y
+        # query, key and value projections in one fused launch (m = 3 x 2048, one read of X, one C) against the
+        # vendor GEMM of the same width plus the stand-alone compress
+        Wq = (torch.randn((3 * m, d), generator=g, device=dev) * 0.02).to(torch.bfloat16)
+        Yq = torch.empty((N, 3 * m), dtype=torch.bfloat16, device=dev)
+        ctx.compress_fused_fwd(Xs[0], Wq, P, w_layout=1, P_lp=lp, Y=Yq, out=Cs[0], layout=C_PACKED)
+        ctx.profile_select(KERNEL_KINDS["fused_fwd"])
+        for t in range(4):
+            ctx.compress_fused_fwd(Xs[t % w["n_sets"]], Wq, P, w_layout=1, P_lp=lp, Y=Yq, out=Cs[t % w["n_sets"]],
+                                   layout=C_PACKED)
+        ms, n = ctx.profile_read()
+        other_us["fused_fwd_qkv"] = 1e3 * ms / max(n, 1)
+        torch.matmul(Xs[0], Wq.t(), out=Yq)
+        e0.record()
+        for t in range(4):
+            torch.matmul(Xs[t % w["n_sets"]], Wq.t(), out=Yq)
+        e1.record()
+        torch.cuda.synchronize()
+        other_us["fwd_vendor_gemm_qkv"] = 1e3 * e0.elapsed_time(e1) / 4
+        del Wq, Yq
         # query / key / value gradients from the one compressed activation they share (Section 5.1):
         # one call for the three against three calls, wall clock over 8 repetitions each
         dY3 = [dYs[0], dYs[1], dYs[2]]
@@ -536,11 +560,12 @@ def main():
     # that one step's short tail kernels (slab reduction, P T) overlap the next step's streaming kernels.  Within a
     # step compress -> weight gradient stay in order on the step's stream; a refresh waits for every stream and
     # every stream waits for it (P is shared).
-    side = [torch.cuda.Stream() for _ in range(n_streams)] if n_streams > 1 else []
+    side = [torch.cuda.Stream() for _ in range(max_streams)] if max_streams > 1 else []
     side_ctx = [Prac(0, stream=st) for st in side]
     side_dw = [torch.empty_like(dW) for _ in side]
     for cx in side_ctx:
         cx.reserve_workspace(cx.workspace_bytes(call_shape("weight_grad", N, d, k, r, m=[m])))
+    use = dict(n=len(side))      # streams in use (0 or 1: everything on the main stream)
 
     def side_launches(j: int, i: int):
         side_ctx[j].compress(Xs[i], P, P_lp=lp, out=Cs[i], layout=C_PACKED)
@@ -548,15 +573,15 @@ def main():
 
     def timed_step(t: int):
         if t % T == 0:
-            for st in side:
+            for st in side[:use["n"]]:
                 main_stream.wait_stream(st)
             refresh(t)
-            for st in side:
+            for st in side[:use["n"]]:
                 st.wait_stream(main_stream)
         if graphs is not None:
             graphs[t % w["n_sets"]].replay()
-        elif side:
-            side_launches(t % n_streams, t % w["n_sets"])
+        elif use["n"] > 1:
+            side_launches(t % use["n"], t % w["n_sets"])
         else:
             launches(t % w["n_sets"])
 
@@ -571,20 +596,21 @@ def main():
 
     for st in side:
         st.wait_stream(main_stream)
-    for i in range(2 * w["n_sets"]):      # (re-)warm the path the timed region takes
-        timed_step(W + i)
+    # short trial of each stream count (also warms the path the timed region takes); steps chosen without a
+    # refresh unless every step has one
+    trial_first = (W // T + 1) * T + 1 if T > 16 else W
+    trial_ms = {}
+    for n_try in ([1] if not side else ([1, len(side)] if args.streams == 0 else [len(side)])):
+        use["n"] = n_try
+        timed_run(trial_first, 2 * w["n_sets"])
+        trial_ms[n_try] = 1e3 * timed_run(trial_first, 16) / 16
+    use["n"] = min(trial_ms, key=trial_ms.get)
+    n_streams = max(use["n"], 1)
     elapsed = timed_run(W, args.steps)
     fits_in_region = state["fits"]
     ctx.sync_status()
     for cx in side_ctx:
         cx.sync_status()
-    one_stream_ms = None
-    if side:
-        # the same steps on one stream, for comparison (outside the timed region)
-        keep, side = side, []
-        n_cmp = min(args.steps, 100)
-        one_stream_ms = 1e3 * timed_run(W, n_cmp) / n_cmp
-        side = keep
 
     # the dominant kernel over the same steps again, launched one by one so that every launch can carry a
     # HIP event pair on the ctx stream (events cannot be attached to the nodes of a replayed graph)
@@ -664,7 +690,7 @@ def main():
                   "kind": REFIT_LABEL},
         "value_with_amortised_refit": N / (ms_amortised * 1e-3),
         "streams": n_streams,
-        "one_stream_ms_per_step": one_stream_ms,
+        "trial_ms_per_step_by_streams": {str(kk): vv for kk, vv in trial_ms.items()},
         "other_entry_points_us": other_us,
         "llama1b_block": block,
         "fit_basis_ms": fit_ms,

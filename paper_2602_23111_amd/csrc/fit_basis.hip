@@ -611,7 +611,8 @@ FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool n
 
 // the two panel kernels keep up to 128 KB / 64 KB in LDS (n <= 1024)
 int set_dyn_smem(prac_ctx* ctx) {
-  static bool done = false;
+  static bool done_dev[PRAC_MAX_DEVICES] = {};  // the attribute is per device
+  bool& done = done_dev[ctx->device % PRAC_MAX_DEVICES];
   if (!done) {
     PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_upper_kernel),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, CH_NB * (CH_MAX + 2) * 8));
@@ -882,7 +883,8 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       // fp32 afterwards, so anything far below fp32 rounding is spent effort
       constexpr double JACOBI_TOL = 1e-10;
       unsigned* counts = reinterpret_cast<unsigned*>(ctx->ws + L.X64);
-      static bool smem_set = false;
+      static bool smem_dev[PRAC_MAX_DEVICES] = {};
+      bool& smem_set = smem_dev[ctx->device % PRAC_MAX_DEVICES];
       if (!smem_set) {
         PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_block_kernel),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));

@@ -292,7 +292,8 @@ int launch_cfg(prac_ctx* ctx, const GemmBf16Args& g) {
   a.partial = g.partial;
   a.out_bf16 = g.out_bf16 ? 1 : 0;
   auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC>;
-  static bool attr_set = false;  // one ctx per host thread at a time; benign if raced
+  static bool attr_dev[PRAC_MAX_DEVICES] = {};  // per device; one ctx per host thread at a time, benign if raced
+  bool& attr_set = attr_dev[ctx->device % PRAC_MAX_DEVICES];
   if (!attr_set) {
     PRAC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM));

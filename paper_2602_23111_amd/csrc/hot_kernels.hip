@@ -660,7 +660,8 @@ int launch_pt(prac_ctx* ctx, const bf16_t* Pa, int n_out, const bf16_t* const* T
   const dim3 grid(((total + 7) / 8) * 8), block(256);
   const size_t smem = !tiled ? (size_t)128 * PT_TLD * sizeof(float)
                              : std::max((size_t)2 * (128 / 32 + 4) * PT2_KC * 1024, (size_t)4 * 64 * PT2_ELD * sizeof(float));
-  static bool done[4] = {false, false, false, false};
+  static bool done_dev[PRAC_MAX_DEVICES][4] = {};  // the attribute is per device
+  bool* done = done_dev[ctx->device % PRAC_MAX_DEVICES];
   const int idx = (tiled ? 2 : 0) + (out_bf16 ? 1 : 0);
 #define PRAC_PT_CASE(I, KERN)                          \
   case I: {                                            \

@@ -13,7 +13,7 @@ static __device__ __align__(256) unsigned char scratch[PRAC_STATIC_SCRATCH_BYTES
 
 namespace {
 
-constexpr int kMaxDevices = 64;
+constexpr int kMaxDevices = PRAC_MAX_DEVICES;
 char* g_static_scratch[kMaxDevices] = {};  // device address of `scratch` on each GPU, set by prac_create
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }

@@ -13,6 +13,7 @@
 #include "prac.h"
 
 typedef unsigned short bf16_t;  // raw bf16 bit pattern
+#define PRAC_MAX_DEVICES 64      // per-device tables (kernel attributes, the static scratch block's address)
 
 struct prac_ctx {
   int device;

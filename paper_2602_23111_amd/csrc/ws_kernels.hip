@@ -1334,7 +1334,8 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
   const size_t smem = (size_t)WS_STAGES * WS_STAGE;
   const int total = a.tiles_m * a.col_groups;
   const dim3 grid(((total + 7) / 8) * 8), block(512);
-  static bool s1 = false, s2 = false;
+  static bool f1[PRAC_MAX_DEVICES] = {}, f2[PRAC_MAX_DEVICES] = {};  // the attribute is per device
+  bool &s1 = f1[ctx->device % PRAC_MAX_DEVICES], &s2 = f2[ctx->device % PRAC_MAX_DEVICES];
   constexpr auto kern1 = compress_ws_kernel<1, WS_NCH, WS_NIF>;
   constexpr auto kern2 = compress_ws_kernel<2, WS_NCH, WS_NIF>;
   if (FN == 1) {
@@ -1357,8 +1358,8 @@ int launch_reconstruct_ws(prac_ctx* ctx, const bf16_t* C, int64_t ldc, bool pack
   a.C = C; a.ldc = ldc; a.packed = packed ? 1 : 0; a.ccb = (c + 31) / 32; a.N = N; a.c = c; a.d = d; a.Ptfrag = Ptfrag; a.ncb = ncb; a.Xh = Xh; a.ldxh = ldxh;
   a.tiles_m = (N + WS_BM - 1) / WS_BM;
   a.groups = (d + 255) / 256;
-  static bool s = false;
-  int rc = set_smem(ctx, reconstruct_ws_kernel, (size_t)RW_SMEM, s);
+  static bool f[PRAC_MAX_DEVICES] = {};
+  int rc = set_smem(ctx, reconstruct_ws_kernel, (size_t)RW_SMEM, f[ctx->device % PRAC_MAX_DEVICES]);
   if (rc) return rc;
   PRAC_LAUNCH(ctx, reconstruct_ws_kernel, dim3(((a.tiles_m + 7) / 8) * 8), dim3(512), (size_t)RW_SMEM, a);
   PRAC_HIP_TRY(ctx, hipGetLastError());
@@ -1390,8 +1391,8 @@ int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, int N, int n_out, co
   fill_ctdy_args(a, Cpk, c, N, n_out, dY, lddy, m, slabs, splits);
   const size_t smem = (size_t)CW_STAGES * CW_STAGE;
   const int total = a.tiles_n * a.row_groups * splits;
-  static bool s = false;
-  int rc = set_smem(ctx, ctdy_ws_kernel<0>, smem, s);
+  static bool f[PRAC_MAX_DEVICES] = {};
+  int rc = set_smem(ctx, ctdy_ws_kernel<0>, smem, f[ctx->device % PRAC_MAX_DEVICES]);
   if (rc) return rc;
   PRAC_LAUNCH(ctx, ctdy_ws_kernel<0>, dim3(((total + 7) / 8) * 8), dim3(512), smem, a);
   PRAC_HIP_TRY(ctx, hipGetLastError());
@@ -1439,7 +1440,8 @@ int launch_wgrad_fused(prac_ctx* ctx, const bf16_t* Cpk, int c, int N, int n_out
     a.vec_ok[h] = (reinterpret_cast<uintptr_t>(dW[h]) % 16 == 0 && lddw[h] % (out_bf16 ? 8 : 4) == 0) ? 1 : 0;
   }
   const size_t smem = std::max((size_t)CW_STAGES * CW_STAGE, (size_t)WG_SMEM);
-  static bool s1 = false, s2 = false;
+  static bool f1[PRAC_MAX_DEVICES] = {}, f2[PRAC_MAX_DEVICES] = {};
+  bool &s1 = f1[ctx->device % PRAC_MAX_DEVICES], &s2 = f2[ctx->device % PRAC_MAX_DEVICES];
   const dim3 grid(8 * per_xcd), block(512);
   if (out_bf16) {
     int rc = set_smem(ctx, ctdy_ws_kernel<2>, smem, s2);

@@ -320,14 +320,15 @@ def test_llama7b_layer_compress_and_weight_grad(ctx, d, m):
         assert abs(a - b) <= 1e-2 * b, (c0, a, b)
 
 
-def test_llama7b_per_step_refit_from_token_subsample(ctx):
-    # cold fit on batch 0, then the per-step refit as that workload runs it: two tracking steps from
+@pytest.mark.parametrize("iters", [1, 2])      # bench.py's LLaMA-7B workloads run one tracking step per refit
+def test_llama7b_per_step_refit_from_token_subsample(ctx, iters):
+    # cold fit on batch 0, then the per-step refit as that workload runs it: tracking steps from
     # the previous Q1 on every fourth token of the next batch
     stride, D7 = 4, 4096
     X0 = si.activation_torch(N7, D7, 0.8, 5000, 16, 50.0, torch.bfloat16, DEV, batch=0)
     X1 = si.activation_torch(N7, D7, 0.8, 5000, 16, 50.0, torch.bfloat16, DEV, batch=1)
     P, _, _ = ctx.fit_basis(X0, K7, R7, seed=77, draw=0, row_stride=stride)
-    P, _, scale = ctx.fit_basis(X1, K7, R7, seed=77, draw=1, P=P, warm_start=True, iters=2, oversample=-1,
+    P, _, scale = ctx.fit_basis(X1, K7, R7, seed=77, draw=1, P=P, warm_start=True, iters=iters, oversample=-1,
                                 row_stride=stride)
     ctx.sync_status()
     assert scale == pytest.approx((D7 - K7) / R7)
