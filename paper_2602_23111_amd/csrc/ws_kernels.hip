@@ -44,7 +44,19 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// Development builds only (-DPRAC_WS_TIMESTAMPS): thread 0 of every workgroup writes wall-clock stamps.
+#ifdef PRAC_WS_TIMESTAMPS
+#define PRAC_STAMP(a, i) \
+  do { if ((a).stamps && threadIdx.x == 0) (a).stamps[(long long)blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+long long* g_ws_stamps = nullptr;
+#else
+#define PRAC_STAMP(a, i) do { } while (0)
+#endif
+
 struct CompressWsArgs {
+#ifdef PRAC_WS_TIMESTAMPS
+  long long* stamps;
+#endif
   const bf16_t* X;
   int64_t ldx;
   int N, d;
@@ -199,6 +211,7 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  PRAC_STAMP(a, 0);
   const int m0 = tm * WS_BM;
   const int nk = (a.d + WS_BK - 1) / WS_BK;
   // Step kt of this workgroup works on k-tile act(kt): the sum over k may run in any order, and
@@ -330,6 +343,7 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
       (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw + (unsigned)(li * WS_LD * 2 + lh * 16);
   u32x4 fa[4], fb[4];
   __builtin_amdgcn_s_barrier();  // tile 0 is in LDS
+  PRAC_STAMP(a, 1);
   frag_read4(fa, lds0);
   for (int kt = 0; kt < nk; ++kt) {
     const unsigned cur = lds0 + (unsigned)(kt & 1) * WS_STAGE;
@@ -355,6 +369,7 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
 
   // epilogue: block (i, j) = acc[i * FN + j]; register v of lane (li, lh) is token row
   // 8*(v/4) + 4*lh + v%4 of row block i, column li of column block cb0 + j.
+  PRAC_STAMP(a, 2);
   if (a.packed && !fwd) {
     // registers v = 8 tb .. 8 tb + 7 are exactly the 8 slots of the 16-token block tb
     u32x4* Cp = reinterpret_cast<u32x4*>(a.C);
@@ -431,6 +446,10 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
       }
     }
   }
+#ifdef PRAC_WS_TIMESTAMPS
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  PRAC_STAMP(a, 3);
+#endif
 }
 
 // ------------------------------------------------------------------ reconstruction
@@ -737,13 +756,7 @@ struct CtdyWsArgs {
   long long* stamps;   // development builds only: 8 wall-clock stamps per workgroup
 #endif
 };
-#ifdef PRAC_WS_TIMESTAMPS
-#define PRAC_STAMP(a, i) \
-  do { if ((a).stamps && threadIdx.x == 0) (a).stamps[(long long)blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-long long* g_ws_stamps = nullptr;
-#else
-#define PRAC_STAMP(a, i) do { } while (0)
-#endif
+
 
 constexpr int CW_BK = 128, CW_BN = 128;
 constexpr int CW_STAGE = 8 * 4 * 1024;  // bytes per LDS stage
@@ -1316,6 +1329,9 @@ int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d
                        bf16_t* C, int64_t ldc, bool packed, const bf16_t* Wfrag, int ncb_w, int m, bf16_t* Y,
                        int64_t ldy) {
   CompressWsArgs a;
+#ifdef PRAC_WS_TIMESTAMPS
+  a.stamps = g_ws_stamps;
+#endif
   a.X = X; a.ldx = ldx; a.N = N; a.d = d; a.Pfrag = Pfrag; a.ncb = ncb; a.c = c;
   a.C = C; a.ldc = ldc; a.ccb = (c + 31) / 32; a.packed = packed ? 1 : 0;
   a.tiles_m = (N + WS_BM - 1) / WS_BM;
