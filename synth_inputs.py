@@ -96,16 +96,21 @@ def orthonormal_basis(d: int, c: int, seed: int) -> np.ndarray:
 # ------------------------------------------------- full-size, on a torch device
 def activation_torch(N: int, d: int, alpha: float, seed: int, n_out: int,
                      out_scale: float, dtype: torch.dtype, device,
-                     ld: int | None = None, chunk: int = 4096, batch: int = 0) -> torch.Tensor:
+                     ld: int | None = None, chunk: int = 4096, batch: int = 0,
+                     gap_after: int = 0, gap_shrink: float = 1.0) -> torch.Tensor:
     """Same recipe as activation(), drawn with torch's generator on `device`
     in fp32 and rounded to `dtype`.  `seed` fixes the layer (R, sigma, outlier
     channels); `batch` picks the token draw Z, so that different batches of one
     layer share their spectrum and principal subspace, as successive training
     batches do.  Returns an (N, d) view into an (N, ld) buffer when ld > d
-    (padded leading dimension)."""
+    (padded leading dimension).  gap_after = k > 0 multiplies sigma_{k+1..d} by gap_shrink, which opens an
+    eigenvalue gap after the k-th direction (for tests that compare projectors)."""
     # the layer's mixing matrix diag(sigma) R is built on the host (numpy QR), like activation()
     rng = np.random.default_rng(seed)
-    M64 = power_law_sigma(d, alpha)[:, None] * haar_orthogonal(d, rng)
+    sig = power_law_sigma(d, alpha)
+    if gap_after > 0:
+        sig[gap_after:] *= gap_shrink
+    M64 = sig[:, None] * haar_orthogonal(d, rng)
     if n_out:
         M64[:, outlier_channels(d, n_out, rng)] *= out_scale
     M = torch.from_numpy(M64.astype(np.float32)).to(device)

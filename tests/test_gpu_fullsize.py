@@ -191,7 +191,38 @@ def test_weight_grad_shared_full_size_every_element(ctx):
         check_weight_grad_columns(dWh, C64, si.as_f64(dYh), P64, k, s)
 
 
-# ------------------------------------------------------------------------- fit
+# ------------------------------------------------------------------------- Gram, fit
+def test_gram_full_size_every_element(ctx):
+    # the streaming Gram path at the headline size against the oracle's X^T X, element by element: fp32 sums
+    # of N bf16 products, |err| <= a few 1e-6 of |x_i| |x_j| (column norms), checked against 2e-5 of it
+    d = 2048
+    X = si.activation_torch(N, d, 0.8, 3000, 8, 30.0, torch.bfloat16, DEV)
+    G = ctx.gram(X)
+    torch.cuda.synchronize()
+    X64 = si.as_f64(X)
+    ref = orc.gram(X64)
+    got = si.as_f64(G)
+    cn = np.linalg.norm(X64, axis=0)
+    assert rel_fro(got, ref) < 2e-5
+    assert np.max(np.abs(got - ref) / (cn[:, None] * cn[None, :])) < 2e-5
+    assert np.array_equal(got, got.T)
+
+
+def test_fit_basis_full_size_projector_with_gap(ctx):
+    # the cold fit at the headline size on an activation whose spectrum drops after the k-th direction:
+    # projector of Q1 against the oracle's exact top-k eigenvectors of X^T X
+    d, k, r = 2048, 128, 128
+    X = si.activation_torch(N, d, 0.8, 3000, 8, 30.0, torch.bfloat16, DEV, gap_after=k, gap_shrink=0.8)
+    P, _, _ = ctx.fit_basis(X, k, r, seed=1234, draw=0)
+    ctx.sync_status()
+    Q1, lam = orc.principal_subspace(orc.gram(si.as_f64(X)), k)
+    assert lam[k - 1] / lam[k] >= 1.05
+    U = si.as_f64(P)[:, :k]
+    assert np.abs(U @ U.T - Q1 @ Q1.T).max() < 1e-3
+    P64 = si.as_f64(P)
+    assert np.abs(P64.T @ P64 - np.eye(k + r)).max() < 1e-5
+
+
 def test_fit_basis_full_size_invariants(ctx):
     d, k, r = 2048, 128, 128
     X = si.activation_torch(N, d, 0.8, 3000, 8, 30.0, torch.bfloat16, DEV)
