@@ -674,6 +674,48 @@ def test_hip_graph_replays_match_eager_launches(ctx):
         ctx.sync_status()
 
 
+# ------------------------------------------------- failure reporting, repeatability
+def test_non_finite_activation_is_reported_not_hidden(ctx):
+    """A fit on an activation with a NaN in it cannot produce a basis: the Cholesky factorisation sees a
+    non-finite pivot, replaces it so that every kernel still runs to its end, and raises the device-side
+    flag that prac_sync_status turns into PRAC_ENUMERIC (once; the next status is clean)."""
+    from paper_2602_23111_amd.prac import PracError
+    N, d, k, r = 512, 128, 8, 8
+    Xt = si.round_to(si.activation(N, d, 0.8, seed=3)[0], "f32")
+    Xt[7, 5] = float("nan")
+    ctx.fit_basis(Xt.to(DEV), k, r, seed=1, draw=0, pack=False)
+    with pytest.raises(PracError) as e:
+        ctx.sync_status()
+    assert e.value.status == -4
+    ctx.sync_status()                                   # the flag was cleared by the report
+    good = si.round_to(si.activation(N, d, 0.8, seed=3)[0], "f32")
+    P, _, _ = ctx.fit_basis(good.to(DEV), k, r, seed=1, draw=0, pack=False)
+    ctx.sync_status()                                   # and the ctx works on
+    P64 = si.as_f64(P)
+    assert np.abs(P64.T @ P64 - np.eye(k + r)).max() < 1e-5
+
+
+def test_results_are_repeatable_bit_for_bit(ctx):
+    """Token-split sums are reduced in a fixed order (no floating-point atomics anywhere): the same call on
+    the same inputs gives the same bits, whatever ran in between."""
+    from paper_2602_23111_amd.prac import C_PACKED
+    N, d, m, k, r = 4096, 512, 640, 32, 32
+    Xd = si.round_to(si.activation(N, d, 0.8, seed=70, n_out=2, out_scale=20.0)[0], "bf16").to(DEV)
+    dYd = si.round_to(si.grad_output(N, m, 1e-2, seed=71), "bf16").to(DEV)
+    runs = []
+    for rep in range(2):
+        P, lp, s = ctx.fit_basis(Xd, k, r, seed=5, draw=2)
+        Cm = ctx.compress(Xd, P, P_lp=lp, layout=C_PACKED)
+        dW = ctx.weight_grad(Cm, dYd, P, k, r, s, P_lp=lp, layout=C_PACKED)
+        G = ctx.gram(Xd)
+        Xh = ctx.reconstruct(Cm, P, k, r, s, N=N, layout=C_PACKED)
+        ctx.sync_status()
+        runs.append((P.clone(), Cm.clone(), dW.clone(), G.clone(), Xh.clone()))
+        ctx.compress(dYd, torch.eye(m, 16, device=DEV))        # something else in between
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)
+
+
 # ------------------------------------------------- per-kernel timing hook
 def test_profile_hook_counts_selected_launches_only(ctx):
     N, d, c = 1024, 256, 64
