@@ -343,7 +343,7 @@ def main():
                     help="consecutive steps (independent batches) alternate over this many HIP streams, one library context "
                          "each, so that the small tail kernels of one step overlap the streaming kernels of the next; "
                          "1: everything on one stream; 0 (default): one or two, whichever a short trial after the warm-up "
-                         "finds faster for the workload")
+                         "finds faster for the workload (best of three runs of 24 steps each)")
     ap.add_argument("--refresh-every", type=int, default=0, help="override the refresh interval (0: the workload's, 500)")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="after the timed region, also run three plain device copies of this many MB "
@@ -603,7 +603,7 @@ def main():
     for n_try in ([1] if not side else ([1, len(side)] if args.streams == 0 else [len(side)])):
         use["n"] = n_try
         timed_run(trial_first, 2 * w["n_sets"])
-        trial_ms[n_try] = 1e3 * timed_run(trial_first, 16) / 16
+        trial_ms[n_try] = min(1e3 * timed_run(trial_first, 24) / 24 for _ in range(3))
     use["n"] = min(trial_ms, key=trial_ms.get)
     n_streams = max(use["n"], 1)
     elapsed = timed_run(W, args.steps)
