@@ -71,6 +71,8 @@ def algorithmic_bytes(kind: str, w: dict) -> float:
         return 4.0 * c * m + 2.0 * c * m
     if kind == "p_t":
         return 2.0 * (d * c + c * m + d * m)
+    if kind == "sum_p_t":           # slab sum and P T in one launch: the slabs are overhead, T never leaves the chip
+        return 2.0 * (d * c + d * m) + 4.0 * c * m
     if kind == "weight_grad":       # the whole weight gradient in one launch; the c x m intermediate is not counted
         return 2.0 * (N * c + N * m) + 2.0 * d * c + 2.0 * d * m
     raise KeyError(kind)
@@ -79,7 +81,7 @@ def algorithmic_bytes(kind: str, w: dict) -> float:
 def algorithmic_flops(kind: str, w: dict) -> float:
     N, d, m, c = w["N"], w["d"], w["m"], w["k"] + w["r"]
     return {"compress": 2.0 * N * d * c, "ct_dy": 2.0 * N * c * m, "t_reduce": float(c * m),
-            "p_t": 2.0 * d * c * m, "weight_grad": 2.0 * N * c * m + 2.0 * d * c * m}[kind]
+            "p_t": 2.0 * d * c * m, "sum_p_t": 2.0 * d * c * m + c * m, "weight_grad": 2.0 * N * c * m + 2.0 * d * c * m}[kind]
 
 
 def read_traffic(kind: str, workload: str):
@@ -433,7 +435,7 @@ def main():
         step(t)
     torch.cuda.synchronize()
     per_kernel_us = {}
-    for kind in ("compress", "weight_grad", "ct_dy", "t_reduce", "p_t"):
+    for kind in ("compress", "weight_grad", "ct_dy", "t_reduce", "p_t", "sum_p_t"):
         ctx.profile_select(KERNEL_KINDS[kind])
         for i in range(8):
             launches(i % w["n_sets"])

@@ -147,8 +147,10 @@ enum {
   PRAC_KERNEL_GRAM = 5,       /* X^T X partial sums */
   PRAC_KERNEL_FUSED_FWD = 6,  /* [Y | C] = X [W | P] */
   PRAC_KERNEL_RECONSTRUCT = 7, /* Xh = C Ps^T */
-  PRAC_KERNEL_WEIGHT_GRAD = 8  /* the whole weight gradient in one launch (PRAC_TUNE_WGRAD_ONE_LAUNCH): partial
+  PRAC_KERNEL_WEIGHT_GRAD = 8, /* the whole weight gradient in one launch (PRAC_TUNE_WGRAD_ONE_LAUNCH): partial
                                   sums of C^T dY, their sum T and dW = P T (kinds 2 - 4 then see no launch) */
+  PRAC_KERNEL_SUM_P_T = 9      /* slab reduction + scaling factor and dW = P T as one launch (PRAC_TUNE_WGRAD_TAIL;
+                                  kinds 3 and 4 then see no launch) */
 };
 int prac_profile_select(prac_ctx* ctx, int kind);
 int prac_profile_read(prac_ctx* ctx, double* total_ms, int64_t* launches);
@@ -163,8 +165,13 @@ int prac_profile_read_each(prac_ctx* ctx, float* each_ms, int64_t cap, int64_t* 
  * PRAC_TUNE_WGRAD_ONE_LAUNCH = 1: the bf16 weight gradient runs as one launch (the workgroups of a
  * column tile of T meet inside the kernel to sum their partial sums and to form dW = P T) instead of
  * three (partial sums, their reduction, P T); 0 restores the default.  Results are bit-identical; the
- * three launches are the faster of the two on an MI355X at every benchmarked shape. */
-enum { PRAC_TUNE_CTDY_SPLITS = 1, PRAC_TUNE_PROFILE_STRIDE = 2, PRAC_TUNE_WGRAD_ONE_LAUNCH = 3 };
+ * three launches are the faster of the two on an MI355X at every benchmarked shape.
+ * PRAC_TUNE_WGRAD_TAIL: what follows the partial sums of C^T dY in the bf16 weight gradient.  2: their
+ * reduction (with the scaling factor) and dW = P T run as one launch, T staying in LDS (for output widths
+ * that are multiples of 4 and token-range counts that are multiples of 4; other shapes keep the two
+ * launches); 1: as two launches with T (bf16, fragment order) in ctx scratch between them; 0 restores
+ * the built-in choice (one launch for k + r > 256).  Results are bit-identical. */
+enum { PRAC_TUNE_CTDY_SPLITS = 1, PRAC_TUNE_PROFILE_STRIDE = 2, PRAC_TUNE_WGRAD_ONE_LAUNCH = 3, PRAC_TUNE_WGRAD_TAIL = 4 };
 int prac_set_tuning(prac_ctx* ctx, int key, int value);
 
 /* ---- Gaussian draw (Eq. (S_o): S_ij ~ N(0,1) i.i.d.) -------------------- */

@@ -53,3 +53,31 @@ static __device__ __forceinline__ bf16x8 as_frag(u32x4 v) {
   c.u = v;
   return c.f;
 }
+
+// A kernel's arguments sit in memory no cache holds yet when its first waves start, and the compiler
+// fetches them where they are first used: a few dependent rounds of scalar loads, each to another
+// 64-byte line, each a full memory round trip before the first byte of data can be requested.  This
+// asks for one word of every line of the first BYTES argument bytes at once and waits for them: one
+// round trip, after which the compiler's own loads hit the scalar cache.  The workgroup index is handed
+// through, so that everything computed from it (all of a kernel's set-up) is ordered after the wait.
+template <int BYTES>
+static __device__ __forceinline__ int touch_kernel_args(int block_index) {
+  const auto ka = __builtin_amdgcn_kernarg_segment_ptr();
+  uint32_t t0, t1, t2, t3, t4, t5;
+  static_assert(BYTES > 0 && BYTES <= 384, "six lines at most");
+  constexpr int L1 = BYTES > 64 ? 64 : 0, L2 = BYTES > 128 ? 128 : 0, L3 = BYTES > 192 ? 192 : 0,
+                L4 = BYTES > 256 ? 256 : 0, L5 = BYTES > 320 ? 320 : 0;
+  asm volatile(
+      "s_load_dword %0, %7, 0x0\n"
+      "s_load_dword %1, %7, %8\n"
+      "s_load_dword %2, %7, %9\n"
+      "s_load_dword %3, %7, %10\n"
+      "s_load_dword %4, %7, %11\n"
+      "s_load_dword %5, %7, %12\n"
+      "s_waitcnt lgkmcnt(0)\n"
+      : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4), "=&s"(t5), "+s"(block_index)
+      : "s"(ka), "n"(L1), "n"(L2), "n"(L3), "n"(L4), "n"(L5)
+      : "memory");
+  return block_index;
+}
+

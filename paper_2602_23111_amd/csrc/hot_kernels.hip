@@ -555,6 +555,231 @@ __global__ __launch_bounds__(256) void pt_tiled_kernel(PtArgs a) {
   }
 }
 
+// ---------------------------------------------- dW = P (sum of the slabs), one launch
+// The slab sum and dW = P T as one kernel, without T ever leaving the compute unit: a workgroup owns
+// 32 columns of one output and a range of at most SP_RBW 32-row blocks of dW.  It sums the token-split
+// partial slabs of its 32 columns of T (in slab order, rows >= k_lo weighted by the scaling factor,
+// rounded to bf16: the same arithmetic in the same order as reduce_to_tfrag_kernel) into LDS in
+// fragment order, 256 rows of T at a time, and multiplies: each of the 8 waves holds up to two
+// 32 x 32 tiles of dW, the fragments of P come straight from L2 and are requested before the sum
+// starts.  The workgroups that share a column block (the row ranges) sum the same slabs again; they
+// sit next to each other on one XCD, so the slabs cross the fabric once and the repeats are L2 hits.
+// What this buys over the two kernels: one launch, and no round trip of T through memory between them.
+constexpr int SP_KC = 16;                   // k-blocks of T in LDS at a time
+constexpr int SP_RBW = 16;                  // 32-row blocks of dW per workgroup at most
+constexpr int SP_SLD = 36;                  // floats per row of a wave's 32 x 32 output staging tile
+constexpr int SP_T_BYTES = SP_KC * 1024;
+constexpr int SP_SMEM = SP_T_BYTES + 8 * 32 * SP_SLD * 4;
+constexpr int SP_ZB = 4;                    // slabs requested together
+
+struct SumPtArgs {
+  int n_out, splits, c, k_lo, nkb;
+  float scale_hi, beta;
+  const bf16_t* Pa;  // [nrb_pa][nkb][64][8]
+  int d, nrb_pa;
+  int row_parts, rb_per_part;
+  int cblks;         // 32-column blocks over all outputs
+  const float* slabs[PRAC_CTDY_MAX_OUT];  // [splits][c][m_h]
+  void* dW[PRAC_CTDY_MAX_OUT];
+  int64_t lddw[PRAC_CTDY_MAX_OUT];
+  int m[PRAC_CTDY_MAX_OUT];
+  int vec_ok[PRAC_CTDY_MAX_OUT];
+  int cblk0[PRAC_CTDY_MAX_OUT + 1];       // first column block of output h in the launch
+};
+
+template <bool OUT_BF16>
+__global__ __launch_bounds__(512) void sum_pt_kernel(SumPtArgs a) {
+  extern __shared__ __align__(16) unsigned char sp_smem[];
+  const int total = a.cblks * a.row_parts;
+  const int per_xcd = (total + 7) / 8;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int logical = xcd * per_xcd + slot;
+  if (slot >= per_xcd || logical >= total) return;
+  const int cbg = logical / a.row_parts, rp = logical % a.row_parts;
+  int h = 0;
+#pragma unroll
+  for (int q = 1; q < PRAC_CTDY_MAX_OUT; ++q)
+    if (q < a.n_out && cbg >= a.cblk0[q]) h = q;
+  const int n0 = (cbg - a.cblk0[h]) * 32;
+  const float* __restrict__ slabs = a.slabs[h];
+  const int mh = a.m[h], c = a.c, splits = a.splits, nkb = a.nkb;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 31, lh = lane >> 5;
+  const int nrb = (a.d + 31) / 32;
+  const int rb_end = min((rp + 1) * a.rb_per_part, nrb);
+  const int rbA = rp * a.rb_per_part + wave, rbB = rbA + 8;
+  const bool hasA = rbA < rb_end, hasB = rbB < rb_end;  // wave-uniform
+  const u32x4* __restrict__ PaA = reinterpret_cast<const u32x4*>(a.Pa) + (int64_t)min(rbA, a.nrb_pa - 1) * nkb * 64 + lane;
+  const u32x4* __restrict__ PaB = reinterpret_cast<const u32x4*>(a.Pa) + (int64_t)min(rbB, a.nrb_pa - 1) * nkb * 64 + lane;
+
+  f32x16 accA, accB;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) accA[v] = accB[v] = 0.f;
+
+  // summing: thread (pr, col4) takes rows 2 pr, 2 pr + 1 (+ 128) of the chunk and 4 columns
+  const int pr = tid >> 3, col4 = (tid & 7) * 4, n = n0 + col4;
+  const int64_t slab = (int64_t)c * mh;
+  const int nchunks = (nkb + SP_KC - 1) / SP_KC;
+#pragma nounroll
+  for (int ch = 0; ch < nchunks; ++ch) {
+    const int kb0 = ch * SP_KC;
+    // the fragments of P do not depend on T: the first tile's are requested before the sum starts, the
+    // second tile's once the sum's registers are free
+    u32x4 fa[SP_KC];
+#pragma unroll
+    for (int q = 0; q < SP_KC; ++q) fa[q] = PaA[(int64_t)min(kb0 + q, nkb - 1) * 64];
+    if (ch > 0) __syncthreads();  // the previous chunk of T has been multiplied
+    // rows kl, kl + 1 of the chunk, 4 columns: into fragment order (row 16 kb + 8 hh + e of T, column j ->
+    // lane 32 hh + j, element e; the two rows are the elements e, e + 1, e even, of one 32-bit word)
+    auto put = [&](int q2, float4 s0, float4 s1) {
+      const int kl = 128 * q2 + 2 * pr, k = kb0 * 16 + kl;
+      if (k >= c || n >= mh) s0 = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (k + 1 >= c || n >= mh) s1 = make_float4(0.f, 0.f, 0.f, 0.f);
+      const float w0 = k >= a.k_lo ? a.scale_hi : 1.f, w1 = k + 1 >= a.k_lo ? a.scale_hi : 1.f;
+      unsigned char* t = sp_smem + (kl >> 4) * 1024 + (((kl >> 3) & 1) * 32 + col4) * 16 + ((kl & 7) >> 1) * 4;
+      *reinterpret_cast<uint32_t*>(t) = pack2_hw(s0.x * w0, s1.x * w1);
+      *reinterpret_cast<uint32_t*>(t + 16) = pack2_hw(s0.y * w0, s1.y * w1);
+      *reinterpret_cast<uint32_t*>(t + 32) = pack2_hw(s0.z * w0, s1.z * w1);
+      *reinterpret_cast<uint32_t*>(t + 48) = pack2_hw(s0.w * w0, s1.w * w1);
+    };
+    {
+      // SP_ZB slabs of a row pair per batch, the next batch requested before this one is summed, so that
+      // the memory round trips of a thread's 4 x splits loads overlap (the launcher sends only column
+      // counts that are multiples of 4 and slab counts that are multiples of SP_ZB here).  Threads whose
+      // rows or columns lie outside T read a valid element instead and store zeros.
+      const int nzf = splits / SP_ZB, nb = 2 * nzf;
+      const int k0 = kb0 * 16 + 2 * pr, k1 = k0 + 128;
+      const float* const pb0 = slabs + (int64_t)min(k0, c - 1) * mh + min(n, mh - 4);
+      const float* const pb1 = slabs + (int64_t)min(k1, c - 1) * mh + min(n, mh - 4);
+      const int64_t st0 = k0 + 1 < c ? mh : 0, st1 = k1 + 1 < c ? mh : 0;
+      auto issue = [&](int b, float4 (&v0)[SP_ZB], float4 (&v1)[SP_ZB]) {
+        const bool hi = b >= nzf;
+        const float* p0 = (hi ? pb1 : pb0) + (int64_t)((hi ? b - nzf : b) * SP_ZB) * slab;
+        const float* p1 = p0 + (hi ? st1 : st0);
+#pragma unroll
+        for (int z = 0; z < SP_ZB; ++z) {
+          v0[z] = *reinterpret_cast<const float4*>(p0 + z * slab);
+          v1[z] = *reinterpret_cast<const float4*>(p1 + z * slab);
+        }
+      };
+      float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0;
+      auto add = [&](int b, const float4 (&v0)[SP_ZB], const float4 (&v1)[SP_ZB]) {
+#pragma unroll
+        for (int z = 0; z < SP_ZB; ++z) {
+          s0.x += v0[z].x; s0.y += v0[z].y; s0.z += v0[z].z; s0.w += v0[z].w;
+          s1.x += v1[z].x; s1.y += v1[z].y; s1.z += v1[z].z; s1.w += v1[z].w;
+        }
+        if (b == nzf - 1 || b == nb - 1) {  // the row pair's last batch
+          put(b >= nzf ? 1 : 0, s0, s1);
+          s0 = make_float4(0.f, 0.f, 0.f, 0.f);
+          s1 = s0;
+        }
+      };
+      float4 va0[SP_ZB], va1[SP_ZB], vb0[SP_ZB], vb1[SP_ZB];
+      issue(0, va0, va1);
+#pragma nounroll
+      for (int b = 0; b < nb; b += 2) {
+        issue(b + 1, vb0, vb1);
+        add(b, va0, va1);
+        issue(min(b + 2, nb - 1), va0, va1);  // past the end: the last batch again, not summed
+        add(b + 1, vb0, vb1);
+      }
+    }
+    __syncthreads();
+    {
+      u32x4 fb[SP_KC];
+      if (hasB) {
+#pragma unroll
+        for (int q = 0; q < SP_KC; ++q) fb[q] = PaB[(int64_t)min(kb0 + q, nkb - 1) * 64];
+      }
+      // all SP_KC k-blocks of the chunk, also past the last row of T: those fragments of T are zeros
+      // (put), the fragments of P repeat the last k-block
+      if (hasA) {
+#pragma unroll
+        for (int q = 0; q < SP_KC; ++q)
+          accA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              as_frag(fa[q]), as_frag(*reinterpret_cast<const u32x4*>(sp_smem + q * 1024 + lane * 16)), accA, 0, 0, 0);
+      }
+      if (hasB) {
+#pragma unroll
+        for (int q = 0; q < SP_KC; ++q)
+          accB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              as_frag(fb[q]), as_frag(*reinterpret_cast<const u32x4*>(sp_smem + q * 1024 + lane * 16)), accB, 0, 0, 0);
+      }
+    }
+  }
+
+  // register v of lane (li, lh) is row 8 (v / 4) + 4 lh + v % 4, column li of the tile: through this
+  // wave's own LDS tile, so that the stores are 16 bytes per lane along rows
+  float* stage = reinterpret_cast<float*>(sp_smem + SP_T_BYTES) + wave * (32 * SP_SLD);
+  void* const odW = a.dW[h];
+  const int64_t olddw = a.lddw[h];
+  const int ovec = a.vec_ok[h];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    if (!(t == 0 ? hasA : hasB)) continue;
+    const f32x16& acc = t == 0 ? accA : accB;
+    const int row0 = (t == 0 ? rbA : rbB) * 32;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) stage[(8 * (v / 4) + 4 * lh + (v % 4)) * SP_SLD + li] = acc[v];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (OUT_BF16) {
+      const int er = lane >> 2, ec = (lane & 3) * 8;  // 4 lanes per row (16 bytes each), 16 rows per pass
+#pragma unroll
+      for (int p = 0; p < 2; ++p) {
+        const int row = er + 16 * p, grow = row0 + row, gcol = n0 + ec;
+        const float4 lo = *reinterpret_cast<const float4*>(stage + row * SP_SLD + ec);
+        const float4 hi = *reinterpret_cast<const float4*>(stage + row * SP_SLD + ec + 4);
+        if (grow >= a.d || gcol >= mh) continue;
+        float x[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        bf16_t* o = reinterpret_cast<bf16_t*>(odW) + (int64_t)grow * olddw + gcol;
+        if (ovec && gcol + 8 <= mh) {
+          if (a.beta != 0.f) {
+            const u32x4 old = *reinterpret_cast<const u32x4*>(o);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              x[e] += a.beta * __uint_as_float(((e & 1) ? (old[e >> 1] >> 16) : (old[e >> 1] & 0xFFFFu)) << 16);
+          }
+          u32x4 w;
+          w.x = pack2_hw(x[0], x[1]);
+          w.y = pack2_hw(x[2], x[3]);
+          w.z = pack2_hw(x[4], x[5]);
+          w.w = pack2_hw(x[6], x[7]);
+          *reinterpret_cast<u32x4*>(o) = w;
+        } else {
+          for (int e = 0; e < 8 && gcol + e < mh; ++e)
+            o[e] = f32_to_bf16(a.beta == 0.f ? x[e] : x[e] + a.beta * __uint_as_float(((uint32_t)o[e]) << 16));
+        }
+      }
+    } else {
+      const int er = lane >> 3, ec = (lane & 7) * 4;  // 8 lanes per row (16 bytes each), 8 rows per pass
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int row = er + 8 * p, grow = row0 + row, gcol = n0 + ec;
+        float4 x = *reinterpret_cast<const float4*>(stage + row * SP_SLD + ec);
+        if (grow >= a.d || gcol >= mh) continue;
+        float* o = reinterpret_cast<float*>(odW) + (int64_t)grow * olddw + gcol;
+        if (ovec && gcol + 4 <= mh) {
+          if (a.beta != 0.f) {
+            const float4 old = *reinterpret_cast<const float4*>(o);
+            x.x += a.beta * old.x; x.y += a.beta * old.y; x.z += a.beta * old.z; x.w += a.beta * old.w;
+          }
+          *reinterpret_cast<float4*>(o) = x;
+        } else {
+          const float xs[4] = {x.x, x.y, x.z, x.w};
+          for (int e = 0; e < 4 && gcol + e < mh; ++e) o[e] = a.beta == 0.f ? xs[e] : xs[e] + a.beta * o[e];
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
 inline int grid_for(int64_t n, int n_cu) {
   int64_t g = (n + 255) / 256;
   const int64_t cap = (int64_t)n_cu * 8;
@@ -681,3 +906,64 @@ int launch_pt(prac_ctx* ctx, const bf16_t* Pa, int n_out, const bf16_t* const* T
   PRAC_HIP_TRY(ctx, hipGetLastError());
   return PRAC_OK;
 }
+
+// Row ranges of the one-launch slab sum + P T: at most SP_RBW 32-row blocks per workgroup; more, smaller
+// ranges when the launch would otherwise leave compute units idle (the repeated slab sums are cheap then).
+int sum_pt_row_parts(int n_cu, int d, int n_out, const int* m) {
+  const int nrb = (d + 31) / 32;
+  int cblks = 0;
+  for (int h = 0; h < n_out; ++h) cblks += (m[h] + 31) / 32;
+  int parts = (nrb + SP_RBW - 1) / SP_RBW;
+  const int fill = n_cu / (cblks > 0 ? cblks : 1);
+  if (fill > parts) parts = fill < nrb ? fill : nrb;
+  return parts;
+}
+
+// The one-launch form covers column counts that are multiples of 4 (16-byte slab loads) and slab counts that
+// are multiples of SP_ZB (whole batches); everything else runs as the two launches.
+bool sum_pt_eligible(int n_out, const int* m, int splits) {
+  if (n_out < 1 || n_out > PRAC_CTDY_MAX_OUT || splits < SP_ZB || splits % SP_ZB != 0) return false;
+  for (int h = 0; h < n_out; ++h)
+    if (m[h] < 4 || (m[h] & 3) != 0) return false;
+  return true;
+}
+
+int launch_sum_pt(prac_ctx* ctx, const bf16_t* Pa, int n_out, const float* const* slabs, int splits, int c, int k_lo,
+                  float scale_hi, int nkb, int d, const int* m, void* const* dW, const int64_t* lddw, bool out_bf16,
+                  float beta) {
+  if (!sum_pt_eligible(n_out, m, splits)) return PRAC_EINVAL;
+  SumPtArgs a{};
+  a.n_out = n_out; a.splits = splits; a.c = c; a.k_lo = k_lo; a.nkb = nkb; a.scale_hi = scale_hi; a.beta = beta;
+  a.Pa = Pa; a.d = d; a.nrb_pa = ((d + 127) / 128) * 4;
+  const int nrb = (d + 31) / 32;
+  const int parts = sum_pt_row_parts(ctx->n_cu, d, n_out, m);
+  a.rb_per_part = (nrb + parts - 1) / parts;
+  a.row_parts = (nrb + a.rb_per_part - 1) / a.rb_per_part;
+  if (a.rb_per_part > SP_RBW) return PRAC_EINVAL;
+  int cblks = 0;
+  for (int h = 0; h < n_out; ++h) {
+    a.slabs[h] = slabs[h]; a.dW[h] = dW[h]; a.lddw[h] = lddw[h]; a.m[h] = m[h];
+    a.vec_ok[h] = (reinterpret_cast<uintptr_t>(dW[h]) % 16 == 0 && lddw[h] % (out_bf16 ? 8 : 4) == 0) ? 1 : 0;
+    a.cblk0[h] = cblks;
+    cblks += (m[h] + 31) / 32;
+  }
+  for (int h = n_out; h <= PRAC_CTDY_MAX_OUT; ++h) a.cblk0[h] = cblks;
+  a.cblks = cblks;
+  const int64_t total = (int64_t)cblks * a.row_parts;
+  if (total > (1 << 28)) return PRAC_EINVAL;
+  const dim3 grid((unsigned)(((total + 7) / 8) * 8)), block(512);
+  static bool done_dev[PRAC_MAX_DEVICES][2] = {};
+  bool* done = done_dev[ctx->device % PRAC_MAX_DEVICES];
+  if (out_bf16) {
+    int rc = set_smem(ctx, sum_pt_kernel<true>, (size_t)SP_SMEM, done[1]);
+    if (rc) return rc;
+    PRAC_LAUNCH(ctx, sum_pt_kernel<true>, grid, block, (size_t)SP_SMEM, a);
+  } else {
+    int rc = set_smem(ctx, sum_pt_kernel<false>, (size_t)SP_SMEM, done[0]);
+    if (rc) return rc;
+    PRAC_LAUNCH(ctx, sum_pt_kernel<false>, grid, block, (size_t)SP_SMEM, a);
+  }
+  PRAC_HIP_TRY(ctx, hipGetLastError());
+  return PRAC_OK;
+}
+

@@ -257,6 +257,7 @@ int prac_create(prac_ctx** out, int device, void* hip_stream) {
   c->ev_stop = nullptr;
   c->tune_splits = 0;
   c->tune_one_launch = 0;
+  c->tune_tail = 0;
   c->d_sync = nullptr;
   hipDeviceProp_t prop;
   c->n_cu = (hipGetDeviceProperties(&prop, device) == hipSuccess) ? prop.multiProcessorCount : 256;
@@ -332,7 +333,7 @@ int prac_sync_status(prac_ctx* ctx) {
 int prac_last_hip_error(const prac_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
 
 int prac_profile_select(prac_ctx* ctx, int kind) {
-  if (kind < PRAC_KERNEL_NONE || kind > PRAC_KERNEL_WEIGHT_GRAD) return PRAC_EINVAL;
+  if (kind < PRAC_KERNEL_NONE || kind > PRAC_KERNEL_SUM_P_T) return PRAC_EINVAL;
   if (!ctx) return PRAC_ENOCTX;
   ctx->prof_kind = kind;
   ctx->prof_seen = 0;
@@ -344,6 +345,11 @@ int prac_set_tuning(prac_ctx* ctx, int key, int value) {
     if (value < 0 || value > 1024) return PRAC_EINVAL;
     if (!ctx) return PRAC_ENOCTX;
     ctx->prof_stride = value < 1 ? 1 : value;
+    return PRAC_OK;
+  }
+  if (key == PRAC_TUNE_WGRAD_TAIL) {
+    if (value < 0 || value > 2) return PRAC_EINVAL;
+    ctx->tune_tail = value;
     return PRAC_OK;
   }
   if (key == PRAC_TUNE_WGRAD_ONE_LAUNCH) {
@@ -735,6 +741,16 @@ int weight_grad_fast(prac_ctx* ctx, char* ws, int* cnt, const WgradPlan& q, cons
     rc = launch_ctdy_ws(ctx, Cpk, c, (int)N, n_out, dYp, lddy, mi, part, splits);
   }
   if (rc) return rc;
+  // Slab sum, scaling factor and dW_h = P T_h in one launch where that is the faster form: measured on an
+  // MI355X it is for c > 256 (rank 512 + 512 at d = m = 2048: 159 against 179 us per weight gradient), where
+  // the two launches move a large T through memory and run the LDS-staged product; at c <= 256 the two
+  // small launches overlap each other's start and end and win (61.6 against 66.8 us at the same d, m).
+  const bool tail_one = ctx->tune_tail == 2 || (ctx->tune_tail == 0 && l.nckb > 16);
+  if (tail_one && sum_pt_eligible(n_out, mi, splits)) {
+    ProfScope ps(ctx, PRAC_KERNEL_SUM_P_T);
+    return launch_sum_pt(ctx, reinterpret_cast<const bf16_t*>(lp + l.off_pa), n_out, part, splits, c, k, scale, l.nckb,
+                         (int)d, mi, dW, lddw, odt == PRAC_BF16, beta);
+  }
   {  // T_h in fragment order (bf16): slabs summed, random rows weighted by the scaling factor
     ProfScope ps(ctx, PRAC_KERNEL_T_REDUCE);
     rc = launch_reduce_to_tfrag(ctx, n_out, part, splits, c, mi, k, scale, l.nckb, q.nmb, Tf);

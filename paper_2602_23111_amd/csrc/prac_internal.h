@@ -26,6 +26,7 @@ struct prac_ctx {
   int n_cu;
   int tune_splits;    // > 0: override the token-split count of C^T dY (tuning hook)
   int tune_one_launch;  // 1: the bf16 weight gradient as one launch instead of three (slabs, reduction, P T)
+  int tune_tail;        // after the slabs of C^T dY: 0 built-in choice, 1 slab sum and P T as two launches, 2 as one
   int* d_sync;        // PRAC_SYNC_TILES x 3 counters of the one-launch weight gradient (zero between launches)
   int prof_kind;      // kernel kind bracketed by events (0: none), see prac_profile_select
   int prof_stride;    // every prof_stride-th launch of that kind carries the event pair
@@ -157,6 +158,13 @@ int launch_pack_pafrag(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, in
 // dW_h (d x m_h) = P T_h (+ beta dW_h) for n_out <= PRAC_CTDY_MAX_OUT outputs in one launch
 int launch_pt(prac_ctx* ctx, const bf16_t* Pa, int n_out, const bf16_t* const* Tf, int d, const int* m, int nkb,
               const int* nmb, void* const* dW, const int64_t* lddw, bool out_bf16, float beta);
+
+// dW_h (d x m_h) = P (scaled sum of the slabs of C^T dY_h) (+ beta dW_h) in one launch: the slab reduction and
+// launch_pt without T passing through memory; same arithmetic in the same order, bit-identical results
+bool sum_pt_eligible(int n_out, const int* m, int splits);  // shapes the one-launch form covers
+int launch_sum_pt(prac_ctx* ctx, const bf16_t* Pa, int n_out, const float* const* slabs, int splits, int c, int k_lo,
+                  float scale_hi, int nkb, int d, const int* m, void* const* dW, const int64_t* lddw, bool out_bf16,
+                  float beta);
 
 // P (d x c fp32, ldp) -> B operand of Xh = C Ps^T in fragment order [nkb][ncb][64][8] (bf16, zero padded):
 // element (k = column of P, n = row of P) = P[n][k] * (k >= k_lo ? scale_hi : 1)

@@ -200,11 +200,12 @@ __device__ __forceinline__ void drain_mfma(f32x16 (&acc)[NACC], u32x4 (&ring)[8]
 template <int FN, int NCH, int NIF>
 __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int bid = touch_kernel_args<sizeof(CompressWsArgs)>(blockIdx.x);
 
   // XCD-aware order: consecutive logical tiles (same rows, next column group) on one XCD
   const int total = a.tiles_m * a.col_groups;
   const int per_xcd = (total + 7) / 8;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int xcd = bid & 7, slot = bid >> 3;
   const int logical = xcd * per_xcd + slot;
   if (slot >= per_xcd || logical >= total) return;
   const int cg = logical % a.col_groups, tm = logical / a.col_groups;
@@ -1112,13 +1113,14 @@ __device__ __forceinline__ void wgrad_tail(const CtdyWsArgs& a, unsigned char* s
 template <int MODE>
 __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int bid = touch_kernel_args<(MODE == 0 ? offsetof(CtdyWsArgs, cnt) : sizeof(CtdyWsArgs))>(blockIdx.x);
 
   int tn, rg, split;
   if constexpr (MODE == 0) {
     const int per_split = a.tiles_n * a.row_groups;
     const int total = per_split * a.splits;
     const int per_xcd = (total + 7) / 8;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int xcd = bid & 7, slot = bid >> 3;
     const int logical = xcd * per_xcd + slot;
     if (slot >= per_xcd || logical >= total) return;
     tn = logical % a.tiles_n;
@@ -1128,7 +1130,7 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
     // the workgroups of a column tile (its token ranges and row groups) take neighbouring slots of one XCD
     const int members = a.splits * a.row_groups;
     const int per_xcd = a.groups_per_xcd * members;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int xcd = bid & 7, slot = bid >> 3;
     tn = xcd * a.groups_per_xcd + slot / members;
     if (slot >= per_xcd || tn >= a.tiles_n) return;
     const int member = slot % members;

@@ -17,9 +17,9 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libprac.so
 PRAC_F32, PRAC_BF16 = 0, 1
 PRAC_REFRESH_PRINCIPAL, PRAC_REFRESH_RANDOM = 1, 2
 C_ROWMAJOR, C_PACKED = 0, 1
-TUNE_CTDY_SPLITS, TUNE_PROFILE_STRIDE, TUNE_WGRAD_ONE_LAUNCH = 1, 2, 3
+TUNE_CTDY_SPLITS, TUNE_PROFILE_STRIDE, TUNE_WGRAD_ONE_LAUNCH, TUNE_WGRAD_TAIL = 1, 2, 3, 4
 KERNEL_KINDS = {"compress": 1, "ct_dy": 2, "t_reduce": 3, "p_t": 4, "gram": 5, "fused_fwd": 6, "reconstruct": 7,
-                "weight_grad": 8}
+                "weight_grad": 8, "sum_p_t": 9}
 STATUS = {0: "PRAC_OK", -1: "PRAC_EINVAL", -2: "PRAC_ENOMEM", -3: "PRAC_EHIP",
           -4: "PRAC_ENUMERIC", -5: "PRAC_EUNSUPPORTED", -6: "PRAC_ENOCTX", -7: "PRAC_ETOOBIG"}
 STATIC_SCRATCH_BYTES = 48 << 20

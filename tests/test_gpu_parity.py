@@ -350,6 +350,60 @@ def test_weight_grad_one_launch_equals_three_launches(ctx, N, d, ms, k, r, odt, 
         assert rel_fro(si.as_f64(out), ref) < 1e-2
 
 
+@pytest.mark.parametrize("N,d,ms,k,r,odt,beta,splits", [
+    (3000, 328, [264], 40, 32, "f32", 0.0, 4),      # ragged rows (328 = 10 row blocks + 8) and columns (264 = 8 blocks + 8)
+    (4096, 512, [640], 32, 32, "bf16", 0.0, 8),
+    (900, 320, [520], 130, 130, "bf16", 0.5, 4),    # c = 260: 17 k-blocks of T, two chunks in LDS
+    (1500, 300, [204], 150, 140, "f32", 0.25, 4),   # 290 rows of T in two chunks, ragged column block
+    (5000, 1100, [96], 10, 23, "f32", 0.0, 12),     # 35 row blocks of dW: several row ranges per column block
+    (2048, 256, [200, 72, 136], 24, 40, "bf16", 0.0, 8),   # three outputs sharing C
+    (2100, 64, [40], 4, 4, "f32", 0.0, 8),          # one k-block; the last two token ranges are empty
+    (2048, 2048, [2048], 128, 128, "bf16", 0.0, 0), # the headline layer on a short batch: 16 row blocks per workgroup
+])
+def test_weight_grad_tail_one_launch_equals_two(ctx, N, d, ms, k, r, odt, beta, splits):
+    """After the partial sums of C^T dY: their reduction and dW = P T as one launch (T never leaves LDS)
+    against the two launches with T in scratch between them.  Same sums in the same order, so equal bit
+    for bit; the two-launch result is compared with the oracle.  The one-launch form takes token-range
+    counts that are multiples of 4, so the count is set here (0: the built-in choice, 8 at that shape)."""
+    from paper_2602_23111_amd.prac import C_PACKED, KERNEL_KINDS, TUNE_CTDY_SPLITS, TUNE_WGRAD_TAIL
+    c = k + r
+    s = orc.scaling_factor(d, k, r)
+    X64, _ = si.activation(N, d, 0.8, seed=N + d)
+    P32, P64 = basis32(d, c, seed=k + 3 * r)
+    Ct = si.round_to(orc.compress(X64, P64), "bf16")
+    Cpk = pack_c_reference(Ct).to(DEV)
+    ld8 = lambda n: (n + 7) // 8 * 8
+    dYs = [dev_padded(si.round_to(si.grad_output(N, m, 1e-2, seed=m + 7), "bf16"), ld8(m)) for m in ms]
+    Pd = P32.to(DEV)
+    lp = ctx.pack_basis(Pd)
+    torch.manual_seed(6)
+    base = [torch.randn((d, m), dtype=TORCH_DT[odt], device=DEV) * 1e-2 for m in ms]
+
+    def run(mode):
+        ctx.set_tuning(TUNE_WGRAD_TAIL, mode)
+        outs = [b.clone() for b in base]
+        ctx.weight_grad_shared(Cpk, dYs, Pd, k, r, s, P_lp=lp, outs=outs, beta=beta, layout=C_PACKED)
+        ctx.sync_status()
+        return outs
+
+    try:
+        ctx.set_tuning(TUNE_CTDY_SPLITS, splits)
+        two = run(1)
+        ctx.profile_select(KERNEL_KINDS["sum_p_t"])
+        one = run(2)
+        _, launches = ctx.profile_read()
+    finally:
+        ctx.profile_select(0)
+        ctx.set_tuning(TUNE_WGRAD_TAIL, 0)
+        ctx.set_tuning(TUNE_CTDY_SPLITS, 0)
+    assert launches == 1                      # the one-launch form did run
+    for a, b in zip(one, two):
+        assert torch.equal(a, b)
+    for dYh, out, b in zip(dYs, two, base):
+        ref = orc.weight_grad(si.as_f64(Ct), si.as_f64(dYh), P64, k, s) + beta * si.as_f64(b)
+        assert rel_fro(si.as_f64(out), ref) < 1e-2
+
+
 def test_weight_grad_exact_gradient_when_complement_is_full(ctx):
     # r = d - k: the estimator is the plain X^T dY (Lemma 1), whatever the basis
     N, d, m, k = 600, 64, 40, 24
