@@ -164,8 +164,9 @@ struct ReduceTfArgs {
 
 __global__ __launch_bounds__(256) void reduce_to_tfrag_kernel(ReduceTfArgs a) {
   __shared__ float patch[16][68];
+  const int bid = touch_kernel_args<sizeof(ReduceTfArgs)>(blockIdx.x);
   const int pairs = a.pair0[a.n_out];
-  const int kb = blockIdx.x / pairs, gp = blockIdx.x % pairs;
+  const int kb = bid / pairs, gp = bid % pairs;
   int h = 0;
 #pragma unroll
   for (int q = 1; q < PRAC_CTDY_MAX_OUT; ++q)
@@ -273,9 +274,10 @@ constexpr int PT_PD = 16;
 constexpr int PT_TLD = 128 + 4;  // floats per row of the output staging tile
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
+  const int bid = touch_kernel_args<sizeof(PtArgs)>(blockIdx.x);
   const int total = a.tiles_m * a.tiles_n;
   const int per_xcd = (total + 7) / 8;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int xcd = bid & 7, slot = bid >> 3;
   const int logical = xcd * per_xcd + slot;
   if (slot >= per_xcd || logical >= total) return;
   const int tn_g = logical % a.tiles_n, tm = logical / a.tiles_n;
@@ -414,9 +416,10 @@ __global__ __launch_bounds__(256) void pt_tiled_kernel(PtArgs a) {
   constexpr int A_LD = A_BYTES / 4096, B_LD = B_BYTES / 4096;  // 16-byte loads per thread and chunk
   extern __shared__ __align__(16) unsigned char pt_smem[];
 
+  const int bid = touch_kernel_args<sizeof(PtArgs)>(blockIdx.x);
   const int total = a.tiles_m * a.tiles_n;
   const int per_xcd = (total + 7) / 8;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int xcd = bid & 7, slot = bid >> 3;
   const int logical = xcd * per_xcd + slot;
   if (slot >= per_xcd || logical >= total) return;
   const int tn_g = logical % a.tiles_n, tm = logical / a.tiles_n;
@@ -590,9 +593,10 @@ struct SumPtArgs {
 template <bool OUT_BF16>
 __global__ __launch_bounds__(512) void sum_pt_kernel(SumPtArgs a) {
   extern __shared__ __align__(16) unsigned char sp_smem[];
+  const int bid = touch_kernel_args<sizeof(SumPtArgs)>(blockIdx.x);
   const int total = a.cblks * a.row_parts;
   const int per_xcd = (total + 7) / 8;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int xcd = bid & 7, slot = bid >> 3;
   const int logical = xcd * per_xcd + slot;
   if (slot >= per_xcd || logical >= total) return;
   const int cbg = logical / a.row_parts, rp = logical % a.row_parts;

@@ -537,8 +537,9 @@ constexpr int RW_SMEM = WS_STAGE + WS_BM * RW_OLD;
 
 __global__ __launch_bounds__(512) void reconstruct_ws_kernel(ReconWsArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int bid = touch_kernel_args<sizeof(ReconWsArgs)>(blockIdx.x);
   const int per_xcd = (a.tiles_m + 7) / 8;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int xcd = bid & 7, slot = bid >> 3;
   const int tm = xcd * per_xcd + slot;
   if (slot >= per_xcd || tm >= a.tiles_m) return;
   const int tid = threadIdx.x;
