@@ -10,6 +10,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // memcpy, which keeps whole register sets in scratch memory)
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 static __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   // round to nearest even; NaN keeps its payload's top bits and is made quiet (branch-free)
@@ -43,6 +44,17 @@ static __device__ __forceinline__ u32x4 keep_first(u32x4 v, int n) {
   v.z &= (n > 4 ? 0x0000FFFFu : 0u) | (n > 5 ? 0xFFFF0000u : 0u);
   v.w &= (n > 6 ? 0x0000FFFFu : 0u) | (n > 7 ? 0xFFFF0000u : 0u);
   return v;
+}
+
+// Output a kernel does not read again is stored with the non-temporal hint: it streams out to memory
+// instead of staying dirty in L2 until the write-back at the kernel's end, behind which the kernel's
+// completion waits (measured at N = 32768, d = m = 2048: 2 us per step for the 17 MB of C, 1 us for dW;
+// the 134 MB of the reconstruction are the opposite case, 54 against 46 us, and keep plain stores).
+// Inputs that are read once (X, dY, the partial sums) are loaded with the same hint, which keeps the
+// operand every workgroup shares (P, C) in L2.
+template <typename V>
+static __device__ __forceinline__ void stream_store(V* dst, V v) {
+  __builtin_nontemporal_store(v, dst);
 }
 
 static __device__ __forceinline__ bf16x8 as_frag(u32x4 v) {

@@ -184,7 +184,8 @@ __global__ __launch_bounds__(256) void reduce_to_tfrag_kernel(ReduceTfArgs a) {
     if (n + 3 < m && (m & 3) == 0) {
 #pragma unroll 8
       for (int z = 0; z < splits; ++z) {
-        const float4 v = *reinterpret_cast<const float4*>(p + z * slab);
+        // read once
+        const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p + z * slab));
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
       }
     } else {
@@ -369,7 +370,7 @@ __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
         o.y = pack2_hw(x[2], x[3]);
         o.z = pack2_hw(x[4], x[5]);
         o.w = pack2_hw(x[6], x[7]);
-        *reinterpret_cast<u32x4*>(q) = o;
+        stream_store(reinterpret_cast<u32x4*>(q), o);
       } else {
         for (int e = 0; e < 8 && gcol + e < om; ++e)
           q[e] = f32_to_bf16(a.beta == 0.f ? x[e] : x[e] + a.beta * __uint_as_float(((uint32_t)q[e]) << 16));
@@ -390,7 +391,7 @@ __global__ __launch_bounds__(256) void pt_kernel(PtArgs a) {
           const float4 old = *reinterpret_cast<const float4*>(q);
           x.x += a.beta * old.x; x.y += a.beta * old.y; x.z += a.beta * old.z; x.w += a.beta * old.w;
         }
-        *reinterpret_cast<float4*>(q) = x;
+        stream_store(reinterpret_cast<f32x4_t*>(q), f32x4_t{x.x, x.y, x.z, x.w});
       } else {
         const float xs[4] = {x.x, x.y, x.z, x.w};
         for (int e = 0; e < 4 && gcol + e < om; ++e) q[e] = a.beta == 0.f ? xs[e] : xs[e] + a.beta * q[e];
@@ -535,7 +536,7 @@ __global__ __launch_bounds__(256) void pt_tiled_kernel(PtArgs a) {
           w.y = pack2_hw(x[2], x[3]);
           w.z = pack2_hw(x[4], x[5]);
           w.w = pack2_hw(x[6], x[7]);
-          *reinterpret_cast<u32x4*>(o) = w;
+          stream_store(reinterpret_cast<u32x4*>(o), w);
         } else {
           for (int e = 0; e < 8 && gcol + e < om; ++e)
             o[e] = f32_to_bf16(a.beta == 0.f ? x[e] : x[e] + a.beta * __uint_as_float(((uint32_t)o[e]) << 16));
@@ -548,8 +549,8 @@ __global__ __launch_bounds__(256) void pt_tiled_kernel(PtArgs a) {
             x[0] += a.beta * o0.x; x[1] += a.beta * o0.y; x[2] += a.beta * o0.z; x[3] += a.beta * o0.w;
             x[4] += a.beta * o1.x; x[5] += a.beta * o1.y; x[6] += a.beta * o1.z; x[7] += a.beta * o1.w;
           }
-          *reinterpret_cast<float4*>(o) = make_float4(x[0], x[1], x[2], x[3]);
-          *reinterpret_cast<float4*>(o + 4) = make_float4(x[4], x[5], x[6], x[7]);
+          stream_store(reinterpret_cast<f32x4_t*>(o), f32x4_t{x[0], x[1], x[2], x[3]});
+          stream_store(reinterpret_cast<f32x4_t*>(o + 4), f32x4_t{x[4], x[5], x[6], x[7]});
         } else {
           for (int e = 0; e < 8 && gcol + e < om; ++e) o[e] = a.beta == 0.f ? x[e] : x[e] + a.beta * o[e];
         }
@@ -752,7 +753,7 @@ __global__ __launch_bounds__(512) void sum_pt_kernel(SumPtArgs a) {
           w.y = pack2_hw(x[2], x[3]);
           w.z = pack2_hw(x[4], x[5]);
           w.w = pack2_hw(x[6], x[7]);
-          *reinterpret_cast<u32x4*>(o) = w;
+          stream_store(reinterpret_cast<u32x4*>(o), w);
         } else {
           for (int e = 0; e < 8 && gcol + e < mh; ++e)
             o[e] = f32_to_bf16(a.beta == 0.f ? x[e] : x[e] + a.beta * __uint_as_float(((uint32_t)o[e]) << 16));
@@ -771,7 +772,7 @@ __global__ __launch_bounds__(512) void sum_pt_kernel(SumPtArgs a) {
             const float4 old = *reinterpret_cast<const float4*>(o);
             x.x += a.beta * old.x; x.y += a.beta * old.y; x.z += a.beta * old.z; x.w += a.beta * old.w;
           }
-          *reinterpret_cast<float4*>(o) = x;
+          stream_store(reinterpret_cast<f32x4_t*>(o), f32x4_t{x.x, x.y, x.z, x.w});
         } else {
           const float xs[4] = {x.x, x.y, x.z, x.w};
           for (int e = 0; e < 4 && gcol + e < mh; ++e) o[e] = a.beta == 0.f ? xs[e] : xs[e] + a.beta * o[e];

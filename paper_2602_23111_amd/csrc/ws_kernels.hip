@@ -253,8 +253,8 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
       const bool live = kt < nk;
 #pragma unroll
       for (int j = 0; j < CR; ++j)
-        ra[Q * CR + j] =
-            *reinterpret_cast<const u32x4*>(xbase + (live ? roff[Q * CR + j] + kb : roff[0] + (uint32_t)ccol * 2u));
+        ra[Q * CR + j] = __builtin_nontemporal_load(
+            reinterpret_cast<const u32x4*>(xbase + (live ? roff[Q * CR + j] + kb : roff[0] + (uint32_t)ccol * 2u)));
     };
     // chunk g -> stage (g / NCH) % 2; columns past d are zeroed (only the last tile has any)
     auto cstore = [&](int g, auto qc) {
@@ -398,7 +398,7 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
             o.y = pack2_hw(x[2], x[3]);
             o.z = pack2_hw(x[4], x[5]);
             o.w = pack2_hw(x[6], x[7]);
-            Cp[((int64_t)gtb * a.ccb + cb) * 64 + lane] = o;
+            stream_store(&Cp[((int64_t)gtb * a.ccb + cb) * 64 + lane], o);
           }
         }
       }
@@ -619,7 +619,7 @@ __global__ __launch_bounds__(512) void reconstruct_ws_kernel(ReconWsArgs a) {
         if (mrow < a.N && n < a.d) {
           bf16_t* o = a.Xh + (int64_t)mrow * a.ldxh + n;
           if (vec_ok && n + 8 <= a.d) {
-            *reinterpret_cast<u32x4*>(o) = ro[q];
+            *reinterpret_cast<u32x4*>(o) = ro[q];  // (plain: the streaming hint costs this kernel 8 us of its 46)
           } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
@@ -1078,7 +1078,7 @@ __device__ __forceinline__ void wgrad_tail(const CtdyWsArgs& a, unsigned char* s
           w.y = pack2_hw(x[2], x[3]);
           w.z = pack2_hw(x[4], x[5]);
           w.w = pack2_hw(x[6], x[7]);
-          *reinterpret_cast<u32x4*>(o) = w;
+          stream_store(reinterpret_cast<u32x4*>(o), w);
         } else {
           for (int e = 0; e < 8 && gcol + e < mh; ++e)
             o[e] = f32_to_bf16(a.beta == 0.f ? x[e] : x[e] + a.beta * __uint_as_float(((uint32_t)o[e]) << 16));
@@ -1097,7 +1097,7 @@ __device__ __forceinline__ void wgrad_tail(const CtdyWsArgs& a, unsigned char* s
             const float4 old = *reinterpret_cast<const float4*>(o);
             x.x += a.beta * old.x; x.y += a.beta * old.y; x.z += a.beta * old.z; x.w += a.beta * old.w;
           }
-          *reinterpret_cast<float4*>(o) = x;
+          stream_store(reinterpret_cast<f32x4_t*>(o), f32x4_t{x.x, x.y, x.z, x.w});
         } else {
           const float xs[4] = {x.x, x.y, x.z, x.w};
           for (int e = 0; e < 4 && gcol + e < mh; ++e) o[e] = a.beta == 0.f ? xs[e] : xs[e] + a.beta * o[e];
@@ -1178,7 +1178,7 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int row = min(16 * kb + c_slot_tok(h, e), a.N - 1 - t0);
-        rr[e] = *reinterpret_cast<const u32x4*>(base + (live ? (uint32_t)row * rowb : 0u));
+        rr[e] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (live ? (uint32_t)row * rowb : 0u)));
       }
     };
     auto sstore = [&](int stage, const u32x4 (&rr)[8]) {
