@@ -170,7 +170,7 @@ int prac_profile_read_each(prac_ctx* ctx, float* each_ms, int64_t cap, int64_t* 
  * reduction (with the scaling factor) and dW = P T run as one launch, T staying in LDS (for output widths
  * that are multiples of 4 and token-range counts that are multiples of 4; other shapes keep the two
  * launches); 1: as two launches with T (bf16, fragment order) in ctx scratch between them; 0 restores
- * the built-in choice (one launch for k + r > 256).  Results are bit-identical. */
+ * the built-in choice (one launch for k + r > 256 and d <= 2048).  Results are bit-identical. */
 enum { PRAC_TUNE_CTDY_SPLITS = 1, PRAC_TUNE_PROFILE_STRIDE = 2, PRAC_TUNE_WGRAD_ONE_LAUNCH = 3, PRAC_TUNE_WGRAD_TAIL = 4 };
 int prac_set_tuning(prac_ctx* ctx, int key, int value);
 

@@ -745,7 +745,9 @@ int weight_grad_fast(prac_ctx* ctx, char* ws, int* cnt, const WgradPlan& q, cons
   // MI355X it is for c > 256 (rank 512 + 512 at d = m = 2048: 159 against 179 us per weight gradient), where
   // the two launches move a large T through memory and run the LDS-staged product; at c <= 256 the two
   // small launches overlap each other's start and end and win (61.6 against 66.8 us at the same d, m).
-  const bool tail_one = ctx->tune_tail == 2 || (ctx->tune_tail == 0 && l.nckb > 16);
+  // (every 512 rows of dW are one more workgroup per column block that repeats the slab sum: at d = 11008,
+  // 22 of them, the one launch takes 180 us against 98 us for the two, so it is limited to d <= 2048)
+  const bool tail_one = ctx->tune_tail == 2 || (ctx->tune_tail == 0 && l.nckb > 16 && d <= 2048);
   if (tail_one && sum_pt_eligible(n_out, mi, splits)) {
     ProfScope ps(ctx, PRAC_KERNEL_SUM_P_T);
     return launch_sum_pt(ctx, reinterpret_cast<const bf16_t*>(lp + l.off_pa), n_out, part, splits, c, k, scale, l.nckb,
