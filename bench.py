@@ -646,6 +646,12 @@ def main():
                              f"between a HIP event pair on the ctx stream ({n_ev} steps)",
                     hbm_gbs=ach_gbs, hbm_frac=ach_gbs / HBM_PEAK_GBS, mfma_tflops=ach_tf, mfma_frac=ach_tf / MFMA_BF16_PEAK_TFLOPS)
 
+    # every kernel of the step against the HBM roofline over its own algorithmic bytes (event times of the
+    # launches issued one by one before the timed region), and the weight gradient as a whole over C, dY, P and dW
+    kernels_frac = {kk: algorithmic_bytes(kk, w) / (vv * 1e-6) / 1e9 / HBM_PEAK_GBS for kk, vv in per_kernel_us.items()}
+    wg_us = sum(vv for kk, vv in per_kernel_us.items() if kk != "compress")
+    if wg_us > 0:
+        kernels_frac["weight_grad_all_launches"] = algorithmic_bytes("weight_grad", w) / (wg_us * 1e-6) / 1e9 / HBM_PEAK_GBS
     cpu = None
     if args.calib_copy_mb > 0:
         src = torch.empty(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev)
@@ -689,6 +695,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels_us": per_kernel_us,
+        "kernels_hbm_frac": kernels_frac,
         "refit": {"ms": fit_ms, "in_timed_region": fits_in_region, "every": T, "amortised_us_per_step": 1e3 * fit_ms / T,
                   "kind": REFIT_LABEL},
         "value_with_amortised_refit": N / (ms_amortised * 1e-3),

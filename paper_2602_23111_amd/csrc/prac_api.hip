@@ -349,6 +349,7 @@ int prac_set_tuning(prac_ctx* ctx, int key, int value) {
   }
   if (key == PRAC_TUNE_WGRAD_TAIL) {
     if (value < 0 || value > 2) return PRAC_EINVAL;
+    if (!ctx) return PRAC_ENOCTX;
     ctx->tune_tail = value;
     return PRAC_OK;
   }

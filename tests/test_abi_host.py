@@ -138,7 +138,8 @@ def test_other_entry_points_reject_bad_arguments(lib):
     assert lib.prac_unpack_compressed(None, DUMMY, 8, 4, DUMMY, 4) == -6
     assert lib.prac_unpack_compressed(None, DUMMY, 8, 4, DUMMY, 3) == -1
     assert lib.prac_set_tuning(None, 1, 8) == -6 and lib.prac_set_tuning(None, 3, 8) == -1 and lib.prac_set_tuning(None, 2, 2000) == -1
-    assert lib.prac_profile_select(None, 9) == -1 and lib.prac_profile_select(None, 1) == -6
+    assert lib.prac_set_tuning(None, 4, 3) == -1 and lib.prac_set_tuning(None, 4, 2) == -6 and lib.prac_set_tuning(None, 5, 0) == -1
+    assert lib.prac_profile_select(None, 10) == -1 and lib.prac_profile_select(None, 9) == -6
     n64 = C.c_int64(0)
     assert lib.prac_profile_read_each(None, None, 4, C.byref(n64)) == -1       # cap > 0 needs a buffer
     assert lib.prac_profile_read_each(None, None, 0, C.byref(n64)) == -6
