@@ -344,8 +344,8 @@ def main():
     ap.add_argument("--streams", type=int, default=0,
                     help="consecutive steps (independent batches) alternate over this many HIP streams, one library context "
                          "each, so that the small tail kernels of one step overlap the streaming kernels of the next; "
-                         "1: everything on one stream; 0 (default): one or two, whichever a short trial after the warm-up "
-                         "finds faster for the workload (best of three runs of 24 steps each)")
+                         "1: everything on one stream; 0 (default): one, two or three, whichever a short trial after the "
+                         "warm-up finds fastest for the workload (best of three runs of 24 steps each)")
     ap.add_argument("--refresh-every", type=int, default=0, help="override the refresh interval (0: the workload's, 500)")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="after the timed region, also run three plain device copies of this many MB "
@@ -385,7 +385,7 @@ def main():
     torch.cuda.set_device(0)
     ctx = Prac(0)
     main_stream = torch.cuda.current_stream()
-    max_streams = 2 if args.streams == 0 else max(1, min(args.streams, 4))
+    max_streams = 3 if args.streams == 0 else max(1, min(args.streams, 4))
     if args.graph:
         max_streams = 1
 
@@ -602,7 +602,7 @@ def main():
     # refresh unless every step has one
     trial_first = (W // T + 1) * T + 1 if T > 16 else W
     trial_ms = {}
-    for n_try in ([1] if not side else ([1, len(side)] if args.streams == 0 else [len(side)])):
+    for n_try in ([1] if not side else (list(range(1, len(side) + 1)) if args.streams == 0 else [len(side)])):
         use["n"] = n_try
         timed_run(trial_first, 2 * w["n_sets"])
         trial_ms[n_try] = min(1e3 * timed_run(trial_first, 24) / 24 for _ in range(3))
