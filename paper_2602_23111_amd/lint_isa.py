@@ -6,7 +6,8 @@ or that ring registers have loads in flight.  That is safe only while no instruc
 the assembly blocks touches an accumulator register between a matrix block and the block that
 drains the matrix pipeline, or a ring register (a destination of an in-assembly
 `global_load_dwordx4`) between the first matrix block and the block holding `s_waitcnt vmcnt(0)`.
-This script compiles the file to ISA and checks it.
+This script compiles the file to ISA and checks it, and also that none of these kernels spills a
+vector register.
 
 Usage: python -m paper_2602_23111_amd.lint_isa      (exit status 0 = clean)
 """
@@ -87,6 +88,13 @@ def lint_text(isa: str) -> list[str]:
                 problems.append(f"{name}: accumulator register touched outside assembly: {text}")
             elif ring_busy and used & ring:
                 problems.append(f"{name}: ring register touched outside assembly: {text}")
+    # A spilled register in these kernels is a performance bug (every wave is given the register count of the
+    # hungriest one, and the streaming loops have no slack for scratch traffic) and moves values through memory
+    # behind the back of the in-flight loads above: the kernel metadata must report none.
+    for m in re.finditer(r"\.name:\s+(\S*_ws_kernel\S*)(.*?)\.wavefront_size", isa, re.S):
+        sp = re.search(r"\.vgpr_spill_count:\s+(\d+)", m.group(2))
+        if sp and int(sp.group(1)) != 0:
+            problems.append(f"{m.group(1)}: {sp.group(1)} vector registers spilled to scratch")
     return problems
 
 

@@ -201,6 +201,12 @@ s_waitcnt vmcnt(0)
                                                                 "\t;;#ASMEND\n\tv_accvgpr_read_b32 v30, a3\n")
     found = lint_isa.lint_text(drained)
     assert len(found) == 1 and "ring register" in found[0]
+    # a streaming kernel whose metadata reports spilled vector registers is reported too
+    meta = "\n  - .name:           _Zfake_ws_kernelv\n    .vgpr_count:     256\n    .vgpr_spill_count: 12\n    .wavefront_size: 64\n"
+    clean = planted.replace("\tv_accvgpr_read_b32 v30, a3\n\tv_mov_b32_e32 v11, v40\n", "")
+    assert lint_isa.lint_text(clean) == []
+    found = lint_isa.lint_text(clean + meta)
+    assert len(found) == 1 and "spilled" in found[0]
 
 
 # ---- scratch sizing (prac_workspace_bytes / prac_reserve_workspace) ----------------------------
