@@ -1220,14 +1220,18 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
         *reinterpret_cast<u32x4*>(s + ((j & 3) * 1024 + (j < 4 ? sA : sB))) = o;
       }
     };
-    // the first two tiles are requested together (one memory round trip before the first
-    // barrier); afterwards one tile is in flight per loader thread and two more are complete in LDS
+    // the first two tiles are requested together; afterwards one tile is in flight per loader thread and two
+    // more are complete in LDS
     gload(0, ry);
     gload(1, rz);
     sstore(0, ry);
     gload(2, ry);
+    // The matrix waves start as soon as tile 0 is in LDS: at a kernel's start all workgroups ask for their
+    // first tiles at once, and what holds the first multiplication back is the time HBM needs to deliver
+    // them (8 MB per tile over the 256 workgroups of the headline shape).  Tile 1 is first read at k-block 7
+    // of tile 0, behind the loop's first barrier, and is stored before that barrier.
+    __syncthreads();  // tile 0 is in LDS
     if (nk > 1) sstore(1, rz);
-    __syncthreads();  // tiles 0 and 1 are in LDS
     int stage = 2;
     for (int kt = 0; kt < nk; ++kt) {
       if (kt + 2 < nk) sstore(stage, ry);
@@ -1284,7 +1288,7 @@ __global__ __launch_bounds__(512) void ctdy_ws_kernel(CtdyWsArgs a) {
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw +
                           (unsigned)(frag_slot(li, lh) * 16);
     u32x4 fa[4], fb[4];
-    __builtin_amdgcn_s_barrier();  // tiles 0 and 1 are in LDS
+    __builtin_amdgcn_s_barrier();  // tile 0 is in LDS
     frag_read4_ct(fa, lds0);
     int stage = 0;
     for (int kt = 0; kt < nk; ++kt) {
