@@ -32,7 +32,11 @@
  *     1 <= d, m <= 2^20 features.
  *   - bf16 fast paths need 16-byte aligned base pointers and leading
  *     dimensions that are multiples of 8 elements; otherwise a slower generic
- *     kernel runs (same results to rounding).
+ *     kernel runs (same results to rounding).  They read rows in whole 16-byte
+ *     chunks: a matrix of R rows with leading dimension ld must own R * ld
+ *     elements (the up to 7 elements after a row's last column may be read,
+ *     never used, also in the last row); nothing outside those R * ld elements
+ *     is ever read or written.
  */
 #ifndef PRAC_H
 #define PRAC_H

@@ -245,7 +245,10 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
     constexpr int CR = 16 / NCH;  // 16-byte loads per thread and chunk
     u32x4 ra[16];                 // chunk g lives in ra[(g % NCH) * CR ...]
     // Requests past the last tile stay in the instruction stream (the loop has no load-free tail
-    // version) but all go to this thread's first chunk, which the L1 cache already holds.
+    // version) but all go to one chunk of this thread's first row, which the caches already hold.  Like
+    // every other request it is clamped to the row's last chunk: with d < 256 the thread's own column
+    // lies past the end of the row, and in the last row of X past the end of the buffer.
+    const uint32_t dead_off = roff[0] + (uint32_t)min(ccol, last_chunk) * 2u;
     auto cload = [&](int g, auto qc) {
       constexpr int Q = decltype(qc)::value;  // g % NCH
       const int kt = g / NCH;
@@ -254,7 +257,7 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(CompressWsArgs a) {
 #pragma unroll
       for (int j = 0; j < CR; ++j)
         ra[Q * CR + j] = __builtin_nontemporal_load(
-            reinterpret_cast<const u32x4*>(xbase + (live ? roff[Q * CR + j] + kb : roff[0] + (uint32_t)ccol * 2u)));
+            reinterpret_cast<const u32x4*>(xbase + (live ? roff[Q * CR + j] + kb : dead_off)));
     };
     // chunk g -> stage (g / NCH) % 2; columns past d are zeroed (only the last tile has any)
     auto cstore = [&](int g, auto qc) {

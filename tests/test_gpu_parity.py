@@ -125,6 +125,23 @@ def test_compress_matches_oracle(ctx, dt, N, d, c, ldx, ldc):
         assert rel_fro(si.as_f64(out), orc.compress(si.as_f64(Xt), P64)) < TOL[dt]
 
 
+@pytest.mark.parametrize("N,d,c", [(1, 8, 4), (2048, 8, 2), (300, 72, 33), (129, 200, 64)])
+def test_compress_narrow_x_at_the_end_of_its_allocation(ctx, N, d, c):
+    """Feature counts below one 256-column k-tile, X ending on the last byte of a device allocation of its own:
+    every request of the kernel, also the ones issued past the last k-tile, must stay inside X."""
+    X64, _ = si.activation(N, d, 0.8, seed=N + d)
+    Xt = si.round_to(X64, "bf16")
+    P32, P64 = basis32(d, c, seed=c)
+    block = torch.empty(32 << 20, dtype=torch.uint8, device=DEV)   # large enough to be an allocation of its own
+    Xd = block[block.numel() - N * d * 2:].view(torch.bfloat16).view(N, d)
+    Xd.copy_(Xt.to(DEV))
+    ref = orc.compress(si.as_f64(Xt), P64)
+    for lp in (None, ctx.pack_basis(P32.to(DEV))):
+        got = ctx.compress(Xd, P32.to(DEV), P_lp=lp)
+        torch.cuda.synchronize()
+        assert rel_fro(si.as_f64(got), ref) < 1e-2
+
+
 @pytest.mark.parametrize("N,d,c", [(2048, 512, 64), (777, 328, 72), (515, 320, 256), (130, 328, 300), (17, 64, 33)])
 def test_compress_packed_layout(ctx, N, d, c):
     # same numbers as the row-major result, stored in the documented block order, zero padded
