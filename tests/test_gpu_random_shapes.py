@@ -1,0 +1,102 @@
+"""GPU parity on randomly drawn shapes: compress, weight gradient (row-major and packed C), reconstruction and the
+fused forward, bf16 and fp32, through the C ABI binding against the fp64 oracle.
+
+The draws mix what the fixed cases of test_gpu_parity.py hold apart: token counts of 1 to a few thousand, feature
+counts below one k-tile (8, 64, 72, 200) up to 1100, output widths from 8 to 1000, any rank split (k = 0, r = 0,
+k + r up to 600), leading dimensions that are exact, padded by a whole 16-byte chunk or unaligned (the generic
+kernels), a basis packed beforehand or packed inside the call.  Padding is NaN, so any use of it shows.
+Tolerances as in test_gpu_parity.py: relative Frobenius error 1e-2 for bf16 data, 1e-5 for fp32 data.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import prac_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+CASES_PER_SEED = 60
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2602_23111_amd.prac import Prac
+
+    p = Prac(0)
+    yield p
+    p.close()
+
+
+def rel(a, b):
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def pad(t, ld):
+    buf = torch.full((t.shape[0], ld), float("nan"), dtype=t.dtype, device=DEV)
+    buf[:, :t.shape[1]] = t.to(DEV)
+    return buf[:, :t.shape[1]]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_random_shapes_match_oracle(ctx, seed):
+    from paper_2602_23111_amd.prac import C_PACKED
+
+    rng = np.random.default_rng(seed)
+    bad = []
+    for it in range(CASES_PER_SEED):
+        dt = "bf16" if rng.random() < 0.8 else "f32"
+        tol = 1e-2 if dt == "bf16" else 1e-5
+        N = int(rng.choice([1, 7, 100, 129, 500, 1023, 2048, 3001, 4097]))
+        d = int(rng.choice([8, 64, 72, 200, 256, 264, 333, 512, 520, 768, 1100]))
+        m = int(rng.choice([8, 40, 96, 128, 136, 200, 203, 512, 640, 1000]))
+        c = int(rng.integers(1, min(d, 600) + 1))
+        k = int(rng.integers(0, c + 1))
+        r = c - k
+        s = float(d - k) / r if r else 0.0
+        ldx = d + int(rng.choice([0, 0, 8, 3]))
+        lddy = m + int(rng.choice([0, 0, 8, 5]))
+        with_lp = rng.random() < 0.7
+        tag = f"seed {seed} case {it}: {dt} N={N} d={d} m={m} k={k} r={r} ldx={ldx} lddy={lddy} lp={with_lp}"
+        print(tag, flush=True)  # names the case should a kernel fault
+
+        X64, _ = si.activation(N, d, 0.8, seed=it + 17)
+        Xt = si.round_to(X64, dt)
+        dYt = si.round_to(si.grad_output(N, m, 1e-2, seed=it), dt)
+        P32 = si.round_to(si.orthonormal_basis(d, c, it), "f32")
+        P64 = si.as_f64(P32)
+        Xd, dYd, Pd = pad(Xt, ldx), pad(dYt, lddy), P32.to(DEV)
+        lp = ctx.pack_basis(Pd) if with_lp else None
+
+        def check(what, got, ref):
+            e = rel(got, ref) if np.linalg.norm(ref) > 0 else float(np.abs(got).max())
+            if not e < tol:
+                bad.append(f"{what}: {tag}: {e:.3g}")
+
+        Cm = ctx.compress(Xd, Pd, P_lp=lp)
+        ctx.sync_status()
+        check("compress", si.as_f64(Cm), orc.compress(si.as_f64(Xt), P64))
+
+        dW = ctx.weight_grad(Cm, dYd, Pd, k, r, s, P_lp=lp)
+        ctx.sync_status()
+        ref_dw = orc.weight_grad(si.as_f64(Cm), si.as_f64(dYt), P64, k, s)
+        check("weight_grad", si.as_f64(dW), ref_dw)
+
+        if dt == "bf16" and ldx % 8 == 0 and lp is not None:
+            Cp = ctx.compress(Xd, Pd, P_lp=lp, layout=C_PACKED)
+            dW2 = ctx.weight_grad(Cp, dYd, Pd, k, r, s, P_lp=lp, layout=C_PACKED)
+            ctx.sync_status()
+            check("weight_grad, packed C", si.as_f64(dW2), ref_dw)
+
+        Xh = ctx.reconstruct(Cm, Pd, k, r, s)
+        ctx.sync_status()
+        check("reconstruct", si.as_f64(Xh), orc.reconstruct(si.as_f64(Cm), P64, k, s))
+
+        if it % 3 == 0:
+            Wt = si.round_to(np.random.default_rng(it).standard_normal((d, m)) * 0.05, dt)
+            Y, C2 = ctx.compress_fused_fwd(Xd, Wt.to(DEV), Pd, w_layout=0, P_lp=lp)
+            ctx.sync_status()
+            check("fused forward Y", si.as_f64(Y), orc.forward(si.as_f64(Xt), si.as_f64(Wt)))
+            check("fused forward C", si.as_f64(C2), orc.compress(si.as_f64(Xt), P64))
+    assert not bad, "\n".join(bad)
