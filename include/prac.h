@@ -76,7 +76,7 @@ typedef struct {
   int warm_start;      /* 1: start the block from the Q1 already in P */
 } prac_fit_opts;
 /* Tracking refit: with warm_start = 1 and oversample < 0 (block width k), bf16 X that is
- * 16-byte aligned with row pitch (ldx * row_stride) a multiple of 8, at least 256 rows in
+ * 16-byte aligned with ldx a multiple of 8, at least 256 rows in
  * the (sub)sample, d >= 128 and k <= 1024, no Gram matrix is formed: each of the `iters`
  * iterations is one subspace-iteration step Q1 <- orth(X^T (X Q1)) through the compress and
  * C^T dY kernels, without the Rayleigh-Ritz step (Q1 spans the tracked subspace; its columns
@@ -212,7 +212,12 @@ int prac_pack_basis(prac_ctx* ctx, const float* P, int64_t d, int64_t ldp, int c
  * from the first k columns of P.  PRAC_REFRESH_RANDOM redraws Q2 from
  * (seed, draw); if clear, columns k.. of P are left as they are.
  * Needs 0 <= k, 0 <= r, 1 <= k+r <= d.  X may be NULL when Q1 is not
- * refreshed or k = 0. */
+ * refreshed or k = 0.  A batch whose (sub)sampled rows are fewer than k has
+ * rank below k: Q1 then holds the principal directions of those rows and an
+ * orthonormal completion drawn from (seed, draw), generator stream 2, like Q2.
+ * prac_sync_status reports PRAC_ENUMERIC afterwards if a factorisation met a
+ * pivot that was not positive or a block did not come out orthonormal (data of
+ * much lower rank than its row count can do that). */
 int prac_fit_basis(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64_t d,
                    int64_t ldx, int k, int r, uint64_t seed, uint64_t draw, int refresh,
                    const prac_fit_opts* opts /* [host], may be NULL */, float* P,

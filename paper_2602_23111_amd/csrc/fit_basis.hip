@@ -532,6 +532,7 @@ struct FitWs {
   size_t trk_pf, trk_c, trk_slabs;  // tracking refit: V in fragment order, packed X V, slabs of (X V)^T X
   int trk_nkb, trk_ncb, trk_splits;
   int b;
+  int kq;         // principal columns the iteration computes (see principal_rank); the other k - kq are drawn
   int splits_bb;  // split count of the b x b fp64 Gram products
   int splits_gv;  // split count of G V
 };
@@ -549,19 +550,31 @@ int block_width(int64_t d, int k, const prac_fit_opts& o) {
 // matrix is formed.  One step is V <- orth(X^T (X V)): the compress kernel forms X V, the C^T dY
 // kernel with X in the place of dY forms (X V)^T X.
 bool can_track(const void* X, prac_dtype xdt, int64_t rows, int64_t d, int64_t ldx, int k, const prac_fit_opts& o) {
-  const int64_t ld = ldx * (o.row_stride > 0 ? o.row_stride : 1);
+  // ldx itself a multiple of 8 (not only the pitch ldx * row_stride of the sampled rows): the streaming kernels
+  // read a row in whole 16-byte chunks, and the last chunk of the last row must lie inside that row's ldx elements
   return o.warm_start && o.oversample < 0 && o.iters >= 1 && k > 0 && k <= 1024 && xdt == PRAC_BF16 &&
-         (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 8 == 0 && rows >= 256 && rows < ((int64_t)1 << 31) &&
-         d >= 128;
+         (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ldx % 8 == 0 && rows >= 256 && rows >= k &&
+         rows < ((int64_t)1 << 31) && d >= 128;
 }
+
+// Principal directions the (sub)sampled rows can define: a batch of fewer rows than k has rank below k, and
+// the columns of Q1 past that rank are an arbitrary orthonormal completion (any one is a valid set of "top-k right
+// singular vectors").  They are drawn like Q2 - Gaussian, projected onto the complement, orthonormalised -
+// instead of being left to the iteration, whose blocks would be rank deficient.
+int principal_rank(int k, int64_t rows) { return rows < k ? (int)rows : k; }
 
 FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool need_g, size_t gram_bytes, bool track,
                int64_t rows) {
   FitWs w{};
   WsPlan p;
-  const int b = track ? k : (need_g ? block_width(d, k, o) : 0);
-  const int bb = b > r ? b : r;  // widest panel that goes through orth()
+  const int kq = (need_g || track) ? principal_rank(k, rows) : k;
+  const int fill = k - kq;  // columns of Q1 drawn at random
+  int b = track ? k : (need_g ? block_width(d, kq, o) : 0);
+  if (need_g && b > rows) b = (int)rows;  // kq <= rows: the block keeps at least kq columns
+  const int rf = r > fill ? r : fill;     // widest random block
+  const int bb = b > rf ? b : rf;         // widest panel that goes through orth()
   w.b = b;
+  w.kq = kq;
   w.G = p.take(need_g ? (size_t)d * d * 4 : 0);
   w.V = p.take((size_t)d * bb * 4);
   w.Y = p.take((size_t)d * bb * 4);
@@ -570,8 +583,8 @@ FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool n
   w.Rinv = p.take((size_t)bb * bb * 4);
   w.lam = p.take((size_t)bb * 8);
   w.Z = p.take((size_t)bb * (k > 0 ? k : 1) * 4);
-  w.S = p.take((size_t)d * (r > 0 ? r : 1) * 4);
-  w.T = p.take((size_t)(k > 0 ? k : 1) * (r > 0 ? r : 1) * 4);
+  w.S = p.take((size_t)d * (rf > 0 ? rf : 1) * 4);
+  w.T = p.take((size_t)(k > 0 ? k : 1) * (rf > 0 ? rf : 1) * 4);
   const int tiles = ((bb + 63) / 64) * ((bb + 63) / 64);
   int s = (2 * n_cu + tiles - 1) / tiles;
   if (s > d / 64) s = (int)(d / 64);
@@ -588,7 +601,7 @@ FitWs plan_fit(int64_t d, int k, int r, const prac_fit_opts& o, int n_cu, bool n
   // the slab block serves every split product of the fit: the bb x bb panel Gram matrices (fp64), G V
   // (d x b, fp32) and Q1^T S (k x r, fp32; wider than a panel Gram when k > 2 r and Q1 is not refreshed)
   const size_t slab_bb = (size_t)s * bb * bb * 8, slab_gv = sg > 1 ? (size_t)sg * d * b * 4 : 0;
-  const size_t slab_kr = (size_t)s * k * r * 4;
+  const size_t slab_kr = (size_t)s * k * rf * 4;  // also the completion's Q1^T S (kq x fill)
   w.slab_bytes = std::max(slab_bb, std::max(slab_gv, slab_kr));
   w.slabs = p.take(w.slab_bytes);
   w.gram = p.take(gram_bytes);
@@ -627,10 +640,17 @@ __global__ __launch_bounds__(256) void f32_to_f64_kernel(const float* __restrict
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) dst[i] = (double)src[i];
 }
 
-// W (n x n) <- 1.5 I - 0.5 W
-__global__ __launch_bounds__(256) void newton_schulz_factor_kernel(float* W, int n) {
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n * n; i += gridDim.x * blockDim.x)
-    W[i] = (i / n == i % n ? 1.5f : 0.f) - 0.5f * W[i];
+// W (n x n) <- 1.5 I - 0.5 W.  W is the Gram matrix of a block that should be close to orthonormal: an entry
+// further than `limit` from the identity (or not finite) raises bit 1 of *flag - the step that follows squares
+// the distance, so a block that far off does not come out orthonormal to fp32 rounding.
+__global__ __launch_bounds__(256) void newton_schulz_factor_kernel(float* W, int n, float limit, int* flag) {
+  bool off = false;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n * n; i += gridDim.x * blockDim.x) {
+    const float id = i / n == i % n ? 1.f : 0.f;
+    off = off || !(fabsf(W[i] - id) <= limit);
+    W[i] = 1.5f * id - 0.5f * W[i];
+  }
+  if (off) atomicOr(flag, 1);
 }
 
 // M (n x n) = src^T src for a d x n block (ld = n): fp64 sums into W64, or fp32 sums on the matrix
@@ -685,11 +705,12 @@ int cholqr_pass(prac_ctx* ctx, const FitWs& w, const float* src, float* dst, int
 // dst = src (1.5 I - 0.5 src^T src): one Newton-Schulz step towards orthonormal columns.  For a block
 // with ||src^T src - I|| = e the result has 0.75 e^2: the cheap second pass after a Cholesky-QR pass,
 // made of two products and no factorisation.
-int polish_pass(prac_ctx* ctx, const FitWs& w, const float* src, float* dst, int64_t d, int n) {
+int polish_pass(prac_ctx* ctx, const FitWs& w, const float* src, float* dst, int64_t d, int n, float limit) {
   float* M32 = reinterpret_cast<float*>(ctx->ws + w.Rinv);
   int rc = panel_gram(ctx, w, src, d, n, nullptr, M32);
   if (rc) return rc;
-  hipLaunchKernelGGL(newton_schulz_factor_kernel, dim3((n * n + 255) / 256), dim3(256), 0, ctx->stream, M32, n);
+  hipLaunchKernelGGL(newton_schulz_factor_kernel, dim3((n * n + 255) / 256), dim3(256), 0, ctx->stream, M32, n, limit,
+                     ctx->d_flag);
   PRAC_HIP_TRY(ctx, hipGetLastError());
   GemmGenArgs g{};
   g.A = src; g.B = M32; g.adt = PRAC_F32; g.bdt = PRAC_F32;
@@ -710,8 +731,10 @@ int cholqr(prac_ctx* ctx, const FitWs& w, float* Y, float* V, int64_t d, int n, 
     // Later passes work on a block that is orthonormal up to the first pass's error, except in
     // directions where the input was rank deficient: there the Gram matrix is zero up to rounding
     // (a few 1e-16), and the shift has to be safely above that for the pivot to stay positive.
+    // the last Newton-Schulz step must start within 3e-3 of orthonormal to end below 1e-5 (0.75 e^2); earlier
+    // ones may start anywhere inside the step's region of convergence
     int rc = pass < passes ? cholqr_pass(ctx, w, src, dst, d, n, pass == 0 ? first_shift : 1e-13, pass > 0 || gram64_first)
-                           : polish_pass(ctx, w, src, dst, d, n);
+                           : polish_pass(ctx, w, src, dst, d, n, pass == passes + polish - 1 ? 3e-3f : 0.5f);
     if (rc) return rc;
     float* t = src; src = dst; dst = t;
   }
@@ -769,7 +792,12 @@ int64_t fit_slab_margin(int n_cu, prac_dtype xdt, int64_t N, int64_t d, int k, i
     const int n = L.b;  // block width of the iteration (k when tracking)
     product(L.splits_bb, n, n, 8);                    // panel Gram matrices of orth(), Rayleigh-Ritz
     if (!f.track) product(L.splits_gv, d, n, 4);      // G V
-    product(L.splits_bb, k, k, 8);                    // tidy pass on Q1
+    product(L.splits_bb, L.kq, L.kq, 8);              // tidy passes on Q1
+    const int fill = k - L.kq;
+    if (fill > 0) {
+      product(L.splits_bb, L.kq, fill, 4);            // the completion's Q1^T S
+      product(L.splits_bb, fill, fill, 8);            // and its panel Gram matrices
+    }
   }
   if (f.do_q2) {
     if (k > 0) product(L.splits_bb, k, r, 4);         // Q1^T S
@@ -824,6 +852,7 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
     PRAC_HIP_TRY(ctx, hipGetLastError());
   } else if (do_q1) {
     const int b = L.b;
+    const int k = L.kq;  // the columns this iteration computes: all of Q1 unless the batch has fewer rows than that
     rc = gram_device(ctx, X, xdt, N, d, ldx, o.row_stride, G, d, ctx->ws + L.gram);
     if (rc) return rc;
 
@@ -919,23 +948,25 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
       rc = launch_gemm_generic(ctx, g);
       if (rc) return rc;
     }
-    // tidy the rounding of the last product (one Cholesky-QR pass and a Newton-Schulz step: with more
+    // tidy the rounding of the last product (two Cholesky-QR passes and a Newton-Schulz step: with more
     // Ritz vectors asked for than the data has rank, the surplus ones are rounding noise, far from
-    // orthogonal to each other, and one fp32 pass leaves 1e-4), then store Q1 into P[:, :k]
-    rc = cholqr(ctx, L, Y, V, d, k, 1, 0.0, 1);
+    // orthogonal to each other, and one pass leaves 1e-4 or more), then store Q1 into P[:, :k]
+    rc = cholqr(ctx, L, Y, V, d, k, 2, 1e-13, 1);
     if (rc) return rc;
     hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, V, (int64_t)k, P, ldp, d, k);
     PRAC_HIP_TRY(ctx, hipGetLastError());
   }
 
-  if (do_q2) {
+  // P[:, kk : kk + rr] = orth((I - Q Q^T)^2 S) for Q = P[:, :kk] and the Gaussian d x rr block S of Philox
+  // stream `stream`
+  auto random_block = [&](int k, int r, uint32_t stream) -> int {
     float* S = reinterpret_cast<float*>(ctx->ws + L.S);
     float* T = reinterpret_cast<float*>(ctx->ws + L.T);
-    rc = launch_philox(ctx, seed, draw, 1u, S, d * r, true);
+    int rc = launch_philox(ctx, seed, draw, stream, S, d * r, true);
     if (rc) return rc;
     if (k > 0) {
       for (int rep = 0; rep < 2; ++rep) {
-        // T = Q1^T S  (k x r), S -= Q1 T
+        // T = Q^T S  (k x r), S -= Q T
         GemmGenArgs g{};
         g.A = P; g.B = S; g.adt = PRAC_F32; g.bdt = PRAC_F32;
         g.a_rs = 1; g.a_cs = ldp; g.b_rs = r; g.b_cs = 1;
@@ -963,6 +994,13 @@ int fit_basis_device(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, in
     if (rc) return rc;
     hipLaunchKernelGGL(copy_cols_kernel, dim3(ctx->n_cu * 4), dim3(256), 0, st, V, (int64_t)r, P + k, ldp, d, r);
     PRAC_HIP_TRY(ctx, hipGetLastError());
+    return PRAC_OK;
+  };
+  // the columns of Q1 that the batch's rows do not define (stream 2), then Q2 (stream 1) against all of Q1
+  if (do_q1 && L.kq < k) {
+    rc = random_block(L.kq, k - L.kq, 2u);
+    if (rc) return rc;
   }
+  if (do_q2) return random_block(k, r, 1u);
   return PRAC_OK;
 }

@@ -319,9 +319,10 @@ int prac_sync_status(prac_ctx* ctx) {
   PRAC_HIP_TRY(ctx, hipMemcpy(&flag, ctx->d_flag, sizeof(int), hipMemcpyDeviceToHost));
   if (flag != 0) {
     PRAC_HIP_TRY(ctx, hipMemset(ctx->d_flag, 0, sizeof(int)));
-    if (flag == 2) {
+    if (flag & 4) {
       // a wait between workgroups of the one-launch weight gradient gave up: its counters may be left
-      // non-zero, clear them for the next launch
+      // non-zero, clear them for the next launch  (bits 1 and 2 are the basis fit's: a pivot that was
+      // not positive or a basis that did not come out orthonormal, an eigen-iteration that did not settle)
       PRAC_HIP_TRY(ctx, hipMemset(ctx->d_sync, 0, PRAC_SYNC_BYTES));
       return PRAC_EHIP;
     }

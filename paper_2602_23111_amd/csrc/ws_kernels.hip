@@ -768,7 +768,7 @@ struct CtdyWsArgs {
   // ---- whole weight gradient in this launch (MODE > 0): the workgroups of one column tile sum their
   // partial slabs into T (bf16, fragment order, random rows scaled) and form dW = P T for that tile
   int* cnt;            // 3 counters per column tile, zero before the launch, zero again after it
-  int* fail;           // set to 2 if a wait between workgroups gave up
+  int* fail;           // set to 4 if a wait between workgroups gave up (bits 1 and 2 belong to the basis fit)
   int nckb;            // 16-row k-blocks of T = ceil(c / 16)
   int k_lo;            // rows >= k_lo of T carry scale_hi
   float scale_hi;
@@ -887,7 +887,7 @@ __device__ __forceinline__ void spin_until(int* cnt, int members, int* fail) {
   while (__hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < members) {
     __builtin_amdgcn_s_sleep(2);
     if (++spins > WG_SPIN_LIMIT) {
-      __hip_atomic_store(fail, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(fail, 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       break;
     }
   }
@@ -909,7 +909,7 @@ __device__ __forceinline__ bool group_meet_first(int* cnt, int members, int* fai
              (unsigned long long)members) {
         __builtin_amdgcn_s_sleep(2);
         if (++spins > WG_SPIN_LIMIT) {
-          __hip_atomic_store(fail, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(fail, 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           break;
         }
       }

@@ -261,5 +261,7 @@ def test_fit_plan_holds_every_split_product():
                 continue
             for refresh in (1, 2, 3):
                 for opts in (dict(), dict(warm_start=True, oversample=-1, iters=2), dict(oversample=8)):
-                    sh = prac.call_shape("fit_basis", 32768, d, k, r, refresh=refresh, **opts)
-                    assert lib.prac_debug_fit_slab_margin(C.byref(sh)) >= 0, (d, k, r, refresh, opts)
+                    # 32768 rows, and batches of fewer rows than k (part of Q1 is then drawn like Q2)
+                    for N in (32768, 300, 1):
+                        sh = prac.call_shape("fit_basis", N, d, k, r, refresh=refresh, **opts)
+                        assert lib.prac_debug_fit_slab_margin(C.byref(sh)) >= 0, (N, d, k, r, refresh, opts)

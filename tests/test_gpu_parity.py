@@ -536,6 +536,32 @@ def test_fit_basis_without_gap_captures_the_energy(ctx):
     assert np.linalg.norm(Xl64 - Xl64 @ Q @ Q.T) < 1e-4 * np.linalg.norm(Xl64)
 
 
+@pytest.mark.parametrize("dt,N,d,k,r,stride,warm", [("bf16", 300, 520, 166, 6, 4, False), ("bf16", 1, 300, 291, 9, 2, False),
+                                                    ("f32", 50, 136, 44, 21, 4, True), ("bf16", 300, 768, 320, 64, 1, True)])
+def test_fit_basis_batch_of_fewer_rows_than_k(ctx, dt, N, d, k, r, stride, warm):
+    """Fewer (sub)sampled rows than k: the data's rank is below k, so only that many principal directions exist
+    and any orthonormal completion is a valid rest of Q1.  The library draws the rest like Q2; what is unique is
+    checked: P orthonormal, Q1 holding all of the rows' energy, Q2 the oracle's complement of the returned Q1."""
+    Xt = si.round_to(si.activation(N, d, 0.8, seed=N + k)[0], dt)
+    P, lp, scale = ctx.fit_basis(Xt.to(DEV), k, r, seed=9, draw=0, row_stride=stride)
+    ctx.sync_status()
+    draw = 0
+    if warm:
+        draw = 1
+        P, lp, scale = ctx.fit_basis(Xt.to(DEV), k, r, seed=9, draw=1, row_stride=stride, iters=2, oversample=-1,
+                                     warm_start=True, P=P.clone())
+        ctx.sync_status()
+    P64, Xs = si.as_f64(P), si.as_f64(Xt)[::stride]
+    assert Xs.shape[0] < k
+    assert np.abs(P64.T @ P64 - np.eye(k + r)).max() < 1e-5
+    total = float(np.sum(Xs ** 2))
+    assert float(np.sum((Xs @ P64[:, :k]) ** 2)) >= (1 - 1e-5) * total
+    Q2 = orc.complement_basis(P64[:, :k], orc.gaussian_matrix(9, draw, d, r))
+    assert np.abs(P64[:, k:] - Q2).max() < 5e-5
+    assert scale == pytest.approx((d - k) / r)
+    assert torch.equal(lp, ctx.pack_basis(P))
+
+
 def test_fit_basis_row_subsample_and_warm_start(ctx):
     N, d, k, r = 4096, 256, 16, 16
     Xt, _ = gapped_activation(N, d, k, 1.0, seed=6, dt="bf16")
