@@ -248,8 +248,10 @@ int prac_compress(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N, int64
                   int64_t ldx, const float* P, const void* P_lp, int64_t ldp, int c,
                   void* C, int64_t ldc, int c_layout);
 
-/* Same C, plus the layer's forward output Y (N x m, ldy >= m, dtype of X) in
- * one pass over X.  W has X's dtype; w_layout 0: d x m row-major (Y = X W,
+/* The same C (equal to prac_compress's up to the order of the fp32 sums over d:
+ * the two walk the k-tiles in different orders, so single elements may differ
+ * in the last bit of the output type), plus the layer's forward output Y
+ * (N x m, ldy >= m, dtype of X) in one pass over X.  W has X's dtype; w_layout 0: d x m row-major (Y = X W,
  * Lemma 1), 1: m x d row-major (Y = X W^T, the layout of Section 5.2). */
 int prac_compress_fused_fwd(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N,
                             int64_t d, int64_t ldx, const void* W, int64_t m, int64_t ldw,

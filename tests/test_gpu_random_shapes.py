@@ -1,6 +1,8 @@
 """GPU parity on randomly drawn shapes, through the C ABI binding against the fp64 oracle: compress, weight
 gradient (row-major and packed C), reconstruction and the fused forward in the first test, the Gram matrix and the
-basis fit with its options and refresh branches in the second; bf16 and fp32.
+basis fit with its options and refresh branches in the second; the gradients of several layers from one shared C
+under every launch form, bf16 gradients with accumulation, the packed layouts and the entry point that allocates
+nothing in the third; bf16 and fp32.
 
 The draws mix what the fixed cases of test_gpu_parity.py hold apart: token counts of 1 to a few thousand, feature
 counts below one k-tile (8, 64, 72, 200) up to 1100, output widths from 8 to 1000, any rank split (k = 0, r = 0,
@@ -187,4 +189,91 @@ def test_random_fit_shapes_match_oracle(ctx, seed):
             bad.append(f"scale {scale}: {tag}")
         if lp is not None and not torch.equal(lp, ctx.pack_basis(P)):
             bad.append(f"packed copy: {tag}")
+    assert not bad, "\n".join(bad)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_random_shared_gradients_and_packed_paths(ctx, seed):
+    """bf16 data: one to four gradients from one shared C (row-major or packed) in fp32 or bf16 with beta 0 or 0.5,
+    under the built-in launch form, the one-launch form, both forms of the tail and forced token-split counts; the
+    entry point with static scratch against the ordinary one bit for bit; the reconstruction from packed C; the fused
+    forward with m x d weights writing packed C."""
+    from paper_2602_23111_amd import prac as pr
+
+    rng = np.random.default_rng(seed)
+    bad = []
+    for it in range(30):
+        N = int(rng.choice([1, 100, 129, 1023, 2048, 4097, 8200]))
+        d = int(rng.choice([8, 72, 200, 256, 333, 520, 768, 1100, 2048]))
+        c = int(rng.integers(1, min(d, 600) + 1))
+        k = int(rng.integers(0, c + 1))
+        r = c - k
+        s = float(d - k) / r if r else 0.0
+        n_out = int(rng.integers(1, 5))
+        ms = [int(rng.choice([8, 40, 96, 128, 136, 200, 203, 512, 640, 1000])) for _ in range(n_out)]
+        pady = [int(rng.choice([0, 0, 8, 5])) for _ in range(n_out)]
+        out_bf16 = rng.random() < 0.5
+        beta = float(rng.choice([0.0, 0.0, 0.5]))
+        packed = rng.random() < 0.5
+        tune = int(rng.choice([0, 0, 1, 2, 3, 4]))  # built-in, one launch, tail as two launches, tail as one, forced splits
+        splits = int(rng.choice([1, 2, 4, 8, 16]))
+        ldx = d + int(rng.choice([0, 8]))
+        ldw = d + int(rng.choice([0, 8, 3]))
+        tag = (f"seed {seed} case {it}: N={N} d={d} k={k} r={r} m={ms} pad={pady} bf16 dW={out_bf16} beta={beta} "
+               f"packed={packed} tune={tune}/{splits} ldx={ldx} ldw={ldw}")
+        print(tag, flush=True)
+        Xt = si.round_to(si.activation(N, d, 0.8, seed=it + 31)[0], "bf16")
+        dYts = [si.round_to(si.grad_output(N, m, 1e-2, seed=it + 7 * h), "bf16") for h, m in enumerate(ms)]
+        P32 = si.round_to(si.orthonormal_basis(d, c, it), "f32")
+        P64 = si.as_f64(P32)
+        Xd, Pd = pad(Xt, ldx), P32.to(DEV)
+        dYd = [pad(t, m + p) for t, m, p in zip(dYts, ms, pady)]
+        lp = ctx.pack_basis(Pd)
+        layout = pr.C_PACKED if packed else pr.C_ROWMAJOR
+        try:
+            ctx.set_tuning(pr.TUNE_WGRAD_ONE_LAUNCH, 1 if tune == 1 else 0)
+            ctx.set_tuning(pr.TUNE_WGRAD_TAIL, 1 if tune == 2 else (2 if tune == 3 else 0))
+            ctx.set_tuning(pr.TUNE_CTDY_SPLITS, splits if tune == 4 else 0)
+            Cm = ctx.compress(Xd, Pd, P_lp=lp)
+            Cp = ctx.compress(Xd, Pd, P_lp=lp, layout=pr.C_PACKED)
+            ctx.sync_status()
+            C64 = si.as_f64(Cm)
+            if not torch.equal(ctx.unpack_compressed(Cp, N, c), Cm):
+                bad.append(f"packed C is not the row-major C: {tag}")
+            old = [si.round_to(np.random.default_rng(it + h).standard_normal((d, m)) * 1e-2, "bf16" if out_bf16 else "f32")
+                   for h, m in enumerate(ms)]
+            got = ctx.weight_grad_shared(Cp if packed else Cm, dYd, Pd, k, r, s, P_lp=lp,
+                                         outs=[o.to(DEV).clone() for o in old], beta=beta, layout=layout)
+            ctx.sync_status()
+            for h in range(n_out):
+                ref = orc.weight_grad(C64, si.as_f64(dYts[h]), P64, k, s) + beta * si.as_f64(old[h])
+                if not rel(si.as_f64(got[h]), ref) < 1e-2:
+                    bad.append(f"gradient {h}: {tag}")
+            o1 = torch.zeros((d, ms[0]), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=DEV)
+            o2 = torch.zeros_like(o1)
+            try:
+                ctx.weight_grad(Cp if packed else Cm, dYd[0], Pd, k, r, s, P_lp=lp, out=o1, layout=layout, static=True)
+                ctx.weight_grad(Cp if packed else Cm, dYd[0], Pd, k, r, s, P_lp=lp, out=o2, layout=layout)
+                ctx.sync_status()
+                if not torch.equal(o1, o2):
+                    bad.append(f"static scratch differs from the ordinary call: {tag}")
+            except pr.PracError as ex:
+                if "TOOBIG" not in str(ex):
+                    raise
+        finally:
+            ctx.set_tuning(pr.TUNE_WGRAD_ONE_LAUNCH, 0)
+            ctx.set_tuning(pr.TUNE_WGRAD_TAIL, 0)
+            ctx.set_tuning(pr.TUNE_CTDY_SPLITS, 0)
+        Xh = ctx.reconstruct(Cp, Pd, k, r, s, N=N, layout=pr.C_PACKED)
+        ctx.sync_status()
+        if not rel(si.as_f64(Xh), orc.reconstruct(C64, P64, k, s)) < 1e-2:
+            bad.append(f"reconstruction from packed C: {tag}")
+        Wt = si.round_to(np.random.default_rng(it).standard_normal((ms[0], d)) * 0.05, "bf16")
+        Y, C2 = ctx.compress_fused_fwd(Xd, pad(Wt, ldw), Pd, w_layout=1, P_lp=lp, layout=pr.C_PACKED)
+        ctx.sync_status()
+        if not rel(si.as_f64(Y), orc.forward(si.as_f64(Xt), si.as_f64(Wt).T)) < 1e-2:
+            bad.append(f"fused forward Y: {tag}")
+        # the fused launch walks the k-tiles in another order than compress: last-bit differences only
+        if not torch.equal(C2, Cp) and not rel(si.as_f64(C2.float()), si.as_f64(Cp.float())) < 1e-3:
+            bad.append(f"fused forward C: {tag}")
     assert not bad, "\n".join(bad)
