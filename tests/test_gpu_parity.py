@@ -142,6 +142,60 @@ def test_compress_narrow_x_at_the_end_of_its_allocation(ctx, N, d, c):
         assert rel_fro(si.as_f64(got), ref) < 1e-2
 
 
+def at_end_of_own_allocation(t_cpu: torch.Tensor, ld: int | None = None) -> torch.Tensor:
+    """The matrix on the last bytes of a 32 MiB device allocation of its own (rows x ld elements, NaN padding):
+    a request past the extent the header grants an argument leaves the allocation."""
+    n, m = t_cpu.shape
+    ld = m if ld is None else ld
+    block = torch.empty(32 << 20, dtype=torch.uint8, device=DEV)
+    buf = block[block.numel() - n * ld * t_cpu.element_size():].view(t_cpu.dtype).view(n, ld)
+    if t_cpu.is_floating_point():
+        buf.fill_(float("nan"))
+    buf[:, :m] = t_cpu.to(DEV)
+    return buf[:, :m]
+
+
+@pytest.mark.parametrize("N,d,m,k,r", [(1, 8, 8, 2, 2), (130, 72, 40, 20, 13), (300, 264, 136, 100, 60), (1023, 520, 8, 200, 120)])
+def test_every_input_at_the_end_of_its_allocation(ctx, N, d, m, k, r):
+    """Weight gradient (row-major and packed C), reconstruction (both) and the fused forward (both weight layouts)
+    with each matrix input closing an allocation of its own; leading dimensions padded by one 16-byte chunk where
+    the columns are not a multiple of 8.  Results against the oracle as everywhere."""
+    from paper_2602_23111_amd.prac import C_PACKED
+    c, s = k + r, (d - k) / r
+    up8 = lambda v: (v + 7) // 8 * 8
+    Xt = si.round_to(si.activation(N, d, 0.8, seed=N + d)[0], "bf16")
+    dYt = si.round_to(si.grad_output(N, m, 1e-2, seed=N), "bf16")
+    P32, P64 = basis32(d, c, seed=c)
+    Pd = P32.to(DEV)
+    lp_src = ctx.pack_basis(Pd)
+    lp = at_end_of_own_allocation(lp_src.cpu().view(1, -1))[0]
+    Xd = at_end_of_own_allocation(Xt, up8(d))
+    dYd = at_end_of_own_allocation(dYt, up8(m))
+    Cm = ctx.compress(Xd, Pd, P_lp=lp)
+    Cp = ctx.compress(Xd, Pd, P_lp=lp, layout=C_PACKED)
+    torch.cuda.synchronize()
+    C64 = si.as_f64(Cm)
+    assert rel_fro(C64, orc.compress(si.as_f64(Xt), P64)) < 1e-2
+    Cm_end = at_end_of_own_allocation(Cm.cpu(), up8(c))
+    Cp_end = at_end_of_own_allocation(Cp.cpu().view(1, -1))[0]
+    ref_dw = orc.weight_grad(C64, si.as_f64(dYt), P64, k, s)
+    ref_xh = orc.reconstruct(C64, P64, k, s)
+    for Cx, layout in ((Cm_end, 0), (Cp_end, C_PACKED)):
+        dW = ctx.weight_grad(Cx, dYd, Pd, k, r, s, P_lp=lp, layout=layout)
+        Xh = ctx.reconstruct(Cx, Pd, k, r, s, N=N, layout=layout)
+        torch.cuda.synchronize()
+        assert rel_fro(si.as_f64(dW), ref_dw) < 1e-2
+        assert rel_fro(si.as_f64(Xh), ref_xh) < 1e-2
+    for w_layout in (0, 1):
+        Wt = si.round_to(np.random.default_rng(m).standard_normal((d, m) if w_layout == 0 else (m, d)) * 0.05, "bf16")
+        Wd = at_end_of_own_allocation(Wt, up8(Wt.shape[1]))
+        Y, C2 = ctx.compress_fused_fwd(Xd, Wd, Pd, w_layout=w_layout, P_lp=lp)
+        torch.cuda.synchronize()
+        W64 = si.as_f64(Wt) if w_layout == 0 else si.as_f64(Wt).T
+        assert rel_fro(si.as_f64(Y), orc.forward(si.as_f64(Xt), W64)) < 1e-2
+        assert rel_fro(si.as_f64(C2), orc.compress(si.as_f64(Xt), P64)) < 1e-2
+
+
 @pytest.mark.parametrize("N,d,c", [(2048, 512, 64), (777, 328, 72), (515, 320, 256), (130, 328, 300), (17, 64, 33)])
 def test_compress_packed_layout(ctx, N, d, c):
     # same numbers as the row-major result, stored in the documented block order, zero padded
