@@ -31,8 +31,9 @@
  *   - Size limits (PRAC_EINVAL beyond them): 1 <= N < 2^31 tokens,
  *     1 <= d, m <= 2^20 features.
  *   - bf16 fast paths need 16-byte aligned base pointers and leading
- *     dimensions that are multiples of 8 elements; otherwise a slower generic
- *     kernel runs (same results to rounding).  They read rows in whole 16-byte
+ *     dimensions that are multiples of 8 elements (and at most 2^23, times the
+ *     row stride where one applies); otherwise a slower generic kernel runs
+ *     (same results to rounding).  They read rows in whole 16-byte
  *     chunks: a matrix of R rows with leading dimension ld must own R * ld
  *     elements (the up to 7 elements after a row's last column may be read,
  *     never used, also in the last row); nothing outside those R * ld elements

@@ -553,7 +553,8 @@ bool can_track(const void* X, prac_dtype xdt, int64_t rows, int64_t d, int64_t l
   // ldx itself a multiple of 8 (not only the pitch ldx * row_stride of the sampled rows): the streaming kernels
   // read a row in whole 16-byte chunks, and the last chunk of the last row must lie inside that row's ldx elements
   return o.warm_start && o.oversample < 0 && o.iters >= 1 && k > 0 && k <= 1024 && xdt == PRAC_BF16 &&
-         (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ldx % 8 == 0 && rows >= 256 && rows >= k &&
+         (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ldx % 8 == 0 &&
+         ldx * (o.row_stride > 0 ? o.row_stride : 1) <= PRAC_MAX_STREAM_PITCH && rows >= 256 && rows >= k &&
          rows < ((int64_t)1 << 31) && d >= 128;
 }
 

@@ -114,7 +114,8 @@ ProfScope::~ProfScope() {
 
 namespace {
 inline bool gram_fast(const void* X, prac_dtype xdt, int64_t rows, int64_t ldx, int64_t row_stride) {
-  return xdt == PRAC_BF16 && aligned16(X) && ldx % 8 == 0 && rows < ((int64_t)1 << 31);
+  return xdt == PRAC_BF16 && aligned16(X) && ldx % 8 == 0 && rows < ((int64_t)1 << 31) &&
+         ldx * (row_stride > 0 ? row_stride : 1) <= PRAC_MAX_STREAM_PITCH;
 }
 inline int gram_splits(int n_cu, int64_t d, int64_t rows) {
   const int tiles = (int)(((d + 127) / 128) * ((d + 127) / 128));
@@ -509,7 +510,8 @@ static int compress_impl(prac_ctx* ctx, const void* X, prac_dtype xdt, int64_t N
                          int64_t ldp, int c, void* Y, int64_t ldy, void* C, int64_t ldc, int c_layout) {
   const bool fused = W != nullptr;
   const bool packed = c_layout == PRAC_C_PACKED;
-  const bool fast = xdt == PRAC_BF16 && aligned16(X) && ldx % 8 == 0 && N < ((int64_t)1 << 31);
+  const bool fast = xdt == PRAC_BF16 && aligned16(X) && ldx % 8 == 0 && ldx <= PRAC_MAX_STREAM_PITCH &&
+                    N < ((int64_t)1 << 31);
   if (packed && (xdt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
   const CompressPlan q = plan_compress(fast, fused, packed, P_lp != nullptr, xdt, N, d, c, m);
   if (q.bytes) {
@@ -784,7 +786,8 @@ int wgrad_check(const void* C, prac_dtype dt, int64_t N, int64_t ldc, int c_layo
 }
 bool wgrad_is_fast(prac_dtype dt, int64_t N, int n_out, const void* const* dY, const int64_t* lddy) {
   bool fast = dt == PRAC_BF16 && N < ((int64_t)1 << 31);
-  for (int h = 0; h < n_out; ++h) fast = fast && aligned16(dY[h]) && lddy[h] % 8 == 0;
+  for (int h = 0; h < n_out; ++h)
+    fast = fast && aligned16(dY[h]) && lddy[h] % 8 == 0 && lddy[h] <= PRAC_MAX_STREAM_PITCH;
   return fast;
 }
 
@@ -901,7 +904,7 @@ int prac_reconstruct(prac_ctx* ctx, const void* C, prac_dtype dt, int64_t N, int
   const int c = k + r;
   const bool packed = c_layout == PRAC_C_PACKED;
   if (packed && (dt != PRAC_BF16 || !aligned16(C))) return PRAC_EUNSUPPORTED;
-  const bool rm_ok = !packed && aligned16(C) && ldc % 8 == 0;
+  const bool rm_ok = !packed && aligned16(C) && ldc % 8 == 0 && ldc <= PRAC_MAX_STREAM_PITCH;
   const bool fast = dt == PRAC_BF16 && (packed || rm_ok) && N < ((int64_t)1 << 31);
   const ReconPlan q = plan_reconstruct(fast, dt, N, d, c, packed, ldc);
   if (q.bytes) {

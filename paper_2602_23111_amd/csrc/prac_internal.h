@@ -56,6 +56,9 @@ struct WsPlan {
 int prac_ws_reserve(prac_ctx* ctx, size_t bytes);  // PRAC_OK / PRAC_ENOMEM / PRAC_EHIP
 
 static inline int64_t round_up64(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+// The streaming kernels address a row of a tile as a 32-bit byte offset from the tile's first row (at most 128
+// rows of `pitch` 2-byte elements): row pitches up to this many elements keep it below 2^32.
+constexpr int64_t PRAC_MAX_STREAM_PITCH = (int64_t)1 << 23;
 
 // ---- bf16 MFMA GEMM ---------------------------------------------------------
 // Out(M x N) = sum_k A(m,k) * B(k,n) over bf16 operands with fp32 accumulation.

@@ -1361,6 +1361,7 @@ int set_smem(prac_ctx* ctx, K kern, size_t bytes, bool& done) {
 int launch_compress_ws(prac_ctx* ctx, const bf16_t* X, int64_t ldx, int N, int d, const bf16_t* Pfrag, int ncb, int c,
                        bf16_t* C, int64_t ldc, bool packed, const bf16_t* Wfrag, int ncb_w, int m, bf16_t* Y,
                        int64_t ldy) {
+  if (ldx > PRAC_MAX_STREAM_PITCH) return PRAC_EINVAL;  // callers route wider pitches to the strided kernels
   CompressWsArgs a;
 #ifdef PRAC_WS_TIMESTAMPS
   a.stamps = g_ws_stamps;
@@ -1436,6 +1437,8 @@ void fill_ctdy_args(CtdyWsArgs& a, const bf16_t* Cpk, int c, int N, int n_out, c
 int launch_ctdy_ws(prac_ctx* ctx, const bf16_t* Cpk, int c, int N, int n_out, const bf16_t* const* dY,
                    const int64_t* lddy, const int* m, float* const* slabs, int splits) {
   if (n_out < 1 || n_out > PRAC_CTDY_MAX_OUT) return PRAC_EINVAL;
+  for (int h = 0; h < n_out; ++h)
+    if (lddy[h] > PRAC_MAX_STREAM_PITCH) return PRAC_EINVAL;
   CtdyWsArgs a{};
   fill_ctdy_args(a, Cpk, c, N, n_out, dY, lddy, m, slabs, splits);
   const size_t smem = (size_t)CW_STAGES * CW_STAGE;
